@@ -1,0 +1,90 @@
+"""Seeded Q/K/V values for a workload.
+
+Values are standard normal times the workload's data_scale, rounded ONCE to the
+pool dtype here; the HIP library and the oracle both consume these rounded
+values (the oracle widens them exactly to fp64), so a parity tolerance covers
+only arithmetic, never input rounding.
+
+Each tree node and each decode step has its own counter-based stream
+(Philox keyed by (seed, kind, index)), so any node's rows can be regenerated
+alone, e.g. for a sampled parity check at a size whose full data would not fit
+in host memory.
+"""
+from __future__ import annotations
+
+from typing import Tuple
+
+import numpy as np
+
+_KIND_NODE = 1
+_KIND_STEP_Q = 2
+_KIND_SPEC = 3
+_KIND_CHILD_ROW = 4
+
+
+def _stream(seed: int, kind: int, index: int) -> np.random.Generator:
+    key = (np.uint64(seed) << np.uint64(8)) | np.uint64(kind)
+    return np.random.Generator(np.random.Philox(key=[int(key), int(index)]))
+
+
+def round_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns (uint16), round-to-nearest-even.  Finite inputs only."""
+    b = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (b >> np.uint32(16)) & np.uint32(1)
+    r = (b + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def quantise(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round fp32 values to the pool dtype and return them as fp32 (exactly representable)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "f32":
+        return x
+    if dtype == "bf16":
+        return bf16_bits_to_f32(round_to_bf16_bits(x))
+    raise ValueError(dtype)
+
+
+def _normal(gen: np.random.Generator, shape, scale: float, dtype: str) -> np.ndarray:
+    x = gen.standard_normal(size=shape, dtype=np.float32) * np.float32(scale)
+    return quantise(x, dtype)
+
+
+def node_kv(w, node_idx: int) -> Tuple[np.ndarray, np.ndarray]:
+    """K and V rows of one tree node: two fp32 arrays [seg_len, n_kv_heads, head_dim]."""
+    h = w.heads
+    n = w.nodes[node_idx].seg_len
+    gen = _stream(w.seed, _KIND_NODE, node_idx)
+    shape = (n, h.n_kv_heads, h.head_dim)
+    k = _normal(gen, shape, w.data_scale, h.dtype)
+    v = _normal(gen, shape, w.data_scale, h.dtype)
+    return k, v
+
+
+def step_q(w, step: int, n_rows: int) -> np.ndarray:
+    """Queries of one decode step: fp32 [n_rows, n_q_heads, head_dim]."""
+    h = w.heads
+    gen = _stream(w.seed, _KIND_STEP_Q, step)
+    return _normal(gen, (n_rows, h.n_q_heads, h.head_dim), w.data_scale, h.dtype)
+
+
+def spec_step_qkv(w, step: int, n_rows: int, n_cand: int):
+    """Candidate q, k, v of one speculative step: q [n, C, Hq, d]; k, v [n, C, Hkv, d]."""
+    h = w.heads
+    gen = _stream(w.seed, _KIND_SPEC, step)
+    q = _normal(gen, (n_rows, n_cand, h.n_q_heads, h.head_dim), w.data_scale, h.dtype)
+    k = _normal(gen, (n_rows, n_cand, h.n_kv_heads, h.head_dim), w.data_scale, h.dtype)
+    v = _normal(gen, (n_rows, n_cand, h.n_kv_heads, h.head_dim), w.data_scale, h.dtype)
+    return q, k, v
+
+
+def child_rows(w, step: int, n_rows: int):
+    """K, V of the single row a freshly forked child receives: [n, Hkv, d] each."""
+    h = w.heads
+    gen = _stream(w.seed, _KIND_CHILD_ROW, step)
+    shape = (n_rows, h.n_kv_heads, h.head_dim)
+    return _normal(gen, shape, w.data_scale, h.dtype), _normal(gen, shape, w.data_scale, h.dtype)

@@ -1,0 +1,288 @@
+"""Pins for the numeric half of the oracle (CPU only).
+
+Each test fixes the oracle to something other than itself: a library routine on a
+special case, a closed form, an invariant, or brute force on tiny inputs.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import DenseThreads, attend, attend_spec
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _python_attend(q, K, V, scale):
+    """Scalar-loop softmax attention in Python floats (fp64), no numpy linear algebra."""
+    n_q, d = len(q), len(q[0])
+    T, n_kv = len(K), len(K[0])
+    g = n_q // n_kv
+    out = [[0.0] * d for _ in range(n_q)]
+    for h in range(n_q):
+        kv = h // g
+        s = []
+        for j in range(T):
+            acc = 0.0
+            for x in range(d):
+                acc += q[h][x] * K[j][kv][x]
+            s.append(acc * scale)
+        m = max(s)
+        e = [math.exp(x - m) for x in s]
+        z = sum(e)
+        for j in range(T):
+            for x in range(d):
+                out[h][x] += (e[j] / z) * V[j][kv][x]
+    return np.array(out)
+
+
+# p1: a thread that never forks is ordinary causal decode attention ------------
+@pytest.mark.parametrize("T,n_q,n_kv,d", [(1, 2, 2, 8), (17, 4, 4, 16), (40, 8, 2, 32)])
+def test_no_fork_equals_causal_sdpa_last_row(T, n_q, n_kv, d):
+    r = _rng(T)
+    k = r.standard_normal((T, n_kv, d))
+    v = r.standard_normal((T, n_kv, d))
+    qs = r.standard_normal((T, n_q, d))  # a query for every position
+    g = n_q // n_kv
+    # library routine: causal self-attention over the whole sequence, fp64
+    tq = torch.from_numpy(qs).permute(1, 0, 2)[None]  # [1, Hq, T, d]
+    tk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(g, dim=0)[None]
+    tv = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(g, dim=0)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)[0]  # [Hq, T, d]
+    o = DenseThreads(n_q, n_kv, d)
+    t = o.create()
+    for j in range(T):
+        o.append(t, k[j:j + 1], v[j:j + 1])  # append first, then decode (own row attended)
+        out = o.decode(qs[j][None], [t])[0]
+        np.testing.assert_allclose(out, ref[:, j, :].numpy(), rtol=0, atol=1e-12)
+
+
+# brute force in scalar Python on tiny inputs --------------------------------
+@pytest.mark.parametrize("T,n_q,n_kv,d", [(1, 1, 1, 1), (3, 2, 1, 2), (5, 4, 2, 3), (7, 6, 3, 2)])
+def test_attend_matches_scalar_python(T, n_q, n_kv, d):
+    r = _rng(100 + T)
+    q = r.standard_normal((n_q, d))
+    K = r.standard_normal((T, n_kv, d))
+    V = r.standard_normal((T, n_kv, d))
+    scale = 0.37
+    np.testing.assert_allclose(attend(q, K, V, scale), _python_attend(q.tolist(), K.tolist(), V.tolist(), scale),
+                               rtol=0, atol=1e-13)
+
+
+# GQA head mapping: q head h must read kv head h // g ---------------------------
+def test_gqa_head_mapping_revealed_by_values():
+    n_q, n_kv, d, T = 8, 2, 4, 6
+    r = _rng(5)
+    K = r.standard_normal((T, n_kv, d))
+    V = np.zeros((T, n_kv, d))
+    for kv in range(n_kv):
+        V[:, kv, :] = 10.0 + kv
+    out = attend(r.standard_normal((n_q, d)), K, V, 0.5)
+    for h in range(n_q):
+        np.testing.assert_allclose(out[h], 10.0 + h // 4, atol=1e-12)
+
+
+# p2: q = 0 gives the mean of V over exactly the root path ---------------------
+def _build_tree_with_token_ids(o, parents, seg_lens, n_kv, d, rng):
+    """Append rows whose V value is the token's global id; returns per-node thread id and id lists."""
+    tid, ids, next_id = {}, {}, 0
+    kids_of = {i: [c for c, p in enumerate(parents) if p == i] for i in range(len(parents))}
+    order = []
+
+    def visit(i):
+        nonlocal next_id
+        own = list(range(next_id, next_id + seg_lens[i]))
+        next_id += seg_lens[i]
+        ids[i] = (ids[parents[i]] if parents[i] >= 0 else []) + own
+        if own:
+            v = np.broadcast_to(np.array(own, dtype=np.float64)[:, None, None], (len(own), n_kv, d))
+            o.append(tid[i], rng.standard_normal((len(own), n_kv, d)), v)
+        if kids_of[i]:
+            new = o.fork(tid[i], len(kids_of[i]))
+            o.free(tid[i])
+            for c, t in zip(kids_of[i], new):
+                tid[c] = t
+            for c in kids_of[i]:
+                visit(c)
+        else:
+            order.append(i)
+
+    for i, p in enumerate(parents):
+        if p < 0:
+            tid[i] = o.create()
+            visit(i)
+    return tid, ids, order
+
+
+def test_zero_query_reveals_attended_token_set():
+    n_q = n_kv = 2
+    d = 4
+    parents = [-1, 0, 0, 0, 2, 2, -1, 6]
+    seg_lens = [24, 8, 5, 12, 1, 17, 3, 16]
+    o = DenseThreads(n_q, n_kv, d)
+    tid, ids, leaves = _build_tree_with_token_ids(o, parents, seg_lens, n_kv, d, _rng(0))
+    threads = [tid[i] for i in leaves]
+    out = o.decode(np.zeros((len(threads), n_q, d)), threads)
+    for row, i in zip(out, leaves):
+        np.testing.assert_allclose(row, np.mean(ids[i]), atol=1e-9)
+        assert o.length(tid[i]) == len(ids[i])
+    # second moment pins the exact multiset, not just its mean: V -> id^2
+    o2 = DenseThreads(n_q, n_kv, d)
+    t = o2.create()
+    vals = np.array(ids[leaves[1]], dtype=np.float64)
+    o2.append(t, np.zeros((len(vals), n_kv, d)), np.broadcast_to((vals ** 2)[:, None, None], (len(vals), n_kv, d)))
+    np.testing.assert_allclose(o2.decode(np.zeros((1, n_q, d)), [t])[0], np.mean(vals ** 2), atol=1e-6)
+
+
+# p3: one key with logit alpha, all others orthogonal -> closed form ---------------
+@pytest.mark.parametrize("where", ["ancestor", "own"])
+def test_peaked_closed_form(where):
+    n_q = n_kv = 1
+    d, alpha = 8, 40.0
+    r = _rng(7)
+    o = DenseThreads(n_q, n_kv, d)
+    q = r.standard_normal(d)
+    scale = o.scale
+
+    def orth_rows(n):
+        x = r.standard_normal((n, d))
+        return x - np.outer(x @ q, q) / (q @ q)
+
+    kstar = alpha * q / (scale * (q @ q))
+    root = o.create()
+    k_root, v_root = orth_rows(20), r.standard_normal((20, d))
+    k_leaf, v_leaf = orth_rows(9), r.standard_normal((9, d))
+    if where == "ancestor":
+        k_root[3], star_v = kstar, v_root[3]
+    else:
+        k_leaf[5], star_v = kstar, v_leaf[5]
+    o.append(root, k_root[:, None, :], v_root[:, None, :])
+    a, b = o.fork(root, 2)
+    o.free(root)
+    o.append(a, k_leaf[:, None, :], v_leaf[:, None, :])
+    o.append(b, orth_rows(4)[:, None, :], r.standard_normal((4, 1, d)))
+    out = o.decode(q[None, None, :], [a])[0, 0]
+    T = 29
+    others = v_root.sum(0) + v_leaf.sum(0) - star_v
+    expect = (math.exp(alpha) * star_v + others) / (math.exp(alpha) + T - 1)
+    np.testing.assert_allclose(out, expect, rtol=0, atol=1e-9)
+    np.testing.assert_allclose(out, star_v, atol=1e-12 + 40 * T * math.exp(-alpha))
+
+
+# softmax shift invariance and the scale actually being applied -----------------
+def test_scale_is_applied_and_default_is_inv_sqrt_d():
+    r = _rng(11)
+    q, K, V = r.standard_normal((2, 16)), r.standard_normal((5, 2, 16)), r.standard_normal((5, 2, 16))
+    o = DenseThreads(2, 2, 16)
+    assert o.scale == pytest.approx(0.25)
+    t = o.create()
+    o.append(t, K, V)
+    np.testing.assert_allclose(o.decode(q[None], [t])[0], attend(q, K, V, 0.25), atol=0)
+    # scaling q by c equals scaling the softmax scale by c
+    np.testing.assert_allclose(attend(3.0 * q, K, V, 0.25), attend(q, K, V, 0.75), atol=1e-13)
+    assert np.abs(attend(q, K, V, 0.25) - attend(q, K, V, 0.75)).max() > 1e-3
+
+
+# p4: children of one fork see identical prefix logits -------------------------
+def test_siblings_see_identical_prefix_logits():
+    n_q, n_kv, d = 4, 2, 8
+    r = _rng(3)
+    o = DenseThreads(n_q, n_kv, d)
+    root = o.create()
+    o.append(root, r.standard_normal((21, n_kv, d)), r.standard_normal((21, n_kv, d)))
+    kids = o.fork(root, 3)
+    for k, n in zip(kids, (8, 5, 12)):
+        o.append(k, r.standard_normal((n, n_kv, d)), r.standard_normal((n, n_kv, d)))
+    q = r.standard_normal((n_q, d))
+    base = o.logits(q, root)
+    for k in kids:
+        lg = o.logits(q, k)
+        assert np.array_equal(lg[:, :21], base)  # bit-identical on the shared prefix
+    # and a fork is a deep copy: growing one child leaves the parent and its siblings untouched
+    assert o.length(root) == 21 and [o.length(k) for k in kids] == [29, 26, 33]
+
+
+# p5: attention is a set operation over the root path ---------------------------
+def test_order_invariance():
+    r = _rng(9)
+    q, K, V = r.standard_normal((3, 8)), r.standard_normal((33, 3, 8)), r.standard_normal((33, 3, 8))
+    perm = r.permutation(33)
+    np.testing.assert_allclose(attend(q, K, V, 0.3), attend(q, K[perm], V[perm], 0.3), atol=1e-14)
+
+
+# p6: log-sum-exp merge of partial results over any split equals the whole --------
+def test_merge_identity_every_split_point():
+    r = _rng(21)
+    T, d = 11, 4
+    q, K, V = r.standard_normal((1, d)), 3 * r.standard_normal((T, 1, d)), r.standard_normal((T, 1, d))
+    scale = 0.9
+    whole = attend(q, K, V, scale)[0]
+
+    def partial(lo, hi):
+        s = scale * (K[lo:hi, 0] @ q[0])
+        m = s.max()
+        p = np.exp(s - m)
+        return m, p.sum(), p @ V[lo:hi, 0]
+
+    for cuts in itertools.chain(itertools.combinations(range(1, T), 1), itertools.combinations(range(1, T), 2)):
+        edges = (0,) + cuts + (T,)
+        parts = [partial(a, b) for a, b in zip(edges[:-1], edges[1:])]
+        m = max(p[0] for p in parts)
+        l = sum(p[1] * math.exp(p[0] - m) for p in parts)
+        acc = sum(p[2] * math.exp(p[0] - m) for p in parts)
+        np.testing.assert_allclose(acc / l, whole, atol=1e-13)
+
+
+# p8: the multi-candidate step ----------------------------------------------------
+def test_spec_single_candidate_equals_append_then_decode():
+    n_q, n_kv, d = 4, 2, 8
+    r = _rng(13)
+    o = DenseThreads(n_q, n_kv, d)
+    t = o.create()
+    o.append(t, r.standard_normal((19, n_kv, d)), r.standard_normal((19, n_kv, d)))
+    q = r.standard_normal((1, 1, n_q, d))
+    ck, cv = r.standard_normal((1, 1, n_kv, d)), r.standard_normal((1, 1, n_kv, d))
+    spec = o.decode_spec(q, ck, cv, np.array([[1]], dtype=np.uint8), [t])[0, 0]
+    o.append(t, ck[0], cv[0])
+    np.testing.assert_allclose(spec, o.decode(q[0], [t])[0], atol=1e-14)
+
+
+def test_spec_chain_mask_equals_sequential_steps():
+    n_q, n_kv, d, C = 2, 2, 4, 5
+    r = _rng(17)
+    o = DenseThreads(n_q, n_kv, d)
+    t = o.create()
+    o.append(t, r.standard_normal((7, n_kv, d)), r.standard_normal((7, n_kv, d)))
+    q = r.standard_normal((1, C, n_q, d))
+    ck, cv = r.standard_normal((1, C, n_kv, d)), r.standard_normal((1, C, n_kv, d))
+    chain = np.array([[(1 << (c + 1)) - 1 for c in range(C)]], dtype=np.uint8)
+    spec = o.decode_spec(q, ck, cv, chain, [t])[0]
+    for c in range(C):
+        o.append(t, ck[0, c:c + 1], cv[0, c:c + 1])
+        np.testing.assert_allclose(spec[c], o.decode(q[0, c][None], [t])[0], atol=1e-14)
+
+
+def test_spec_tree_mask_hides_other_branch():
+    # candidates 1 and 2 are both children of 0: 2 must not see 1
+    n_q = n_kv = 1
+    d = 2
+    K = np.zeros((1, 1, d))
+    V = np.zeros((1, 1, d))
+    ck = np.zeros((3, 1, d))
+    cv = np.array([[[1.0, 0.0]], [[100.0, 0.0]], [[0.0, 1.0]]])
+    masks = np.array([0b001, 0b011, 0b101], dtype=np.uint8)
+    out = attend_spec(np.zeros((3, 1, d)), K, V, ck, cv, masks, 1.0)
+    np.testing.assert_allclose(out[0, 0], [0.5, 0.0])  # cached row + itself
+    np.testing.assert_allclose(out[1, 0], [101.0 / 3, 0.0])
+    np.testing.assert_allclose(out[2, 0], [1.0 / 3, 1.0 / 3])  # no 100 from the other branch
+
+
+def test_empty_thread_is_rejected():
+    o = DenseThreads(1, 1, 2)
+    t = o.create()
+    with pytest.raises(ValueError):
+        o.decode(np.zeros((1, 1, 2)), [t])
