@@ -23,5 +23,9 @@ from .data import (  # noqa: F401
     node_kv,
     step_q,
     quantise,
+    spec_step_qkv,
+    child_rows,
+    node_kv_device,
+    rows_device,
 )
 from .spec_loop import SpecLoopPlan, SpecStep, draw_candidate_tree, mask_rows_from_parents  # noqa: F401

@@ -88,3 +88,34 @@ def child_rows(w, step: int, n_rows: int):
     gen = _stream(w.seed, _KIND_CHILD_ROW, step)
     shape = (n_rows, h.n_kv_heads, h.head_dim)
     return _normal(gen, shape, w.data_scale, h.dtype), _normal(gen, shape, w.data_scale, h.dtype)
+
+
+# ---------------------------------------------------------------------------
+# Device-side twins for full-size runs, where drawing gigabytes on the host would
+# dominate the run.  Same recipe (standard normal * data_scale, rounded once to the
+# pool dtype) from torch's generator on the GPU; values differ from the numpy
+# streams above but are just as reproducible.  The oracle receives the very
+# tensors that were handed to the library, copied to the host.
+# ---------------------------------------------------------------------------
+def _torch_normal(shape, scale: float, dtype: str, seed: int, device):
+    import torch
+
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) & 0x7FFFFFFFFFFFFFFF)
+    x = torch.randn(shape, generator=g, device=device, dtype=torch.float32) * float(scale)
+    return x if dtype == "f32" else x.to(torch.bfloat16)
+
+
+def node_kv_device(w, node_idx: int, device="cuda:0"):
+    h = w.heads
+    shape = (w.nodes[node_idx].seg_len, h.n_kv_heads, h.head_dim)
+    base = (int(w.seed) << 40) + (int(node_idx) << 2)
+    return (_torch_normal(shape, w.data_scale, h.dtype, base + 1, device),
+            _torch_normal(shape, w.data_scale, h.dtype, base + 2, device))
+
+
+def rows_device(w, tag: int, index: int, shape, device="cuda:0"):
+    """Any other seeded tensor of a run (queries, per-step rows): stream (tag, index)."""
+    h = w.heads
+    seed = (int(w.seed) << 40) + (int(tag) << 32) + (int(index) << 2) + 3
+    return _torch_normal(tuple(shape), w.data_scale, h.dtype, seed, device)

@@ -1,0 +1,238 @@
+/*
+ * apar.h - C ABI of the fork-tree paged-KV decode path of APAR
+ * (auto-parallel auto-regressive decoding, arXiv 2401.06761) for AMD MI355X.
+ *
+ * The library keeps a fixed pool of 16-token KV blocks in caller-owned device
+ * memory.  A generation thread (the paper's "sequence", Sec. 2.3) is a length
+ * and a table of block ids.  A fork gives children the parent's table instead
+ * of copies of its KV rows (Sec. 2.3: the fork shares the prefix and copies at
+ * most one block), a finished thread gives back the blocks only it holds
+ * (Alg. 1 ReleaseCache; Sec. 2.4 feature 2), and a decoding token attends to
+ * the tokens on its own root path and to nothing else (Sec. 2.2 "Training
+ * attention"; Sec. 2.4 feature 3).
+ *
+ * Conventions for every call
+ *   - returns an apar_status; never throws, never aborts;
+ *   - pointers named *_dev are DEVICE pointers, every other pointer is a HOST
+ *     pointer.  The caller owns all of them, the KV pool buffer included, and
+ *     must keep device buffers alive until the stream has run the work;
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream).  Device work is enqueued on it and the call returns without
+ *     waiting.  Host bookkeeping changes at call time, so introspection
+ *     reflects every earlier call.  Calls on one pool must be issued from one
+ *     host thread, and on one stream at a time (work on different streams
+ *     must be ordered by the caller);
+ *   - a call that fails with any status but APAR_ERR_HIP leaves the pool exactly
+ *     as it was; after APAR_ERR_HIP the pool should be destroyed;
+ *   - the layout of the pool buffer is private to the library (KV tiles are
+ *     stored in the operand order of the matrix cores, not row-major).
+ */
+#ifndef APAR_H
+#define APAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__) || defined(__clang__)
+#define APAR_API __attribute__((visibility("default")))
+#else
+#define APAR_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct apar_pool apar_pool; /* opaque; created and destroyed by the library */
+typedef int32_t apar_thread;        /* >= 0; issued 0, 1, 2, ... per pool; never reused */
+
+typedef enum apar_status {
+    APAR_OK = 0,
+    APAR_ERR_INVALID_ARG = -1,     /* bad pointer, size, count or configuration          */
+    APAR_ERR_INVALID_THREAD = -2,  /* id never issued, or already freed                  */
+    APAR_ERR_OUT_OF_BLOCKS = -3,   /* the pool cannot supply the blocks the call needs   */
+    APAR_ERR_THREAD_CAPACITY = -4, /* more than max_threads ids would be issued          */
+    APAR_ERR_HIP = -5,             /* a HIP runtime call failed (see apar_last_hip_error) */
+    APAR_ERR_UNSUPPORTED = -6      /* shape outside what the kernels are built for       */
+} apar_status;
+
+enum { APAR_F32 = 0, APAR_BF16 = 1 };
+
+typedef struct apar_pool_config {
+    int32_t n_q_heads;   /* Hq; multiple of n_kv_heads                                   */
+    int32_t n_kv_heads;  /* Hkv                                                          */
+    int32_t head_dim;    /* d: 128 for APAR_BF16; 64 or 128 for APAR_F32                 */
+    int32_t block_size;  /* tokens per KV block; must be 16                              */
+    int32_t dtype;       /* APAR_F32 or APAR_BF16: type of K, V, Q and of the output     */
+    int32_t max_threads; /* upper bound on ids ever issued by this pool                  */
+    int64_t num_blocks;  /* N: blocks in the pool, < 2^27                                */
+    float softmax_scale; /* 0 means 1/sqrt(head_dim)                                     */
+} apar_pool_config;
+
+typedef struct apar_stats {
+    int64_t total_blocks;
+    int64_t used_blocks;    /* blocks with refcount > 0                                  */
+    int64_t free_blocks;
+    int64_t live_threads;
+    int64_t threads_issued;
+    int64_t cow_copies;     /* copy-on-write block copies since creation                 */
+    int64_t block_bytes;    /* 2 * Hkv * 16 * d * element size                           */
+    int64_t bytes_resident; /* used_blocks * block_bytes                                 */
+    int64_t bytes_vanilla;  /* sum over live threads of ceil(len/16) * block_bytes: what */
+                            /* a layout that copies the prefix on every fork would hold  */
+                            /* (the paper's contiguous-cache setting, App. C.1)          */
+} apar_stats;
+
+/* What the last apar_decode_attention[_spec] call on this pool scheduled. */
+typedef struct apar_plan_info {
+    int64_t n_threads;         /* listed threads                                         */
+    int64_t n_segments;        /* maximal runs of blocks shared by one set of threads    */
+    int64_t n_units;           /* (block run, kv head) work units launched               */
+    int64_t n_partial_rows;    /* (unit, thread) partial results merged afterwards       */
+    int64_t unique_blocks;     /* distinct blocks read                                   */
+    int64_t unique_tokens;     /* filled slots in those blocks: each cached row once     */
+    int64_t path_tokens;       /* sum of the listed threads' lengths                     */
+    int64_t algorithmic_bytes; /* unique_tokens * 2*Hkv*d*e + q read + output written    */
+                               /* (+ candidates' k, v for the multi-candidate call)      */
+} apar_plan_info;
+
+/* Device time measured with HIP events on the caller's stream while profiling is on. */
+typedef struct apar_profile {
+    int64_t n_decode_calls;
+    double attention_kernel_ms; /* sum over calls: the partial-attention kernel           */
+    double merge_kernel_ms;     /* sum over calls: the merge / normalise kernel            */
+    double plan_host_ms;        /* sum over calls: host time building + staging the plan   */
+    int64_t n_append_calls;
+    double append_kernels_ms;   /* sum over calls: copy-on-write copies + row writes       */
+} apar_profile;
+
+/*
+ * Create a pool over caller-owned device memory.
+ *   kv_dev/kv_bytes : device buffer of at least num_blocks * block_bytes bytes,
+ *                     256-byte aligned; contents need not be initialised.
+ * kv_dev == NULL with kv_bytes == 0 creates a DRY-RUN pool: it keeps the same
+ * books (tables, refcounts, free list) and builds the same plans, but owns no
+ * device memory and launches nothing, e.g. to size a pool from a trace.  On a
+ * dry-run pool every *_dev argument of the other calls must be NULL and
+ * apar_read_kv_rows is an error; no call of it touches the GPU.
+ * Errors: INVALID_ARG (null pointers, block_size != 16, heads not divisible,
+ * num_blocks out of range, buffer too small or misaligned), UNSUPPORTED
+ * (head_dim / dtype combination), HIP.
+ */
+APAR_API int apar_pool_create(const apar_pool_config* cfg, void* kv_dev, size_t kv_bytes, apar_pool** out);
+
+/* Waits for the pool's outstanding device work, frees bookkeeping and staging
+ * memory (never the KV buffer).  NULL is accepted. */
+APAR_API int apar_pool_destroy(apar_pool* pool);
+
+/* A new empty root thread (the prompt sequence that starts a sequence group,
+ * Alg. 1).  Errors: THREAD_CAPACITY. */
+APAR_API int apar_thread_create(apar_pool* pool, apar_thread* out);
+
+/*
+ * Fork (Alg. 1: s' <- s; Sec. 2.3): n_children new threads whose table and
+ * length equal the parent's; every block the parent holds gains n_children
+ * references.  Allocates no block and copies nothing; the copy of a shared,
+ * partly filled tail block is deferred to the first append that needs it.  The
+ * parent stays live until freed.  children_out receives n_children
+ * consecutive ids.  Errors: INVALID_THREAD, INVALID_ARG (n_children < 1),
+ * THREAD_CAPACITY.
+ */
+APAR_API int apar_fork(apar_pool* pool, apar_thread parent, int n_children, apar_thread* children_out);
+
+/*
+ * Append n_tokens rows to one thread (Alg. 1: s.append_token).
+ *   k_dev, v_dev : [n_tokens, Hkv, d], pool dtype, row-major, contiguous.
+ * Token by token: at a block boundary a fresh block is taken; otherwise a tail
+ * block that other threads also hold is first copied to a fresh block
+ * (copy-on-write; at most one copy per call), then the row is written.
+ * n_tokens == 0 is a no-op.  Errors: INVALID_THREAD, INVALID_ARG,
+ * OUT_OF_BLOCKS (checked before anything changes), HIP.
+ */
+APAR_API int apar_append_kv(apar_pool* pool, apar_thread thread, const void* k_dev, const void* v_dev,
+                   int n_tokens, void* hip_stream);
+
+/* One row for each listed thread, processed in list order (a thread may be
+ * listed more than once).  k_dev, v_dev: [n, Hkv, d]. */
+APAR_API int apar_append_kv_batch(apar_pool* pool, const apar_thread* threads, int n, const void* k_dev,
+                         const void* v_dev, void* hip_stream);
+
+/*
+ * Decode attention (Sec. 2.2 "Training attention", Sec. 2.4 feature 3).  For
+ * listed thread i and query head h:
+ *   out[i,h] = sum_j softmax_j(scale * <q[i,h], K_j[h / (Hq/Hkv)]>) * V_j[h / (Hq/Hkv)]
+ * with j over all len(threads[i]) rows reachable through that thread's table
+ * (its ancestors' rows up to each fork point and its own rows, the newest
+ * included).  Blocks shared by several listed threads are read once and
+ * applied to all of their queries.
+ *   q_dev, out_dev : [n, Hq, d], pool dtype.   threads : host array of n ids
+ *   (duplicates allowed).  n == 0 is a no-op.
+ * Errors: INVALID_THREAD, INVALID_ARG (null pointers, n < 0, or a listed
+ * thread of length 0: softmax over no rows is undefined), HIP.
+ */
+APAR_API int apar_decode_attention(apar_pool* pool, const void* q_dev, const apar_thread* threads, int n,
+                          void* out_dev, void* hip_stream);
+
+/*
+ * Multi-candidate decode attention (verification step of speculative decoding
+ * with tree attention, Sec. 3.2 Medusa-APAR, App. C.1).  Every listed thread
+ * carries n_cand candidate tokens; candidate c attends to all cached rows of
+ * the thread and to candidate c' iff bit c' of mask_dev[i*n_cand + c] is set
+ * (every row must have its own bit set).  Candidates' K, V are not cached by
+ * this call; append the accepted ones afterwards.
+ *   q_dev, out_dev : [n, n_cand, Hq, d];  cand_k_dev, cand_v_dev : [n, n_cand, Hkv, d];
+ *   mask_dev : [n, n_cand] uint8;  1 <= n_cand <= 8.
+ */
+APAR_API int apar_decode_attention_spec(apar_pool* pool, const void* q_dev, const void* cand_k_dev,
+                               const void* cand_v_dev, const uint8_t* mask_dev, int n_cand,
+                               const apar_thread* threads, int n, void* out_dev, void* hip_stream);
+
+/* Release (Alg. 1 ReleaseCache): walks the table from its last block to its
+ * first, drops one reference from each and returns a block to the pool when no
+ * thread holds it any more.  Errors: INVALID_THREAD. */
+APAR_API int apar_free_thread(apar_pool* pool, apar_thread thread);
+
+/* ---- introspection (parity checks and reports) -------------------------- */
+APAR_API int apar_thread_len(apar_pool* pool, apar_thread thread, int64_t* len_out);
+/* Copies up to cap ids into table_out and stores the table length in n_out
+ * (INVALID_ARG if cap is too small; n_out is still set). */
+APAR_API int apar_thread_block_table(apar_pool* pool, apar_thread thread, int32_t* table_out, int cap, int* n_out);
+APAR_API int apar_block_refcount(apar_pool* pool, int32_t block, int32_t* refcount_out);
+APAR_API int apar_pool_stats(apar_pool* pool, apar_stats* out);
+APAR_API int apar_last_plan_info(apar_pool* pool, apar_plan_info* out);
+/* Tables of the last decode call's plan, for inspection.  `which`:
+ *   APAR_PLAN_UNITS    6 int32 per unit family: first index into BLOCKS, block
+ *                      count, filled slots of the last block, first index into
+ *                      SHARERS, thread count, first partial-result row; one work
+ *                      unit per family and kv head is launched;
+ *   APAR_PLAN_BLOCKS   flat block ids;   APAR_PLAN_SHARERS  flat indices into the
+ *                      listed threads;
+ *   APAR_PLAN_PATH_OFS [n+1] offsets into PATH_IDS;  APAR_PLAN_PATH_IDS  partial-
+ *                      result rows merged for each listed thread (family f, its
+ *                      j-th thread -> row first_partial_row + j).
+ * Stores the element count in n_out; INVALID_ARG if cap is too small. */
+enum { APAR_PLAN_UNITS = 0, APAR_PLAN_BLOCKS = 1, APAR_PLAN_SHARERS = 2, APAR_PLAN_PATH_OFS = 3,
+       APAR_PLAN_PATH_IDS = 4 };
+APAR_API int apar_last_plan_export(apar_pool* pool, int which, int32_t* out, int64_t cap, int64_t* n_out);
+/* Gathers rows [first, first+n) of a thread out of the pool's private layout
+ * into row-major k_out_dev, v_out_dev : [n, Hkv, d]. */
+APAR_API int apar_read_kv_rows(apar_pool* pool, apar_thread thread, int64_t first, int n, void* k_out_dev,
+                      void* v_out_dev, void* hip_stream);
+
+/* ---- measurement -------------------------------------------------------- */
+/* While on, every decode and append call brackets its kernels with HIP events. */
+APAR_API int apar_profile_enable(apar_pool* pool, int on);
+/* Waits for the recorded events, adds up the elapsed times since the last
+ * read, stores them in out and resets the sums. */
+APAR_API int apar_profile_read(apar_pool* pool, apar_profile* out);
+/* Tuning knob: blocks per work unit of the attention kernel (1..64; default 8). */
+APAR_API int apar_set_chunk_blocks(apar_pool* pool, int blocks_per_unit);
+
+APAR_API const char* apar_status_string(int status);
+/* Text of the last HIP error seen on this host thread by the library ("" if none). */
+APAR_API const char* apar_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APAR_H */

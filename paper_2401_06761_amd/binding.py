@@ -1,0 +1,299 @@
+"""ctypes binding of include/apar.h.  Names and argument order follow the header."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libapar.so")
+
+APAR_F32, APAR_BF16 = 0, 1
+
+
+class AparError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        msg = f"{where}: {apar_status_string(status)} ({status})"
+        if detail:
+            msg += f": {detail}"
+        super().__init__(msg)
+
+
+class AparPoolConfig(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("block_size", C.c_int32), ("dtype", C.c_int32), ("max_threads", C.c_int32),
+                ("num_blocks", C.c_int64), ("softmax_scale", C.c_float)]
+
+
+class AparStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("total_blocks", "used_blocks", "free_blocks", "live_threads",
+                                         "threads_issued", "cow_copies", "block_bytes", "bytes_resident",
+                                         "bytes_vanilla")]
+
+
+class AparPlanInfo(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("n_threads", "n_segments", "n_units", "n_partial_rows", "unique_blocks",
+                                         "unique_tokens", "path_tokens", "algorithmic_bytes")]
+
+
+class AparProfile(C.Structure):
+    _fields_ = [("n_decode_calls", C.c_int64), ("attention_kernel_ms", C.c_double), ("merge_kernel_ms", C.c_double),
+                ("plan_host_ms", C.c_double), ("n_append_calls", C.c_int64), ("append_kernels_ms", C.c_double)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(or python paper_2401_06761_amd/build.py).  There is no fallback path.")
+    lib = C.CDLL(_LIB_PATH)
+    P, I, V = C.c_void_p, C.c_int, C.c_void_p
+    I32P = C.POINTER(C.c_int32)
+    sig = {
+        "apar_pool_create": [C.POINTER(AparPoolConfig), V, C.c_size_t, C.POINTER(P)],
+        "apar_pool_destroy": [P],
+        "apar_thread_create": [P, I32P],
+        "apar_fork": [P, C.c_int32, I, I32P],
+        "apar_append_kv": [P, C.c_int32, V, V, I, V],
+        "apar_append_kv_batch": [P, I32P, I, V, V, V],
+        "apar_decode_attention": [P, V, I32P, I, V, V],
+        "apar_decode_attention_spec": [P, V, V, V, V, I, I32P, I, V, V],
+        "apar_free_thread": [P, C.c_int32],
+        "apar_thread_len": [P, C.c_int32, C.POINTER(C.c_int64)],
+        "apar_thread_block_table": [P, C.c_int32, I32P, I, C.POINTER(C.c_int)],
+        "apar_block_refcount": [P, C.c_int32, I32P],
+        "apar_pool_stats": [P, C.POINTER(AparStats)],
+        "apar_last_plan_info": [P, C.POINTER(AparPlanInfo)],
+        "apar_read_kv_rows": [P, C.c_int32, C.c_int64, I, V, V, V],
+        "apar_last_plan_export": [P, I, I32P, C.c_int64, C.POINTER(C.c_int64)],
+        "apar_profile_enable": [P, I],
+        "apar_profile_read": [P, C.POINTER(AparProfile)],
+        "apar_set_chunk_blocks": [P, I],
+    }
+    for name, args in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = C.c_int
+    lib.apar_status_string.argtypes = [C.c_int]
+    lib.apar_status_string.restype = C.c_char_p
+    lib.apar_last_hip_error.argtypes = []
+    lib.apar_last_hip_error.restype = C.c_char_p
+    return lib
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def _L() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = _load()
+    return _lib
+
+
+def exported_symbols() -> List[str]:
+    """Names the loaded library resolves, out of those apar.h declares."""
+    import re
+
+    hdr = open(os.path.join(os.path.dirname(_HERE), "include", "apar.h")).read()
+    names = re.findall(r"\b(apar_[a-z_0-9]+)\s*\(", hdr)
+    lib = _L()
+    return [n for n in dict.fromkeys(names) if hasattr(lib, n)]
+
+
+def apar_status_string(status: int) -> str:
+    return _L().apar_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        detail = _L().apar_last_hip_error().decode() if status == -5 else ""
+        raise AparError(status, where, detail)
+
+
+def _ids(seq: Sequence[int]):
+    n = len(seq)
+    return (C.c_int32 * max(n, 1))(*[int(x) for x in seq]), n
+
+
+def _ptr(t) -> int:
+    """Device pointer of a torch tensor (must be contiguous and on the GPU)."""
+    if t is None:
+        return 0
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous GPU tensor")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+
+        if not torch.cuda.is_available():
+            return 0  # only dry-run pools can be used without a GPU; they ignore the stream
+        return torch.cuda.current_stream().cuda_stream
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def apar_pool_create(cfg: AparPoolConfig, kv_dev, kv_bytes: Optional[int] = None) -> C.c_void_p:
+    """kv_dev: a GPU tensor, a raw device address, or None for a dry-run (bookkeeping-only) pool."""
+    if kv_dev is None:
+        ptr, kv_bytes = 0, 0
+    else:
+        ptr = kv_dev if isinstance(kv_dev, int) else _ptr(kv_dev)
+        if kv_bytes is None:
+            kv_bytes = kv_dev.numel() * kv_dev.element_size()
+    out = C.c_void_p()
+    _check(_L().apar_pool_create(C.byref(cfg), ptr, kv_bytes, C.byref(out)), "apar_pool_create")
+    return out
+
+
+def apar_pool_destroy(pool) -> None:
+    _check(_L().apar_pool_destroy(pool), "apar_pool_destroy")
+
+
+def apar_thread_create(pool) -> int:
+    out = C.c_int32()
+    _check(_L().apar_thread_create(pool, C.byref(out)), "apar_thread_create")
+    return out.value
+
+
+def apar_fork(pool, parent: int, n_children: int) -> List[int]:
+    out = (C.c_int32 * max(n_children, 1))()
+    _check(_L().apar_fork(pool, parent, n_children, out), "apar_fork")
+    return list(out[:n_children])
+
+
+def apar_append_kv(pool, thread: int, k, v, n_tokens: Optional[int] = None, stream=None) -> None:
+    if n_tokens is None:
+        n_tokens = k.shape[0]
+    _check(_L().apar_append_kv(pool, thread, _ptr(k), _ptr(v), n_tokens, _stream(stream)), "apar_append_kv")
+
+
+def apar_append_kv_batch(pool, threads: Sequence[int], k, v, stream=None) -> None:
+    arr, n = _ids(threads)
+    _check(_L().apar_append_kv_batch(pool, arr, n, _ptr(k), _ptr(v), _stream(stream)), "apar_append_kv_batch")
+
+
+def apar_decode_attention(pool, q, threads: Sequence[int], out, stream=None) -> None:
+    arr, n = _ids(threads)
+    _check(_L().apar_decode_attention(pool, _ptr(q), arr, n, _ptr(out), _stream(stream)), "apar_decode_attention")
+
+
+def apar_decode_attention_spec(pool, q, cand_k, cand_v, mask, n_cand: int, threads: Sequence[int], out,
+                               stream=None) -> None:
+    arr, n = _ids(threads)
+    _check(_L().apar_decode_attention_spec(pool, _ptr(q), _ptr(cand_k), _ptr(cand_v), _ptr(mask), n_cand, arr, n,
+                                           _ptr(out), _stream(stream)), "apar_decode_attention_spec")
+
+
+def apar_free_thread(pool, thread: int) -> None:
+    _check(_L().apar_free_thread(pool, thread), "apar_free_thread")
+
+
+def apar_thread_len(pool, thread: int) -> int:
+    out = C.c_int64()
+    _check(_L().apar_thread_len(pool, thread, C.byref(out)), "apar_thread_len")
+    return out.value
+
+
+def apar_thread_block_table(pool, thread: int) -> List[int]:
+    n = C.c_int()
+    st = _L().apar_thread_block_table(pool, thread, None, 0, C.byref(n))
+    if st not in (0, -1):
+        _check(st, "apar_thread_block_table")
+    if st == -1 and n.value == 0:
+        _check(st, "apar_thread_block_table")
+    buf = (C.c_int32 * max(n.value, 1))()
+    _check(_L().apar_thread_block_table(pool, thread, buf, n.value, C.byref(n)), "apar_thread_block_table")
+    return list(buf[: n.value])
+
+
+def apar_block_refcount(pool, block: int) -> int:
+    out = C.c_int32()
+    _check(_L().apar_block_refcount(pool, block, C.byref(out)), "apar_block_refcount")
+    return out.value
+
+
+def apar_pool_stats(pool) -> AparStats:
+    out = AparStats()
+    _check(_L().apar_pool_stats(pool, C.byref(out)), "apar_pool_stats")
+    return out
+
+
+def apar_last_plan_info(pool) -> AparPlanInfo:
+    out = AparPlanInfo()
+    _check(_L().apar_last_plan_info(pool, C.byref(out)), "apar_last_plan_info")
+    return out
+
+
+APAR_PLAN_UNITS, APAR_PLAN_BLOCKS, APAR_PLAN_SHARERS, APAR_PLAN_PATH_OFS, APAR_PLAN_PATH_IDS = range(5)
+
+
+def apar_last_plan_export(pool, which: int) -> List[int]:
+    n = C.c_int64()
+    _L().apar_last_plan_export(pool, which, None, 0, C.byref(n))
+    buf = (C.c_int32 * max(n.value, 1))()
+    _check(_L().apar_last_plan_export(pool, which, buf, n.value, C.byref(n)), "apar_last_plan_export")
+    return list(buf[: n.value])
+
+
+def apar_read_kv_rows(pool, thread: int, first: int, n: int, k_out, v_out, stream=None) -> None:
+    _check(_L().apar_read_kv_rows(pool, thread, first, n, _ptr(k_out), _ptr(v_out), _stream(stream)),
+           "apar_read_kv_rows")
+
+
+def apar_profile_enable(pool, on: bool) -> None:
+    _check(_L().apar_profile_enable(pool, int(bool(on))), "apar_profile_enable")
+
+
+def apar_profile_read(pool) -> AparProfile:
+    out = AparProfile()
+    _check(_L().apar_profile_read(pool, C.byref(out)), "apar_profile_read")
+    return out
+
+
+def apar_set_chunk_blocks(pool, blocks_per_unit: int) -> None:
+    _check(_L().apar_set_chunk_blocks(pool, blocks_per_unit), "apar_set_chunk_blocks")
+
+
+class Pool:
+    """Owns the KV buffer (a torch tensor: device memory is PyTorch's job here) and the handle."""
+
+    def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: str, num_blocks: int,
+                 max_threads: int = 1 << 20, softmax_scale: float = 0.0, device: str = "cuda:0",
+                 dry_run: bool = False):
+        import torch
+
+        self.torch_dtype = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+        e = 4 if dtype == "f32" else 2
+        self.block_bytes = 2 * n_kv_heads * 16 * head_dim * e
+        self.kv = None if dry_run else torch.empty(num_blocks * self.block_bytes, dtype=torch.uint8, device=device)
+        self.cfg = AparPoolConfig(n_q_heads, n_kv_heads, head_dim, 16, APAR_F32 if dtype == "f32" else APAR_BF16,
+                                  max_threads, num_blocks, softmax_scale)
+        self.n_q, self.n_kv, self.d = n_q_heads, n_kv_heads, head_dim
+        self.device = device
+        self.handle = apar_pool_create(self.cfg, self.kv)
+
+    def close(self) -> None:
+        if self.handle is not None:
+            apar_pool_destroy(self.handle)
+            self.handle = None
+            self.kv = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,807 @@
+// Host side of libapar: the C ABI, the block/refcount/fork bookkeeping, the
+// plan builder that groups threads by the blocks they share, and the staging of
+// small tables to the device.  Every device step runs in the HIP kernels; this
+// file only decides which blocks they touch.
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "apar_internal.hpp"
+
+using namespace apar;
+
+namespace {
+
+thread_local std::string g_last_hip_error;
+
+bool hip_ok(hipError_t e, const char* what) {
+    if (e == hipSuccess) return true;
+    g_last_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return false;
+}
+#define HIP_TRY(expr)                                  \
+    do {                                               \
+        if (!hip_ok((expr), #expr)) return APAR_ERR_HIP; \
+    } while (0)
+
+struct Thread {
+    bool live = false;
+    int64_t len = 0;
+    std::vector<int32_t> table;
+};
+
+// A pinned host buffer and its device twin, reused round-robin.  The event marks
+// the last device work that read the pair, so a slot is only rewritten after it.
+struct StageSlot {
+    char* host = nullptr;
+    char* dev = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool pending = false;
+};
+constexpr int kStageSlots = 4;
+
+struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr, c = nullptr;  // a..b first kernel(s), b..c second (c may be null)
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Segment {
+    int32_t blk_ofs, n_blk, last_valid, n_shr, shr_ofs, part_base, fill;
+};
+
+struct PlanHost {
+    std::vector<UnitDesc> units;
+    std::vector<int32_t> blocks, sharers, path_ofs, path_ids;
+    std::vector<Segment> segs;
+    std::vector<int32_t> thread_seg, thread_seg_ofs, thread_rank;
+    int64_t n_partial_rows = 0;
+    int32_t class_count[3] = {0, 0, 0};
+    void clear() {
+        units.clear(), blocks.clear(), sharers.clear(), path_ofs.clear(), path_ids.clear(), segs.clear();
+        thread_seg.clear(), thread_seg_ofs.clear(), thread_rank.clear();
+        n_partial_rows = 0;
+        class_count[0] = class_count[1] = class_count[2] = 0;
+    }
+};
+
+}  // namespace
+
+struct apar_pool {
+    apar_pool_config cfg{};
+    Shape shape{};
+    char* kv = nullptr;
+    int device = 0;
+    bool dry_run = false;  // bookkeeping and planning only: no device memory, nothing is launched
+
+    std::vector<int32_t> ref;
+    std::vector<int32_t> free_stack;
+    std::vector<Thread> threads;  // index = thread id
+    int64_t live_threads = 0;
+    int64_t cow_copies = 0;
+
+    // plan builder scratch (pool sized, kept clean between calls)
+    std::vector<int32_t> cnt;     // listed threads holding each block
+    std::vector<int32_t> seg_of;  // segment that starts at each block, -1 if none
+    int chunk_blocks = 8;
+    apar_plan_info last_plan{};
+    PlanHost plan;  // the last plan, kept for reuse of its storage and for inspection
+
+    StageSlot stage[kStageSlots];
+    int next_slot = 0;
+    PartialBuf part{};
+    size_t part_slots_cap = 0;
+
+    bool profiling = false;
+    std::vector<EventPair> decode_events, append_events;
+    std::vector<hipEvent_t> spare_events;
+    double plan_host_ms = 0.0;
+    int64_t n_decode_calls = 0, n_append_calls = 0;
+};
+
+namespace {
+
+struct DeviceGuard {
+    int prev = 0;
+    bool switched = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess && prev != dev) switched = (hipSetDevice(dev) == hipSuccess);
+    }
+    ~DeviceGuard() {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+Thread* live_thread(apar_pool* p, apar_thread t) {
+    if (t < 0 || (size_t)t >= p->threads.size() || !p->threads[t].live) return nullptr;
+    return &p->threads[t];
+}
+
+int32_t pop_block(apar_pool* p) {
+    int32_t b = p->free_stack.back();
+    p->free_stack.pop_back();
+    p->ref[b] = 1;
+    return b;
+}
+
+int acquire_stage(apar_pool* p, size_t bytes, StageSlot** out) {
+    StageSlot& s = p->stage[p->next_slot];
+    p->next_slot = (p->next_slot + 1) % kStageSlots;
+    if (s.pending) {
+        HIP_TRY(hipEventSynchronize(s.ev));
+        s.pending = false;
+    }
+    if (!s.ev) HIP_TRY(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
+    if (s.cap < bytes) {
+        if (s.host) HIP_TRY(hipHostFree(s.host));
+        if (s.dev) HIP_TRY(hipFree(s.dev));
+        s.host = s.dev = nullptr;
+        s.cap = 0;
+        size_t cap = align_up(std::max(bytes + bytes / 2, (size_t)1 << 16), 4096);
+        HIP_TRY(hipHostMalloc((void**)&s.host, cap, hipHostMallocDefault));
+        HIP_TRY(hipMalloc((void**)&s.dev, cap));
+        s.cap = cap;
+    }
+    *out = &s;
+    return APAR_OK;
+}
+
+int new_event(apar_pool* p, hipEvent_t* ev) {
+    if (!p->spare_events.empty()) {
+        *ev = p->spare_events.back();
+        p->spare_events.pop_back();
+        return APAR_OK;
+    }
+    HIP_TRY(hipEventCreate(ev));
+    return APAR_OK;
+}
+
+// Where token slot `pos` of a thread lives: block * 16 + slot.
+inline int32_t slot_code(const Thread& t, int64_t pos) {
+    return t.table[pos / kBlockTokens] * kBlockTokens + (int32_t)(pos % kBlockTokens);
+}
+
+// Advances one thread by one token following the allocator policy; the caller
+// has already made sure enough free blocks exist.
+inline int32_t append_one(apar_pool* p, Thread& t, std::vector<int32_t>& copies) {
+    const int slot = (int)(t.len % kBlockTokens);
+    if (slot == 0) {
+        t.table.push_back(pop_block(p));
+    } else {
+        const int32_t tail = t.table.back();
+        if (p->ref[tail] > 1) {  // shared, partly filled tail: copy on write
+            const int32_t fresh = pop_block(p);
+            copies.push_back(tail);
+            copies.push_back(fresh);
+            p->ref[tail] -= 1;
+            t.table.back() = fresh;
+            p->cow_copies += 1;
+        }
+    }
+    const int32_t code = t.table.back() * kBlockTokens + slot;
+    t.len += 1;
+    return code;
+}
+
+int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vector<int32_t>& copies, const void* k,
+               const void* v, hipStream_t st) {
+    const size_t copy_bytes = align_up(copies.size() * sizeof(int32_t), 256);
+    const size_t code_bytes = codes.size() * sizeof(int32_t);
+    StageSlot* s = nullptr;
+    int rc = acquire_stage(p, copy_bytes + code_bytes, &s);
+    if (rc != APAR_OK) return rc;
+    if (!copies.empty()) memcpy(s->host, copies.data(), copies.size() * sizeof(int32_t));
+    memcpy(s->host + copy_bytes, codes.data(), code_bytes);
+    HIP_TRY(hipMemcpyAsync(s->dev, s->host, copy_bytes + code_bytes, hipMemcpyHostToDevice, st));
+    EventPair ev;
+    if (p->profiling) {
+        if ((rc = new_event(p, &ev.a)) != APAR_OK || (rc = new_event(p, &ev.b)) != APAR_OK) return rc;
+        HIP_TRY(hipEventRecord(ev.a, st));
+    }
+    if (!copies.empty())
+        HIP_TRY(launch_block_copies(p->shape, p->kv, (const int32_t*)s->dev, (int)(copies.size() / 2), st));
+    HIP_TRY(launch_append_rows(p->shape, p->kv, k, v, (const int32_t*)(s->dev + copy_bytes), (int)codes.size(), st));
+    if (p->profiling) {
+        HIP_TRY(hipEventRecord(ev.b, st));
+        p->append_events.push_back(ev);
+        p->n_append_calls += 1;
+    }
+    HIP_TRY(hipEventRecord(s->ev, st));
+    s->pending = true;
+    return APAR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Plan: group the listed threads by the blocks they share.
+//
+// Sharing only ever comes from forks, which hand a child the parent's whole
+// table, and copy-on-write only replaces a tail.  Hence two tables that agree
+// at one position agree at every earlier one, the set of listed threads holding
+// a table's block can only shrink along the table, and a maximal run of
+// positions with one holder count is a run with one holder set: a segment.
+// Each segment is cut into units of at most chunk_blocks blocks and at most
+// max_rows query rows; a unit is read once and applied to all of its rows.
+// ---------------------------------------------------------------------------
+int build_plan(apar_pool* p, const apar_thread* ids, int n, int n_cand, PlanHost& ph, apar_plan_info& info) {
+    const int B = kBlockTokens;
+    for (int i = 0; i < n; ++i) {
+        Thread* t = live_thread(p, ids[i]);
+        if (!t) return APAR_ERR_INVALID_THREAD;
+        if (t->len == 0) return APAR_ERR_INVALID_ARG;
+    }
+    int64_t path_tokens = 0;
+    for (int i = 0; i < n; ++i) {
+        const Thread& t = p->threads[ids[i]];
+        for (int32_t b : t.table) p->cnt[b] += 1;
+        path_tokens += t.len;
+    }
+    ph.thread_seg_ofs.assign(n + 1, 0);
+    for (int i = 0; i < n; ++i) {
+        const Thread& t = p->threads[ids[i]];
+        const int nb = (int)t.table.size();
+        int pos = 0;
+        while (pos < nb) {
+            const int32_t first = t.table[pos];
+            const int32_t c = p->cnt[first];
+            int end = pos + 1;
+            while (end < nb && p->cnt[t.table[end]] == c) ++end;
+            int32_t sid = p->seg_of[first];
+            if (sid < 0) {
+                sid = (int32_t)ph.segs.size();
+                p->seg_of[first] = sid;
+                Segment s{};
+                s.blk_ofs = (int32_t)ph.blocks.size();
+                s.n_blk = end - pos;
+                s.last_valid = (end == nb) ? (int32_t)(t.len - (int64_t)(nb - 1) * B) : B;
+                ph.blocks.insert(ph.blocks.end(), t.table.begin() + pos, t.table.begin() + end);
+                ph.segs.push_back(s);
+            }
+            ph.segs[sid].n_shr += 1;
+            ph.thread_seg.push_back(sid);
+            pos = end;
+        }
+        ph.thread_seg_ofs[i + 1] = (int32_t)ph.thread_seg.size();
+    }
+    // leave the pool-sized scratch clean for the next call
+    for (int i = 0; i < n; ++i)
+        for (int32_t b : p->threads[ids[i]].table) p->cnt[b] = 0;
+    for (const Segment& s : ph.segs) p->seg_of[ph.blocks[s.blk_ofs]] = -1;
+
+    const int rows_per_thread = n_cand * p->shape.group;
+    const int max_rows = attention_max_rows_per_unit(p->shape);
+    if (rows_per_thread > max_rows) return APAR_ERR_UNSUPPORTED;
+    const int grp = std::max(1, max_rows / rows_per_thread);  // threads per unit
+
+    // A unit writes one partial result per row and reads 16 tokens of K and V per
+    // block; runs shared by many rows get longer units so the partial results stay a
+    // small fraction of the bytes moved.
+    auto chunk_of = [&](const Segment& s) {
+        const int rows = std::min(s.n_shr * rows_per_thread, max_rows);
+        return std::max(p->chunk_blocks, (rows * 3 + 1) / 2);
+    };
+    int32_t shr_total = 0;
+    int64_t part_total = 0, unique_tokens = 0;
+    for (Segment& s : ph.segs) {
+        s.shr_ofs = shr_total;
+        shr_total += s.n_shr;
+        const int chunk = chunk_of(s);
+        const int n_chunks = (s.n_blk + chunk - 1) / chunk;
+        s.part_base = (int32_t)part_total;
+        part_total += (int64_t)n_chunks * s.n_shr;
+        unique_tokens += (int64_t)(s.n_blk - 1) * B + s.last_valid;
+    }
+    if (part_total > INT32_MAX / 2) return APAR_ERR_UNSUPPORTED;
+    ph.n_partial_rows = part_total;
+    ph.sharers.resize(shr_total);
+    ph.thread_rank.resize(ph.thread_seg.size());
+    ph.path_ofs.assign(n + 1, 0);
+    for (int i = 0; i < n; ++i) {
+        for (int32_t k = ph.thread_seg_ofs[i]; k < ph.thread_seg_ofs[i + 1]; ++k) {
+            Segment& s = ph.segs[ph.thread_seg[k]];
+            const int32_t rank = s.fill++;
+            ph.sharers[s.shr_ofs + rank] = i;
+            const int chunk = chunk_of(s);
+            const int n_chunks = (s.n_blk + chunk - 1) / chunk;
+            for (int c = 0; c < n_chunks; ++c) ph.path_ids.push_back(s.part_base + c * s.n_shr + rank);
+        }
+        ph.path_ofs[i + 1] = (int32_t)ph.path_ids.size();
+    }
+    // units by row-tile class, longest first inside a class so each launch ends on short ones
+    struct Keyed {
+        int32_t key;
+        UnitDesc u;
+    };
+    std::vector<Keyed> keyed;
+    for (const Segment& s : ph.segs) {
+        const int chunk = chunk_of(s);
+        const int n_chunks = (s.n_blk + chunk - 1) / chunk;
+        for (int c = 0; c < n_chunks; ++c) {
+            const int b0 = c * chunk;
+            const int nb = std::min(chunk, s.n_blk - b0);
+            for (int g0 = 0; g0 < s.n_shr; g0 += grp) {
+                UnitDesc u;
+                u.blk_ofs = s.blk_ofs + b0;
+                u.n_blk = nb;
+                u.last_valid = (b0 + nb == s.n_blk) ? s.last_valid : B;
+                u.shr_ofs = s.shr_ofs + g0;
+                u.n_shr = std::min(grp, s.n_shr - g0);
+                u.part_base = s.part_base + c * s.n_shr + g0;
+                const int tiles = (u.n_shr * rows_per_thread + 15) / 16;
+                const int cls = tiles > 2 ? 0 : (tiles == 2 ? 1 : 2);
+                ph.class_count[cls] += 1;
+                keyed.push_back({cls * 65536 + (65535 - nb), u});
+            }
+        }
+    }
+    std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) { return a.key < b.key; });
+    ph.units.reserve(keyed.size());
+    for (const Keyed& k : keyed) ph.units.push_back(k.u);
+
+    const int64_t e = p->shape.dtype == APAR_F32 ? 4 : 2;
+    info.n_threads = n;
+    info.n_segments = (int64_t)ph.segs.size();
+    info.n_units = (int64_t)ph.units.size() * p->shape.n_kv;
+    info.n_partial_rows = part_total;
+    info.unique_blocks = (int64_t)ph.blocks.size();
+    info.unique_tokens = unique_tokens;
+    info.path_tokens = path_tokens;
+    info.algorithmic_bytes = unique_tokens * 2 * p->shape.n_kv * p->shape.d * e +
+                             2 * (int64_t)n * n_cand * p->shape.n_q * p->shape.d * e;
+    return APAR_OK;
+}
+
+int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* cand_v, const uint8_t* mask,
+                  int n_cand, const apar_thread* ids, int n, void* out, void* stream, bool spec) {
+    if (!p || n < 0) return APAR_ERR_INVALID_ARG;
+    if (n == 0) return APAR_OK;
+    if (!ids) return APAR_ERR_INVALID_ARG;
+    if (spec && (n_cand < 1 || n_cand > 8)) return APAR_ERR_INVALID_ARG;
+    if (p->dry_run) {
+        if (q || out || cand_k || cand_v || mask) return APAR_ERR_INVALID_ARG;
+    } else {
+        if (!q || !out) return APAR_ERR_INVALID_ARG;
+        if (spec && (!cand_k || !cand_v || !mask)) return APAR_ERR_INVALID_ARG;
+    }
+    const auto t0 = std::chrono::steady_clock::now();
+
+    PlanHost& ph = p->plan;
+    ph.clear();
+    apar_plan_info info{};
+    int rc = build_plan(p, ids, n, n_cand, ph, info);
+    if (rc != APAR_OK) return rc;
+    if (spec) {
+        const int64_t e = p->shape.dtype == APAR_F32 ? 4 : 2;
+        info.algorithmic_bytes += 2 * (int64_t)n * n_cand * p->shape.n_kv * p->shape.d * e;
+    }
+    if (p->dry_run) {
+        p->last_plan = info;
+        return APAR_OK;
+    }
+    DeviceGuard guard(p->device);
+    hipStream_t st = (hipStream_t)stream;
+
+    // stage the five tables in one copy
+    size_t ofs[6];
+    ofs[0] = 0;
+    ofs[1] = align_up(ofs[0] + ph.units.size() * sizeof(UnitDesc), 256);
+    ofs[2] = align_up(ofs[1] + ph.blocks.size() * 4, 256);
+    ofs[3] = align_up(ofs[2] + ph.sharers.size() * 4, 256);
+    ofs[4] = align_up(ofs[3] + ph.path_ofs.size() * 4, 256);
+    ofs[5] = align_up(ofs[4] + ph.path_ids.size() * 4, 256);
+    StageSlot* s = nullptr;
+    if ((rc = acquire_stage(p, ofs[5], &s)) != APAR_OK) return rc;
+    memcpy(s->host + ofs[0], ph.units.data(), ph.units.size() * sizeof(UnitDesc));
+    memcpy(s->host + ofs[1], ph.blocks.data(), ph.blocks.size() * 4);
+    memcpy(s->host + ofs[2], ph.sharers.data(), ph.sharers.size() * 4);
+    memcpy(s->host + ofs[3], ph.path_ofs.data(), ph.path_ofs.size() * 4);
+    memcpy(s->host + ofs[4], ph.path_ids.data(), ph.path_ids.size() * 4);
+
+    // partial-result buffer
+    const size_t slots = (size_t)ph.n_partial_rows * n_cand * p->shape.n_q;
+    if (slots > p->part_slots_cap) {
+        HIP_TRY(hipDeviceSynchronize());
+        if (p->part.o) HIP_TRY(hipFree(p->part.o));
+        if (p->part.ml) HIP_TRY(hipFree(p->part.ml));
+        p->part = PartialBuf{};
+        p->part_slots_cap = 0;
+        const size_t cap = slots + slots / 4 + 1024;
+        HIP_TRY(hipMalloc((void**)&p->part.o, cap * p->shape.d * sizeof(float)));
+        HIP_TRY(hipMalloc((void**)&p->part.ml, cap * 2 * sizeof(float)));
+        p->part_slots_cap = cap;
+    }
+
+    HIP_TRY(hipMemcpyAsync(s->dev, s->host, ofs[5], hipMemcpyHostToDevice, st));
+    PlanDev pd;
+    pd.units = (const UnitDesc*)(s->dev + ofs[0]);
+    pd.blocks = (const int32_t*)(s->dev + ofs[1]);
+    pd.sharers = (const int32_t*)(s->dev + ofs[2]);
+    pd.path_ofs = (const int32_t*)(s->dev + ofs[3]);
+    pd.path_ids = (const int32_t*)(s->dev + ofs[4]);
+    pd.n_units = (int32_t)ph.units.size();
+    pd.n_threads = n;
+    for (int c = 0; c < 3; ++c) pd.class_count[c] = ph.class_count[c];
+
+    EventPair ev;
+    if (p->profiling) {
+        if ((rc = new_event(p, &ev.a)) != APAR_OK || (rc = new_event(p, &ev.b)) != APAR_OK ||
+            (rc = new_event(p, &ev.c)) != APAR_OK)
+            return rc;
+        HIP_TRY(hipEventRecord(ev.a, st));
+    }
+    HIP_TRY(launch_attention_partial(p->shape, p->kv, q, pd, n_cand, attention_max_rows_per_unit(p->shape), p->part, st));
+    if (p->profiling) HIP_TRY(hipEventRecord(ev.b, st));
+    HIP_TRY(launch_merge(p->shape, pd, p->part, q, cand_k, cand_v, mask, n_cand, out, st));
+    if (p->profiling) {
+        HIP_TRY(hipEventRecord(ev.c, st));
+        p->decode_events.push_back(ev);
+        p->n_decode_calls += 1;
+    }
+    HIP_TRY(hipEventRecord(s->ev, st));
+    s->pending = true;
+    p->last_plan = info;
+    if (p->profiling)
+        p->plan_host_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    return APAR_OK;
+}
+
+}  // namespace
+
+// ===========================================================================
+// C ABI
+// ===========================================================================
+extern "C" {
+
+int apar_pool_create(const apar_pool_config* cfg, void* kv_dev, size_t kv_bytes, apar_pool** out) {
+    if (!cfg || !out) return APAR_ERR_INVALID_ARG;
+    if (!kv_dev && kv_bytes != 0) return APAR_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (cfg->block_size != kBlockTokens) return APAR_ERR_INVALID_ARG;
+    if (cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return APAR_ERR_INVALID_ARG;
+    if (cfg->num_blocks < 1 || cfg->num_blocks >= ((int64_t)1 << 27) || cfg->max_threads < 1)
+        return APAR_ERR_INVALID_ARG;
+    if (cfg->dtype != APAR_F32 && cfg->dtype != APAR_BF16) return APAR_ERR_INVALID_ARG;
+    if (!(cfg->softmax_scale >= 0.0f) || !std::isfinite(cfg->softmax_scale)) return APAR_ERR_INVALID_ARG;
+    if (cfg->dtype == APAR_BF16 && cfg->head_dim != 128) return APAR_ERR_UNSUPPORTED;
+    if (cfg->dtype == APAR_F32 && cfg->head_dim != 64 && cfg->head_dim != 128) return APAR_ERR_UNSUPPORTED;
+    if (cfg->n_q_heads / cfg->n_kv_heads > 16) return APAR_ERR_UNSUPPORTED;
+    const int64_t e = cfg->dtype == APAR_F32 ? 4 : 2;
+    const int64_t tile = 2 * (int64_t)kBlockTokens * cfg->head_dim * e;
+    const int64_t block = tile * cfg->n_kv_heads;
+    if (kv_dev && ((uint64_t)kv_bytes < (uint64_t)(block * cfg->num_blocks) || ((uintptr_t)kv_dev & 255)))
+        return APAR_ERR_INVALID_ARG;
+
+    apar_pool* p = new (std::nothrow) apar_pool();
+    if (!p) return APAR_ERR_INVALID_ARG;
+    p->cfg = *cfg;
+    p->kv = (char*)kv_dev;
+    p->dry_run = kv_dev == nullptr;
+    if (!p->dry_run) {
+        if (!hip_ok(hipGetDevice(&p->device), "hipGetDevice")) {
+            delete p;
+            return APAR_ERR_HIP;
+        }
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, kv_dev) == hipSuccess) p->device = attr.device;
+        else (void)hipGetLastError();
+    }
+    const float scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+    p->shape.n_q = cfg->n_q_heads;
+    p->shape.n_kv = cfg->n_kv_heads;
+    p->shape.d = cfg->head_dim;
+    p->shape.group = cfg->n_q_heads / cfg->n_kv_heads;
+    p->shape.dtype = cfg->dtype;
+    p->shape.scale_log2e = scale * 1.4426950408889634f;
+    p->shape.tile_bytes = tile;
+    p->shape.block_bytes = block;
+    p->ref.assign(cfg->num_blocks, 0);
+    p->free_stack.resize(cfg->num_blocks);
+    for (int64_t i = 0; i < cfg->num_blocks; ++i) p->free_stack[i] = (int32_t)(cfg->num_blocks - 1 - i);
+    p->cnt.assign(cfg->num_blocks, 0);
+    p->seg_of.assign(cfg->num_blocks, -1);
+    *out = p;
+    return APAR_OK;
+}
+
+int apar_pool_destroy(apar_pool* p) {
+    if (!p) return APAR_OK;
+    if (p->dry_run) {
+        delete p;
+        return APAR_OK;
+    }
+    DeviceGuard guard(p->device);
+    int rc = APAR_OK;
+    if (!hip_ok(hipDeviceSynchronize(), "hipDeviceSynchronize")) rc = APAR_ERR_HIP;
+    for (StageSlot& s : p->stage) {
+        if (s.host) (void)hipHostFree(s.host);
+        if (s.dev) (void)hipFree(s.dev);
+        if (s.ev) (void)hipEventDestroy(s.ev);
+    }
+    if (p->part.o) (void)hipFree(p->part.o);
+    if (p->part.ml) (void)hipFree(p->part.ml);
+    auto drop = [](hipEvent_t e) {
+        if (e) (void)hipEventDestroy(e);
+    };
+    for (EventPair& e : p->decode_events) drop(e.a), drop(e.b), drop(e.c);
+    for (EventPair& e : p->append_events) drop(e.a), drop(e.b), drop(e.c);
+    for (hipEvent_t e : p->spare_events) drop(e);
+    delete p;
+    return rc;
+}
+
+int apar_thread_create(apar_pool* p, apar_thread* out) {
+    if (!p || !out) return APAR_ERR_INVALID_ARG;
+    if ((int64_t)p->threads.size() >= p->cfg.max_threads) return APAR_ERR_THREAD_CAPACITY;
+    p->threads.emplace_back();
+    p->threads.back().live = true;
+    p->live_threads += 1;
+    *out = (apar_thread)(p->threads.size() - 1);
+    return APAR_OK;
+}
+
+int apar_fork(apar_pool* p, apar_thread parent, int n_children, apar_thread* children_out) {
+    if (!p || !children_out) return APAR_ERR_INVALID_ARG;
+    if (!live_thread(p, parent)) return APAR_ERR_INVALID_THREAD;
+    if (n_children < 1) return APAR_ERR_INVALID_ARG;
+    if ((int64_t)p->threads.size() + n_children > p->cfg.max_threads) return APAR_ERR_THREAD_CAPACITY;
+    p->threads.reserve(p->threads.size() + n_children);
+    for (int c = 0; c < n_children; ++c) {
+        p->threads.emplace_back();
+        Thread& child = p->threads.back();
+        const Thread& par = p->threads[parent];
+        child.live = true;
+        child.len = par.len;
+        child.table = par.table;
+        children_out[c] = (apar_thread)(p->threads.size() - 1);
+    }
+    for (int32_t b : p->threads[parent].table) p->ref[b] += n_children;
+    p->live_threads += n_children;
+    return APAR_OK;
+}
+
+int apar_append_kv(apar_pool* p, apar_thread thread, const void* k_dev, const void* v_dev, int n_tokens,
+                   void* hip_stream) {
+    if (!p || n_tokens < 0) return APAR_ERR_INVALID_ARG;
+    Thread* t = live_thread(p, thread);
+    if (!t) return APAR_ERR_INVALID_THREAD;
+    if (n_tokens == 0) return APAR_OK;
+    if (p->dry_run ? (k_dev || v_dev) : (!k_dev || !v_dev)) return APAR_ERR_INVALID_ARG;
+    const int64_t B = kBlockTokens;
+    int64_t need = (t->len + n_tokens + B - 1) / B - (t->len + B - 1) / B;
+    if (t->len % B != 0 && p->ref[t->table.back()] > 1) need += 1;
+    if (need > (int64_t)p->free_stack.size()) return APAR_ERR_OUT_OF_BLOCKS;
+    std::vector<int32_t> codes(n_tokens), copies;
+    for (int i = 0; i < n_tokens; ++i) codes[i] = append_one(p, *t, copies);
+    if (p->dry_run) return APAR_OK;
+    DeviceGuard guard(p->device);
+    return run_append(p, codes, copies, k_dev, v_dev, (hipStream_t)hip_stream);
+}
+
+int apar_append_kv_batch(apar_pool* p, const apar_thread* threads, int n, const void* k_dev, const void* v_dev,
+                         void* hip_stream) {
+    if (!p || n < 0) return APAR_ERR_INVALID_ARG;
+    if (n == 0) return APAR_OK;
+    if (!threads) return APAR_ERR_INVALID_ARG;
+    if (p->dry_run ? (k_dev || v_dev) : (!k_dev || !v_dev)) return APAR_ERR_INVALID_ARG;
+    for (int i = 0; i < n; ++i)
+        if (!live_thread(p, threads[i])) return APAR_ERR_INVALID_THREAD;
+    if ((int64_t)p->free_stack.size() < n) {
+        // Each row takes at most one block, so only a nearly full pool needs the
+        // exact count: replay the policy on scratch copies of what it reads.
+        struct Sim {
+            int64_t len;
+            bool private_tail;  // an earlier row of this call already made the tail this thread's own
+        };
+        std::unordered_map<int32_t, Sim> sim;         // by thread id
+        std::unordered_map<int32_t, int32_t> dropped;  // references copy-on-write took off a block so far
+        int64_t need = 0;
+        for (int i = 0; i < n; ++i) {
+            const Thread& t = p->threads[threads[i]];
+            auto it = sim.find(threads[i]);
+            if (it == sim.end()) it = sim.emplace(threads[i], Sim{t.len, false}).first;
+            Sim& s = it->second;
+            if (s.len % kBlockTokens == 0) {
+                need += 1;
+                s.private_tail = true;
+            } else if (!s.private_tail) {
+                const int32_t tail = t.table.back();
+                int32_t& d = dropped[tail];
+                if (p->ref[tail] - d > 1) {
+                    need += 1;
+                    d += 1;
+                    s.private_tail = true;
+                }
+            }
+            s.len += 1;
+        }
+        if (need > (int64_t)p->free_stack.size()) return APAR_ERR_OUT_OF_BLOCKS;
+    }
+    std::vector<int32_t> codes(n), copies;
+    for (int i = 0; i < n; ++i) codes[i] = append_one(p, p->threads[threads[i]], copies);
+    if (p->dry_run) return APAR_OK;
+    DeviceGuard guard(p->device);
+    return run_append(p, codes, copies, k_dev, v_dev, (hipStream_t)hip_stream);
+}
+
+int apar_decode_attention(apar_pool* p, const void* q_dev, const apar_thread* threads, int n, void* out_dev,
+                          void* hip_stream) {
+    return decode_common(p, q_dev, nullptr, nullptr, nullptr, 1, threads, n, out_dev, hip_stream, false);
+}
+
+int apar_decode_attention_spec(apar_pool* p, const void* q_dev, const void* cand_k_dev, const void* cand_v_dev,
+                               const uint8_t* mask_dev, int n_cand, const apar_thread* threads, int n, void* out_dev,
+                               void* hip_stream) {
+    return decode_common(p, q_dev, cand_k_dev, cand_v_dev, mask_dev, n_cand, threads, n, out_dev, hip_stream, true);
+}
+
+int apar_free_thread(apar_pool* p, apar_thread thread) {
+    if (!p) return APAR_ERR_INVALID_ARG;
+    Thread* t = live_thread(p, thread);
+    if (!t) return APAR_ERR_INVALID_THREAD;
+    for (size_t i = t->table.size(); i-- > 0;) {
+        const int32_t b = t->table[i];
+        if (--p->ref[b] == 0) p->free_stack.push_back(b);
+    }
+    t->live = false;
+    t->len = 0;
+    std::vector<int32_t>().swap(t->table);
+    p->live_threads -= 1;
+    return APAR_OK;
+}
+
+int apar_thread_len(apar_pool* p, apar_thread thread, int64_t* len_out) {
+    if (!p || !len_out) return APAR_ERR_INVALID_ARG;
+    Thread* t = live_thread(p, thread);
+    if (!t) return APAR_ERR_INVALID_THREAD;
+    *len_out = t->len;
+    return APAR_OK;
+}
+
+int apar_thread_block_table(apar_pool* p, apar_thread thread, int32_t* table_out, int cap, int* n_out) {
+    if (!p || !n_out || cap < 0 || (cap > 0 && !table_out)) return APAR_ERR_INVALID_ARG;
+    Thread* t = live_thread(p, thread);
+    if (!t) return APAR_ERR_INVALID_THREAD;
+    *n_out = (int)t->table.size();
+    if ((size_t)cap < t->table.size()) return APAR_ERR_INVALID_ARG;
+    if (!t->table.empty()) memcpy(table_out, t->table.data(), t->table.size() * sizeof(int32_t));
+    return APAR_OK;
+}
+
+int apar_block_refcount(apar_pool* p, int32_t block, int32_t* refcount_out) {
+    if (!p || !refcount_out || block < 0 || block >= p->cfg.num_blocks) return APAR_ERR_INVALID_ARG;
+    *refcount_out = p->ref[block];
+    return APAR_OK;
+}
+
+int apar_pool_stats(apar_pool* p, apar_stats* out) {
+    if (!p || !out) return APAR_ERR_INVALID_ARG;
+    out->total_blocks = p->cfg.num_blocks;
+    out->free_blocks = (int64_t)p->free_stack.size();
+    out->used_blocks = out->total_blocks - out->free_blocks;
+    out->live_threads = p->live_threads;
+    out->threads_issued = (int64_t)p->threads.size();
+    out->cow_copies = p->cow_copies;
+    out->block_bytes = p->shape.block_bytes;
+    out->bytes_resident = out->used_blocks * p->shape.block_bytes;
+    int64_t vanilla = 0;
+    for (const Thread& t : p->threads)
+        if (t.live) vanilla += (int64_t)t.table.size();
+    out->bytes_vanilla = vanilla * p->shape.block_bytes;
+    return APAR_OK;
+}
+
+int apar_last_plan_info(apar_pool* p, apar_plan_info* out) {
+    if (!p || !out) return APAR_ERR_INVALID_ARG;
+    *out = p->last_plan;
+    return APAR_OK;
+}
+
+int apar_last_plan_export(apar_pool* p, int which, int32_t* out, int64_t cap, int64_t* n_out) {
+    if (!p || !n_out || cap < 0 || (cap > 0 && !out)) return APAR_ERR_INVALID_ARG;
+    const PlanHost& ph = p->plan;
+    const int32_t* src = nullptr;
+    int64_t n = 0;
+    switch (which) {
+        case APAR_PLAN_UNITS: src = (const int32_t*)ph.units.data(), n = (int64_t)ph.units.size() * 6; break;
+        case APAR_PLAN_BLOCKS: src = ph.blocks.data(), n = (int64_t)ph.blocks.size(); break;
+        case APAR_PLAN_SHARERS: src = ph.sharers.data(), n = (int64_t)ph.sharers.size(); break;
+        case APAR_PLAN_PATH_OFS: src = ph.path_ofs.data(), n = (int64_t)ph.path_ofs.size(); break;
+        case APAR_PLAN_PATH_IDS: src = ph.path_ids.data(), n = (int64_t)ph.path_ids.size(); break;
+        default: return APAR_ERR_INVALID_ARG;
+    }
+    *n_out = n;
+    if (cap < n) return APAR_ERR_INVALID_ARG;
+    if (n > 0) memcpy(out, src, (size_t)n * sizeof(int32_t));
+    return APAR_OK;
+}
+
+int apar_read_kv_rows(apar_pool* p, apar_thread thread, int64_t first, int n, void* k_out_dev, void* v_out_dev,
+                      void* hip_stream) {
+    if (!p || n < 0 || first < 0) return APAR_ERR_INVALID_ARG;
+    Thread* t = live_thread(p, thread);
+    if (!t) return APAR_ERR_INVALID_THREAD;
+    if (first + n > t->len || p->dry_run) return APAR_ERR_INVALID_ARG;
+    if (n == 0) return APAR_OK;
+    if (!k_out_dev || !v_out_dev) return APAR_ERR_INVALID_ARG;
+    DeviceGuard guard(p->device);
+    hipStream_t st = (hipStream_t)hip_stream;
+    StageSlot* s = nullptr;
+    int rc = acquire_stage(p, (size_t)n * sizeof(int32_t), &s);
+    if (rc != APAR_OK) return rc;
+    int32_t* codes = (int32_t*)s->host;
+    for (int i = 0; i < n; ++i) codes[i] = slot_code(*t, first + i);
+    HIP_TRY(hipMemcpyAsync(s->dev, s->host, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(launch_read_rows(p->shape, p->kv, (const int32_t*)s->dev, n, k_out_dev, v_out_dev, st));
+    HIP_TRY(hipEventRecord(s->ev, st));
+    s->pending = true;
+    return APAR_OK;
+}
+
+int apar_profile_enable(apar_pool* p, int on) {
+    if (!p) return APAR_ERR_INVALID_ARG;
+    p->profiling = on != 0;
+    return APAR_OK;
+}
+
+int apar_profile_read(apar_pool* p, apar_profile* out) {
+    if (!p || !out) return APAR_ERR_INVALID_ARG;
+    memset(out, 0, sizeof(*out));
+    if (p->dry_run) return APAR_OK;
+    DeviceGuard guard(p->device);
+    for (EventPair& e : p->decode_events) {
+        float ms = 0.0f;
+        HIP_TRY(hipEventSynchronize(e.c));
+        HIP_TRY(hipEventElapsedTime(&ms, e.a, e.b));
+        out->attention_kernel_ms += ms;
+        HIP_TRY(hipEventElapsedTime(&ms, e.b, e.c));
+        out->merge_kernel_ms += ms;
+        p->spare_events.push_back(e.a);
+        p->spare_events.push_back(e.b);
+        p->spare_events.push_back(e.c);
+    }
+    for (EventPair& e : p->append_events) {
+        float ms = 0.0f;
+        HIP_TRY(hipEventSynchronize(e.b));
+        HIP_TRY(hipEventElapsedTime(&ms, e.a, e.b));
+        out->append_kernels_ms += ms;
+        p->spare_events.push_back(e.a);
+        p->spare_events.push_back(e.b);
+    }
+    out->n_decode_calls = p->n_decode_calls;
+    out->n_append_calls = p->n_append_calls;
+    out->plan_host_ms = p->plan_host_ms;
+    p->decode_events.clear();
+    p->append_events.clear();
+    p->n_decode_calls = p->n_append_calls = 0;
+    p->plan_host_ms = 0.0;
+    return APAR_OK;
+}
+
+int apar_set_chunk_blocks(apar_pool* p, int blocks_per_unit) {
+    if (!p || blocks_per_unit < 1 || blocks_per_unit > 64) return APAR_ERR_INVALID_ARG;
+    p->chunk_blocks = blocks_per_unit;
+    return APAR_OK;
+}
+
+const char* apar_status_string(int status) {
+    switch (status) {
+        case APAR_OK: return "ok";
+        case APAR_ERR_INVALID_ARG: return "invalid argument";
+        case APAR_ERR_INVALID_THREAD: return "invalid thread";
+        case APAR_ERR_OUT_OF_BLOCKS: return "out of blocks";
+        case APAR_ERR_THREAD_CAPACITY: return "thread capacity exceeded";
+        case APAR_ERR_HIP: return "HIP runtime error";
+        case APAR_ERR_UNSUPPORTED: return "unsupported shape";
+        default: return "unknown status";
+    }
+}
+
+const char* apar_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,323 @@
+// Row writes, copy-on-write block copies, row read-back, the fp32 attention
+// kernel and the merge kernel (gfx950).
+#include <hip/hip_runtime.h>
+
+#include "apar_internal.hpp"
+
+namespace apar {
+
+namespace {
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+// ---------------------------------------------------------------------------
+// Row writes.  One wavefront per (row, kv head).
+// bf16: the K row goes out as sixteen 16-byte pieces and the V row as 128
+// two-byte pieces, each to its place in the matrix-core tile order.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void append_rows_bf16(char* __restrict__ pool, const uint16_t* __restrict__ k,
+                                                       const uint16_t* __restrict__ v,
+                                                       const int32_t* __restrict__ codes, int n_kv,
+                                                       int64_t tile_bytes) {
+    const int row = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    const int32_t code = codes[row];
+    const int slot = code & 15;
+    char* tile = pool + ((int64_t)(code >> 4) * n_kv + h) * tile_bytes;
+    const uint16_t* ksrc = k + ((int64_t)row * n_kv + h) * 128;
+    const uint16_t* vsrc = v + ((int64_t)row * n_kv + h) * 128;
+    if (lane < 16) {
+        const uint4 piece = *reinterpret_cast<const uint4*>(ksrc + lane * 8);
+        *reinterpret_cast<uint4*>(tile + bf16_k_offset(slot, lane * 8)) = piece;
+    }
+    char* vt = tile + 4096;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int dim = lane + 64 * e;
+        *reinterpret_cast<uint16_t*>(vt + bf16_v_offset(slot, dim)) = vsrc[dim];
+    }
+}
+
+__global__ __launch_bounds__(64) void append_rows_f32(char* __restrict__ pool, const float* __restrict__ k,
+                                                      const float* __restrict__ v, const int32_t* __restrict__ codes,
+                                                      int n_kv, int d, int64_t tile_bytes) {
+    const int row = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    const int32_t code = codes[row];
+    const int slot = code & 15;
+    float* tile = reinterpret_cast<float*>(pool + ((int64_t)(code >> 4) * n_kv + h) * tile_bytes);
+    const float* ksrc = k + ((int64_t)row * n_kv + h) * d;
+    const float* vsrc = v + ((int64_t)row * n_kv + h) * d;
+    for (int x = lane; x < d; x += 64) {
+        tile[slot * d + x] = ksrc[x];
+        tile[16 * d + slot * d + x] = vsrc[x];
+    }
+}
+
+__global__ __launch_bounds__(64) void read_rows_bf16(const char* __restrict__ pool, uint16_t* __restrict__ k,
+                                                     uint16_t* __restrict__ v, const int32_t* __restrict__ codes,
+                                                     int n_kv, int64_t tile_bytes) {
+    const int row = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    const int32_t code = codes[row];
+    const int slot = code & 15;
+    const char* tile = pool + ((int64_t)(code >> 4) * n_kv + h) * tile_bytes;
+    uint16_t* kdst = k + ((int64_t)row * n_kv + h) * 128;
+    uint16_t* vdst = v + ((int64_t)row * n_kv + h) * 128;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int dim = lane + 64 * e;
+        kdst[dim] = *reinterpret_cast<const uint16_t*>(tile + bf16_k_offset(slot, dim));
+        vdst[dim] = *reinterpret_cast<const uint16_t*>(tile + 4096 + bf16_v_offset(slot, dim));
+    }
+}
+
+__global__ __launch_bounds__(64) void read_rows_f32(const char* __restrict__ pool, float* __restrict__ k,
+                                                    float* __restrict__ v, const int32_t* __restrict__ codes,
+                                                    int n_kv, int d, int64_t tile_bytes) {
+    const int row = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    const int32_t code = codes[row];
+    const int slot = code & 15;
+    const float* tile = reinterpret_cast<const float*>(pool + ((int64_t)(code >> 4) * n_kv + h) * tile_bytes);
+    for (int x = lane; x < d; x += 64) {
+        k[((int64_t)row * n_kv + h) * d + x] = tile[slot * d + x];
+        v[((int64_t)row * n_kv + h) * d + x] = tile[16 * d + slot * d + x];
+    }
+}
+
+// Copy-on-write: whole blocks, 16 bytes per lane.  grid = (pairs, slices).
+__global__ __launch_bounds__(256) void copy_blocks(char* __restrict__ pool, const int32_t* __restrict__ pairs,
+                                                   int64_t block_bytes) {
+    const int32_t src = pairs[2 * blockIdx.x], dst = pairs[2 * blockIdx.x + 1];
+    const uint4* s = reinterpret_cast<const uint4*>(pool + (int64_t)src * block_bytes);
+    uint4* d = reinterpret_cast<uint4*>(pool + (int64_t)dst * block_bytes);
+    const int64_t n16 = block_bytes / 16;
+    for (int64_t i = (int64_t)blockIdx.y * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.y * blockDim.x)
+        d[i] = s[i];
+}
+
+// ---------------------------------------------------------------------------
+// fp32 partial attention: one wavefront per (unit, kv head, query row), plain
+// vector arithmetic, row-major tiles.  Used by fp32 pools, where results must
+// hold to 1e-5 and the matrix cores' bf16 inputs would not.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void attention_partial_f32(const char* __restrict__ pool,
+                                                            const float* __restrict__ q, PlanDev plan, int n_cand,
+                                                            int n_q, int n_kv, int group, float scale_log2e,
+                                                            int64_t tile_bytes, PartialBuf part) {
+    constexpr int E = D / 64;
+    const int lane = threadIdx.x;
+    const int kvh = blockIdx.y;
+    const UnitDesc u = plan.units[blockIdx.x];
+    const int rows = u.n_shr * n_cand * group;
+    const int row = blockIdx.z;
+    if (row >= rows) return;
+    const int gi = row % group, c = (row / group) % n_cand, s = row / (group * n_cand);
+    const int listed = plan.sharers[u.shr_ofs + s];
+    const int hq = kvh * group + gi;
+    const float* qrow = q + (((int64_t)listed * n_cand + c) * n_q + hq) * D;
+    float qv[E], acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) qv[e] = qrow[lane + 64 * e], acc[e] = 0.0f;
+    float m = -INFINITY, l = 0.0f;
+    for (int b = 0; b < u.n_blk; ++b) {
+        const int32_t blk = plan.blocks[u.blk_ofs + b];
+        const float* tile = reinterpret_cast<const float*>(pool + ((int64_t)blk * n_kv + kvh) * tile_bytes);
+        const int valid = (b == u.n_blk - 1) ? u.last_valid : 16;
+        for (int t = 0; t < valid; ++t) {
+            float dot = 0.0f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) dot += qv[e] * tile[t * D + lane + 64 * e];
+            const float sc = wave_sum(dot) * scale_log2e;
+            const float m_new = fmaxf(m, sc);
+            const float alpha = exp2f(m - m_new), pr = exp2f(sc - m_new);
+            l = l * alpha + pr;
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] = acc[e] * alpha + pr * tile[16 * D + t * D + lane + 64 * e];
+            m = m_new;
+        }
+    }
+    const int64_t slot = ((int64_t)(u.part_base + s) * n_cand + c) * n_q + hq;
+#pragma unroll
+    for (int e = 0; e < E; ++e) part.o[slot * D + lane + 64 * e] = acc[e];
+    if (lane == 0) {
+        part.ml[slot * 2] = m;
+        part.ml[slot * 2 + 1] = l;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Merge: one wavefront per (listed thread, candidate, q head).  Folds the partial
+// results on the thread's root path (log-sum-exp in base 2), adds the candidate
+// keys the mask lets this candidate see, normalises and writes the output row.
+// ---------------------------------------------------------------------------
+template <int D, bool BF16>
+__global__ __launch_bounds__(64) void merge_rows(PlanDev plan, PartialBuf part, const void* __restrict__ qv,
+                                                 const void* __restrict__ ckv, const void* __restrict__ cvv,
+                                                 const uint8_t* __restrict__ mask, int n_cand, int n_q, int n_kv,
+                                                 int group, float scale_log2e, void* __restrict__ outv) {
+    constexpr int E = D / 64;
+    const int lane = threadIdx.x;
+    const int hq = blockIdx.x, c = blockIdx.y, i = blockIdx.z;
+    const int p0 = plan.path_ofs[i], p1 = plan.path_ofs[i + 1];
+    float m = -INFINITY;
+    for (int p = p0; p < p1; ++p) {
+        const int64_t slot = ((int64_t)plan.path_ids[p] * n_cand + c) * n_q + hq;
+        m = fmaxf(m, part.ml[slot * 2]);
+    }
+    auto load = [&](const void* base, int64_t idx) -> float {
+        if (BF16) return bf16_to_f32(reinterpret_cast<const uint16_t*>(base)[idx]);
+        return reinterpret_cast<const float*>(base)[idx];
+    };
+    // logits of the visible candidates
+    float cs[8];
+    uint32_t bits = 0;
+    if (mask != nullptr) {
+        bits = mask[(int64_t)i * n_cand + c];
+        const int64_t qbase = (((int64_t)i * n_cand + c) * n_q + hq) * D;
+        for (int cp = 0; cp < n_cand; ++cp) {
+            cs[cp] = -INFINITY;
+            if ((bits >> cp) & 1u) {
+                const int64_t kbase = (((int64_t)i * n_cand + cp) * n_kv + hq / group) * D;
+                float dot = 0.0f;
+#pragma unroll
+                for (int e = 0; e < E; ++e) dot += load(qv, qbase + lane + 64 * e) * load(ckv, kbase + lane + 64 * e);
+                cs[cp] = wave_sum(dot) * scale_log2e;
+                m = fmaxf(m, cs[cp]);
+            }
+        }
+    }
+    float l = 0.0f, acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] = 0.0f;
+    for (int p = p0; p < p1; ++p) {
+        const int64_t slot = ((int64_t)plan.path_ids[p] * n_cand + c) * n_q + hq;
+        const float w = exp2f(part.ml[slot * 2] - m);
+        l += w * part.ml[slot * 2 + 1];
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] += w * part.o[slot * D + lane + 64 * e];
+    }
+    if (mask != nullptr) {
+        for (int cp = 0; cp < n_cand; ++cp) {
+            if ((bits >> cp) & 1u) {
+                const float w = exp2f(cs[cp] - m);
+                const int64_t vbase = (((int64_t)i * n_cand + cp) * n_kv + hq / group) * D;
+                l += w;
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[e] += w * load(cvv, vbase + lane + 64 * e);
+            }
+        }
+    }
+    const float inv = 1.0f / l;
+    const int64_t obase = (((int64_t)i * n_cand + c) * n_q + hq) * D;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const float r = acc[e] * inv;
+        if (BF16) reinterpret_cast<uint16_t*>(outv)[obase + lane + 64 * e] = f32_to_bf16_rne(r);
+        else reinterpret_cast<float*>(outv)[obase + lane + 64 * e] = r;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attention_partial_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan,
+                                         int n_cand, PartialBuf part, hipStream_t st);
+
+hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const void* v, const int32_t* dst_codes,
+                              int n_rows, hipStream_t st) {
+    if (n_rows <= 0) return hipSuccess;
+    // grid.x carries the rows: go through them in slices that fit the grid limits
+    const int kMaxRows = 1 << 20;
+    for (int r0 = 0; r0 < n_rows; r0 += kMaxRows) {
+        const int nr = n_rows - r0 < kMaxRows ? n_rows - r0 : kMaxRows;
+        dim3 grid(nr, s.n_kv);
+        const int64_t row_elems = (int64_t)s.n_kv * s.d;
+        if (s.dtype == APAR_BF16) {
+            hipLaunchKernelGGL(append_rows_bf16, grid, dim3(64), 0, st, (char*)pool,
+                               (const uint16_t*)k + r0 * row_elems, (const uint16_t*)v + r0 * row_elems,
+                               dst_codes + r0, s.n_kv, s.tile_bytes);
+        } else {
+            hipLaunchKernelGGL(append_rows_f32, grid, dim3(64), 0, st, (char*)pool, (const float*)k + r0 * row_elems,
+                               (const float*)v + r0 * row_elems, dst_codes + r0, s.n_kv, s.d, s.tile_bytes);
+        }
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_block_copies(const Shape& s, void* pool, const int32_t* pairs, int n_pairs, hipStream_t st) {
+    if (n_pairs <= 0) return hipSuccess;
+    int slices = (int)((s.block_bytes / 16 + 255) / 256);
+    if (slices > 64) slices = 64;
+    if (slices < 1) slices = 1;
+    hipLaunchKernelGGL(copy_blocks, dim3(n_pairs, slices), dim3(256), 0, st, (char*)pool, pairs, s.block_bytes);
+    return hipGetLastError();
+}
+
+hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src_codes, int n_rows, void* k_out,
+                            void* v_out, hipStream_t st) {
+    if (n_rows <= 0) return hipSuccess;
+    dim3 grid(n_rows, s.n_kv);
+    if (s.dtype == APAR_BF16)
+        hipLaunchKernelGGL(read_rows_bf16, grid, dim3(64), 0, st, (const char*)pool, (uint16_t*)k_out,
+                           (uint16_t*)v_out, src_codes, s.n_kv, s.tile_bytes);
+    else
+        hipLaunchKernelGGL(read_rows_f32, grid, dim3(64), 0, st, (const char*)pool, (float*)k_out, (float*)v_out,
+                           src_codes, s.n_kv, s.d, s.tile_bytes);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention_partial(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
+                                    int max_rows, PartialBuf part, hipStream_t st) {
+    if (plan.n_units <= 0) return hipSuccess;
+    if (s.dtype == APAR_BF16) return launch_attention_partial_bf16(s, pool, q, plan, n_cand, part, st);
+    dim3 grid(plan.n_units, s.n_kv, max_rows);
+    if (s.d == 64)
+        hipLaunchKernelGGL(attention_partial_f32<64>, grid, dim3(64), 0, st, (const char*)pool, (const float*)q, plan,
+                           n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part);
+    else
+        hipLaunchKernelGGL(attention_partial_f32<128>, grid, dim3(64), 0, st, (const char*)pool, (const float*)q,
+                           plan, n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part);
+    return hipGetLastError();
+}
+
+hipError_t launch_merge(const Shape& s, const PlanDev& plan, PartialBuf part, const void* q, const void* cand_k,
+                        const void* cand_v, const uint8_t* mask, int n_cand, void* out, hipStream_t st) {
+    if (plan.n_threads <= 0) return hipSuccess;
+    // grid.z carries the listed threads (limit 65535): go through them in slices
+    const int kSlice = 32768;
+    for (int i0 = 0; i0 < plan.n_threads; i0 += kSlice) {
+        const int ni = plan.n_threads - i0 < kSlice ? plan.n_threads - i0 : kSlice;
+        PlanDev pl = plan;
+        pl.path_ofs = plan.path_ofs + i0;
+        const int64_t e = s.dtype == APAR_F32 ? 4 : 2;
+        const int64_t qofs = (int64_t)i0 * n_cand * s.n_q * s.d * e;
+        const int64_t kofs = (int64_t)i0 * n_cand * s.n_kv * s.d * e;
+        const void* q2 = (const char*)q + qofs;
+        const void* ck2 = cand_k ? (const char*)cand_k + kofs : nullptr;
+        const void* cv2 = cand_v ? (const char*)cand_v + kofs : nullptr;
+        const uint8_t* mk2 = mask ? mask + (int64_t)i0 * n_cand : nullptr;
+        void* out2 = (char*)out + qofs;
+        dim3 grid(s.n_q, n_cand, ni);
+#define APAR_MERGE(DD, BF)                                                                                        \
+    hipLaunchKernelGGL((merge_rows<DD, BF>), grid, dim3(64), 0, st, pl, part, q2, ck2, cv2, mk2, n_cand, s.n_q, \
+                       s.n_kv, s.group, s.scale_log2e, out2)
+        if (s.dtype == APAR_BF16) APAR_MERGE(128, true);
+        else if (s.d == 64) APAR_MERGE(64, false);
+        else APAR_MERGE(128, false);
+#undef APAR_MERGE
+    }
+    return hipGetLastError();
+}
+
+}  // namespace apar

@@ -1,0 +1,259 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI (GPU only).
+
+Tolerances (max abs error of attention outputs): 1e-5 for fp32 pools, 2e-2 for bf16 pools (bf16
+inputs, fp32 accumulation, probabilities rounded to bf16 before the P.V product, bf16 output).
+Block tables, lengths and refcounts are compared bit-exactly."""
+import numpy as np
+import pytest
+
+import paper_2401_06761_amd as ap
+from apar_workloads import (HeadConfig, make_config, manual_tree, mask_rows_from_parents, draw_candidate_tree,
+                            node_kv, quantise, step_q, tiny_tree)
+from oracle import BlockLedger, DenseThreads
+
+from harness import blocks_upper_bound, books_equal, pool_for, replay_trace, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def torch():
+    import torch as t
+
+    return t
+
+
+def poison(pool):
+    """Fill the KV buffer with NaN bit patterns so that any read of an unwritten slot shows."""
+    pool.kv.fill_(0xFF)
+
+
+def decode_both(w, pool, dense, live, step=0, q=None):
+    t = torch()
+    hd = w.heads
+    if q is None:
+        q = step_q(w, step, len(live))
+    qd = to_dev(q, hd.dtype)
+    out = t.empty_like(qd)
+    ap.apar_decode_attention(pool.handle, qd, live, out)
+    t.cuda.synchronize()
+    got = to_host(out)
+    want = dense.decode(q, live)
+    return got, want
+
+
+def run_workload(w, chunk=None, check_each=False, sample=None):
+    N = blocks_upper_bound(w)
+    hd = w.heads
+    with pool_for(w, N) as pool:
+        poison(pool)
+        if chunk:
+            ap.apar_set_chunk_blocks(pool.handle, chunk)
+        led = BlockLedger(N)
+        dense = DenseThreads(hd.n_q_heads, hd.n_kv_heads, hd.head_dim)
+        live, nodes = replay_trace(w, pool, led, dense, check_each=check_each)
+        books_equal(pool.handle, led)
+        got, want = decode_both(w, pool, dense, live)
+        err = np.abs(got - want).max()
+        assert np.isfinite(got).all()
+        assert err <= TOL[hd.dtype], f"max abs err {err}"
+        info = ap.apar_last_plan_info(pool.handle)
+        assert info.unique_blocks == led.used_blocks()
+        return err, info
+
+
+def test_tiny_fp32_tree_tables_and_attention():
+    w = tiny_tree()
+    with pool_for(w, 8) as pool:
+        poison(pool)
+        led = BlockLedger(8)
+        dense = DenseThreads(2, 2, 64)
+        live, _ = replay_trace(w, pool, led, dense, check_each=True)
+        assert live == [1, 2, 3]
+        assert [ap.apar_thread_block_table(pool.handle, t) for t in live] == [[0, 2], [0, 3], [0, 1, 4]]
+        got, want = decode_both(w, pool, dense, live)
+        assert np.abs(got - want).max() <= 1e-5
+        st = ap.apar_pool_stats(pool.handle)
+        assert st.bytes_resident == 5 * 16 * 1024 and st.bytes_vanilla == 7 * 16 * 1024
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("f32", 128), ("bf16", 128)])
+def test_rows_read_back_exactly_after_appends_forks_and_copies(dtype, d):
+    t = torch()
+    heads = HeadConfig(4, 2, d, dtype)
+    w = manual_tree([-1, 0, 0, 1, 1, 2, -1, 6], [21, 3, 30, 1, 17, 16, 5, 40], heads, seed=3)
+    N = blocks_upper_bound(w)
+    with pool_for(w, N) as pool:
+        poison(pool)
+        led = BlockLedger(N)
+        dense = DenseThreads(4, 2, d)
+        live, _ = replay_trace(w, pool, led, dense, check_each=True)
+        for th in live:
+            L = dense.length(th)
+            k = t.empty((L, 2, d), dtype=pool.torch_dtype, device="cuda:0")
+            v = t.empty_like(k)
+            ap.apar_read_kv_rows(pool.handle, th, 0, L, k, v)
+            t.cuda.synchronize()
+            K, V = dense.rows(th)
+            assert np.array_equal(to_host(k), K) and np.array_equal(to_host(v), V)
+        # one-row batch appends (with copy-on-write among siblings) land in the right slots too
+        for step in range(3):
+            k = quantise(np.random.default_rng(step).standard_normal((len(live), 2, d)).astype(np.float32), dtype)
+            v = quantise(np.random.default_rng(100 + step).standard_normal((len(live), 2, d)).astype(np.float32), dtype)
+            ap.apar_append_kv_batch(pool.handle, live, to_dev(k, dtype), to_dev(v, dtype))
+            led.append_batch(live)
+            for i, th in enumerate(live):
+                dense.append(th, k[i:i + 1], v[i:i + 1])
+        books_equal(pool.handle, led)
+        for th in live:
+            L = dense.length(th)
+            k = t.empty((3, 2, d), dtype=pool.torch_dtype, device="cuda:0")
+            v = t.empty_like(k)
+            ap.apar_read_kv_rows(pool.handle, th, L - 3, 3, k, v)
+            t.cuda.synchronize()
+            K, V = dense.rows(th)
+            assert np.array_equal(to_host(k), K[-3:]) and np.array_equal(to_host(v), V[-3:])
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("f32", 128), ("bf16", 128)])
+@pytest.mark.parametrize("chunk", [1, 2, 8])
+def test_ragged_trees_every_block_boundary(dtype, d, chunk):
+    heads = HeadConfig(4, 4, d, dtype)
+    parents = [-1, 0, 0, 0, 1, 1, 3, 3, 3, -1, -1, 10, 10]
+    segs = [1, 15, 16, 17, 1, 33, 16, 15, 2, 1, 47, 1, 130]
+    w = manual_tree(parents, segs, heads, seed=11)
+    err, info = run_workload(w, chunk=chunk, check_each=(chunk == 1))
+    assert info.n_threads == 8
+
+
+@pytest.mark.parametrize("g", [1, 4, 8])
+def test_grouped_query_heads_bf16(g):
+    heads = HeadConfig(8, 8 // g, 128, "bf16")
+    w = manual_tree([-1, 0, 0, 0, 2, 2], [70, 9, 20, 33, 5, 18], heads, seed=2)
+    run_workload(w)
+
+
+def test_many_siblings_split_into_row_groups():
+    # 70 children of one root: more than 64 rows share the root's blocks
+    heads = HeadConfig(2, 2, 128, "bf16")
+    parents = [-1] + [0] * 70
+    segs = [100] + [1 + (i % 19) for i in range(70)]
+    w = manual_tree(parents, segs, heads, seed=4)
+    err, info = run_workload(w)
+    assert info.n_threads == 70
+
+
+@pytest.mark.parametrize("name,n_req,scale", [("mha64", 4, None), ("mha64", 4, 1.0), ("ht256", 16, None),
+                                              ("ht256", 6, 1.0), ("gqa1024", 2, None), ("gqa1024", 1, 1.0)])
+def test_config_shaped_subsets_bf16(name, n_req, scale):
+    w = make_config(name, n_requests=n_req, data_scale=scale)
+    err, info = run_workload(w)
+    print(f"{name} x{n_req} scale={scale}: max abs err {err:.3e}, {info.n_threads} threads")
+
+
+def test_zero_query_gives_mean_of_values_on_the_root_path():
+    t = torch()
+    heads = HeadConfig(2, 2, 128, "bf16")
+    w = manual_tree([-1, 0, 0, 2, 2], [40, 13, 20, 7, 30], heads, seed=8)
+    N = blocks_upper_bound(w)
+    with pool_for(w, N) as pool:
+        poison(pool)
+        dense = DenseThreads(2, 2, 128)
+        live, _ = replay_trace(w, pool, None, dense)
+        q = np.zeros((len(live), 2, 128), dtype=np.float32)
+        got, want = decode_both(w, pool, dense, live, q=q)
+        for i, th in enumerate(live):
+            mean = dense.rows(th)[1].mean(axis=0)
+            assert np.abs(want[i] - mean).max() < 1e-12
+            assert np.abs(got[i] - mean).max() <= 2e-3
+
+
+def test_listed_threads_may_repeat_and_come_in_any_order():
+    w = make_config("ht256", n_requests=3)
+    N = blocks_upper_bound(w)
+    with pool_for(w, N) as pool:
+        poison(pool)
+        dense = DenseThreads(32, 32, 128)
+        live, _ = replay_trace(w, pool, None, dense)
+        rng = np.random.default_rng(0)
+        listed = [int(x) for x in rng.permutation(live)] + [live[0], live[0], live[-1]]
+        got, want = decode_both(w, pool, dense, listed, step=3)
+        assert np.abs(got - want).max() <= 2e-2
+        one, want1 = decode_both(w, pool, dense, [live[2]], step=4)
+        assert np.abs(one - want1).max() <= 2e-2
+
+
+def test_parent_that_keeps_decoding_after_a_fork():
+    # the paper's own shape (Alg. 1): the parent continues, a single child hangs off it
+    t = torch()
+    hd = HeadConfig(4, 4, 128, "bf16")
+    w = manual_tree([-1], [0], hd, seed=6, data_scale=0.5)
+    N = 64
+    with pool_for(w, N) as pool:
+        poison(pool)
+        led = BlockLedger(N)
+        dense = DenseThreads(4, 4, 128)
+        rng = np.random.default_rng(6)
+
+        def rows(n):
+            return (quantise(0.5 * rng.standard_normal((n, 4, 128)).astype(np.float32), "bf16"),
+                    quantise(0.5 * rng.standard_normal((n, 4, 128)).astype(np.float32), "bf16"))
+
+        def append(th, n):
+            k, v = rows(n)
+            ap.apar_append_kv(pool.handle, th, to_dev(k, "bf16"), to_dev(v, "bf16"), n)
+            led.append(th, n)
+            dense.append(th, k, v)
+
+        root = ap.apar_thread_create(pool.handle)
+        assert led.create() == root == dense.create()
+        append(root, 37)
+        live = [root]
+        for step in range(40):
+            if step % 9 == 4:  # fork one child off the newest thread; both continue
+                par = live[-1]
+                kid = ap.apar_fork(pool.handle, par, 1)
+                assert kid == led.fork(par, 1) == dense.fork(par, 1)
+                live += kid
+            for th in live:
+                append(th, 1)
+            books_equal(pool.handle, led)
+            got, want = decode_both(w, pool, dense, live, step=step)
+            assert np.abs(got - want).max() <= 2e-2
+            if step == 30:  # early release of a finished thread while the rest go on
+                gone = live.pop(1)
+                ap.apar_free_thread(pool.handle, gone)
+                led.free(gone)
+                dense.free(gone)
+        led.check_invariants()
+
+
+@pytest.mark.parametrize("dtype,d,C", [("f32", 64, 5), ("f32", 128, 1), ("bf16", 128, 5), ("bf16", 128, 3)])
+def test_multi_candidate_step(dtype, d, C):
+    t = torch()
+    heads = HeadConfig(4, 2, d, dtype)
+    w = manual_tree([-1, 0, 0, 2, 2, -1], [30, 16, 9, 1, 25, 3], heads, seed=9, data_scale=0.7)
+    N = blocks_upper_bound(w)
+    with pool_for(w, N) as pool:
+        poison(pool)
+        dense = DenseThreads(4, 2, d)
+        live, _ = replay_trace(w, pool, None, dense)
+        n = len(live)
+        rng = np.random.default_rng(1)
+        q = quantise(0.7 * rng.standard_normal((n, C, 4, d)).astype(np.float32), dtype)
+        ck = quantise(0.7 * rng.standard_normal((n, C, 2, d)).astype(np.float32), dtype)
+        cv = quantise(0.7 * rng.standard_normal((n, C, 2, d)).astype(np.float32), dtype)
+        masks = np.stack([mask_rows_from_parents(draw_candidate_tree(rng, C)) for _ in range(n)])
+        qd = to_dev(q, dtype)
+        out = t.empty_like(qd)
+        ap.apar_decode_attention_spec(pool.handle, qd, to_dev(ck, dtype), to_dev(cv, dtype),
+                                      t.from_numpy(masks).cuda(), C, live, out)
+        t.cuda.synchronize()
+        want = dense.decode_spec(q, ck, cv, masks, live)
+        err = np.abs(to_host(out) - want).max()
+        assert err <= TOL[dtype], err
+        info = ap.apar_last_plan_info(pool.handle)
+        e = heads.elem_bytes
+        assert info.algorithmic_bytes == info.unique_tokens * heads.kv_bytes_per_token + \
+            2 * n * C * 4 * d * e + 2 * n * C * 2 * d * e

@@ -1,0 +1,182 @@
+"""Host side of libapar without a GPU: the library loads, exports what apar.h declares, and its
+bookkeeping and plan builder (run on dry-run pools, which never touch a device) match the ledger."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2401_06761_amd as ap
+from apar_workloads import HeadConfig, make_config, manual_tree, tiny_tree
+from oracle import BlockLedger
+
+from harness import blocks_upper_bound, books_equal, check_plan_covers_tables, pool_for, replay_trace
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "apar.h")).read()
+    declared = list(dict.fromkeys(re.findall(r"APAR_API\s+(?:const\s+char\*|int)\s+(apar_[a-z_0-9]+)\s*\(", hdr)))
+    assert len(declared) >= 20
+    assert set(declared) <= set(ap.exported_symbols())
+    for name in ("apar_pool_create", "apar_fork", "apar_append_kv", "apar_decode_attention", "apar_free_thread"):
+        assert name in declared
+    assert ap.apar_status_string(0) == "ok" and "blocks" in ap.apar_status_string(-3)
+
+
+def test_tiny_books_match_ledger_after_every_op():
+    w = tiny_tree()
+    with pool_for(w, 8, dry_run=True) as pool:
+        led = BlockLedger(8)
+        live, _ = replay_trace(w, pool, led, dry_run=True, check_each=True)
+        assert live == [1, 2, 3]
+        assert [ap.apar_thread_block_table(pool.handle, t) for t in live] == [[0, 2], [0, 3], [0, 1, 4]]
+        ap.apar_decode_attention(pool.handle, None, live, None)
+        info = ap.apar_last_plan_info(pool.handle)
+        assert info.unique_blocks == 5 and info.path_tokens == 97
+        check_plan_covers_tables(pool.handle, live, 2)
+
+
+@pytest.mark.parametrize("name,n_req", [("mha64", 6), ("ht256", 24), ("gqa1024", 3), ("spec128", 10)])
+def test_config_books_and_plans(name, n_req):
+    w = make_config(name, n_requests=n_req)
+    N = blocks_upper_bound(w)
+    with pool_for(w, N, dry_run=True) as pool:
+        led = BlockLedger(N)
+        live, _ = replay_trace(w, pool, led, dry_run=True)
+        books_equal(pool.handle, led)
+        led.check_invariants()
+        for chunk in (1, 8, 64):
+            ap.apar_set_chunk_blocks(pool.handle, chunk)
+            ap.apar_decode_attention(pool.handle, None, live, None)
+            res = check_plan_covers_tables(pool.handle, live, w.heads.n_kv_heads, w.heads.n_q_heads // w.heads.n_kv_heads)
+            groups_extra = res["unit_block_reads"] - res["unique_blocks"]
+            # a block is read once per row group; only runs shared by more than 64 rows are split
+            assert groups_extra >= 0
+            if w.heads.n_q_heads == w.heads.n_kv_heads:
+                assert groups_extra == 0
+        info = ap.apar_last_plan_info(pool.handle)
+        e = w.heads.elem_bytes
+        assert info.algorithmic_bytes == info.unique_tokens * w.heads.kv_bytes_per_token + \
+            2 * len(live) * w.heads.n_q_heads * w.heads.head_dim * e
+        # a shuffled and partly repeated list is planned just as well
+        rng = np.random.default_rng(0)
+        some = [int(x) for x in rng.permutation(live)[: max(2, len(live) // 2)]]
+        some += some[:2]
+        ap.apar_decode_attention(pool.handle, None, some, None)
+        check_plan_covers_tables(pool.handle, some, w.heads.n_kv_heads, w.heads.n_q_heads // w.heads.n_kv_heads)
+        # the speculative call plans 5 rows per thread and head
+        ap.apar_decode_attention_spec(pool.handle, None, None, None, None, 5, live, None)
+        check_plan_covers_tables(pool.handle, live, w.heads.n_kv_heads, 5 * w.heads.n_q_heads // w.heads.n_kv_heads)
+        # releasing everything returns every block
+        for t in live:
+            ap.apar_free_thread(pool.handle, t)
+            led.free(t)
+        books_equal(pool.handle, led)
+        assert ap.apar_pool_stats(pool.handle).free_blocks == N
+
+
+def test_random_interleavings_match_ledger():
+    rng = np.random.default_rng(5)
+    for trial in range(25):
+        N = int(rng.integers(6, 40))
+        heads = HeadConfig(2, 1, 64, "f32")
+        with ap.Pool(2, 1, 64, "f32", N, max_threads=64, dry_run=True) as pool:
+            h = pool.handle
+            led = BlockLedger(N, max_threads=64)
+            assert ap.apar_thread_create(h) == led.create()
+            for _ in range(80):
+                live = led.live()
+                op = rng.choice(["append", "append", "batch", "fork", "free", "create"])
+                t = int(rng.choice(live)) if live else -1
+                if op == "create" or not live:
+                    try:
+                        want = led.create()
+                    except Exception:
+                        with pytest.raises(ap.AparError) as ei:
+                            ap.apar_thread_create(h)
+                        assert ei.value.status == -4
+                        continue
+                    assert ap.apar_thread_create(h) == want
+                elif op == "append":
+                    n = int(rng.choice([1, 3, 15, 16, 17, 40]))
+                    try:
+                        led.append(t, n)
+                    except Exception:
+                        with pytest.raises(ap.AparError) as ei:
+                            ap.apar_append_kv(h, t, None, None, n)
+                        assert ei.value.status == -3
+                    else:
+                        ap.apar_append_kv(h, t, None, None, n)
+                elif op == "batch":
+                    ts = [int(x) for x in rng.choice(live, size=int(rng.integers(1, 7)))]
+                    try:
+                        led.append_batch(ts)
+                    except Exception:
+                        with pytest.raises(ap.AparError) as ei:
+                            ap.apar_append_kv_batch(h, ts, None, None)
+                        assert ei.value.status == -3
+                    else:
+                        ap.apar_append_kv_batch(h, ts, None, None)
+                elif op == "fork":
+                    n = int(rng.integers(1, 4))
+                    try:
+                        want = led.fork(t, n)
+                    except Exception:
+                        with pytest.raises(ap.AparError) as ei:
+                            ap.apar_fork(h, t, n)
+                        assert ei.value.status == -4
+                    else:
+                        assert ap.apar_fork(h, t, n) == want
+                else:
+                    led.free(t)
+                    ap.apar_free_thread(h, t)
+                books_equal(h, led)
+            led.check_invariants()
+            listed = [t for t in led.live() if led.len[t] > 0]
+            if listed:
+                ap.apar_decode_attention(h, None, listed, None)
+                check_plan_covers_tables(h, listed, 1, 2)
+
+
+def test_error_codes_and_noops():
+    with ap.Pool(4, 2, 64, "f32", 4, max_threads=3, dry_run=True) as pool:
+        h = pool.handle
+        t = ap.apar_thread_create(h)
+
+        def status(fn, *a):
+            with pytest.raises(ap.AparError) as ei:
+                fn(*a)
+            return ei.value.status
+
+        assert status(ap.apar_fork, h, t, 0) == -1
+        assert status(ap.apar_fork, h, 7, 1) == -2
+        assert status(ap.apar_fork, h, t, 3) == -4  # would issue ids 1..3 with max_threads = 3
+        assert status(ap.apar_decode_attention, h, None, [t], None) == -1  # empty thread
+        assert status(ap.apar_append_kv, h, t, None, None, 65) == -3  # needs 5 blocks of 4
+        assert ap.apar_pool_stats(h).free_blocks == 4 and ap.apar_thread_len(h, t) == 0
+        ap.apar_append_kv(h, t, None, None, 0)
+        ap.apar_decode_attention(h, None, [], None)
+        ap.apar_append_kv(h, t, None, None, 64)
+        assert status(ap.apar_append_kv, h, t, None, None, 1) == -3
+        (c,) = ap.apar_fork(h, t, 1)
+        ap.apar_free_thread(h, t)
+        assert status(ap.apar_free_thread, h, t) == -2
+        assert status(ap.apar_thread_len, h, t) == -2
+        assert status(ap.apar_append_kv, h, t, None, None, 1) == -2
+        assert status(ap.apar_decode_attention, h, None, [c, t], None) == -2
+        assert status(ap.apar_block_refcount, h, 4) == -1
+        assert ap.apar_thread_block_table(h, c) == [0, 1, 2, 3]
+        ap.apar_free_thread(h, c)
+        assert ap.apar_pool_stats(h).free_blocks == 4
+    for bad in (dict(block_size=8), dict(n_q_heads=3), dict(num_blocks=0), dict(dtype=7)):
+        kw = dict(n_q_heads=4, n_kv_heads=2, head_dim=64, block_size=16, dtype=0, max_threads=8, num_blocks=4,
+                  softmax_scale=0.0)
+        kw.update(bad)
+        with pytest.raises(ap.AparError) as ei:
+            ap.apar_pool_create(ap.AparPoolConfig(**kw), None)
+        assert ei.value.status == -1
+    with pytest.raises(ap.AparError) as ei:
+        ap.apar_pool_create(ap.AparPoolConfig(4, 4, 96, 16, 1, 8, 4, 0.0), None)
+    assert ei.value.status == -6
