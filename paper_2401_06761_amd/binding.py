@@ -51,6 +51,10 @@ def _load() -> C.CDLL:
         raise ImportError(
             f"{_LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
             "(or python paper_2401_06761_amd/build.py).  There is no fallback path.")
+    # PyTorch ships its own HIP runtime.  Import it first so that libapar binds to that
+    # copy (the loader matches it by soname); two runtimes in one process do not share devices.
+    import torch  # noqa: F401
+
     lib = C.CDLL(_LIB_PATH)
     P, I, V = C.c_void_p, C.c_int, C.c_void_p
     I32P = C.POINTER(C.c_int32)

@@ -124,7 +124,7 @@ def test_ragged_trees_every_block_boundary(dtype, d, chunk):
     segs = [1, 15, 16, 17, 1, 33, 16, 15, 2, 1, 47, 1, 130]
     w = manual_tree(parents, segs, heads, seed=11)
     err, info = run_workload(w, chunk=chunk, check_each=(chunk == 1))
-    assert info.n_threads == 8
+    assert info.n_threads == 9
 
 
 @pytest.mark.parametrize("g", [1, 4, 8])
