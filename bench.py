@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the APAR decode path on one MI355X.
+
+A step is one pass of the whole hot path over the live threads of a synthetic fork-tree
+workload: a few threads finish and a forked child carries on in their place (apar_fork +
+apar_free_thread), every live thread appends the new token's K,V row (apar_append_kv_batch,
+with copy-on-write where a tail is shared), and all live threads attend over their root
+paths (apar_decode_attention).  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def cpu_baseline(w_name: str, seed: int, n_req: int, device: str):
+    """The fp64 oracle, as it stands, on the first n_req requests of the same workload."""
+    import numpy as np
+    import torch
+
+    from apar_workloads import build_trace, make_config, node_kv_device, rows_device
+    from oracle import DenseThreads
+
+    w = make_config(w_name, seed=seed, n_requests=n_req)
+    hd = w.heads
+    dense = DenseThreads(hd.n_q_heads, hd.n_kv_heads, hd.head_dim)
+    ops, live, _ = build_trace(w)
+    t0 = time.perf_counter()
+    for op in ops:
+        if op.kind == "create":
+            dense.create()
+        elif op.kind == "append":
+            k, v = node_kv_device(w, op.node, device)
+            dense.append(op.tid, k.float().cpu().numpy(), v.float().cpu().numpy())
+        elif op.kind == "fork":
+            dense.fork(op.tid, len(op.children))
+        else:
+            dense.free(op.tid)
+    t_mat = time.perf_counter() - t0
+    q = rows_device(w, 1, 0, (len(live), hd.n_q_heads, hd.head_dim), device).float().cpu().numpy()
+    try:
+        from threadpoolctl import threadpool_info
+
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    t0 = time.perf_counter()
+    dense.decode(q, live)
+    t_dec = time.perf_counter() - t0
+    attended = sum(dense.length(t) for t in live)
+    return {
+        "value": len(live) / t_dec,
+        "unit": "thread-queries/s",
+        "cores": int(cores),
+        "host_cpus": os.cpu_count(),
+        "kind": "oracle",
+        "sample": f"first {n_req} requests of {w_name} (seed {seed}): {len(live)} threads, {attended} attended "
+                  f"tokens, fp64 dense attention over deep-copied per-thread rows; decode {t_dec:.2f} s "
+                  f"(materialising the copies took another {t_mat:.2f} s, not counted)",
+        "effective_GBps": attended * hd.kv_bytes_per_token / t_dec / 1e9,
+    }
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch of the attention kernel from the committed rocprofv3 counter summary."""
+    path = os.path.join(ROOT, "profiles", f"attention_partial_{workload}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap_ = argparse.ArgumentParser()
+    ap_.add_argument("--gpus", type=int, default=1)
+    ap_.add_argument("--steps", type=int, default=20)
+    ap_.add_argument("--warmup", type=int, default=5)
+    ap_.add_argument("--config", default="ht256", choices=["mha64", "ht256", "gqa1024"])
+    ap_.add_argument("--seed", type=int, default=0)
+    ap_.add_argument("--requests", type=int, default=None, help="first n requests only (debugging)")
+    ap_.add_argument("--chunk", type=int, default=None, help="blocks per work unit")
+    ap_.add_argument("--churn", type=float, default=0.01)
+    ap_.add_argument("--cpu-requests", type=int, default=16)
+    ap_.add_argument("--no-cpu-baseline", action="store_true")
+    ap_.add_argument("--copy-calibration", action="store_true",
+                     help="also run one plain 4 GiB device copy (reference for HBM byte counters)")
+    args = ap_.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by request with no exchange; "
+              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2401_06761_amd as ap
+    from apar_workloads import make_config
+    from paper_2401_06761_amd.driver import TreeRun
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = "cuda:0"
+    w = make_config(args.config, seed=args.seed, n_requests=args.requests)
+    hd = w.heads
+    t_build = time.perf_counter()
+    run = TreeRun(w, headroom_steps=args.steps + args.warmup + 8, churn=args.churn, device=dev)
+    run.build()
+    t_build = time.perf_counter() - t_build
+    if args.chunk:
+        ap.apar_set_chunk_blocks(run.h, args.chunk)
+    st0 = ap.apar_pool_stats(run.h)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        run.step()
+    torch.cuda.synchronize()
+    ap.apar_profile_read(run.h)
+    ap.apar_profile_enable(run.h, True)
+    alg_bytes = 0
+    unique_tokens = path_tokens = 0
+    n_queries = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run.step()
+        info = ap.apar_last_plan_info(run.h)
+        alg_bytes += info.algorithmic_bytes
+        unique_tokens += info.unique_tokens
+        path_tokens += info.path_tokens
+        n_queries += info.n_threads
+    t_host = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = ap.apar_profile_read(run.h)
+    ap.apar_profile_enable(run.h, False)
+    st1 = ap.apar_pool_stats(run.h)
+    info = ap.apar_last_plan_info(run.h)
+
+    K = args.steps
+    attn_ms = prof.attention_kernel_ms / K
+    merge_ms = prof.merge_kernel_ms / K
+    append_ms = prof.append_kernels_ms / max(prof.n_append_calls, 1)
+    achieved = (alg_bytes / K) / (attn_ms * 1e-3) / 1e9
+    result = {
+        "metric": "decode-attn thread-queries/s + achieved HBM GB/s on fork-tree paged KV",
+        "value": n_queries / elapsed,
+        "unit": "thread-queries/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / K * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": hd.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{args.config}: {w.n_requests} requests, fork trees of depth "
+                        f"{max(n.depth for n in w.nodes)}, {len(run.live)} live threads, Hq={hd.n_q_heads} "
+                        f"Hkv={hd.n_kv_heads} d={hd.head_dim} block=16, seed {args.seed}",
+            "step": "fork+free churn %.3g of threads, append 1 KV row per thread, decode attention over all "
+                    "threads" % args.churn,
+            "threads_per_step": n_queries // K,
+            "unique_kv_tokens_per_step": unique_tokens // K,
+            "attended_tokens_per_step": path_tokens // K,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "attention_partial_bf16 (its 1-, 2- and 4-row-tile instantiations, launched back to back)",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": read_traffic(args.config),
+            "algorithmic_bytes_per_launch": alg_bytes / K,
+            "kernel_ms_per_launch": attn_ms,
+        },
+        "breakdown_ms_per_step": {
+            "attention_kernel": attn_ms,
+            "merge_kernel": merge_ms,
+            "append_kernels": append_ms,
+            "plan_host": prof.plan_host_ms / K,
+            "host_issue": t_host / K * 1e3,
+        },
+        "attention_call_thread_queries_per_s": (n_queries / K) / ((attn_ms + merge_ms) * 1e-3),
+        "kv_bytes": {
+            "resident": st1.bytes_resident,
+            "vanilla_copy_each_prefix": st1.bytes_vanilla,
+            "ratio": st1.bytes_vanilla / max(st1.bytes_resident, 1),
+            "resident_after_build": st0.bytes_resident,
+            "vanilla_after_build": st0.bytes_vanilla,
+        },
+        "plan": {"segments": info.n_segments, "units": info.n_units, "partial_rows": info.n_partial_rows,
+                 "unique_blocks": info.unique_blocks},
+        "build_s": t_build,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args.config, args.seed, min(args.cpu_requests, w.n_requests), dev)
+    run.close()
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

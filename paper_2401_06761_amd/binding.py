@@ -120,9 +120,16 @@ def _check(status: int, where: str) -> None:
         raise AparError(status, where, detail)
 
 
-def _ids(seq: Sequence[int]):
-    n = len(seq)
-    return (C.c_int32 * max(n, 1))(*[int(x) for x in seq]), n
+def _ids(seq):
+    """Host array of thread ids as int32*; numpy int32 arrays are passed without a copy."""
+    import numpy as np
+
+    arr = np.ascontiguousarray(seq, dtype=np.int32)
+    if arr.ndim != 1:
+        raise ValueError("thread ids must be a 1-d sequence")
+    ptr = arr.ctypes.data_as(C.POINTER(C.c_int32))
+    ptr._keepalive = arr  # the array must outlive the call
+    return ptr, int(arr.shape[0])
 
 
 def _ptr(t) -> int:
