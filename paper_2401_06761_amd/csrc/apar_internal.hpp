@@ -35,7 +35,7 @@ __host__ __device__ inline int bf16_v_offset(int token, int dim) {  // byte offs
 }
 
 // One work unit family: a run of blocks read for one set of sharing threads.
-// The kernel launches one unit per (UnitDesc, kv head).
+// The kernels launch one unit per (UnitDesc, kv head).
 struct UnitDesc {
     int32_t blk_ofs;     // first entry in the flat block-id array
     int32_t n_blk;       // blocks in the run (>= 1)
@@ -45,17 +45,30 @@ struct UnitDesc {
     int32_t part_base;   // first partial-result row of this unit
 };
 
+// A unit of at most 16 query rows and at most 8 blocks, self-contained in 64 bytes so
+// that one scalar load tells a wavefront everything it needs to start streaming.
+constexpr int kNarrowBlocks = 8;
+struct NarrowDesc {
+    int32_t n_blk;       // 1..8
+    int32_t last_valid;  // filled slots of the last block
+    int32_t n_shr;       // threads sharing the run
+    int32_t part_base;   // first partial-result row
+    int32_t shr;         // n_shr == 1: the listed-thread index itself; else first entry in the sharer array
+    int32_t pad[3];
+    int32_t blk[kNarrowBlocks];
+};
+
 struct PlanDev {              // device pointers of one staged plan
-    const UnitDesc* units;
+    const UnitDesc* units;    // all units; bf16 pools: the wide ones first, then the narrow ones
+    const NarrowDesc* narrow; // bf16 pools: the narrow units again, in the same order, in their own format
     const int32_t* blocks;    // flat block ids
     const int32_t* sharers;   // flat listed-thread indices
     const int32_t* path_ofs;  // [n_threads + 1]
     const int32_t* path_ids;  // partial-result rows on each listed thread's root path
     int32_t n_units;          // UnitDesc count
+    int32_t n_wide;           // units carrying more than 16 query rows (longest runs first)
+    int32_t n_narrow;         // units carrying at most 16 (longest first)
     int32_t n_threads;
-    // units are sorted by the number of 16-row query tiles they carry:
-    // class 0 = 3..4 tiles, class 1 = 2 tiles, class 2 = 1 tile; longest runs first in each
-    int32_t class_count[3];
 };
 
 struct Shape {

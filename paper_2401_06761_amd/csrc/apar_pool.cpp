@@ -54,21 +54,24 @@ struct EventPair {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Segment {
-    int32_t blk_ofs, n_blk, last_valid, n_shr, shr_ofs, part_base, fill;
+    int32_t blk_ofs, n_blk, last_valid, n_shr, shr_ofs, part_base, fill, chunk;
 };
 
 struct PlanHost {
-    std::vector<UnitDesc> units;
+    std::vector<UnitDesc> units;      // wide units first, then narrow ones
+    std::vector<NarrowDesc> narrow;   // bf16 pools: the narrow units in device format
+    std::vector<UnitDesc> scratch_units;
     std::vector<int32_t> blocks, sharers, path_ofs, path_ids;
     std::vector<Segment> segs;
-    std::vector<int32_t> thread_seg, thread_seg_ofs, thread_rank;
+    std::vector<int32_t> thread_seg, thread_seg_ofs;
     int64_t n_partial_rows = 0;
-    int32_t class_count[3] = {0, 0, 0};
+    int32_t n_wide = 0, n_narrow = 0;
     void clear() {
-        units.clear(), blocks.clear(), sharers.clear(), path_ofs.clear(), path_ids.clear(), segs.clear();
-        thread_seg.clear(), thread_seg_ofs.clear(), thread_rank.clear();
+        units.clear(), narrow.clear(), scratch_units.clear();
+        blocks.clear(), sharers.clear(), path_ofs.clear(), path_ids.clear(), segs.clear();
+        thread_seg.clear(), thread_seg_ofs.clear();
         n_partial_rows = 0;
-        class_count[0] = class_count[1] = class_count[2] = 0;
+        n_wide = n_narrow = 0;
     }
 };
 
@@ -88,7 +91,6 @@ struct apar_pool {
     int64_t cow_copies = 0;
 
     // plan builder scratch (pool sized, kept clean between calls)
-    std::vector<int32_t> cnt;     // listed threads holding each block
     std::vector<int32_t> seg_of;  // segment that starts at each block, -1 if none
     int chunk_blocks = 8;
     apar_plan_info last_plan{};
@@ -223,11 +225,16 @@ int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vecto
 //
 // Sharing only ever comes from forks, which hand a child the parent's whole
 // table, and copy-on-write only replaces a tail.  Hence two tables that agree
-// at one position agree at every earlier one, the set of listed threads holding
-// a table's block can only shrink along the table, and a maximal run of
-// positions with one holder count is a run with one holder set: a segment.
-// Each segment is cut into units of at most chunk_blocks blocks and at most
-// max_rows query rows; a unit is read once and applied to all of its rows.
+// at one position agree at every earlier one, and the set of live threads
+// holding a table's block can only shrink along the table.  A maximal run of
+// positions with one refcount is therefore a run with one set of holders: a
+// segment.  Every holder has the same run, so only the first listed holder
+// walks it; the others find it by its first block and skip over it.
+//
+// A segment is cut into units of bounded length and at most 64 query rows; a
+// unit's blocks are read once and applied to all of its rows.  Units of up to
+// 16 rows ("narrow": private tails, small groups) and larger ones ("wide":
+// prefixes shared by many siblings) go to different code paths of the kernel.
 // ---------------------------------------------------------------------------
 int build_plan(apar_pool* p, const apar_thread* ids, int n, int n_cand, PlanHost& ph, apar_plan_info& info) {
     const int B = kBlockTokens;
@@ -236,24 +243,24 @@ int build_plan(apar_pool* p, const apar_thread* ids, int n, int n_cand, PlanHost
         if (!t) return APAR_ERR_INVALID_THREAD;
         if (t->len == 0) return APAR_ERR_INVALID_ARG;
     }
+    const int rows_per_thread = n_cand * p->shape.group;
+    const int max_rows = attention_max_rows_per_unit(p->shape);
+    if (rows_per_thread > max_rows) return APAR_ERR_UNSUPPORTED;
+
     int64_t path_tokens = 0;
-    for (int i = 0; i < n; ++i) {
-        const Thread& t = p->threads[ids[i]];
-        for (int32_t b : t.table) p->cnt[b] += 1;
-        path_tokens += t.len;
-    }
     ph.thread_seg_ofs.assign(n + 1, 0);
     for (int i = 0; i < n; ++i) {
         const Thread& t = p->threads[ids[i]];
         const int nb = (int)t.table.size();
+        path_tokens += t.len;
         int pos = 0;
         while (pos < nb) {
             const int32_t first = t.table[pos];
-            const int32_t c = p->cnt[first];
-            int end = pos + 1;
-            while (end < nb && p->cnt[t.table[end]] == c) ++end;
             int32_t sid = p->seg_of[first];
             if (sid < 0) {
+                const int32_t r = p->ref[first];
+                int end = pos + 1;
+                while (end < nb && p->ref[t.table[end]] == r) ++end;
                 sid = (int32_t)ph.segs.size();
                 p->seg_of[first] = sid;
                 Segment s{};
@@ -263,36 +270,32 @@ int build_plan(apar_pool* p, const apar_thread* ids, int n, int n_cand, PlanHost
                 ph.blocks.insert(ph.blocks.end(), t.table.begin() + pos, t.table.begin() + end);
                 ph.segs.push_back(s);
             }
-            ph.segs[sid].n_shr += 1;
+            Segment& s = ph.segs[sid];
+            s.n_shr += 1;
             ph.thread_seg.push_back(sid);
-            pos = end;
+            pos += s.n_blk;
         }
         ph.thread_seg_ofs[i + 1] = (int32_t)ph.thread_seg.size();
     }
-    // leave the pool-sized scratch clean for the next call
-    for (int i = 0; i < n; ++i)
-        for (int32_t b : p->threads[ids[i]].table) p->cnt[b] = 0;
-    for (const Segment& s : ph.segs) p->seg_of[ph.blocks[s.blk_ofs]] = -1;
+    for (const Segment& s : ph.segs) p->seg_of[ph.blocks[s.blk_ofs]] = -1;  // leave the scratch clean
 
-    const int rows_per_thread = n_cand * p->shape.group;
-    const int max_rows = attention_max_rows_per_unit(p->shape);
-    if (rows_per_thread > max_rows) return APAR_ERR_UNSUPPORTED;
+    const bool mfma_path = p->shape.dtype == APAR_BF16;
     const int grp = std::max(1, max_rows / rows_per_thread);  // threads per unit
-
-    // A unit writes one partial result per row and reads 16 tokens of K and V per
-    // block; runs shared by many rows get longer units so the partial results stay a
-    // small fraction of the bytes moved.
-    auto chunk_of = [&](const Segment& s) {
-        const int rows = std::min(s.n_shr * rows_per_thread, max_rows);
-        return std::max(p->chunk_blocks, (rows * 3 + 1) / 2);
-    };
     int32_t shr_total = 0;
     int64_t part_total = 0, unique_tokens = 0;
     for (Segment& s : ph.segs) {
         s.shr_ofs = shr_total;
         shr_total += s.n_shr;
-        const int chunk = chunk_of(s);
-        const int n_chunks = (s.n_blk + chunk - 1) / chunk;
+        const int rows = std::min(s.n_shr * rows_per_thread, max_rows);
+        if (mfma_path && rows <= 16) {
+            s.chunk = std::min(p->chunk_blocks, kNarrowBlocks);
+        } else {
+            // A unit writes one partial result per row and reads 16 tokens of K and V per block:
+            // runs shared by many rows get longer units, so that partial results stay a small
+            // fraction of the bytes moved.
+            s.chunk = std::max(p->chunk_blocks, (rows * 3 + 1) / 2);
+        }
+        const int n_chunks = (s.n_blk + s.chunk - 1) / s.chunk;
         s.part_base = (int32_t)part_total;
         part_total += (int64_t)n_chunks * s.n_shr;
         unique_tokens += (int64_t)(s.n_blk - 1) * B + s.last_valid;
@@ -300,31 +303,27 @@ int build_plan(apar_pool* p, const apar_thread* ids, int n, int n_cand, PlanHost
     if (part_total > INT32_MAX / 2) return APAR_ERR_UNSUPPORTED;
     ph.n_partial_rows = part_total;
     ph.sharers.resize(shr_total);
-    ph.thread_rank.resize(ph.thread_seg.size());
     ph.path_ofs.assign(n + 1, 0);
     for (int i = 0; i < n; ++i) {
         for (int32_t k = ph.thread_seg_ofs[i]; k < ph.thread_seg_ofs[i + 1]; ++k) {
             Segment& s = ph.segs[ph.thread_seg[k]];
             const int32_t rank = s.fill++;
             ph.sharers[s.shr_ofs + rank] = i;
-            const int chunk = chunk_of(s);
-            const int n_chunks = (s.n_blk + chunk - 1) / chunk;
+            const int n_chunks = (s.n_blk + s.chunk - 1) / s.chunk;
             for (int c = 0; c < n_chunks; ++c) ph.path_ids.push_back(s.part_base + c * s.n_shr + rank);
         }
         ph.path_ofs[i + 1] = (int32_t)ph.path_ids.size();
     }
-    // units by row-tile class, longest first inside a class so each launch ends on short ones
-    struct Keyed {
-        int32_t key;
-        UnitDesc u;
-    };
-    std::vector<Keyed> keyed;
+
+    // units: wide ones first, longest first, so the launch ends on short narrow ones
+    std::vector<UnitDesc>& wide = ph.units;
+    std::vector<UnitDesc>& narrow = ph.scratch_units;
+    int32_t narrow_count[kNarrowBlocks + 1] = {0};
     for (const Segment& s : ph.segs) {
-        const int chunk = chunk_of(s);
-        const int n_chunks = (s.n_blk + chunk - 1) / chunk;
+        const int n_chunks = (s.n_blk + s.chunk - 1) / s.chunk;
         for (int c = 0; c < n_chunks; ++c) {
-            const int b0 = c * chunk;
-            const int nb = std::min(chunk, s.n_blk - b0);
+            const int b0 = c * s.chunk;
+            const int nb = std::min(s.chunk, s.n_blk - b0);
             for (int g0 = 0; g0 < s.n_shr; g0 += grp) {
                 UnitDesc u;
                 u.blk_ofs = s.blk_ofs + b0;
@@ -333,16 +332,37 @@ int build_plan(apar_pool* p, const apar_thread* ids, int n, int n_cand, PlanHost
                 u.shr_ofs = s.shr_ofs + g0;
                 u.n_shr = std::min(grp, s.n_shr - g0);
                 u.part_base = s.part_base + c * s.n_shr + g0;
-                const int tiles = (u.n_shr * rows_per_thread + 15) / 16;
-                const int cls = tiles > 2 ? 0 : (tiles == 2 ? 1 : 2);
-                ph.class_count[cls] += 1;
-                keyed.push_back({cls * 65536 + (65535 - nb), u});
+                if (mfma_path && u.n_shr * rows_per_thread <= 16 && nb <= kNarrowBlocks) {
+                    narrow.push_back(u);
+                    narrow_count[nb] += 1;
+                } else {
+                    wide.push_back(u);
+                }
             }
         }
     }
-    std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) { return a.key < b.key; });
-    ph.units.reserve(keyed.size());
-    for (const Keyed& k : keyed) ph.units.push_back(k.u);
+    std::stable_sort(wide.begin(), wide.end(), [](const UnitDesc& a, const UnitDesc& b) { return a.n_blk > b.n_blk; });
+    ph.n_wide = (int32_t)wide.size();
+    ph.n_narrow = (int32_t)narrow.size();
+    if (ph.n_narrow > 0) {
+        int32_t start[kNarrowBlocks + 1];
+        int32_t acc = ph.n_wide;
+        for (int nb = kNarrowBlocks; nb >= 1; --nb) start[nb] = acc, acc += narrow_count[nb];
+        wide.resize(ph.n_wide + ph.n_narrow);
+        ph.narrow.resize(ph.n_narrow);
+        for (const UnitDesc& u : narrow) {
+            const int32_t at = start[u.n_blk]++;
+            wide[at] = u;
+            NarrowDesc& d = ph.narrow[at - ph.n_wide];
+            d.n_blk = u.n_blk;
+            d.last_valid = u.last_valid;
+            d.n_shr = u.n_shr;
+            d.part_base = u.part_base;
+            d.shr = u.n_shr == 1 ? ph.sharers[u.shr_ofs] : u.shr_ofs;
+            d.pad[0] = d.pad[1] = d.pad[2] = 0;
+            for (int b = 0; b < kNarrowBlocks; ++b) d.blk[b] = b < u.n_blk ? ph.blocks[u.blk_ofs + b] : 0;
+        }
+    }
 
     const int64_t e = p->shape.dtype == APAR_F32 ? 4 : 2;
     info.n_threads = n;
@@ -388,20 +408,22 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     hipStream_t st = (hipStream_t)stream;
 
     // stage the five tables in one copy
-    size_t ofs[6];
+    size_t ofs[7];
     ofs[0] = 0;
     ofs[1] = align_up(ofs[0] + ph.units.size() * sizeof(UnitDesc), 256);
     ofs[2] = align_up(ofs[1] + ph.blocks.size() * 4, 256);
     ofs[3] = align_up(ofs[2] + ph.sharers.size() * 4, 256);
     ofs[4] = align_up(ofs[3] + ph.path_ofs.size() * 4, 256);
     ofs[5] = align_up(ofs[4] + ph.path_ids.size() * 4, 256);
+    ofs[6] = align_up(ofs[5] + ph.narrow.size() * sizeof(NarrowDesc), 256);
     StageSlot* s = nullptr;
-    if ((rc = acquire_stage(p, ofs[5], &s)) != APAR_OK) return rc;
+    if ((rc = acquire_stage(p, ofs[6], &s)) != APAR_OK) return rc;
     memcpy(s->host + ofs[0], ph.units.data(), ph.units.size() * sizeof(UnitDesc));
     memcpy(s->host + ofs[1], ph.blocks.data(), ph.blocks.size() * 4);
     memcpy(s->host + ofs[2], ph.sharers.data(), ph.sharers.size() * 4);
     memcpy(s->host + ofs[3], ph.path_ofs.data(), ph.path_ofs.size() * 4);
     memcpy(s->host + ofs[4], ph.path_ids.data(), ph.path_ids.size() * 4);
+    if (!ph.narrow.empty()) memcpy(s->host + ofs[5], ph.narrow.data(), ph.narrow.size() * sizeof(NarrowDesc));
 
     // partial-result buffer
     const size_t slots = (size_t)ph.n_partial_rows * n_cand * p->shape.n_q;
@@ -417,16 +439,18 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
         p->part_slots_cap = cap;
     }
 
-    HIP_TRY(hipMemcpyAsync(s->dev, s->host, ofs[5], hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(s->dev, s->host, ofs[6], hipMemcpyHostToDevice, st));
     PlanDev pd;
     pd.units = (const UnitDesc*)(s->dev + ofs[0]);
     pd.blocks = (const int32_t*)(s->dev + ofs[1]);
     pd.sharers = (const int32_t*)(s->dev + ofs[2]);
     pd.path_ofs = (const int32_t*)(s->dev + ofs[3]);
     pd.path_ids = (const int32_t*)(s->dev + ofs[4]);
+    pd.narrow = (const NarrowDesc*)(s->dev + ofs[5]);
     pd.n_units = (int32_t)ph.units.size();
+    pd.n_wide = ph.n_wide;
+    pd.n_narrow = ph.n_narrow;
     pd.n_threads = n;
-    for (int c = 0; c < 3; ++c) pd.class_count[c] = ph.class_count[c];
 
     EventPair ev;
     if (p->profiling) {
@@ -503,7 +527,6 @@ int apar_pool_create(const apar_pool_config* cfg, void* kv_dev, size_t kv_bytes,
     p->ref.assign(cfg->num_blocks, 0);
     p->free_stack.resize(cfg->num_blocks);
     for (int64_t i = 0; i < cfg->num_blocks; ++i) p->free_stack[i] = (int32_t)(cfg->num_blocks - 1 - i);
-    p->cnt.assign(cfg->num_blocks, 0);
     p->seg_of.assign(cfg->num_blocks, -1);
     *out = p;
     return APAR_OK;
