@@ -87,7 +87,7 @@ typedef struct apar_stats {
 typedef struct apar_plan_info {
     int64_t n_threads;         /* listed threads                                         */
     int64_t n_segments;        /* maximal runs of blocks shared by one set of threads    */
-    int64_t n_units;           /* (block run, kv head) work units launched               */
+    int64_t n_units;           /* workgroups launched (plan workgroups x kv heads)        */
     int64_t n_partial_rows;    /* (unit, thread) partial results merged afterwards       */
     int64_t unique_blocks;     /* distinct blocks read                                   */
     int64_t unique_tokens;     /* filled slots in those blocks: each cached row once     */
@@ -200,19 +200,24 @@ APAR_API int apar_thread_block_table(apar_pool* pool, apar_thread thread, int32_
 APAR_API int apar_block_refcount(apar_pool* pool, int32_t block, int32_t* refcount_out);
 APAR_API int apar_pool_stats(apar_pool* pool, apar_stats* out);
 APAR_API int apar_last_plan_info(apar_pool* pool, apar_plan_info* out);
-/* Tables of the last decode call's plan, for inspection.  `which`:
- *   APAR_PLAN_UNITS    6 int32 per unit family: first index into BLOCKS, block
- *                      count, filled slots of the last block, first index into
- *                      SHARERS, thread count, first partial-result row; one work
- *                      unit per family and kv head is launched;
- *   APAR_PLAN_BLOCKS   flat block ids;   APAR_PLAN_SHARERS  flat indices into the
- *                      listed threads;
- *   APAR_PLAN_PATH_OFS [n+1] offsets into PATH_IDS;  APAR_PLAN_PATH_IDS  partial-
- *                      result rows merged for each listed thread (family f, its
- *                      j-th thread -> row first_partial_row + j).
+/* Tables of the last decode call's plan, for inspection (int32 arrays).  The listed threads are
+ * numbered depth-first along their sharing tree ("rank"); a thread's query rows are cut into
+ * `slices` slices of at most 16 rows, and row group = rank * slices + slice.  `which`:
+ *   APAR_PLAN_WORKGROUPS  32 ints per workgroup: [0] first shared tile, [1] shared tile count,
+ *                         [2] row group the shared tiles' ranges are relative to, [3] unused, then
+ *                         4 wavefronts x 6: first own tile, own tile count, first row group, row
+ *                         group count, first partial-result row (of the thread owning the first
+ *                         row group), flags (bit 0: writes output rows directly); [28..31] unused;
+ *   APAR_PLAN_TILES       2 ints per tile: block id, lo | hi << 8 | filled_slots << 16, where
+ *                         [lo, hi) are the row groups the block applies to, relative to the
+ *                         wavefront's first row group (own tiles) or to [2] (shared tiles);
+ *   APAR_PLAN_DFS_THREADS rank -> index into the listed threads;
+ *   APAR_PLAN_PATH_OFS    [n+1] offsets into PATH_IDS by listed index;  APAR_PLAN_PATH_IDS  the
+ *                         partial-result rows merged for each listed thread (none: written directly);
+ *   APAR_PLAN_GEOMETRY    rows per thread, rows per slice, slices.
  * Stores the element count in n_out; INVALID_ARG if cap is too small. */
-enum { APAR_PLAN_UNITS = 0, APAR_PLAN_BLOCKS = 1, APAR_PLAN_SHARERS = 2, APAR_PLAN_PATH_OFS = 3,
-       APAR_PLAN_PATH_IDS = 4 };
+enum { APAR_PLAN_WORKGROUPS = 0, APAR_PLAN_TILES = 1, APAR_PLAN_DFS_THREADS = 2, APAR_PLAN_PATH_OFS = 3,
+       APAR_PLAN_PATH_IDS = 4, APAR_PLAN_GEOMETRY = 5 };
 APAR_API int apar_last_plan_export(apar_pool* pool, int which, int32_t* out, int64_t cap, int64_t* n_out);
 /* Gathers rows [first, first+n) of a thread out of the pool's private layout
  * into row-major k_out_dev, v_out_dev : [n, Hkv, d]. */
@@ -225,7 +230,9 @@ APAR_API int apar_profile_enable(apar_pool* pool, int on);
 /* Waits for the recorded events, adds up the elapsed times since the last
  * read, stores them in out and resets the sums. */
 APAR_API int apar_profile_read(apar_pool* pool, apar_profile* out);
-/* Tuning knob: blocks per work unit of the attention kernel (1..64; default 8). */
+/* Tuning knob: the most blocks one wavefront is given in one work unit (1..65536; default 512).
+ * Sharing subtrees with more blocks than that are cut into several units whose partial results are
+ * merged afterwards; small values exist to exercise that path. */
 APAR_API int apar_set_chunk_blocks(apar_pool* pool, int blocks_per_unit);
 
 APAR_API const char* apar_status_string(int status);

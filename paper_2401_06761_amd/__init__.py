@@ -22,11 +22,12 @@ from .binding import (  # noqa: F401
     apar_free_thread,
     apar_last_plan_export,
     apar_last_plan_info,
-    APAR_PLAN_UNITS,
-    APAR_PLAN_BLOCKS,
-    APAR_PLAN_SHARERS,
+    APAR_PLAN_WORKGROUPS,
+    APAR_PLAN_TILES,
+    APAR_PLAN_DFS_THREADS,
     APAR_PLAN_PATH_OFS,
     APAR_PLAN_PATH_IDS,
+    APAR_PLAN_GEOMETRY,
     apar_pool_create,
     apar_pool_destroy,
     apar_pool_stats,

@@ -243,7 +243,8 @@ def apar_last_plan_info(pool) -> AparPlanInfo:
     return out
 
 
-APAR_PLAN_UNITS, APAR_PLAN_BLOCKS, APAR_PLAN_SHARERS, APAR_PLAN_PATH_OFS, APAR_PLAN_PATH_IDS = range(5)
+(APAR_PLAN_WORKGROUPS, APAR_PLAN_TILES, APAR_PLAN_DFS_THREADS, APAR_PLAN_PATH_OFS, APAR_PLAN_PATH_IDS,
+ APAR_PLAN_GEOMETRY) = range(6)
 
 
 def apar_last_plan_export(pool, which: int) -> List[int]:

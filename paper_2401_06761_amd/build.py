@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libapar.so")
-SOURCES = ["apar_pool.cpp", "kernels_misc.hip", "kernels_attn_bf16.hip"]
+SOURCES = ["apar_pool.cpp", "plan.cpp", "kernels_misc.hip", "kernels_attn_bf16.hip"]
 
 
 def hipcc() -> str:
@@ -27,10 +27,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     cmd += list(extra_flags)
     for s in SOURCES:
-        if s.endswith(".cpp"):
-            cmd += ["-x", "hip", os.path.join(CSRC, s)]
-        else:
-            cmd += [os.path.join(CSRC, s)]
+        cmd += ["-x", "hip", os.path.join(CSRC, s)]
     tmp = LIB + ".tmp"
     cmd += ["-o", tmp]
     if verbose:

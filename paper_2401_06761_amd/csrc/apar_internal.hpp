@@ -34,41 +34,49 @@ __host__ __device__ inline int bf16_v_offset(int token, int dim) {  // byte offs
     return (dim >> 5) * 1024 + (((token >> 2) * 16 + (dim & 15)) * 16) + ((dim >> 4) & 1) * 8 + (token & 3) * 2;
 }
 
-// One work unit family: a run of blocks read for one set of sharing threads.
-// The kernels launch one unit per (UnitDesc, kv head).
-struct UnitDesc {
-    int32_t blk_ofs;     // first entry in the flat block-id array
-    int32_t n_blk;       // blocks in the run (>= 1)
-    int32_t last_valid;  // filled slots in the run's last block (1..16); all others are full
-    int32_t shr_ofs;     // first entry in the flat sharer array (indices into the listed threads)
-    int32_t n_shr;       // threads sharing the run (rows = n_shr * n_cand * group size)
-    int32_t part_base;   // first partial-result row of this unit
+// ---------------------------------------------------------------------------
+// Plan tables (built on the host, read by the attention and merge kernels).
+//
+// The listed threads are numbered in depth-first order of their sharing tree, so
+// the threads that hold any given block are a contiguous range of ranks.  A
+// thread's query rows (candidates x q heads of one kv group) are cut into
+// `n_slices` slices of at most 16 rows; (thread, slice) is a "row group" with
+// index rank * n_slices + slice.  A wavefront holds up to 16 / rows_per_slice
+// consecutive row groups as the columns of its 16x16 tiles.
+// ---------------------------------------------------------------------------
+struct TileRef {     // one block to read, and the row groups it applies to
+    int32_t blk;
+    int32_t meta;    // lo | hi << 8 | valid << 16: row groups [lo, hi) relative to the list owner's first
+                     // row group (the workgroup's for shared lists, the wavefront's for its own list);
+                     // valid = filled token slots (1..16)
 };
 
-// A unit of at most 16 query rows and at most 8 blocks, self-contained in 64 bytes so
-// that one scalar load tells a wavefront everything it needs to start streaming.
-constexpr int kNarrowBlocks = 8;
-struct NarrowDesc {
-    int32_t n_blk;       // 1..8
-    int32_t last_valid;  // filled slots of the last block
-    int32_t n_shr;       // threads sharing the run
-    int32_t part_base;   // first partial-result row
-    int32_t shr;         // n_shr == 1: the listed-thread index itself; else first entry in the sharer array
-    int32_t pad[3];
-    int32_t blk[kNarrowBlocks];
+struct WaveItem {    // what one wavefront computes
+    int32_t tile_ofs, n_tiles;  // its own tile list
+    int32_t grp_lo, n_grp;      // its row groups [grp_lo, grp_lo + n_grp); n_grp == 0: nothing to compute
+    int32_t part_base;          // partial-result row of the thread that owns row group grp_lo
+    int32_t flags;              // kWaveDirect: normalise and write the output rows instead of partial results
 };
+constexpr int32_t kWaveDirect = 1;
+
+struct WgDesc {      // one 256-thread workgroup: a shared tile list, then one private list per wavefront
+    int32_t coop_ofs, n_coop;   // tiles every wavefront of the group sees (staged once through LDS)
+    int32_t grp_base;           // row group that the shared list's ranges are relative to
+    int32_t pad;
+    WaveItem w[4];
+    int32_t pad2[4];
+};
+static_assert(sizeof(WgDesc) == 128, "WgDesc is read with aligned scalar loads");
 
 struct PlanDev {              // device pointers of one staged plan
-    const UnitDesc* units;    // all units; bf16 pools: the wide ones first, then the narrow ones
-    const NarrowDesc* narrow; // bf16 pools: the narrow units again, in the same order, in their own format
-    const int32_t* blocks;    // flat block ids
-    const int32_t* sharers;   // flat listed-thread indices
-    const int32_t* path_ofs;  // [n_threads + 1]
-    const int32_t* path_ids;  // partial-result rows on each listed thread's root path
-    int32_t n_units;          // UnitDesc count
-    int32_t n_wide;           // units carrying more than 16 query rows (longest runs first)
-    int32_t n_narrow;         // units carrying at most 16 (longest first)
+    const WgDesc* wgs;
+    const TileRef* tiles;
+    const int32_t* dfs_threads;  // rank -> index into the listed threads
+    const int32_t* path_ofs;     // [n_threads + 1], by listed index
+    const int32_t* path_ids;     // partial-result rows to merge for each listed thread (none: written directly)
+    int32_t n_wg;
     int32_t n_threads;
+    int32_t rows_per_thread, rows_per_slice, n_slices;
 };
 
 struct Shape {
@@ -94,11 +102,9 @@ hipError_t launch_block_copies(const Shape& s, void* pool, const int32_t* src_ds
 hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src_codes, int n_rows, void* k_out,
                             void* v_out, hipStream_t st);
 hipError_t launch_attention_partial(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
-                                    int max_rows, PartialBuf part, hipStream_t st);
+                                    PartialBuf part, void* out, hipStream_t st);
 hipError_t launch_merge(const Shape& s, const PlanDev& plan, PartialBuf part, const void* q, const void* cand_k,
                         const void* cand_v, const uint8_t* mask, int n_cand, void* out, hipStream_t st);
 
-// Largest number of query rows (threads * candidates * group) one unit may carry.
-int attention_max_rows_per_unit(const Shape& s);
 
 }  // namespace apar

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "apar_internal.hpp"
+#include "plan.hpp"
 
 using namespace apar;
 
@@ -53,28 +54,6 @@ struct EventPair {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-struct Segment {
-    int32_t blk_ofs, n_blk, last_valid, n_shr, shr_ofs, part_base, fill, chunk;
-};
-
-struct PlanHost {
-    std::vector<UnitDesc> units;      // wide units first, then narrow ones
-    std::vector<NarrowDesc> narrow;   // bf16 pools: the narrow units in device format
-    std::vector<UnitDesc> scratch_units;
-    std::vector<int32_t> blocks, sharers, path_ofs, path_ids;
-    std::vector<Segment> segs;
-    std::vector<int32_t> thread_seg, thread_seg_ofs;
-    int64_t n_partial_rows = 0;
-    int32_t n_wide = 0, n_narrow = 0;
-    void clear() {
-        units.clear(), narrow.clear(), scratch_units.clear();
-        blocks.clear(), sharers.clear(), path_ofs.clear(), path_ids.clear(), segs.clear();
-        thread_seg.clear(), thread_seg_ofs.clear();
-        n_partial_rows = 0;
-        n_wide = n_narrow = 0;
-    }
-};
-
 }  // namespace
 
 struct apar_pool {
@@ -92,9 +71,11 @@ struct apar_pool {
 
     // plan builder scratch (pool sized, kept clean between calls)
     std::vector<int32_t> seg_of;  // segment that starts at each block, -1 if none
-    int chunk_blocks = 8;
+    int max_unit_tiles = 512;  // longest tile list given to one wavefront
+    std::vector<PlanThreadView> views;
     apar_plan_info last_plan{};
     PlanHost plan;  // the last plan, kept for reuse of its storage and for inspection
+    int32_t plan_geom[3] = {1, 1, 1};  // rows per thread, rows per slice, slices of the last plan
 
     StageSlot stage[kStageSlots];
     int next_slot = 0;
@@ -220,163 +201,6 @@ int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vecto
     return APAR_OK;
 }
 
-// ---------------------------------------------------------------------------
-// Plan: group the listed threads by the blocks they share.
-//
-// Sharing only ever comes from forks, which hand a child the parent's whole
-// table, and copy-on-write only replaces a tail.  Hence two tables that agree
-// at one position agree at every earlier one, and the set of live threads
-// holding a table's block can only shrink along the table.  A maximal run of
-// positions with one refcount is therefore a run with one set of holders: a
-// segment.  Every holder has the same run, so only the first listed holder
-// walks it; the others find it by its first block and skip over it.
-//
-// A segment is cut into units of bounded length and at most 64 query rows; a
-// unit's blocks are read once and applied to all of its rows.  Units of up to
-// 16 rows ("narrow": private tails, small groups) and larger ones ("wide":
-// prefixes shared by many siblings) go to different code paths of the kernel.
-// ---------------------------------------------------------------------------
-int build_plan(apar_pool* p, const apar_thread* ids, int n, int n_cand, PlanHost& ph, apar_plan_info& info) {
-    const int B = kBlockTokens;
-    for (int i = 0; i < n; ++i) {
-        Thread* t = live_thread(p, ids[i]);
-        if (!t) return APAR_ERR_INVALID_THREAD;
-        if (t->len == 0) return APAR_ERR_INVALID_ARG;
-    }
-    const int rows_per_thread = n_cand * p->shape.group;
-    const int max_rows = attention_max_rows_per_unit(p->shape);
-    if (rows_per_thread > max_rows) return APAR_ERR_UNSUPPORTED;
-
-    int64_t path_tokens = 0;
-    ph.thread_seg_ofs.assign(n + 1, 0);
-    for (int i = 0; i < n; ++i) {
-        const Thread& t = p->threads[ids[i]];
-        const int nb = (int)t.table.size();
-        path_tokens += t.len;
-        int pos = 0;
-        while (pos < nb) {
-            const int32_t first = t.table[pos];
-            int32_t sid = p->seg_of[first];
-            if (sid < 0) {
-                const int32_t r = p->ref[first];
-                int end = pos + 1;
-                while (end < nb && p->ref[t.table[end]] == r) ++end;
-                sid = (int32_t)ph.segs.size();
-                p->seg_of[first] = sid;
-                Segment s{};
-                s.blk_ofs = (int32_t)ph.blocks.size();
-                s.n_blk = end - pos;
-                s.last_valid = (end == nb) ? (int32_t)(t.len - (int64_t)(nb - 1) * B) : B;
-                ph.blocks.insert(ph.blocks.end(), t.table.begin() + pos, t.table.begin() + end);
-                ph.segs.push_back(s);
-            }
-            Segment& s = ph.segs[sid];
-            s.n_shr += 1;
-            ph.thread_seg.push_back(sid);
-            pos += s.n_blk;
-        }
-        ph.thread_seg_ofs[i + 1] = (int32_t)ph.thread_seg.size();
-    }
-    for (const Segment& s : ph.segs) p->seg_of[ph.blocks[s.blk_ofs]] = -1;  // leave the scratch clean
-
-    const bool mfma_path = p->shape.dtype == APAR_BF16;
-    const int grp = std::max(1, max_rows / rows_per_thread);  // threads per unit
-    int32_t shr_total = 0;
-    int64_t part_total = 0, unique_tokens = 0;
-    for (Segment& s : ph.segs) {
-        s.shr_ofs = shr_total;
-        shr_total += s.n_shr;
-        const int rows = std::min(s.n_shr * rows_per_thread, max_rows);
-        if (mfma_path && rows <= 16) {
-            s.chunk = std::min(p->chunk_blocks, kNarrowBlocks);
-        } else {
-            // A unit writes one partial result per row and reads 16 tokens of K and V per block:
-            // runs shared by many rows get longer units, so that partial results stay a small
-            // fraction of the bytes moved.
-            s.chunk = std::max(p->chunk_blocks, (rows * 3 + 1) / 2);
-        }
-        const int n_chunks = (s.n_blk + s.chunk - 1) / s.chunk;
-        s.part_base = (int32_t)part_total;
-        part_total += (int64_t)n_chunks * s.n_shr;
-        unique_tokens += (int64_t)(s.n_blk - 1) * B + s.last_valid;
-    }
-    if (part_total > INT32_MAX / 2) return APAR_ERR_UNSUPPORTED;
-    ph.n_partial_rows = part_total;
-    ph.sharers.resize(shr_total);
-    ph.path_ofs.assign(n + 1, 0);
-    for (int i = 0; i < n; ++i) {
-        for (int32_t k = ph.thread_seg_ofs[i]; k < ph.thread_seg_ofs[i + 1]; ++k) {
-            Segment& s = ph.segs[ph.thread_seg[k]];
-            const int32_t rank = s.fill++;
-            ph.sharers[s.shr_ofs + rank] = i;
-            const int n_chunks = (s.n_blk + s.chunk - 1) / s.chunk;
-            for (int c = 0; c < n_chunks; ++c) ph.path_ids.push_back(s.part_base + c * s.n_shr + rank);
-        }
-        ph.path_ofs[i + 1] = (int32_t)ph.path_ids.size();
-    }
-
-    // units: wide ones first, longest first, so the launch ends on short narrow ones
-    std::vector<UnitDesc>& wide = ph.units;
-    std::vector<UnitDesc>& narrow = ph.scratch_units;
-    int32_t narrow_count[kNarrowBlocks + 1] = {0};
-    for (const Segment& s : ph.segs) {
-        const int n_chunks = (s.n_blk + s.chunk - 1) / s.chunk;
-        for (int c = 0; c < n_chunks; ++c) {
-            const int b0 = c * s.chunk;
-            const int nb = std::min(s.chunk, s.n_blk - b0);
-            for (int g0 = 0; g0 < s.n_shr; g0 += grp) {
-                UnitDesc u;
-                u.blk_ofs = s.blk_ofs + b0;
-                u.n_blk = nb;
-                u.last_valid = (b0 + nb == s.n_blk) ? s.last_valid : B;
-                u.shr_ofs = s.shr_ofs + g0;
-                u.n_shr = std::min(grp, s.n_shr - g0);
-                u.part_base = s.part_base + c * s.n_shr + g0;
-                if (mfma_path && u.n_shr * rows_per_thread <= 16 && nb <= kNarrowBlocks) {
-                    narrow.push_back(u);
-                    narrow_count[nb] += 1;
-                } else {
-                    wide.push_back(u);
-                }
-            }
-        }
-    }
-    std::stable_sort(wide.begin(), wide.end(), [](const UnitDesc& a, const UnitDesc& b) { return a.n_blk > b.n_blk; });
-    ph.n_wide = (int32_t)wide.size();
-    ph.n_narrow = (int32_t)narrow.size();
-    if (ph.n_narrow > 0) {
-        int32_t start[kNarrowBlocks + 1];
-        int32_t acc = ph.n_wide;
-        for (int nb = kNarrowBlocks; nb >= 1; --nb) start[nb] = acc, acc += narrow_count[nb];
-        wide.resize(ph.n_wide + ph.n_narrow);
-        ph.narrow.resize(ph.n_narrow);
-        for (const UnitDesc& u : narrow) {
-            const int32_t at = start[u.n_blk]++;
-            wide[at] = u;
-            NarrowDesc& d = ph.narrow[at - ph.n_wide];
-            d.n_blk = u.n_blk;
-            d.last_valid = u.last_valid;
-            d.n_shr = u.n_shr;
-            d.part_base = u.part_base;
-            d.shr = u.n_shr == 1 ? ph.sharers[u.shr_ofs] : u.shr_ofs;
-            d.pad[0] = d.pad[1] = d.pad[2] = 0;
-            for (int b = 0; b < kNarrowBlocks; ++b) d.blk[b] = b < u.n_blk ? ph.blocks[u.blk_ofs + b] : 0;
-        }
-    }
-
-    const int64_t e = p->shape.dtype == APAR_F32 ? 4 : 2;
-    info.n_threads = n;
-    info.n_segments = (int64_t)ph.segs.size();
-    info.n_units = (int64_t)ph.units.size() * p->shape.n_kv;
-    info.n_partial_rows = part_total;
-    info.unique_blocks = (int64_t)ph.blocks.size();
-    info.unique_tokens = unique_tokens;
-    info.path_tokens = path_tokens;
-    info.algorithmic_bytes = unique_tokens * 2 * p->shape.n_kv * p->shape.d * e +
-                             2 * (int64_t)n * n_cand * p->shape.n_q * p->shape.d * e;
-    return APAR_OK;
-}
-
 int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* cand_v, const uint8_t* mask,
                   int n_cand, const apar_thread* ids, int n, void* out, void* stream, bool spec) {
     if (!p || n < 0) return APAR_ERR_INVALID_ARG;
@@ -391,15 +215,39 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     }
     const auto t0 = std::chrono::steady_clock::now();
 
-    PlanHost& ph = p->plan;
-    ph.clear();
-    apar_plan_info info{};
-    int rc = build_plan(p, ids, n, n_cand, ph, info);
-    if (rc != APAR_OK) return rc;
-    if (spec) {
-        const int64_t e = p->shape.dtype == APAR_F32 ? 4 : 2;
-        info.algorithmic_bytes += 2 * (int64_t)n * n_cand * p->shape.n_kv * p->shape.d * e;
+    for (int i = 0; i < n; ++i) {
+        Thread* t = live_thread(p, ids[i]);
+        if (!t) return APAR_ERR_INVALID_THREAD;
+        if (t->len == 0) return APAR_ERR_INVALID_ARG;
     }
+    p->views.resize(n);
+    for (int i = 0; i < n; ++i) {
+        const Thread& t = p->threads[ids[i]];
+        p->views[i] = PlanThreadView{t.table.data(), (int32_t)t.table.size(), t.len};
+    }
+    PlanHost& ph = p->plan;
+    PlanParams prm;
+    prm.rows_per_thread = n_cand * p->shape.group;
+    prm.max_unit_tiles = p->max_unit_tiles;
+    prm.allow_direct = !spec;  // the merge kernel is where candidates are folded in
+    prm.fuse = true;
+    int rc = build_plan(p->views.data(), n, p->ref.data(), p->seg_of.data(), prm, ph);
+    if (rc != APAR_OK) return rc;
+    const int64_t e = p->shape.dtype == APAR_F32 ? 4 : 2;
+    apar_plan_info info{};
+    info.n_threads = n;
+    info.n_segments = ph.n_segments;
+    info.n_units = (int64_t)ph.wgs.size() * p->shape.n_kv;
+    info.n_partial_rows = ph.n_partial_rows;
+    info.unique_blocks = ph.unique_blocks;
+    info.unique_tokens = ph.unique_tokens;
+    info.path_tokens = ph.path_tokens;
+    info.algorithmic_bytes = ph.unique_tokens * 2 * p->shape.n_kv * p->shape.d * e +
+                             2 * (int64_t)n * n_cand * p->shape.n_q * p->shape.d * e;
+    if (spec) info.algorithmic_bytes += 2 * (int64_t)n * n_cand * p->shape.n_kv * p->shape.d * e;
+    p->plan_geom[0] = prm.rows_per_thread;
+    p->plan_geom[2] = (prm.rows_per_thread + 15) / 16;
+    p->plan_geom[1] = (prm.rows_per_thread + p->plan_geom[2] - 1) / p->plan_geom[2];
     if (p->dry_run) {
         p->last_plan = info;
         return APAR_OK;
@@ -408,22 +256,20 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     hipStream_t st = (hipStream_t)stream;
 
     // stage the five tables in one copy
-    size_t ofs[7];
+    size_t ofs[6];
     ofs[0] = 0;
-    ofs[1] = align_up(ofs[0] + ph.units.size() * sizeof(UnitDesc), 256);
-    ofs[2] = align_up(ofs[1] + ph.blocks.size() * 4, 256);
-    ofs[3] = align_up(ofs[2] + ph.sharers.size() * 4, 256);
+    ofs[1] = align_up(ofs[0] + ph.wgs.size() * sizeof(WgDesc), 256);
+    ofs[2] = align_up(ofs[1] + ph.tiles.size() * sizeof(TileRef), 256);
+    ofs[3] = align_up(ofs[2] + ph.dfs_threads.size() * 4, 256);
     ofs[4] = align_up(ofs[3] + ph.path_ofs.size() * 4, 256);
     ofs[5] = align_up(ofs[4] + ph.path_ids.size() * 4, 256);
-    ofs[6] = align_up(ofs[5] + ph.narrow.size() * sizeof(NarrowDesc), 256);
     StageSlot* s = nullptr;
-    if ((rc = acquire_stage(p, ofs[6], &s)) != APAR_OK) return rc;
-    memcpy(s->host + ofs[0], ph.units.data(), ph.units.size() * sizeof(UnitDesc));
-    memcpy(s->host + ofs[1], ph.blocks.data(), ph.blocks.size() * 4);
-    memcpy(s->host + ofs[2], ph.sharers.data(), ph.sharers.size() * 4);
+    if ((rc = acquire_stage(p, ofs[5], &s)) != APAR_OK) return rc;
+    memcpy(s->host + ofs[0], ph.wgs.data(), ph.wgs.size() * sizeof(WgDesc));
+    memcpy(s->host + ofs[1], ph.tiles.data(), ph.tiles.size() * sizeof(TileRef));
+    memcpy(s->host + ofs[2], ph.dfs_threads.data(), ph.dfs_threads.size() * 4);
     memcpy(s->host + ofs[3], ph.path_ofs.data(), ph.path_ofs.size() * 4);
-    memcpy(s->host + ofs[4], ph.path_ids.data(), ph.path_ids.size() * 4);
-    if (!ph.narrow.empty()) memcpy(s->host + ofs[5], ph.narrow.data(), ph.narrow.size() * sizeof(NarrowDesc));
+    if (!ph.path_ids.empty()) memcpy(s->host + ofs[4], ph.path_ids.data(), ph.path_ids.size() * 4);
 
     // partial-result buffer
     const size_t slots = (size_t)ph.n_partial_rows * n_cand * p->shape.n_q;
@@ -439,18 +285,18 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
         p->part_slots_cap = cap;
     }
 
-    HIP_TRY(hipMemcpyAsync(s->dev, s->host, ofs[6], hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(s->dev, s->host, ofs[5], hipMemcpyHostToDevice, st));
     PlanDev pd;
-    pd.units = (const UnitDesc*)(s->dev + ofs[0]);
-    pd.blocks = (const int32_t*)(s->dev + ofs[1]);
-    pd.sharers = (const int32_t*)(s->dev + ofs[2]);
+    pd.wgs = (const WgDesc*)(s->dev + ofs[0]);
+    pd.tiles = (const TileRef*)(s->dev + ofs[1]);
+    pd.dfs_threads = (const int32_t*)(s->dev + ofs[2]);
     pd.path_ofs = (const int32_t*)(s->dev + ofs[3]);
     pd.path_ids = (const int32_t*)(s->dev + ofs[4]);
-    pd.narrow = (const NarrowDesc*)(s->dev + ofs[5]);
-    pd.n_units = (int32_t)ph.units.size();
-    pd.n_wide = ph.n_wide;
-    pd.n_narrow = ph.n_narrow;
+    pd.n_wg = (int32_t)ph.wgs.size();
     pd.n_threads = n;
+    pd.rows_per_thread = p->plan_geom[0];
+    pd.rows_per_slice = p->plan_geom[1];
+    pd.n_slices = p->plan_geom[2];
 
     EventPair ev;
     if (p->profiling) {
@@ -459,9 +305,10 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
             return rc;
         HIP_TRY(hipEventRecord(ev.a, st));
     }
-    HIP_TRY(launch_attention_partial(p->shape, p->kv, q, pd, n_cand, attention_max_rows_per_unit(p->shape), p->part, st));
+    HIP_TRY(launch_attention_partial(p->shape, p->kv, q, pd, n_cand, p->part, out, st));
     if (p->profiling) HIP_TRY(hipEventRecord(ev.b, st));
-    HIP_TRY(launch_merge(p->shape, pd, p->part, q, cand_k, cand_v, mask, n_cand, out, st));
+    if (ph.any_partial || spec)
+        HIP_TRY(launch_merge(p->shape, pd, p->part, q, cand_k, cand_v, mask, n_cand, out, st));
     if (p->profiling) {
         HIP_TRY(hipEventRecord(ev.c, st));
         p->decode_events.push_back(ev);
@@ -731,11 +578,12 @@ int apar_last_plan_export(apar_pool* p, int which, int32_t* out, int64_t cap, in
     const int32_t* src = nullptr;
     int64_t n = 0;
     switch (which) {
-        case APAR_PLAN_UNITS: src = (const int32_t*)ph.units.data(), n = (int64_t)ph.units.size() * 6; break;
-        case APAR_PLAN_BLOCKS: src = ph.blocks.data(), n = (int64_t)ph.blocks.size(); break;
-        case APAR_PLAN_SHARERS: src = ph.sharers.data(), n = (int64_t)ph.sharers.size(); break;
+        case APAR_PLAN_WORKGROUPS: src = (const int32_t*)ph.wgs.data(), n = (int64_t)ph.wgs.size() * 32; break;
+        case APAR_PLAN_TILES: src = (const int32_t*)ph.tiles.data(), n = (int64_t)ph.tiles.size() * 2; break;
+        case APAR_PLAN_DFS_THREADS: src = ph.dfs_threads.data(), n = (int64_t)ph.dfs_threads.size(); break;
         case APAR_PLAN_PATH_OFS: src = ph.path_ofs.data(), n = (int64_t)ph.path_ofs.size(); break;
         case APAR_PLAN_PATH_IDS: src = ph.path_ids.data(), n = (int64_t)ph.path_ids.size(); break;
+        case APAR_PLAN_GEOMETRY: src = p->plan_geom, n = 3; break;
         default: return APAR_ERR_INVALID_ARG;
     }
     *n_out = n;
@@ -807,8 +655,8 @@ int apar_profile_read(apar_pool* p, apar_profile* out) {
 }
 
 int apar_set_chunk_blocks(apar_pool* p, int blocks_per_unit) {
-    if (!p || blocks_per_unit < 1 || blocks_per_unit > 64) return APAR_ERR_INVALID_ARG;
-    p->chunk_blocks = blocks_per_unit;
+    if (!p || blocks_per_unit < 1 || blocks_per_unit > 65536) return APAR_ERR_INVALID_ARG;
+    p->max_unit_tiles = blocks_per_unit;
     return APAR_OK;
 }
 

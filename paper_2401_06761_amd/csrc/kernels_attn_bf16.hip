@@ -1,9 +1,7 @@
-// Partial decode attention over bf16 KV tiles on the gfx950 matrix cores.
+// Decode attention over bf16 KV tiles on the gfx950 matrix cores.
 //
-// A work unit is (run of blocks shared by one set of threads, kv head).  Its
-// query rows - every sharing thread x candidate x q head of the kv group - sit
-// on the N side of 16x16 matrix-core tiles, the 16 token slots of a block on
-// the M side:
+// Query rows - (thread, candidate, q head of one kv group) - sit on the N side
+// of 16x16 matrix-core tiles, the 16 token slots of a block on the M side:
 //
 //   S^T[token][row] = K[token][:] . Q[row][:]          4 x mfma_f32_16x16x32_bf16
 //   O^T[dim][row]  += V^T[dim][token] . P^T[token][row] 8 x mfma_f32_16x16x16_bf16
@@ -14,23 +12,28 @@
 // S^T (lane = 16*g + c holds tokens 4g..4g+3 of row c) is already the
 // B-operand layout of P^T, so probabilities never move between lanes.
 //
-// One launch, two kinds of workgroup (256 threads = 4 wavefronts):
-//   * wide   - a unit with 17..64 rows, e.g. a prefix shared by many sibling
-//              threads.  The four wavefronts fetch a quarter of each tile,
-//              stage it in LDS (double buffered, one barrier per tile) and all
-//              read it back from there; each applies it to its own 16 rows.
-//              The shared block leaves HBM once and serves every sibling.
-//   * narrow - four independent units of at most 16 rows and 8 blocks (private
-//              tails, small groups), one per wavefront, tiles straight from
-//              HBM into operand registers.
-// Wide workgroups come first in the grid, so the launch tails off on the many
-// short narrow units.
+// A workgroup (4 wavefronts, 16 rows each) is given by the host plan
+//   * a shared tile list: blocks whose holders sit in more than one wavefront
+//     (prefixes shared by many sibling threads).  Each wavefront fetches a
+//     quarter of every tile, the tile is staged once in LDS (double buffered,
+//     one barrier per tile) and every wavefront applies it to those of its rows
+//     that hold the block;
+//   * one private tile list per wavefront: blocks held only by rows of that
+//     wavefront (private tails, small sibling groups), loaded straight from HBM
+//     into operand registers with no barrier.  K registers are refilled right
+//     after the K.Q^T products and V registers after the V^T.P^T products, so
+//     the next tile is in flight while the current one is consumed.
+// Every tile names the range of row groups it applies to; other rows see -inf
+// logits.  A row's softmax state stays in registers across all the blocks of
+// its root path that the unit covers; attention is a set operation, so the
+// order in which a unit visits them does not matter.  Rows whose whole path
+// lies in the unit are normalised and written out here; the others leave a
+// partial result (reference, sum, unnormalised output) for the merge kernel.
 //
 // Softmax runs in base 2 with a lazily updated reference: a row's reference
 // logit m only moves when some logit exceeds it by more than kSlack, which
 // keeps the cross-lane maximum and the rescale of the accumulators off the
-// common path.  Each (unit, row) ends as one partial result (reference, sum,
-// unnormalised output) that the merge kernel folds along the thread's root path.
+// common path.
 #include <hip/hip_runtime.h>
 
 #include "apar_internal.hpp"
@@ -43,6 +46,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 union Frag {  // 16 bytes seen as a load, as an 8-wide bf16 operand, or as two 4-wide ones
     u32x4 u;
@@ -60,52 +64,21 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
     return (a >> 16) | (b & 0xffff0000u);
 }
 
-// Rows of one wavefront: query operands, running softmax state, partial-result slot.
+// The 16 rows of one wavefront: query operands and running softmax state.
 struct RowState {
     Frag q[4];
     f32x4 o[8];
     float m, l;
-    int64_t slot;  // -1: this lane's row does not exist
 };
 
-__device__ __forceinline__ void init_rows(RowState& st, const uint16_t* __restrict__ q, const int32_t* sharers,
-                                          int shr, int n_shr, int part_base, int row0, int n_cand, int n_q, int group,
-                                          int kvh, int lane) {
-    const int g4 = lane >> 4, c = lane & 15;
-    const int row = row0 + c;
-    const int rows = n_shr * n_cand * group;
-    st.slot = -1;
-    st.m = -INFINITY;
-    st.l = 0.0f;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) st.q[kk].u = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int j = 0; j < 8; ++j) st.o[j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    if (row < rows) {
-        const int gi = row % group, cc = (row / group) % n_cand, s = row / (group * n_cand);
-        const int listed = sharers ? sharers[shr + s] : shr;
-        const int hq = kvh * group + gi;
-        const u32x4* qp =
-            reinterpret_cast<const u32x4*>(q + (((int64_t)listed * n_cand + cc) * n_q + hq) * 128 + g4 * 32);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) st.q[kk].u = qp[kk];
-        st.slot = ((int64_t)(part_base + s) * n_cand + cc) * n_q + hq;
-    }
-}
-
-// S^T = K.Q^T for one tile, scaled to base-2 logits; slots >= valid become -inf.
-__device__ __forceinline__ void scores(const Frag (&k)[4], const RowState& st, float scale_log2e, int valid, int g4,
-                                       float (&sv)[4]) {
+// S^T = K.Q^T for one tile in base-2 logits; rows outside [lo, hi) and slots >= valid get -inf.
+__device__ __forceinline__ void scores(const Frag (&k)[4], const RowState& st, float scale_log2e, int valid,
+                                       bool row_on, int g4, float (&sv)[4]) {
     f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[kk].b8, st.q[kk].b8, s, 0, 0, 0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) sv[i] = s[i] * scale_log2e;
-    if (valid < 16) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (4 * g4 + i >= valid) sv[i] = -INFINITY;
-    }
+    for (int i = 0; i < 4; ++i) sv[i] = (row_on && 4 * g4 + i < valid) ? s[i] * scale_log2e : -INFINITY;
 }
 
 // Online softmax step and O^T += V^T.P^T for one tile.
@@ -117,7 +90,8 @@ __device__ __forceinline__ void accumulate(Frag (&v)[4], RowState& st, const flo
         float mx = fmaxf(top, __shfl_xor(top, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(st.m, mx);
-        const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);  // first tile: exp2(-inf) = 0
+        // a row that has seen nothing yet keeps m = -inf and sums of zero
+        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(st.m - m_new);
         st.l *= alpha;
 #pragma unroll
         for (int j = 0; j < 8; ++j) st.o[j] *= alpha;
@@ -125,7 +99,7 @@ __device__ __forceinline__ void accumulate(Frag (&v)[4], RowState& st, const flo
     }
     float p[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(sv[i] - st.m);
+    for (int i = 0; i < 4; ++i) p[i] = (sv[i] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(sv[i] - st.m);
     st.l += (p[0] + p[1]) + (p[2] + p[3]);
     if (valid < 16) {
         // slots past the fill count hold whatever the buffer held: clear their V so that a
@@ -153,100 +127,110 @@ __device__ __forceinline__ void accumulate(Frag (&v)[4], RowState& st, const flo
     }
 }
 
-__device__ __forceinline__ void store_partial(const RowState& st, PartialBuf part, int lane) {
-    const int g4 = lane >> 4;
-    float lt = st.l;
-    lt += __shfl_xor(lt, 16, 64);
-    lt += __shfl_xor(lt, 32, 64);
-    if (st.slot >= 0) {
-        float* dst = part.o + st.slot * 128 + 4 * g4;
-#pragma unroll
-        // streaming stores: the partial results are read once, by the merge kernel
-        for (int j = 0; j < 8; ++j) __builtin_nontemporal_store(st.o[j], reinterpret_cast<f32x4*>(dst + 16 * j));
-        if (g4 == 0) {
-            __builtin_nontemporal_store(st.m, part.ml + st.slot * 2);
-            __builtin_nontemporal_store(lt, part.ml + st.slot * 2 + 1);
-        }
-    }
-}
-
-__global__ __launch_bounds__(256) void attention_partial_bf16(const char* __restrict__ pool,
-                                                              const uint16_t* __restrict__ q, PlanDev plan,
-                                                              int n_wide_wg, int n_cand, int n_q, int n_kv, int group,
-                                                              float scale_log2e, PartialBuf part) {
+__global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ pool, const uint16_t* __restrict__ q,
+                                                      PlanDev plan, int n_cand, int n_q, int n_kv, int group,
+                                                      float scale_log2e, PartialBuf part,
+                                                      uint16_t* __restrict__ out) {
     __shared__ __attribute__((aligned(16))) char stage[2][kTileBytes];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int g4 = lane >> 4;
-    RowState st;
+    const int g4 = lane >> 4, c = lane & 15;
+    const int kvh = blockIdx.x % n_kv;
+    const WgDesc* wg = plan.wgs + blockIdx.x / n_kv;
+    const WaveItem wi = wg->w[wave];
+    const int n_coop = wg->n_coop;
+    const TileRef* coop = plan.tiles + wg->coop_ofs;
+    const TileRef* mine = plan.tiles + wi.tile_ofs;
+    const char* head_base = pool + (int64_t)kvh * kTileBytes;
+    const int64_t block_stride = (int64_t)n_kv * kTileBytes;
 
-    if ((int)blockIdx.x < n_wide_wg) {
-        // ---- wide unit: the workgroup shares each tile through LDS ------------------------
-        const int kvh = blockIdx.x % n_kv;
-        const UnitDesc u = plan.units[blockIdx.x / n_kv];
-        const int rows = u.n_shr * n_cand * group;
-        init_rows(st, q, plan.sharers, u.shr_ofs, u.n_shr, u.part_base, wave * 16, n_cand, n_q, group, kvh, lane);
-        const bool active = wave * 16 < rows;  // wavefronts without rows still help to fetch
-        const int32_t* blk = plan.blocks + u.blk_ofs;
-        // this wavefront's quarter of a tile: K load index `wave` and V load index `wave`
-        const int my_ofs = wave * 1024 + lane * 16;
-        auto fetch = [&](int b, u32x4& kq, u32x4& vq) {
-            const char* tile = pool + ((int64_t)blk[b] * n_kv + kvh) * kTileBytes;
+    // Row geometry: column c of this wavefront is row `within` of row group grp_lo + j.
+    const int rps = plan.rows_per_slice, n_sl = plan.n_slices, rpt = plan.rows_per_thread;
+    const int j = c / rps, within = c - j * rps;
+    const int grp = wi.grp_lo + j;
+    const int rank = grp / n_sl, rr = (grp - rank * n_sl) * rps + within;
+    const bool row_ok = j < wi.n_grp && rr < rpt;
+    const int my_j = row_ok ? j : 0x7fff;  // never inside a tile's [lo, hi)
+    RowState st;
+    st.m = -INFINITY;
+    st.l = 0.0f;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) st.q[kk].u = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) st.o[jj] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    int64_t qrow = -1, slot = -1;
+    if (row_ok) {
+        const int listed = plan.dfs_threads[rank];
+        const int cc = rr / group, hq = kvh * group + (rr - cc * group);
+        qrow = ((int64_t)listed * n_cand + cc) * n_q + hq;
+        slot = ((int64_t)(wi.part_base + rank - wi.grp_lo / n_sl) * n_cand + cc) * n_q + hq;
+        const u32x4* qp = reinterpret_cast<const u32x4*>(q + qrow * 128 + g4 * 32);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) st.q[kk].u = qp[kk];
+    }
+
+    // ---- shared tiles: staged once in LDS for the whole workgroup ---------------------------
+    if (n_coop > 0) {
+        const int my_ofs = wave * 1024 + lane * 16;  // this wavefront's quarter: K piece `wave`, V piece `wave`
+        const int shift = wi.grp_lo - wg->grp_base;  // shared ranges are relative to the group's base
+        const int my_jc = row_ok ? j + shift : 0x7fff;
+        u32x4 kq, vq;
+        auto fetch = [&](int t) {
+            const char* tile = head_base + coop[t].blk * block_stride;
             kq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + my_ofs));
             vq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + my_ofs));
         };
-        u32x4 kq, vq;
-        fetch(0, kq, vq);
+        fetch(0);
         *reinterpret_cast<u32x4*>(&stage[0][my_ofs]) = kq;
         *reinterpret_cast<u32x4*>(&stage[0][4096 + my_ofs]) = vq;
         __syncthreads();
-        for (int b = 0; b < u.n_blk; ++b) {
-            const bool more = b + 1 < u.n_blk;
-            if (more) fetch(b + 1, kq, vq);
-            if (active) {
-                const char* sb = stage[b & 1];
-                const int valid = more ? 16 : u.last_valid;
-                Frag k[4], v[4];
+        for (int t = 0; t < n_coop; ++t) {
+            const bool more = t + 1 < n_coop;
+            if (more) fetch(t + 1);
+            const int meta = coop[t].meta;
+            const int lo = meta & 0xff, hi = (meta >> 8) & 0xff, valid = meta >> 16;
+            // does the tile touch any row group of this wavefront?
+            if (wi.n_grp > 0 && lo < shift + wi.n_grp && hi > shift) {
+                const char* sb = stage[t & 1];
+                Frag ks[4], vs[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) k[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
+                for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) v[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
+                for (int r = 0; r < 4; ++r) vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
                 float sv[4];
-                scores(k, st, scale_log2e, valid, g4, sv);
-                accumulate(v, st, sv, valid, g4);
+                scores(ks, st, scale_log2e, valid, my_jc >= lo && my_jc < hi, g4, sv);
+                accumulate(vs, st, sv, valid, g4);
             }
             if (more) {
-                char* nb = stage[(b + 1) & 1];
+                char* nb = stage[(t + 1) & 1];
                 *reinterpret_cast<u32x4*>(nb + my_ofs) = kq;
                 *reinterpret_cast<u32x4*>(nb + 4096 + my_ofs) = vq;
             }
-            __syncthreads();  // tile b+1 is staged, and everyone is done reading tile b
+            __syncthreads();  // tile t+1 is staged, and everyone is done reading tile t
         }
-        if (active) store_partial(st, part, lane);
-        return;
+    }
+    if (wi.n_grp == 0) return;  // a wavefront without rows only helped to fetch
+
+    // Private list: start the first tile's loads (nothing before this point waits on memory when the
+    // group has no shared tiles).
+    Frag k[4], v[4];
+    if (wi.n_tiles > 0) {
+        const u32x4* t0 = reinterpret_cast<const u32x4*>(head_base + mine[0].blk * block_stride) + lane;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) k[r].u = __builtin_nontemporal_load(t0 + r * 64);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(t0 + 256 + r * 64);
     }
 
-    // ---- narrow units: one per wavefront, tiles go straight to operand registers ----------
-    const int w = __builtin_amdgcn_readfirstlane((int)((blockIdx.x - n_wide_wg) * 4) + wave);
-    if (w >= plan.n_narrow * n_kv) return;
-    const int kvh = w % n_kv;
-    const NarrowDesc d = plan.narrow[w / n_kv];
-    const u32x4* t0 = reinterpret_cast<const u32x4*>(pool + ((int64_t)d.blk[0] * n_kv + kvh) * kTileBytes) + lane;
-    Frag k[4], v[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) k[r].u = __builtin_nontemporal_load(t0 + r * 64);
-#pragma unroll
-    for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(t0 + 256 + r * 64);
-    init_rows(st, q, d.n_shr == 1 ? nullptr : plan.sharers, d.shr, d.n_shr, d.part_base, 0, n_cand, n_q, group, kvh,
-              lane);
-    const int32_t* blk = plan.narrow[w / n_kv].blk;
-    for (int b = 0; b < d.n_blk; ++b) {
-        const bool more = b + 1 < d.n_blk;
-        const int valid = more ? 16 : d.last_valid;
+    // ---- private tiles: straight into operand registers -------------------------------------
+    for (int t = 0; t < wi.n_tiles; ++t) {
+        const bool more = t + 1 < wi.n_tiles;
+        const int meta = mine[t].meta;
+        const int lo = meta & 0xff, hi = (meta >> 8) & 0xff, valid = meta >> 16;
         const u32x4* tn = nullptr;
-        if (more) tn = reinterpret_cast<const u32x4*>(pool + ((int64_t)blk[b + 1] * n_kv + kvh) * kTileBytes) + lane;
+        if (more) tn = reinterpret_cast<const u32x4*>(head_base + mine[t + 1].blk * block_stride) + lane;
         float sv[4];
-        scores(k, st, scale_log2e, valid, g4, sv);
+        scores(k, st, scale_log2e, valid, my_j >= lo && my_j < hi, g4, sv);
         if (more) {  // K registers are free again: start fetching the next tile's K
 #pragma unroll
             for (int r = 0; r < 4; ++r) k[r].u = __builtin_nontemporal_load(tn + r * 64);
@@ -257,22 +241,44 @@ __global__ __launch_bounds__(256) void attention_partial_bf16(const char* __rest
             for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(tn + 256 + r * 64);
         }
     }
-    store_partial(st, part, lane);
+
+    // ---- results ------------------------------------------------------------------------------
+    float lt = st.l;
+    lt += __shfl_xor(lt, 16, 64);
+    lt += __shfl_xor(lt, 32, 64);
+    if (!row_ok) return;
+    if (wi.flags & kWaveDirect) {
+        // the row's whole root path was covered here: normalise and write the output row
+        const float inv = 1.0f / lt;
+        uint16_t* dst = out + qrow * 128 + 4 * g4;
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            u32x2 pk;
+            pk.x = pack_bf16_rne(st.o[jj][0] * inv, st.o[jj][1] * inv);
+            pk.y = pack_bf16_rne(st.o[jj][2] * inv, st.o[jj][3] * inv);
+            __builtin_nontemporal_store(pk, reinterpret_cast<u32x2*>(dst + 16 * jj));
+        }
+    } else {
+        // streaming stores: a partial result is read once, by the merge kernel
+        float* dst = part.o + slot * 128 + 4 * g4;
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) __builtin_nontemporal_store(st.o[jj], reinterpret_cast<f32x4*>(dst + 16 * jj));
+        if (g4 == 0) {
+            __builtin_nontemporal_store(st.m, part.ml + slot * 2);
+            __builtin_nontemporal_store(lt, part.ml + slot * 2 + 1);
+        }
+    }
 }
 
 }  // namespace
 
-int attention_max_rows_per_unit(const Shape&) { return 64; }
-
-hipError_t launch_attention_partial_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan,
-                                         int n_cand, PartialBuf part, hipStream_t st) {
-    const int64_t wide_wg = (int64_t)plan.n_wide * s.n_kv;
-    const int64_t narrow_wg = ((int64_t)plan.n_narrow * s.n_kv + 3) / 4;
-    if (wide_wg + narrow_wg <= 0) return hipSuccess;
-    if (wide_wg + narrow_wg > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(attention_partial_bf16, dim3((unsigned)(wide_wg + narrow_wg)), dim3(256), 0, st,
-                       (const char*)pool, (const uint16_t*)q, plan, (int)wide_wg, n_cand, s.n_q, s.n_kv, s.group,
-                       s.scale_log2e, part);
+hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
+                                 PartialBuf part, void* out, hipStream_t st) {
+    const int64_t n_wg = (int64_t)plan.n_wg * s.n_kv;
+    if (n_wg <= 0) return hipSuccess;
+    if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attention_bf16, dim3((unsigned)n_wg), dim3(256), 0, st, (const char*)pool, (const uint16_t*)q,
+                       plan, n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part, (uint16_t*)out);
     return hipGetLastError();
 }
 

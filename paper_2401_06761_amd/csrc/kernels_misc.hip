@@ -107,48 +107,66 @@ __global__ __launch_bounds__(256) void copy_blocks(char* __restrict__ pool, cons
 }
 
 // ---------------------------------------------------------------------------
-// fp32 partial attention: one wavefront per (unit, kv head, query row), plain
-// vector arithmetic, row-major tiles.  Used by fp32 pools, where results must
-// hold to 1e-5 and the matrix cores' bf16 inputs would not.
+// fp32 attention: one wavefront per query row, plain vector arithmetic, row-major
+// tiles.  Used by fp32 pools, where results must hold to 1e-5 and the matrix
+// cores' bf16 inputs would not.  Follows the same plan as the bf16 kernel: row c
+// of wavefront k of a workgroup walks the group's shared tiles and wavefront k's
+// own tiles and takes those whose row-group range contains its own.
+// grid = (plan workgroups, kv heads, 64 rows); block = 64 lanes over the head dim.
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(64) void attention_partial_f32(const char* __restrict__ pool,
-                                                            const float* __restrict__ q, PlanDev plan, int n_cand,
-                                                            int n_q, int n_kv, int group, float scale_log2e,
-                                                            int64_t tile_bytes, PartialBuf part) {
+__global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ pool, const float* __restrict__ q,
+                                                    PlanDev plan, int n_cand, int n_q, int n_kv, int group,
+                                                    float scale_log2e, int64_t tile_bytes, PartialBuf part,
+                                                    float* __restrict__ out) {
     constexpr int E = D / 64;
     const int lane = threadIdx.x;
     const int kvh = blockIdx.y;
-    const UnitDesc u = plan.units[blockIdx.x];
-    const int rows = u.n_shr * n_cand * group;
-    const int row = blockIdx.z;
-    if (row >= rows) return;
-    const int gi = row % group, c = (row / group) % n_cand, s = row / (group * n_cand);
-    const int listed = plan.sharers[u.shr_ofs + s];
-    const int hq = kvh * group + gi;
-    const float* qrow = q + (((int64_t)listed * n_cand + c) * n_q + hq) * D;
+    const int wave = blockIdx.z >> 4, c = blockIdx.z & 15;
+    const WgDesc* wg = plan.wgs + blockIdx.x;
+    const WaveItem wi = wg->w[wave];
+    const int rps = plan.rows_per_slice, n_sl = plan.n_slices, rpt = plan.rows_per_thread;
+    const int j = c / rps, within = c - j * rps;
+    const int grp = wi.grp_lo + j;
+    const int rank = grp / n_sl, rr = (grp - rank * n_sl) * rps + within;
+    if (j >= wi.n_grp || rr >= rpt) return;
+    const int listed = plan.dfs_threads[rank];
+    const int cc = rr / group, hq = kvh * group + (rr - cc * group);
+    const int64_t qrow = ((int64_t)listed * n_cand + cc) * n_q + hq;
     float qv[E], acc[E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) qv[e] = qrow[lane + 64 * e], acc[e] = 0.0f;
+    for (int e = 0; e < E; ++e) qv[e] = q[qrow * D + lane + 64 * e], acc[e] = 0.0f;
     float m = -INFINITY, l = 0.0f;
-    for (int b = 0; b < u.n_blk; ++b) {
-        const int32_t blk = plan.blocks[u.blk_ofs + b];
-        const float* tile = reinterpret_cast<const float*>(pool + ((int64_t)blk * n_kv + kvh) * tile_bytes);
-        const int valid = (b == u.n_blk - 1) ? u.last_valid : 16;
-        for (int t = 0; t < valid; ++t) {
-            float dot = 0.0f;
+    for (int list = 0; list < 2; ++list) {
+        const TileRef* tiles = plan.tiles + (list == 0 ? wg->coop_ofs : wi.tile_ofs);
+        const int n_tiles = list == 0 ? wg->n_coop : wi.n_tiles;
+        const int my_j = list == 0 ? j + (wi.grp_lo - wg->grp_base) : j;
+        for (int t = 0; t < n_tiles; ++t) {
+            const int meta = tiles[t].meta;
+            const int lo = meta & 0xff, hi = (meta >> 8) & 0xff, valid = meta >> 16;
+            if (my_j < lo || my_j >= hi) continue;
+            const float* tile = reinterpret_cast<const float*>(pool + ((int64_t)tiles[t].blk * n_kv + kvh) * tile_bytes);
+            for (int tok = 0; tok < valid; ++tok) {
+                float dot = 0.0f;
 #pragma unroll
-            for (int e = 0; e < E; ++e) dot += qv[e] * tile[t * D + lane + 64 * e];
-            const float sc = wave_sum(dot) * scale_log2e;
-            const float m_new = fmaxf(m, sc);
-            const float alpha = exp2f(m - m_new), pr = exp2f(sc - m_new);
-            l = l * alpha + pr;
+                for (int e = 0; e < E; ++e) dot += qv[e] * tile[tok * D + lane + 64 * e];
+                const float sc = wave_sum(dot) * scale_log2e;
+                const float m_new = fmaxf(m, sc);
+                const float alpha = exp2f(m - m_new), pr = exp2f(sc - m_new);
+                l = l * alpha + pr;
 #pragma unroll
-            for (int e = 0; e < E; ++e) acc[e] = acc[e] * alpha + pr * tile[16 * D + t * D + lane + 64 * e];
-            m = m_new;
+                for (int e = 0; e < E; ++e) acc[e] = acc[e] * alpha + pr * tile[16 * D + tok * D + lane + 64 * e];
+                m = m_new;
+            }
         }
     }
-    const int64_t slot = ((int64_t)(u.part_base + s) * n_cand + c) * n_q + hq;
+    if (wi.flags & kWaveDirect) {
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int e = 0; e < E; ++e) out[qrow * D + lane + 64 * e] = acc[e] * inv;
+        return;
+    }
+    const int64_t slot = ((int64_t)(wi.part_base + rank - wi.grp_lo / n_sl) * n_cand + cc) * n_q + hq;
 #pragma unroll
     for (int e = 0; e < E; ++e) part.o[slot * D + lane + 64 * e] = acc[e];
     if (lane == 0) {
@@ -161,6 +179,7 @@ __global__ __launch_bounds__(64) void attention_partial_f32(const char* __restri
 // Merge: one wavefront per (listed thread, candidate, q head).  Folds the partial
 // results on the thread's root path (log-sum-exp in base 2), adds the candidate
 // keys the mask lets this candidate see, normalises and writes the output row.
+// Threads without partial results were already written by the attention kernel.
 // ---------------------------------------------------------------------------
 template <int D, bool BF16>
 __global__ __launch_bounds__(64) void merge_rows(PlanDev plan, PartialBuf part, const void* __restrict__ qv,
@@ -171,6 +190,7 @@ __global__ __launch_bounds__(64) void merge_rows(PlanDev plan, PartialBuf part, 
     const int lane = threadIdx.x;
     const int hq = blockIdx.x, c = blockIdx.y, i = blockIdx.z;
     const int p0 = plan.path_ofs[i], p1 = plan.path_ofs[i + 1];
+    if (p0 == p1 && mask == nullptr) return;  // the attention kernel wrote this thread's rows itself
     float m = -INFINITY;
     for (int p = p0; p < p1; ++p) {
         const int64_t slot = ((int64_t)plan.path_ids[p] * n_cand + c) * n_q + hq;
@@ -231,8 +251,8 @@ __global__ __launch_bounds__(64) void merge_rows(PlanDev plan, PartialBuf part, 
 
 }  // namespace
 
-hipError_t launch_attention_partial_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan,
-                                         int n_cand, PartialBuf part, hipStream_t st);
+hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
+                                 PartialBuf part, void* out, hipStream_t st);
 
 hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const void* v, const int32_t* dst_codes,
                               int n_rows, hipStream_t st) {
@@ -278,16 +298,16 @@ hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src
 }
 
 hipError_t launch_attention_partial(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
-                                    int max_rows, PartialBuf part, hipStream_t st) {
-    if (plan.n_units <= 0) return hipSuccess;
-    if (s.dtype == APAR_BF16) return launch_attention_partial_bf16(s, pool, q, plan, n_cand, part, st);
-    dim3 grid(plan.n_units, s.n_kv, max_rows);
+                                    PartialBuf part, void* out, hipStream_t st) {
+    if (plan.n_wg <= 0) return hipSuccess;
+    if (s.dtype == APAR_BF16) return launch_attention_bf16(s, pool, q, plan, n_cand, part, out, st);
+    dim3 grid(plan.n_wg, s.n_kv, 64);
     if (s.d == 64)
-        hipLaunchKernelGGL(attention_partial_f32<64>, grid, dim3(64), 0, st, (const char*)pool, (const float*)q, plan,
-                           n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part);
+        hipLaunchKernelGGL(attention_f32<64>, grid, dim3(64), 0, st, (const char*)pool, (const float*)q, plan, n_cand,
+                           s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part, (float*)out);
     else
-        hipLaunchKernelGGL(attention_partial_f32<128>, grid, dim3(64), 0, st, (const char*)pool, (const float*)q,
-                           plan, n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part);
+        hipLaunchKernelGGL(attention_f32<128>, grid, dim3(64), 0, st, (const char*)pool, (const float*)q, plan, n_cand,
+                           s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part, (float*)out);
     return hipGetLastError();
 }
 

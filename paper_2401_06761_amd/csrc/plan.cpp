@@ -1,0 +1,405 @@
+// Plan builder: groups the listed threads by the blocks they share and lays the
+// work out as workgroups of four wavefronts.
+//
+// Sharing only ever comes from forks, which hand a child the parent's whole table,
+// and copy-on-write only replaces a tail.  Hence two tables that agree at one
+// position agree at every earlier one, the set of live threads holding a table's
+// block can only shrink along the table, and a maximal run of positions with one
+// refcount is a run with one set of holders: a segment.  Every holder has the same
+// run, so only the first listed holder walks it; the others find it by its first
+// block and skip over it.  Segments form a forest (a segment's parent is the run
+// before it in any holder's table); numbering the threads depth-first makes every
+// segment's holders a contiguous range of ranks.
+//
+// Units.  Partial results are expensive: small writes mixed into the streaming
+// reads cost far more than their size.  So a whole subtree of the forest is given
+// to ONE unit whenever its query rows fit one workgroup (4 wavefronts x 16 rows):
+// the rows' softmax state then stays in registers from the shared prefix down to
+// each private tail, and threads whose entire path lies inside the unit get their
+// output written directly.  Inside such a unit a block whose holders all sit in one
+// wavefront goes on that wavefront's private list (no barrier, registers only);
+// blocks needed by several wavefronts go on the shared list (staged once in LDS).
+// Subtrees with too many rows or blocks are cut: the top segment stands alone,
+// chunked, with one partial result per (chunk, thread), and its children are tried
+// again.  Attention is a set operation, so a unit may visit its blocks in any order.
+#include "plan.hpp"
+
+#include <algorithm>
+#include <climits>
+
+namespace apar {
+
+void PlanHost::clear() {
+    wgs.clear(), tiles.clear(), dfs_threads.clear(), path_ofs.clear(), path_ids.clear();
+    segs.clear(), seg_blocks.clear(), thread_last_seg.clear(), end_threads.clear(), order.clear(), stack.clear();
+    path_len.clear(), narrow_items.clear(), wide_items.clear(), coop_build.clear();
+    for (WaveBuild& w : wave_build) w.tiles.clear(), w.thr_lo = w.n_thr = 0;
+    n_partial_rows = n_segments = unique_blocks = unique_tokens = path_tokens = n_direct_threads = 0;
+    any_partial = false;
+}
+
+namespace {
+
+constexpr int B = kBlockTokens;
+
+inline int32_t make_meta(int lo, int hi, int valid) { return lo | (hi << 8) | (valid << 16); }
+
+struct Builder {
+    PlanHost& ph;
+    const PlanParams& prm;
+    int n_sl, rps, cap;  // slices per thread, rows per slice, row groups per wavefront
+    // per segment: first partial row it produces itself (stand-alone: n_chunks * n_shr rows; unit root
+    // that is not direct: n_shr rows), and how many chunks
+    std::vector<int32_t> part0, n_chunks;
+
+    Builder(PlanHost& p, const PlanParams& q) : ph(p), prm(q) {
+        n_sl = (q.rows_per_thread + 15) / 16;
+        rps = (q.rows_per_thread + n_sl - 1) / n_sl;
+        cap = 16 / rps;
+    }
+
+    int32_t valid_of(const PlanHost::Segment& s, int b) const { return b == s.n_blk - 1 ? s.last_valid : B; }
+
+    // Pre-order walk of the subtree of `root`; f(segment index).
+    template <class F>
+    void for_subtree(int32_t root, F&& f) {
+        std::vector<int32_t>& st = ph.stack;
+        const size_t base = st.size();
+        st.push_back(root);
+        while (st.size() > base) {
+            const int32_t s = st.back();
+            st.pop_back();
+            f(s);
+            // children in reverse, so that the first child is visited first
+            const size_t mark = st.size();
+            for (int32_t c = ph.segs[s].first_child; c >= 0; c = ph.segs[c].next_sibling) st.push_back(c);
+            std::reverse(st.begin() + mark, st.end());
+        }
+    }
+
+    void emit_narrow(int32_t tile_ofs, int32_t n_tiles, int32_t grp_lo, int32_t n_grp, int32_t part_base, int32_t flags) {
+        PlanHost::NarrowItem it;
+        it.item = WaveItem{tile_ofs, n_tiles, grp_lo, n_grp, part_base, flags};
+        it.cost = n_tiles;
+        ph.narrow_items.push_back(it);
+    }
+
+    void emit_standalone(int32_t sid) {
+        PlanHost::Segment& s = ph.segs[sid];
+        const int groups = s.n_shr * n_sl;
+        const int chunk = std::max(1, prm.max_unit_tiles);
+        const int nch = (s.n_blk + chunk - 1) / chunk;
+        n_chunks[sid] = nch;
+        part0[sid] = (int32_t)ph.n_partial_rows;
+        ph.n_partial_rows += (int64_t)nch * s.n_shr;
+        ph.any_partial = true;
+        const int32_t grp0 = s.t_lo * n_sl;
+        for (int c = 0; c < nch; ++c) {
+            const int b0 = c * chunk, nb = std::min(chunk, s.n_blk - b0);
+            const int32_t pbase = part0[sid] + c * s.n_shr;
+            if (groups <= cap) {
+                const int32_t ofs = (int32_t)ph.tiles.size();
+                for (int b = b0; b < b0 + nb; ++b)
+                    ph.tiles.push_back(TileRef{ph.seg_blocks[s.first_block_pos + b], make_meta(0, groups, valid_of(s, b))});
+                emit_narrow(ofs, nb, grp0, groups, pbase, 0);
+            } else {
+                for (int g0 = 0; g0 < groups; g0 += 4 * cap) {
+                    const int gn = std::min(4 * cap, groups - g0);
+                    PlanHost::WideItem wi{};
+                    wi.wg.coop_ofs = (int32_t)ph.tiles.size();
+                    wi.wg.n_coop = nb;
+                    wi.wg.grp_base = grp0 + g0;
+                    for (int b = b0; b < b0 + nb; ++b)
+                        ph.tiles.push_back(TileRef{ph.seg_blocks[s.first_block_pos + b], make_meta(0, gn, valid_of(s, b))});
+                    for (int k = 0; k < 4; ++k) {
+                        const int lo = k * cap, cnt = std::max(0, std::min(cap, gn - lo));
+                        wi.wg.w[k] = WaveItem{0, 0, grp0 + g0 + lo, cnt, pbase + (g0 + lo) / n_sl, 0};
+                    }
+                    wi.cost = 2 * nb;
+                    ph.wide_items.push_back(wi);
+                }
+            }
+        }
+    }
+
+    void emit_fused(int32_t rid) {
+        PlanHost::Segment& r = ph.segs[rid];
+        const int groups = r.n_shr * n_sl;
+        const bool direct = prm.allow_direct && r.n_above == 0;
+        int32_t pbase = -1;
+        if (!direct) {
+            pbase = (int32_t)ph.n_partial_rows;
+            part0[rid] = pbase;
+            ph.n_partial_rows += r.n_shr;
+            ph.any_partial = true;
+        } else {
+            ph.n_direct_threads += r.n_shr;
+        }
+        const int32_t flags = direct ? kWaveDirect : 0;
+        const int32_t grp0 = r.t_lo * n_sl;
+        if (groups <= cap) {
+            const int32_t ofs = (int32_t)ph.tiles.size();
+            for_subtree(rid, [&](int32_t m) {
+                const PlanHost::Segment& s = ph.segs[m];
+                const int lo = (s.t_lo - r.t_lo) * n_sl, hi = lo + s.n_shr * n_sl;
+                for (int b = 0; b < s.n_blk; ++b)
+                    ph.tiles.push_back(TileRef{ph.seg_blocks[s.first_block_pos + b], make_meta(lo, hi, valid_of(s, b))});
+            });
+            emit_narrow(ofs, (int32_t)ph.tiles.size() - ofs, grp0, groups, pbase, flags);
+            return;
+        }
+        // several wavefronts: give each a contiguous range of row groups, keeping subtrees that fit
+        // one wavefront whole where possible
+        int wave_lo[4] = {0, 0, 0, 0}, wave_n[4] = {0, 0, 0, 0};
+        int cur = 0, fill = 0;
+        bool overflow = false;
+        auto atom = [&](int lo_rel, int cnt) {
+            if (overflow) return;
+            if (fill + cnt > cap) {
+                wave_n[cur] = fill;
+                if (++cur >= 4) {
+                    overflow = true;
+                    return;
+                }
+                wave_lo[cur] = lo_rel;
+                fill = 0;
+            }
+            fill += cnt;
+        };
+        {
+            // a walk that stops descending where a subtree fits one wavefront
+            std::vector<int32_t>& st = ph.stack;
+            const size_t base = st.size();
+            st.push_back(rid);
+            while (st.size() > base && !overflow) {
+                const int32_t m = st.back();
+                st.pop_back();
+                const PlanHost::Segment& s = ph.segs[m];
+                const int lo = (s.t_lo - r.t_lo) * n_sl, mg = s.n_shr * n_sl;
+                if (mg <= cap) {
+                    atom(lo, mg);
+                    continue;
+                }
+                for (int e = 0; e < s.n_end; ++e) {  // threads that end here come first in depth-first order
+                    if (n_sl <= cap) atom(lo + e * n_sl, n_sl);
+                    else
+                        for (int sl = 0; sl < n_sl; ++sl) atom(lo + e * n_sl + sl, 1);
+                }
+                const size_t mark = st.size();
+                for (int32_t c = s.first_child; c >= 0; c = ph.segs[c].next_sibling) st.push_back(c);
+                std::reverse(st.begin() + mark, st.end());
+            }
+            st.resize(base);
+        }
+        if (!overflow) wave_n[cur] = fill;
+        if (overflow) {  // dense packing always fits: groups <= 4 * cap
+            for (int k = 0; k < 4; ++k) {
+                wave_lo[k] = k * cap;
+                wave_n[k] = std::max(0, std::min(cap, groups - k * cap));
+            }
+        }
+        for (PlanHost::WaveBuild& w : ph.wave_build) w.tiles.clear();
+        ph.coop_build.clear();
+        for_subtree(rid, [&](int32_t m) {
+            const PlanHost::Segment& s = ph.segs[m];
+            const int lo = (s.t_lo - r.t_lo) * n_sl, hi = lo + s.n_shr * n_sl;
+            int owner = -1;
+            for (int k = 0; k < 4; ++k)
+                if (wave_n[k] > 0 && lo >= wave_lo[k] && hi <= wave_lo[k] + wave_n[k]) owner = k;
+            for (int b = 0; b < s.n_blk; ++b) {
+                const int32_t blk = ph.seg_blocks[s.first_block_pos + b];
+                const int v = valid_of(s, b);
+                if (owner >= 0)
+                    ph.wave_build[owner].tiles.push_back(TileRef{blk, make_meta(lo - wave_lo[owner], hi - wave_lo[owner], v)});
+                else
+                    ph.coop_build.push_back(TileRef{blk, make_meta(lo, hi, v)});
+            }
+        });
+        PlanHost::WideItem wi{};
+        wi.wg.coop_ofs = (int32_t)ph.tiles.size();
+        wi.wg.n_coop = (int32_t)ph.coop_build.size();
+        wi.wg.grp_base = grp0;
+        ph.tiles.insert(ph.tiles.end(), ph.coop_build.begin(), ph.coop_build.end());
+        int longest = 0;
+        for (int k = 0; k < 4; ++k) {
+            const std::vector<TileRef>& t = ph.wave_build[k].tiles;
+            wi.wg.w[k] = WaveItem{(int32_t)ph.tiles.size(), (int32_t)t.size(), grp0 + wave_lo[k], wave_n[k],
+                                  direct ? -1 : pbase + wave_lo[k] / n_sl, flags};
+            ph.tiles.insert(ph.tiles.end(), t.begin(), t.end());
+            longest = std::max(longest, (int)t.size());
+        }
+        wi.cost = 2 * wi.wg.n_coop + longest;
+        ph.wide_items.push_back(wi);
+    }
+};
+
+}  // namespace
+
+int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, int32_t* seg_of, const PlanParams& prm,
+               PlanHost& ph) {
+    ph.clear();
+    if (prm.rows_per_thread < 1 || prm.rows_per_thread > 64) return APAR_ERR_UNSUPPORTED;
+    Builder bld(ph, prm);
+    std::vector<PlanHost::Segment>& segs = ph.segs;
+
+    // 1. segments and their forest
+    ph.thread_last_seg.resize(n);
+    for (int i = 0; i < n; ++i) {
+        const PlanThreadView& t = threads[i];
+        ph.path_tokens += t.len;
+        int pos = 0;
+        int32_t prev = -1;
+        while (pos < t.n_blocks) {
+            const int32_t first = t.table[pos];
+            int32_t sid = seg_of[first];
+            if (sid < 0) {
+                const int32_t r = refcount[first];
+                int end = pos + 1;
+                while (end < t.n_blocks && refcount[t.table[end]] == r) ++end;
+                sid = (int32_t)segs.size();
+                seg_of[first] = sid;
+                PlanHost::Segment s{};
+                s.first_block_pos = (int32_t)ph.seg_blocks.size();
+                s.n_blk = end - pos;
+                s.last_valid = (end == t.n_blocks) ? (int32_t)(t.len - (int64_t)(t.n_blocks - 1) * B) : B;
+                s.parent = prev;
+                s.first_child = s.last_child = s.next_sibling = -1;
+                s.unit = -1;
+                ph.seg_blocks.insert(ph.seg_blocks.end(), t.table + pos, t.table + end);
+                segs.push_back(s);
+                if (prev >= 0) {
+                    if (segs[prev].last_child >= 0) segs[segs[prev].last_child].next_sibling = sid;
+                    else segs[prev].first_child = sid;
+                    segs[prev].last_child = sid;
+                }
+            }
+            segs[sid].n_shr += 1;
+            prev = sid;
+            pos += segs[sid].n_blk;
+        }
+        ph.thread_last_seg[i] = prev;
+        segs[prev].n_end += 1;
+    }
+    for (const PlanHost::Segment& s : segs) seg_of[ph.seg_blocks[s.first_block_pos]] = -1;  // scratch left clean
+    const int32_t n_seg = (int32_t)segs.size();
+    ph.n_segments = n_seg;
+
+    // 2. threads that end at each segment, in listed order
+    {
+        int32_t acc = 0;
+        for (PlanHost::Segment& s : segs) {
+            s.end_ofs = acc;
+            acc += s.n_end;
+            s.n_end = 0;
+        }
+        ph.end_threads.resize(n);
+        for (int i = 0; i < n; ++i) {
+            PlanHost::Segment& s = segs[ph.thread_last_seg[i]];
+            ph.end_threads[s.end_ofs + s.n_end++] = i;
+        }
+    }
+
+    // 3. depth-first ranks; 4. subtree sizes
+    ph.dfs_threads.resize(n);
+    {
+        int32_t rank = 0;
+        for (int32_t r = 0; r < n_seg; ++r) {
+            if (segs[r].parent >= 0) continue;
+            bld.for_subtree(r, [&](int32_t m) {
+                PlanHost::Segment& s = segs[m];
+                s.t_lo = rank;
+                for (int e = 0; e < s.n_end; ++e) ph.dfs_threads[rank++] = ph.end_threads[s.end_ofs + e];
+            });
+        }
+        for (int32_t m = 0; m < n_seg; ++m) segs[m].tiles_sub = segs[m].n_blk;
+        for (int32_t m = n_seg - 1; m >= 0; --m)  // children are created after their parents
+            if (segs[m].parent >= 0) segs[segs[m].parent].tiles_sub += segs[m].tiles_sub;
+    }
+
+    // 5. cut the forest into units, parents first
+    bld.part0.assign(n_seg, -1);
+    bld.n_chunks.assign(n_seg, 0);
+    const int cap = bld.cap, n_sl = bld.n_sl;
+    for (int32_t m = 0; m < n_seg; ++m) {
+        PlanHost::Segment& s = segs[m];
+        ph.unique_blocks += s.n_blk;
+        ph.unique_tokens += (int64_t)(s.n_blk - 1) * B + s.last_valid;
+        const int32_t par = s.parent;
+        if (par >= 0 && segs[par].unit >= 0) {
+            s.unit = segs[par].unit;
+            s.n_above = segs[par].n_above;
+            continue;
+        }
+        s.n_above = par >= 0 ? segs[par].n_above + bld.n_chunks[par] : 0;
+        const int groups = s.n_shr * n_sl;
+        const bool fits = groups <= 4 * cap && s.tiles_sub <= (groups <= cap ? 1 : 4) * prm.max_unit_tiles;
+        if (prm.fuse && fits) {
+            s.unit = m;  // a unit is named after its root segment
+            bld.emit_fused(m);
+        } else {
+            bld.emit_standalone(m);
+        }
+    }
+    if (ph.n_partial_rows > INT32_MAX / 2 || ph.tiles.size() > (size_t)INT32_MAX / 2) return APAR_ERR_UNSUPPORTED;
+
+    // 6. which partial results each listed thread has to merge
+    ph.path_len.assign(n, 0);
+    ph.path_ofs.assign(n + 1, 0);
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int32_t rank = 0; rank < n; ++rank) {
+            const int i = ph.dfs_threads[rank];
+            int32_t cnt = 0;
+            int32_t* dst = pass ? ph.path_ids.data() + ph.path_ofs[i] : nullptr;
+            for (int32_t m = ph.thread_last_seg[i]; m >= 0; m = segs[m].parent) {
+                const PlanHost::Segment& s = segs[m];
+                if (s.unit >= 0) {
+                    if (s.unit != m) continue;  // the unit's root accounts for the whole unit
+                    if (bld.part0[m] >= 0) {
+                        if (dst) dst[cnt] = bld.part0[m] + (rank - s.t_lo);
+                        ++cnt;
+                    }
+                } else {
+                    for (int c = 0; c < bld.n_chunks[m]; ++c) {
+                        if (dst) dst[cnt] = bld.part0[m] + c * s.n_shr + (rank - s.t_lo);
+                        ++cnt;
+                    }
+                }
+            }
+            if (!pass) ph.path_len[i] = cnt;
+        }
+        if (!pass) {
+            for (int i = 0; i < n; ++i) ph.path_ofs[i + 1] = ph.path_ofs[i] + ph.path_len[i];
+            ph.path_ids.resize(ph.path_ofs[n]);
+        }
+    }
+
+    // 7. workgroups, heaviest first; narrow items are packed four to a workgroup
+    std::stable_sort(ph.wide_items.begin(), ph.wide_items.end(),
+                     [](const PlanHost::WideItem& a, const PlanHost::WideItem& b) { return a.cost > b.cost; });
+    ph.wgs.reserve(ph.wide_items.size() + (ph.narrow_items.size() + 3) / 4);
+    for (const PlanHost::WideItem& w : ph.wide_items) ph.wgs.push_back(w.wg);
+    {
+        // counting sort by cost, descending
+        int32_t max_cost = 0;
+        for (const PlanHost::NarrowItem& it : ph.narrow_items) max_cost = std::max(max_cost, it.cost);
+        std::vector<int32_t>& cnt = ph.order;
+        cnt.assign((size_t)max_cost + 2, 0);
+        for (const PlanHost::NarrowItem& it : ph.narrow_items) cnt[max_cost - it.cost + 1] += 1;
+        for (size_t c = 1; c < cnt.size(); ++c) cnt[c] += cnt[c - 1];
+        std::vector<int32_t>& slot = ph.stack;
+        slot.assign(ph.narrow_items.size(), 0);
+        for (size_t k = 0; k < ph.narrow_items.size(); ++k) slot[cnt[max_cost - ph.narrow_items[k].cost]++] = (int32_t)k;
+        for (size_t k = 0; k < slot.size(); k += 4) {
+            WgDesc wg{};
+            for (int j = 0; j < 4; ++j) {
+                if (k + j < slot.size()) wg.w[j] = ph.narrow_items[slot[k + j]].item;
+                else wg.w[j] = WaveItem{0, 0, 0, 0, -1, 0};
+            }
+            wg.grp_base = wg.w[0].grp_lo;
+            ph.wgs.push_back(wg);
+        }
+    }
+    return APAR_OK;
+}
+
+}  // namespace apar

@@ -1,0 +1,76 @@
+// The decode plan: which workgroup reads which blocks on behalf of which threads.
+// Host-only; the device-side layouts it fills are declared in apar_internal.hpp.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "apar_internal.hpp"
+
+namespace apar {
+
+struct PlanThreadView {  // what the planner needs to know about one listed thread
+    const int32_t* table;
+    int32_t n_blocks;
+    int64_t len;
+};
+
+struct PlanHost {
+    // device-format tables
+    std::vector<WgDesc> wgs;            // heaviest first
+    std::vector<TileRef> tiles;
+    std::vector<int32_t> dfs_threads;   // listed-thread indices in depth-first order of the sharing tree
+    std::vector<int32_t> path_ofs, path_ids;
+    // totals
+    int64_t n_partial_rows = 0, n_segments = 0, unique_blocks = 0, unique_tokens = 0, path_tokens = 0;
+    int64_t n_direct_threads = 0;
+    bool any_partial = false;
+
+    // scratch kept between calls so that steady-state planning does not allocate
+    struct Segment {
+        int32_t first_block_pos;  // index into seg_blocks
+        int32_t n_blk, last_valid, n_shr;
+        int32_t parent, first_child, last_child, next_sibling;
+        int32_t n_end, end_ofs;   // listed threads whose table ends with this segment
+        int32_t t_lo;             // depth-first rank of its first thread
+        int32_t tiles_sub;        // blocks in its whole subtree
+        int32_t unit;             // fused unit it belongs to, -1 if it stands alone
+        int32_t n_above;          // partial results produced above it on the path (same for all its threads)
+    };
+    std::vector<Segment> segs;
+    std::vector<int32_t> seg_blocks, thread_last_seg, end_threads, order, stack;
+    std::vector<int32_t> path_len;
+    struct WaveBuild {
+        std::vector<TileRef> tiles;
+        int32_t thr_lo = 0, n_thr = 0;  // pseudo-thread range (global depth-first rank * slices)
+    };
+    WaveBuild wave_build[4];
+    std::vector<TileRef> coop_build;
+    struct NarrowItem {
+        WaveItem item;
+        int32_t cost;
+    };
+    std::vector<NarrowItem> narrow_items;
+    struct WideItem {
+        WgDesc wg;
+        int32_t cost;
+    };
+    std::vector<WideItem> wide_items;
+
+    void clear();
+};
+
+struct PlanParams {
+    int32_t rows_per_thread;  // candidates * q heads per kv head
+    int32_t chunk_blocks;     // blocks per stand-alone unit (lower bound)
+    int32_t max_unit_tiles;   // longest tile list one wavefront may be given
+    bool allow_direct;        // threads whose whole path is one unit may write their output directly
+    bool fuse;                // build tree-fused units (false: every segment stands alone)
+};
+
+// seg_of: pool-sized scratch, all -1 on entry and on exit.  refcount: the pool's refcounts.
+// Returns 0, or a negative apar_status.
+int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, int32_t* seg_of, const PlanParams& prm,
+               PlanHost& ph);
+
+}  // namespace apar

@@ -89,46 +89,77 @@ def blocks_upper_bound(w) -> int:
 
 
 def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per_thread: int = 1) -> Dict[str, int]:
-    """The exported plan must read, for every listed thread, exactly the blocks of its table, in
-    order, through the partial-result rows on its path; and no block twice for one row group."""
-    units = np.array(ap.apar_last_plan_export(handle, ap.APAR_PLAN_UNITS), dtype=np.int64).reshape(-1, 6)
-    blocks = ap.apar_last_plan_export(handle, ap.APAR_PLAN_BLOCKS)
-    sharers = ap.apar_last_plan_export(handle, ap.APAR_PLAN_SHARERS)
+    """The exported plan must read, on behalf of every row group of every listed thread, exactly the
+    blocks of that thread's table (each once, with the right fill counts); a thread is either written
+    directly by the one unit that covers its whole path, or merged from exactly the partial results
+    of the units that cover it."""
+    wgs = np.array(ap.apar_last_plan_export(handle, ap.APAR_PLAN_WORKGROUPS), dtype=np.int64).reshape(-1, 32)
+    tiles = np.array(ap.apar_last_plan_export(handle, ap.APAR_PLAN_TILES), dtype=np.int64).reshape(-1, 2)
+    dfs = ap.apar_last_plan_export(handle, ap.APAR_PLAN_DFS_THREADS)
     path_ofs = ap.apar_last_plan_export(handle, ap.APAR_PLAN_PATH_OFS)
     path_ids = ap.apar_last_plan_export(handle, ap.APAR_PLAN_PATH_IDS)
-    row_owner = {}
-    for fam, (bo, nb, lv, so, ns, pb) in enumerate(units):
-        assert nb >= 1 and 1 <= lv <= 16 and ns >= 1
-        assert ns * rows_per_thread <= 64
-        for j in range(ns):
-            assert pb + j not in row_owner
-            row_owner[pb + j] = (fam, sharers[so + j])
-    assert len(path_ofs) == len(threads) + 1
-    reads = 0
-    for i, t in enumerate(threads):
+    rpt, rps, n_sl = ap.apar_last_plan_export(handle, ap.APAR_PLAN_GEOMETRY)
+    assert rpt == rows_per_thread and n_sl == -(-rpt // 16) and rps * n_sl >= rpt and rps <= 16
+    cap = 16 // rps
+    n = len(threads)
+    assert sorted(dfs) == list(range(n)) and len(path_ofs) == n + 1
+    seen = {}      # row group -> list of (block, valid)
+    parts = {}     # rank -> set of partial rows
+    direct = {}    # rank -> number of direct units
+    tile_reads = 0
+    for wg in wgs:
+        coop_ofs, n_coop, grp_base = wg[0], wg[1], wg[2]
+        tile_reads += n_coop
+        for k in range(4):
+            t_ofs, n_t, g_lo, n_g, pbase, flags = wg[4 + 6 * k: 10 + 6 * k]
+            assert 0 <= n_g <= cap
+            tile_reads += n_t
+            if n_g == 0:
+                assert n_t == 0
+                continue
+            for g in range(g_lo, g_lo + n_g):
+                rank = g // n_sl
+                lst = seen.setdefault(g, [])
+                for blk, meta in tiles[coop_ofs:coop_ofs + n_coop]:
+                    lo, hi, valid = meta & 0xFF, (meta >> 8) & 0xFF, meta >> 16
+                    assert 1 <= valid <= 16 and lo < hi
+                    if lo <= g - grp_base < hi:
+                        lst.append((int(blk), int(valid)))
+                for blk, meta in tiles[t_ofs:t_ofs + n_t]:
+                    lo, hi, valid = meta & 0xFF, (meta >> 8) & 0xFF, meta >> 16
+                    assert 1 <= valid <= 16 and lo < hi <= n_g
+                    if lo <= g - g_lo < hi:
+                        lst.append((int(blk), int(valid)))
+                if flags & 1:
+                    direct.setdefault(rank, set()).add((tuple(wg[:3]), k if n_coop == 0 else -1))
+                else:
+                    parts.setdefault(rank, set()).add(int(pbase + rank - g_lo // n_sl))
+    assert sorted(seen) == list(range(n * n_sl)), "every row group of every thread must be covered"
+    all_parts = []
+    for rank in range(n):
+        i = dfs[rank]
+        t = threads[i]
         table = ap.apar_thread_block_table(handle, t)
         L = ap.apar_thread_len(handle, t)
-        got: List[int] = []
-        tokens = 0
-        fams = []
-        for p in path_ids[path_ofs[i]:path_ofs[i + 1]]:
-            fam, who = row_owner[p]
-            assert who == i
-            bo, nb, lv = units[fam][:3]
-            fams.append((bo, fam))
-        for bo, fam in sorted(fams):  # block runs of one thread are laid out in table order
-            _, nb, lv = units[fam][:3]
-            got.extend(blocks[bo:bo + nb])
-            tokens += (nb - 1) * 16 + lv
-        assert got == table, f"thread {t}: plan reads {got}, table is {table}"
-        assert tokens == L
+        for sl in range(n_sl):
+            got = seen[rank * n_sl + sl]
+            assert sorted(b for b, _ in got) == sorted(table), f"thread {t}: plan reads {got}, table is {table}"
+            assert sum(v for _, v in got) == L
+            assert all(v == 16 for b, v in got if b != table[-1])
+        mine = set(path_ids[path_ofs[i]:path_ofs[i + 1]])
+        if rank in direct:
+            assert len(direct[rank]) == 1 and rank not in parts and not mine
+        else:
+            assert mine == parts[rank] and len(mine) == path_ofs[i + 1] - path_ofs[i]
+            all_parts += list(mine)
     info = ap.apar_last_plan_info(handle)
-    assert info.n_units == len(units) * n_kv and info.n_partial_rows == len(row_owner)
+    assert len(all_parts) == len(set(all_parts)), "a partial-result row belongs to one thread"
+    assert info.n_partial_rows == len(all_parts)
+    assert info.n_units == len(wgs) * n_kv
     uniq = set()
     for t in threads:
         uniq.update(ap.apar_thread_block_table(handle, t))
-    assert info.unique_blocks == len(uniq) == len(blocks) == len(set(blocks))
+    assert info.unique_blocks == len(uniq)
     assert info.path_tokens == sum(ap.apar_thread_len(handle, t) for t in threads)
-    for (bo, nb, lv, so, ns, pb) in units:
-        reads += nb
-    return {"unit_block_reads": reads, "unique_blocks": len(uniq)}
+    return {"unit_block_reads": tile_reads, "unique_blocks": len(uniq), "partial_rows": len(all_parts),
+            "direct_threads": len(direct)}

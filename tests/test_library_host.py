@@ -47,15 +47,19 @@ def test_config_books_and_plans(name, n_req):
         live, _ = replay_trace(w, pool, led, dry_run=True)
         books_equal(pool.handle, led)
         led.check_invariants()
-        for chunk in (1, 8, 64):
+        for chunk in (1, 8, 64, 512):
             ap.apar_set_chunk_blocks(pool.handle, chunk)
             ap.apar_decode_attention(pool.handle, None, live, None)
             res = check_plan_covers_tables(pool.handle, live, w.heads.n_kv_heads, w.heads.n_q_heads // w.heads.n_kv_heads)
             groups_extra = res["unit_block_reads"] - res["unique_blocks"]
-            # a block is read once per row group; only runs shared by more than 64 rows are split
+            # a block is read once per workgroup that holds rows for it; only runs shared by more
+            # than 64 rows are split over several workgroups
             assert groups_extra >= 0
             if w.heads.n_q_heads == w.heads.n_kv_heads:
                 assert groups_extra == 0
+            if chunk == 512 and name != "gqa1024":
+                # whole trees fit one unit: nothing is left to merge
+                assert res["partial_rows"] == 0 and res["direct_threads"] == len(live)
         info = ap.apar_last_plan_info(pool.handle)
         e = w.heads.elem_bytes
         assert info.algorithmic_bytes == info.unique_tokens * w.heads.kv_bytes_per_token + \
