@@ -9,6 +9,7 @@
 namespace apar {
 
 constexpr int kBlockTokens = 16;
+constexpr int32_t kCodeSealed = 1 << 30;  // flag on a (block * 16 + slot) code: the block is sealed
 
 // ---------------------------------------------------------------------------
 // Pool layout in HBM.
@@ -18,11 +19,16 @@ constexpr int kBlockTokens = 16;
 //
 // f32 pools: both halves are row-major [16][d].
 //
-// bf16 pools (d = 128; tile = 4 KiB of K + 4 KiB of V): both halves are stored
-// in the order the 16x16 matrix-core instructions consume them, so a wavefront
-// fills its operand registers with four fully coalesced 1 KiB loads per half
-// and no shuffle or LDS pass.  With lane = 16*g + c (g = 0..3, c = 0..15) and
-// load index r = 0..3, the 16 bytes at  r*1024 + lane*16  hold
+// bf16 pools (d = 128; tile = 4 KiB of K + 4 KiB of V).  A block that is still
+// filling (fewer than 16 slots written) is row-major too, so that appending a row
+// is a few full-line writes.  When its sixteenth slot is written the block is
+// SEALED: both halves are rewritten in the order the 16x16 matrix-core
+// instructions consume them, so that a wavefront fills its operand registers with
+// four fully coalesced 1 KiB loads per half and no shuffle or LDS pass.  Full
+// blocks are never written again, and every thread that holds a block agrees on
+// its fill count, so "filled slots < 16" is all a reader needs to know the format.
+// Sealed layout, with lane = 16*g + c (g = 0..3, c = 0..15) and load index
+// r = 0..3: the 16 bytes at  r*1024 + lane*16  hold
 //   K half: K[token c][dims 32*g + 8*r .. +8]               (A operand of K.Q^T)
 //   V half: V[tokens 4*g .. 4*g+3][dim 32*r + c] followed by
 //           V[tokens 4*g .. 4*g+3][dim 32*r + 16 + c]       (A operand of V^T.P^T)
@@ -58,6 +64,9 @@ struct WaveItem {    // what one wavefront computes
     int32_t flags;              // kWaveDirect: normalise and write the output rows instead of partial results
 };
 constexpr int32_t kWaveDirect = 1;
+constexpr int32_t kWaveSplit = 2;  // the group's four wavefronts hold the SAME rows and a quarter of the tiles each;
+                                   // their results are combined in LDS and wavefront 0 writes them
+constexpr int kSplitMinTiles = 16; // shorter private units are packed four to a workgroup instead
 
 struct WgDesc {      // one 256-thread workgroup: a shared tile list, then one private list per wavefront
     int32_t coop_ofs, n_coop;   // tiles every wavefront of the group sees (staged once through LDS)
@@ -99,6 +108,7 @@ hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const v
                               int n_rows, hipStream_t st);
 hipError_t launch_block_copies(const Shape& s, void* pool, const int32_t* src_dst_pairs, int n_pairs,
                                hipStream_t st);
+hipError_t launch_seal_blocks(const Shape& s, void* pool, const int32_t* blocks, int n_blocks, hipStream_t st);
 hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src_codes, int n_rows, void* k_out,
                             void* v_out, hipStream_t st);
 hipError_t launch_attention_partial(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,

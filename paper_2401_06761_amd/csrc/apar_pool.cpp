@@ -73,6 +73,7 @@ struct apar_pool {
     std::vector<int32_t> seg_of;  // segment that starts at each block, -1 if none
     int max_unit_tiles = 512;  // longest tile list given to one wavefront
     std::vector<PlanThreadView> views;
+    std::vector<int32_t> scratch_codes, scratch_copies, scratch_seals;
     apar_plan_info last_plan{};
     PlanHost plan;  // the last plan, kept for reuse of its storage and for inspection
     int32_t plan_geom[3] = {1, 1, 1};  // rows per thread, rows per slice, slices of the last plan
@@ -153,7 +154,7 @@ inline int32_t slot_code(const Thread& t, int64_t pos) {
 
 // Advances one thread by one token following the allocator policy; the caller
 // has already made sure enough free blocks exist.
-inline int32_t append_one(apar_pool* p, Thread& t, std::vector<int32_t>& copies) {
+inline int32_t append_one(apar_pool* p, Thread& t, std::vector<int32_t>& copies, std::vector<int32_t>& seals) {
     const int slot = (int)(t.len % kBlockTokens);
     if (slot == 0) {
         t.table.push_back(pop_block(p));
@@ -169,20 +170,23 @@ inline int32_t append_one(apar_pool* p, Thread& t, std::vector<int32_t>& copies)
         }
     }
     const int32_t code = t.table.back() * kBlockTokens + slot;
+    if (slot == kBlockTokens - 1) seals.push_back(t.table.back());  // the block is full after this row
     t.len += 1;
     return code;
 }
 
-int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vector<int32_t>& copies, const void* k,
-               const void* v, hipStream_t st) {
+int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vector<int32_t>& copies,
+               const std::vector<int32_t>& seals, const void* k, const void* v, hipStream_t st) {
     const size_t copy_bytes = align_up(copies.size() * sizeof(int32_t), 256);
-    const size_t code_bytes = codes.size() * sizeof(int32_t);
+    const size_t code_bytes = align_up(codes.size() * sizeof(int32_t), 256);
+    const size_t seal_bytes = seals.size() * sizeof(int32_t);
     StageSlot* s = nullptr;
-    int rc = acquire_stage(p, copy_bytes + code_bytes, &s);
+    int rc = acquire_stage(p, copy_bytes + code_bytes + seal_bytes, &s);
     if (rc != APAR_OK) return rc;
     if (!copies.empty()) memcpy(s->host, copies.data(), copies.size() * sizeof(int32_t));
-    memcpy(s->host + copy_bytes, codes.data(), code_bytes);
-    HIP_TRY(hipMemcpyAsync(s->dev, s->host, copy_bytes + code_bytes, hipMemcpyHostToDevice, st));
+    memcpy(s->host + copy_bytes, codes.data(), codes.size() * sizeof(int32_t));
+    if (!seals.empty()) memcpy(s->host + copy_bytes + code_bytes, seals.data(), seal_bytes);
+    HIP_TRY(hipMemcpyAsync(s->dev, s->host, copy_bytes + code_bytes + seal_bytes, hipMemcpyHostToDevice, st));
     EventPair ev;
     if (p->profiling) {
         if ((rc = new_event(p, &ev.a)) != APAR_OK || (rc = new_event(p, &ev.b)) != APAR_OK) return rc;
@@ -191,6 +195,8 @@ int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vecto
     if (!copies.empty())
         HIP_TRY(launch_block_copies(p->shape, p->kv, (const int32_t*)s->dev, (int)(copies.size() / 2), st));
     HIP_TRY(launch_append_rows(p->shape, p->kv, k, v, (const int32_t*)(s->dev + copy_bytes), (int)codes.size(), st));
+    if (!seals.empty())
+        HIP_TRY(launch_seal_blocks(p->shape, p->kv, (const int32_t*)(s->dev + copy_bytes + code_bytes), (int)seals.size(), st));
     if (p->profiling) {
         HIP_TRY(hipEventRecord(ev.b, st));
         p->append_events.push_back(ev);
@@ -446,11 +452,11 @@ int apar_append_kv(apar_pool* p, apar_thread thread, const void* k_dev, const vo
     int64_t need = (t->len + n_tokens + B - 1) / B - (t->len + B - 1) / B;
     if (t->len % B != 0 && p->ref[t->table.back()] > 1) need += 1;
     if (need > (int64_t)p->free_stack.size()) return APAR_ERR_OUT_OF_BLOCKS;
-    std::vector<int32_t> codes(n_tokens), copies;
-    for (int i = 0; i < n_tokens; ++i) codes[i] = append_one(p, *t, copies);
+    std::vector<int32_t> codes(n_tokens), copies, seals;
+    for (int i = 0; i < n_tokens; ++i) codes[i] = append_one(p, *t, copies, seals);
     if (p->dry_run) return APAR_OK;
     DeviceGuard guard(p->device);
-    return run_append(p, codes, copies, k_dev, v_dev, (hipStream_t)hip_stream);
+    return run_append(p, codes, copies, seals, k_dev, v_dev, (hipStream_t)hip_stream);
 }
 
 int apar_append_kv_batch(apar_pool* p, const apar_thread* threads, int n, const void* k_dev, const void* v_dev,
@@ -492,11 +498,16 @@ int apar_append_kv_batch(apar_pool* p, const apar_thread* threads, int n, const 
         }
         if (need > (int64_t)p->free_stack.size()) return APAR_ERR_OUT_OF_BLOCKS;
     }
-    std::vector<int32_t> codes(n), copies;
-    for (int i = 0; i < n; ++i) codes[i] = append_one(p, p->threads[threads[i]], copies);
+    std::vector<int32_t>& codes = p->scratch_codes;
+    std::vector<int32_t>& copies = p->scratch_copies;
+    std::vector<int32_t>& seals = p->scratch_seals;
+    codes.resize(n);
+    copies.clear();
+    seals.clear();
+    for (int i = 0; i < n; ++i) codes[i] = append_one(p, p->threads[threads[i]], copies, seals);
     if (p->dry_run) return APAR_OK;
     DeviceGuard guard(p->device);
-    return run_append(p, codes, copies, k_dev, v_dev, (hipStream_t)hip_stream);
+    return run_append(p, codes, copies, seals, k_dev, v_dev, (hipStream_t)hip_stream);
 }
 
 int apar_decode_attention(apar_pool* p, const void* q_dev, const apar_thread* threads, int n, void* out_dev,
@@ -606,7 +617,11 @@ int apar_read_kv_rows(apar_pool* p, apar_thread thread, int64_t first, int n, vo
     int rc = acquire_stage(p, (size_t)n * sizeof(int32_t), &s);
     if (rc != APAR_OK) return rc;
     int32_t* codes = (int32_t*)s->host;
-    for (int i = 0; i < n; ++i) codes[i] = slot_code(*t, first + i);
+    for (int i = 0; i < n; ++i) {
+        const int64_t pos = first + i;
+        const bool sealed = p->shape.dtype == APAR_BF16 && (pos / kBlockTokens + 1) * kBlockTokens <= t->len;
+        codes[i] = slot_code(*t, pos) | (sealed ? kCodeSealed : 0);
+    }
     HIP_TRY(hipMemcpyAsync(s->dev, s->host, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HIP_TRY(launch_read_rows(p->shape, p->kv, (const int32_t*)s->dev, n, k_out_dev, v_out_dev, st));
     HIP_TRY(hipEventRecord(s->ev, st));

@@ -30,6 +30,10 @@
 // lies in the unit are normalised and written out here; the others leave a
 // partial result (reference, sum, unnormalised output) for the merge kernel.
 //
+// A block that is still filling (fewer than 16 slots) is stored row-major, not in
+// operand order; such tiles - at most one per segment - take a slower path: K
+// pieces are gathered row by row and V goes through a padded LDS transpose.
+//
 // Softmax runs in base 2 with a lazily updated reference: a row's reference
 // logit m only moves when some logit exceeds it by more than kSlack, which
 // keeps the cross-lane maximum and the rescale of the accumulators off the
@@ -127,11 +131,35 @@ __device__ __forceinline__ void accumulate(Frag (&v)[4], RowState& st, const flo
     }
 }
 
+// V^T operand pieces out of a ROW-MAJOR V half held in LDS (rows `stride` bytes apart):
+// piece r holds V[tokens 4g..4g+3][dim 32r + c] and V[tokens 4g..4g+3][dim 32r + 16 + c].
+__device__ __forceinline__ void v_operands_from_rows(const char* vrows, int stride, int g4, int c, Frag (&v)[4]) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const char* col = vrows + (32 * r + 16 * hh + c) * 2 + 4 * g4 * stride;
+            const uint32_t a0 = *reinterpret_cast<const uint16_t*>(col);
+            const uint32_t a1 = *reinterpret_cast<const uint16_t*>(col + stride);
+            const uint32_t a2 = *reinterpret_cast<const uint16_t*>(col + 2 * stride);
+            const uint32_t a3 = *reinterpret_cast<const uint16_t*>(col + 3 * stride);
+            v[r].u[2 * hh] = a0 | (a1 << 16);
+            v[r].u[2 * hh + 1] = a2 | (a3 << 16);
+        }
+    }
+}
+
+constexpr int kOpenRowStride = 264;                 // padded, so the four token groups hit different LDS banks
+constexpr int kOpenScratch = 16 * kOpenRowStride;   // one wavefront's row-major V half
+
 __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ pool, const uint16_t* __restrict__ q,
                                                       PlanDev plan, int n_cand, int n_q, int n_kv, int group,
                                                       float scale_log2e, PartialBuf part,
                                                       uint16_t* __restrict__ out) {
-    __shared__ __attribute__((aligned(16))) char stage[2][kTileBytes];
+    // two staged tiles during the shared phase; then one V-transpose scratch per wavefront; last, three
+    // wavefronts' row states when a unit is split
+    __shared__ __attribute__((aligned(16))) char lds[3 * 16 * 130 * 4];
+    char(*stage)[kTileBytes] = reinterpret_cast<char(*)[kTileBytes]>(lds);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int g4 = lane >> 4, c = lane & 15;
@@ -193,10 +221,18 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             if (wi.n_grp > 0 && lo < shift + wi.n_grp && hi > shift) {
                 const char* sb = stage[t & 1];
                 Frag ks[4], vs[4];
+                if (valid == 16) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
+                    for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
+                    for (int r = 0; r < 4; ++r)
+                        vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
+                } else {  // an open block: row-major in the stage buffer
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        ks[r].u = *reinterpret_cast<const u32x4*>(sb + c * 256 + g4 * 64 + r * 16);
+                    v_operands_from_rows(sb + 4096, 256, g4, c, vs);
+                }
                 float sv[4];
                 scores(ks, st, scale_log2e, valid, my_jc >= lo && my_jc < hi, g4, sv);
                 accumulate(vs, st, sv, valid, g4);
@@ -211,41 +247,100 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
     }
     if (wi.n_grp == 0) return;  // a wavefront without rows only helped to fetch
 
-    // Private list: start the first tile's loads (nothing before this point waits on memory when the
-    // group has no shared tiles).
-    Frag k[4], v[4];
-    if (wi.n_tiles > 0) {
-        const u32x4* t0 = reinterpret_cast<const u32x4*>(head_base + mine[0].blk * block_stride) + lane;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) k[r].u = __builtin_nontemporal_load(t0 + r * 64);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(t0 + 256 + r * 64);
-    }
-
     // ---- private tiles: straight into operand registers -------------------------------------
+    // K pieces of a sealed tile are 1 KiB apart with the lanes side by side; of an open tile, 16 bytes
+    // apart inside the lane's own 64 bytes of its token's row.  The V half is fetched raw either way.
+    Frag k[4], v[4];
+    const int k_sealed = lane * 16, k_open = c * 256 + g4 * 64;
+    auto issue_k = [&](const char* tile, bool open) {
+        const char* p = tile + (open ? k_open : k_sealed);
+        const int step = open ? 16 : 1024;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) k[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + r * step));
+    };
+    auto issue_v = [&](const char* tile) {
+        const u32x4* p = reinterpret_cast<const u32x4*>(tile + 4096) + lane;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(p + r * 64);
+    };
+    int meta = 16 << 16;
+    if (wi.n_tiles > 0) {  // (nothing before this point waits on memory when the group has no shared tiles)
+        meta = mine[0].meta;
+        const char* t0 = head_base + mine[0].blk * block_stride;
+        issue_k(t0, (meta >> 16) < 16);
+        issue_v(t0);
+    }
+    char* scratch = lds + wave * kOpenScratch;
     for (int t = 0; t < wi.n_tiles; ++t) {
         const bool more = t + 1 < wi.n_tiles;
-        const int meta = mine[t].meta;
         const int lo = meta & 0xff, hi = (meta >> 8) & 0xff, valid = meta >> 16;
-        const u32x4* tn = nullptr;
-        if (more) tn = reinterpret_cast<const u32x4*>(head_base + mine[t + 1].blk * block_stride) + lane;
+        const char* tn = nullptr;
+        int meta_n = 16 << 16;
+        if (more) {
+            tn = head_base + mine[t + 1].blk * block_stride;
+            meta_n = mine[t + 1].meta;
+        }
         float sv[4];
         scores(k, st, scale_log2e, valid, my_j >= lo && my_j < hi, g4, sv);
-        if (more) {  // K registers are free again: start fetching the next tile's K
+        if (more) issue_k(tn, (meta_n >> 16) < 16);  // K registers are free again
+        if (valid < 16) {
+            // open block: its V half arrived row-major; turn it into operand order through LDS
 #pragma unroll
-            for (int r = 0; r < 4; ++r) k[r].u = __builtin_nontemporal_load(tn + r * 64);
+            for (int r = 0; r < 4; ++r)
+                *reinterpret_cast<u32x4*>(scratch + (4 * r + g4) * kOpenRowStride + c * 16) = v[r].u;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            v_operands_from_rows(scratch, kOpenRowStride, g4, c, v);
+            __builtin_amdgcn_wave_barrier();
         }
         accumulate(v, st, sv, valid, g4);
-        if (more) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(tn + 256 + r * 64);
-        }
+        if (more) issue_v(tn);
+        meta = meta_n;
     }
 
     // ---- results ------------------------------------------------------------------------------
     float lt = st.l;
     lt += __shfl_xor(lt, 16, 64);
     lt += __shfl_xor(lt, 32, 64);
+    if (wi.flags & kWaveSplit) {
+        // the four wavefronts hold the same rows over different tiles: fold 1..3 into 0 through LDS
+        float* so = reinterpret_cast<float*>(lds);           // [3][16 rows][128]
+        float* sml = so + 3 * 16 * 128;                       // [3][16 rows][2]
+        __syncthreads();  // every wavefront is done with its transpose scratch, which this area overlaps
+        if (wave > 0) {
+            float* dst = so + ((wave - 1) * 16 + c) * 128 + 4 * g4;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) *reinterpret_cast<f32x4*>(dst + 16 * jj) = st.o[jj];
+            if (g4 == 0) {
+                sml[((wave - 1) * 16 + c) * 2] = st.m;
+                sml[((wave - 1) * 16 + c) * 2 + 1] = lt;
+            }
+        }
+        __syncthreads();
+        if (wave > 0) return;
+        float mw[3], lw[3], mx = st.m;
+#pragma unroll
+        for (int w2 = 0; w2 < 3; ++w2) {
+            mw[w2] = sml[(w2 * 16 + c) * 2];
+            lw[w2] = sml[(w2 * 16 + c) * 2 + 1];
+            mx = fmaxf(mx, mw[w2]);
+        }
+        // a wavefront that saw no tile of a row left m = -inf and sums of zero for it
+        const float a0 = (st.m == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(st.m - mx);
+        lt *= a0;
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) st.o[jj] *= a0;
+#pragma unroll
+        for (int w2 = 0; w2 < 3; ++w2) {
+            const float aw = (mw[w2] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw[w2] - mx);
+            lt += aw * lw[w2];
+            const float* src = so + (w2 * 16 + c) * 128 + 4 * g4;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) st.o[jj] += aw * *reinterpret_cast<const f32x4*>(src + 16 * jj);
+        }
+        st.m = mx;
+    }
     if (!row_ok) return;
     if (wi.flags & kWaveDirect) {
         // the row's whole root path was covered here: normalise and write the output row

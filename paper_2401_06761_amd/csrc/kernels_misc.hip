@@ -25,29 +25,50 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 // ---------------------------------------------------------------------------
 // Row writes.  One wavefront per (row, kv head).
-// bf16: the K row goes out as sixteen 16-byte pieces and the V row as 128
-// two-byte pieces, each to its place in the matrix-core tile order.
+// bf16 pools keep a block that is still filling in plain row-major form (K rows
+// then V rows, 256 contiguous bytes each), so an appended row is two full-line
+// writes per half; seal_blocks_bf16 rewrites a block into matrix-core order once
+// its sixteenth slot is written.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void append_rows_bf16(char* __restrict__ pool, const uint16_t* __restrict__ k,
                                                        const uint16_t* __restrict__ v,
                                                        const int32_t* __restrict__ codes, int n_kv,
                                                        int64_t tile_bytes) {
     const int row = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    if (lane >= 32) return;
     const int32_t code = codes[row];
     const int slot = code & 15;
     char* tile = pool + ((int64_t)(code >> 4) * n_kv + h) * tile_bytes;
-    const uint16_t* ksrc = k + ((int64_t)row * n_kv + h) * 128;
-    const uint16_t* vsrc = v + ((int64_t)row * n_kv + h) * 128;
-    if (lane < 16) {
-        const uint4 piece = *reinterpret_cast<const uint4*>(ksrc + lane * 8);
-        *reinterpret_cast<uint4*>(tile + bf16_k_offset(slot, lane * 8)) = piece;
-    }
-    char* vt = tile + 4096;
+    const uint16_t* src = (lane < 16 ? k : v) + ((int64_t)row * n_kv + h) * 128 + (lane & 15) * 8;
+    *reinterpret_cast<uint4*>(tile + (lane < 16 ? 0 : 4096) + slot * 256 + (lane & 15) * 16) =
+        *reinterpret_cast<const uint4*>(src);
+}
+
+// In-place row-major -> matrix-core order for blocks that just became full.
+// One workgroup per (block, kv head): the 8 KiB tile goes through LDS.
+__global__ __launch_bounds__(256) void seal_blocks_bf16(char* __restrict__ pool, const int32_t* __restrict__ blocks,
+                                                        int n_kv, int64_t tile_bytes) {
+    __shared__ __attribute__((aligned(16))) char raw[8192];
+    const int t = threadIdx.x;
+    char* tile = pool + ((int64_t)blocks[blockIdx.x] * n_kv + blockIdx.y) * tile_bytes;
+    reinterpret_cast<uint4*>(raw)[t] = reinterpret_cast<const uint4*>(tile)[t];
+    reinterpret_cast<uint4*>(raw)[256 + t] = reinterpret_cast<const uint4*>(tile)[256 + t];
+    __syncthreads();
+    // piece t of either half sits at byte t*16 of the half: load index r = t / 64, lane = t % 64
+    const int r = t >> 6, lane = t & 63, g = lane >> 4, c = lane & 15;
+    // K piece: K[token c][dims 32g + 8r .. +8]
+    const uint4 kp = *reinterpret_cast<const uint4*>(raw + c * 256 + (32 * g + 8 * r) * 2);
+    // V piece: V[tokens 4g..4g+3][dim 32r + c], then V[tokens 4g..4g+3][dim 32r + 16 + c]
+    const uint16_t* vr = reinterpret_cast<const uint16_t*>(raw + 4096);
+    uint32_t w[4];
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        const int dim = lane + 64 * e;
-        *reinterpret_cast<uint16_t*>(vt + bf16_v_offset(slot, dim)) = vsrc[dim];
+    for (int hh = 0; hh < 2; ++hh) {
+        const int dim = 32 * r + 16 * hh + c;
+        w[2 * hh] = (uint32_t)vr[(4 * g + 0) * 128 + dim] | ((uint32_t)vr[(4 * g + 1) * 128 + dim] << 16);
+        w[2 * hh + 1] = (uint32_t)vr[(4 * g + 2) * 128 + dim] | ((uint32_t)vr[(4 * g + 3) * 128 + dim] << 16);
     }
+    reinterpret_cast<uint4*>(tile)[t] = kp;
+    reinterpret_cast<uint4*>(tile)[256 + t] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
 __global__ __launch_bounds__(64) void append_rows_f32(char* __restrict__ pool, const float* __restrict__ k,
@@ -70,15 +91,18 @@ __global__ __launch_bounds__(64) void read_rows_bf16(const char* __restrict__ po
                                                      int n_kv, int64_t tile_bytes) {
     const int row = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
     const int32_t code = codes[row];
+    const bool sealed = (code & kCodeSealed) != 0;  // the row's block is full, hence in matrix-core order
     const int slot = code & 15;
-    const char* tile = pool + ((int64_t)(code >> 4) * n_kv + h) * tile_bytes;
+    const char* tile = pool + ((int64_t)((code & ~kCodeSealed) >> 4) * n_kv + h) * tile_bytes;
     uint16_t* kdst = k + ((int64_t)row * n_kv + h) * 128;
     uint16_t* vdst = v + ((int64_t)row * n_kv + h) * 128;
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
         const int dim = lane + 64 * e;
-        kdst[dim] = *reinterpret_cast<const uint16_t*>(tile + bf16_k_offset(slot, dim));
-        vdst[dim] = *reinterpret_cast<const uint16_t*>(tile + 4096 + bf16_v_offset(slot, dim));
+        const int ko = sealed ? bf16_k_offset(slot, dim) : slot * 256 + dim * 2;
+        const int vo = sealed ? bf16_v_offset(slot, dim) : slot * 256 + dim * 2;
+        kdst[dim] = *reinterpret_cast<const uint16_t*>(tile + ko);
+        vdst[dim] = *reinterpret_cast<const uint16_t*>(tile + 4096 + vo);
     }
 }
 
@@ -137,9 +161,14 @@ __global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ poo
 #pragma unroll
     for (int e = 0; e < E; ++e) qv[e] = q[qrow * D + lane + 64 * e], acc[e] = 0.0f;
     float m = -INFINITY, l = 0.0f;
-    for (int list = 0; list < 2; ++list) {
-        const TileRef* tiles = plan.tiles + (list == 0 ? wg->coop_ofs : wi.tile_ofs);
-        const int n_tiles = list == 0 ? wg->n_coop : wi.n_tiles;
+    // a split group's four wavefront items hold the same rows and a quarter of the tiles each
+    const bool split = (wi.flags & kWaveSplit) != 0;
+    if (split && wave != 0) return;
+    const int n_lists = split ? 5 : 2;
+    for (int list = 0; list < n_lists; ++list) {
+        const WaveItem& src = wg->w[list < 2 ? wave : list - 1];
+        const TileRef* tiles = plan.tiles + (list == 0 ? wg->coop_ofs : src.tile_ofs);
+        const int n_tiles = list == 0 ? wg->n_coop : src.n_tiles;
         const int my_j = list == 0 ? j + (wi.grp_lo - wg->grp_base) : j;
         for (int t = 0; t < n_tiles; ++t) {
             const int meta = tiles[t].meta;
@@ -271,6 +300,17 @@ hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const v
             hipLaunchKernelGGL(append_rows_f32, grid, dim3(64), 0, st, (char*)pool, (const float*)k + r0 * row_elems,
                                (const float*)v + r0 * row_elems, dst_codes + r0, s.n_kv, s.d, s.tile_bytes);
         }
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_seal_blocks(const Shape& s, void* pool, const int32_t* blocks, int n_blocks, hipStream_t st) {
+    if (n_blocks <= 0 || s.dtype != APAR_BF16) return hipSuccess;
+    const int kSlice = 1 << 20;
+    for (int b0 = 0; b0 < n_blocks; b0 += kSlice) {
+        const int nb = n_blocks - b0 < kSlice ? n_blocks - b0 : kSlice;
+        hipLaunchKernelGGL(seal_blocks_bf16, dim3(nb, s.n_kv), dim3(256), 0, st, (char*)pool, blocks + b0, s.n_kv,
+                           s.tile_bytes);
     }
     return hipGetLastError();
 }

@@ -373,7 +373,7 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         }
     }
 
-    // 7. workgroups, heaviest first; narrow items are packed four to a workgroup
+    // 7. workgroups, heaviest first
     std::stable_sort(ph.wide_items.begin(), ph.wide_items.end(),
                      [](const PlanHost::WideItem& a, const PlanHost::WideItem& b) { return a.cost > b.cost; });
     ph.wgs.reserve(ph.wide_items.size() + (ph.narrow_items.size() + 3) / 4);
@@ -389,7 +389,19 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         std::vector<int32_t>& slot = ph.stack;
         slot.assign(ph.narrow_items.size(), 0);
         for (size_t k = 0; k < ph.narrow_items.size(); ++k) slot[cnt[max_cost - ph.narrow_items[k].cost]++] = (int32_t)k;
-        for (size_t k = 0; k < slot.size(); k += 4) {
+        // long units get a workgroup of their own and are split four ways; short ones are packed
+        size_t k = 0;
+        for (; k < slot.size() && ph.narrow_items[slot[k]].cost >= kSplitMinTiles; ++k) {
+            const WaveItem& it = ph.narrow_items[slot[k]].item;
+            WgDesc wg{};
+            wg.grp_base = it.grp_lo;
+            for (int j = 0; j < 4; ++j) {
+                const int32_t b = (int32_t)((int64_t)it.n_tiles * j / 4), e = (int32_t)((int64_t)it.n_tiles * (j + 1) / 4);
+                wg.w[j] = WaveItem{it.tile_ofs + b, e - b, it.grp_lo, it.n_grp, it.part_base, it.flags | kWaveSplit};
+            }
+            ph.wgs.push_back(wg);
+        }
+        for (; k < slot.size(); k += 4) {
             WgDesc wg{};
             for (int j = 0; j < 4; ++j) {
                 if (k + j < slot.size()) wg.w[j] = ph.narrow_items[slot[k + j]].item;

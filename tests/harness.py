@@ -107,7 +107,7 @@ def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per
     parts = {}     # rank -> set of partial rows
     direct = {}    # rank -> number of direct units
     tile_reads = 0
-    for wg in wgs:
+    for wg_index, wg in enumerate(wgs):
         coop_ofs, n_coop, grp_base = wg[0], wg[1], wg[2]
         tile_reads += n_coop
         for k in range(4):
@@ -131,7 +131,7 @@ def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per
                     if lo <= g - g_lo < hi:
                         lst.append((int(blk), int(valid)))
                 if flags & 1:
-                    direct.setdefault(rank, set()).add((tuple(wg[:3]), k if n_coop == 0 else -1))
+                    direct.setdefault(rank, set()).add(wg_index)
                 else:
                     parts.setdefault(rank, set()).add(int(pbase + rank - g_lo // n_sl))
     assert sorted(seen) == list(range(n * n_sl)), "every row group of every thread must be covered"
