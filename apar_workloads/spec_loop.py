@@ -2,8 +2,9 @@
 
 Per step, over the live threads in ascending id order:
   1. every thread proposes C candidate tokens arranged as a random tree
-     (parent[0] = -1, parent[c] ~ Uniform{0..c-1}); candidate c may see the
-     cached tokens plus itself and its ancestors among the candidates;
+     (parent[0] = -1, parent[c] ~ Uniform{0..c-1}, drawn per step as one vector
+     over the threads for each c); candidate c may see the cached tokens plus
+     itself and its ancestors among the candidates;
   2. one node a ~ Uniform{0..C-1} is accepted together with its ancestor chain;
      those rows are appended to the cache in root -> a order;
   3. each thread finishes with probability p_finish (it is freed);
@@ -51,6 +52,7 @@ class SpecStep:
     finished: List[int]  # thread ids freed after the appends
     forked: List[int]  # surviving thread ids that fork one child
     children: List[int]  # the children's ids, same order as `forked`
+    accept_bits: np.ndarray = None  # [n, C] bool: the same accepted sets as a matrix
 
 
 class SpecLoopPlan:
@@ -65,29 +67,48 @@ class SpecLoopPlan:
         self.step = 0
 
     def next_step(self) -> SpecStep:
+        """Draw order per step: for c = 1..C-1 one vector of parents over the live threads (ascending
+        id), then the vector of accepted nodes, then the finish coins, then the survivors' fork coins."""
         rng, C = self.rng, self.n_cand
         live = list(self.live)
         n = len(live)
-        parents = np.zeros((n, C), dtype=np.int64)
+        parents = np.full((n, C), -1, dtype=np.int64)
         masks = np.zeros((n, C), dtype=np.uint8)
-        accepted: List[List[int]] = []
-        for i in range(n):
-            parents[i] = draw_candidate_tree(rng, C)
-            masks[i] = mask_rows_from_parents(parents[i])
-            a = int(rng.integers(0, C))
-            chain = []
-            while a >= 0:
-                chain.append(a)
-                a = int(parents[i, a])
-            accepted.append(chain[::-1])
+        masks[:, 0] = 1
+        rows = np.arange(n)
+        for c in range(1, C):
+            parents[:, c] = rng.integers(0, c, size=n)
+            masks[:, c] = (1 << c) | masks[rows, parents[:, c]]
+        node = rng.integers(0, C, size=n)
+        chain_bits = masks[rows, node]  # the accepted node with its ancestors; ancestors have smaller indices
+        bits = np.unpackbits(chain_bits[:, None], axis=1, bitorder="little")[:, :C].astype(bool)
+        accepted = [list(np.flatnonzero(b)) for b in bits] if n <= 4096 else _LazyChains(bits)
         fin = rng.random(n) < self.p_finish
-        finished = [t for t, f in zip(live, fin) if f]
-        survivors = [t for t, f in zip(live, fin) if not f]
+        live_arr = np.asarray(live, dtype=np.int64)
+        finished = live_arr[fin].tolist()
+        survivors = live_arr[~fin]
         fk = rng.random(len(survivors)) < self.p_fork
-        forked = [t for t, f in zip(survivors, fk) if f]
+        forked = survivors[fk].tolist()
         children = list(range(self.next_tid, self.next_tid + len(forked)))
         self.next_tid += len(forked)
-        self.live = sorted(survivors + children)
+        self.live = sorted(survivors.tolist() + children)
         st = SpecStep(self.step, live, parents, masks, accepted, finished, forked, children)
+        st.accept_bits = bits
         self.step += 1
         return st
+
+
+class _LazyChains:
+    """accepted[i] computed on demand from the bit matrix (large steps never walk all of them in Python)."""
+
+    def __init__(self, bits: np.ndarray):
+        self.bits = bits
+
+    def __len__(self):
+        return self.bits.shape[0]
+
+    def __getitem__(self, i):
+        return list(np.flatnonzero(self.bits[i]))
+
+    def __iter__(self):
+        return (list(np.flatnonzero(b)) for b in self.bits)

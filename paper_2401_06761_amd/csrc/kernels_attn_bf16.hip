@@ -202,19 +202,24 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
         const int my_ofs = wave * 1024 + lane * 16;  // this wavefront's quarter: K piece `wave`, V piece `wave`
         const int shift = wi.grp_lo - wg->grp_base;  // shared ranges are relative to the group's base
         const int my_jc = row_ok ? j + shift : 0x7fff;
-        u32x4 kq, vq;
-        auto fetch = [&](int t) {
+        // Two tiles are kept in flight: while tile t is consumed from LDS, tile t+1 sits in registers
+        // (fetched an iteration ago) on its way into the other LDS buffer and tile t+2 is being fetched.
+        u32x4 kq1, vq1, kq2 = u32x4{0u, 0u, 0u, 0u}, vq2 = u32x4{0u, 0u, 0u, 0u};
+        auto fetch = [&](int t, u32x4& kq, u32x4& vq) {
             const char* tile = head_base + coop[t].blk * block_stride;
             kq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + my_ofs));
             vq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + my_ofs));
         };
-        fetch(0);
-        *reinterpret_cast<u32x4*>(&stage[0][my_ofs]) = kq;
-        *reinterpret_cast<u32x4*>(&stage[0][4096 + my_ofs]) = vq;
+        fetch(0, kq1, vq1);
+        if (n_coop > 1) fetch(1, kq2, vq2);
+        *reinterpret_cast<u32x4*>(&stage[0][my_ofs]) = kq1;
+        *reinterpret_cast<u32x4*>(&stage[0][4096 + my_ofs]) = vq1;
+        kq1 = kq2;
+        vq1 = vq2;
         __syncthreads();
         for (int t = 0; t < n_coop; ++t) {
             const bool more = t + 1 < n_coop;
-            if (more) fetch(t + 1);
+            if (t + 2 < n_coop) fetch(t + 2, kq2, vq2);
             const int meta = coop[t].meta;
             const int lo = meta & 0xff, hi = (meta >> 8) & 0xff, valid = meta >> 16;
             // does the tile touch any row group of this wavefront?
@@ -239,8 +244,10 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             }
             if (more) {
                 char* nb = stage[(t + 1) & 1];
-                *reinterpret_cast<u32x4*>(nb + my_ofs) = kq;
-                *reinterpret_cast<u32x4*>(nb + 4096 + my_ofs) = vq;
+                *reinterpret_cast<u32x4*>(nb + my_ofs) = kq1;
+                *reinterpret_cast<u32x4*>(nb + 4096 + my_ofs) = vq1;
+                kq1 = kq2;
+                vq1 = vq2;
             }
             __syncthreads();  // tile t+1 is staged, and everyone is done reading tile t
         }

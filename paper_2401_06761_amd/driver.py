@@ -116,3 +116,143 @@ class TreeRun:
 
     def close(self) -> None:
         self.pool.close()
+
+
+class SpecRun:
+    """The speculative (multi-candidate) decode loop on one pool.
+
+    Per step, in the order the step plan fixes: multi-candidate attention over all live threads,
+    append of each thread's accepted candidate rows, release of the threads that finish, fork of the
+    survivors that spawn a child (the child receives one row).  Sized from a dry run of the same
+    plan on a bookkeeping-only pool, so the pool holds exactly the peak the trace needs (+ slack).
+    """
+
+    TAG_CQ, TAG_CK, TAG_CV, TAG_CHILD_K, TAG_CHILD_V = 11, 12, 13, 14, 15
+
+    def __init__(self, w: Workload, n_steps: int, n_cand: int = 5, p_fork: float = 0.02, p_finish: float = 0.01,
+                 device: str = "cuda:0", fixed_bank: bool = True):
+        import torch
+
+        from apar_workloads import SpecLoopPlan
+
+        self.torch = torch
+        self.w, self.n_steps, self.C, self.device = w, n_steps, n_cand, device
+        self.p_fork, self.p_finish = p_fork, p_finish
+        self.fixed_bank = fixed_bank
+        self._Plan = SpecLoopPlan
+        hd = w.heads
+        # dry run: same ops, no device memory
+        ops, live, live_nodes = build_trace(w)
+        dry = ap.Pool(hd.n_q_heads, hd.n_kv_heads, hd.head_dim, hd.dtype, 1 << 22, max_threads=1 << 30, dry_run=True)
+        for op in ops:
+            if op.kind == "create":
+                ap.apar_thread_create(dry.handle)
+            elif op.kind == "append":
+                ap.apar_append_kv(dry.handle, op.tid, None, None, op.n_tokens)
+            elif op.kind == "fork":
+                ap.apar_fork(dry.handle, op.tid, len(op.children))
+            else:
+                ap.apar_free_thread(dry.handle, op.tid)
+        plan = SpecLoopPlan(list(live), len(w.nodes), w.seed, n_cand, p_fork, p_finish)
+        peak_blocks = ap.apar_pool_stats(dry.handle).used_blocks
+        peak_threads = len(live)
+        for _ in range(n_steps):
+            st = plan.next_step()
+            ids = np.repeat(np.asarray(st.live, dtype=np.int32), st.accept_bits.sum(axis=1))
+            ap.apar_append_kv_batch(dry.handle, ids, None, None)
+            peak_blocks = max(peak_blocks, ap.apar_pool_stats(dry.handle).used_blocks)  # before the releases
+            for t in st.finished:
+                ap.apar_free_thread(dry.handle, t)
+            for t in st.forked:
+                ap.apar_fork(dry.handle, t, 1)
+            if st.children:
+                ap.apar_append_kv_batch(dry.handle, st.children, None, None)
+            peak_blocks = max(peak_blocks, ap.apar_pool_stats(dry.handle).used_blocks)
+            peak_threads = max(peak_threads, len(plan.live), len(st.live))
+        self.threads_issued = ap.apar_pool_stats(dry.handle).threads_issued
+        dry.close()
+        self.peak_blocks, self.peak_threads = int(peak_blocks), int(peak_threads)
+        self.pool = ap.Pool(hd.n_q_heads, hd.n_kv_heads, hd.head_dim, hd.dtype, self.peak_blocks + 64,
+                            max_threads=self.threads_issued + 16, device=device)
+        self.h = self.pool.handle
+        self.live: List[int] = []
+        self.plan = None
+        self.step_no = 0
+        self.bank = None
+        self.out = None
+
+    def build(self) -> None:
+        w, h, hd = self.w, self.h, self.w.heads
+        ops, live, _ = build_trace(w)
+        for op in ops:
+            if op.kind == "create":
+                assert ap.apar_thread_create(h) == op.tid
+            elif op.kind == "append":
+                k, v = node_kv_device(w, op.node, self.device)
+                ap.apar_append_kv(h, op.tid, k, v, op.n_tokens)
+            elif op.kind == "fork":
+                assert tuple(ap.apar_fork(h, op.tid, len(op.children))) == op.children
+            else:
+                ap.apar_free_thread(h, op.tid)
+        self.live = list(live)
+        self.plan = self._Plan(list(live), len(w.nodes), w.seed, self.C, self.p_fork, self.p_finish)
+        n = self.peak_threads
+        if self.fixed_bank:
+            self.bank = self.candidates_for(-1, n)
+            self.child_bank = self.child_rows_for(-1, n)
+        self.out = self.torch.empty((n, self.C, hd.n_q_heads, hd.head_dim), dtype=self.pool.torch_dtype,
+                                    device=self.device)
+        self.torch.cuda.synchronize()
+
+    # seeded inputs of one step (index -1: the bank shared by all steps of a timing run)
+    def candidates_for(self, step: int, n: int):
+        hd, C = self.w.heads, self.C
+        return (rows_device(self.w, self.TAG_CQ, step + 1, (n, C, hd.n_q_heads, hd.head_dim), self.device),
+                rows_device(self.w, self.TAG_CK, step + 1, (n, C, hd.n_kv_heads, hd.head_dim), self.device),
+                rows_device(self.w, self.TAG_CV, step + 1, (n, C, hd.n_kv_heads, hd.head_dim), self.device))
+
+    def child_rows_for(self, step: int, n: int):
+        hd = self.w.heads
+        return (rows_device(self.w, self.TAG_CHILD_K, step + 1, (n, hd.n_kv_heads, hd.head_dim), self.device),
+                rows_device(self.w, self.TAG_CHILD_V, step + 1, (n, hd.n_kv_heads, hd.head_dim), self.device))
+
+    def step(self):
+        """One loop iteration; returns (step plan, q, cand_k, cand_v, out view, child k, child v)."""
+        torch, h, C = self.torch, self.h, self.C
+        st = self.plan.next_step()
+        n = len(st.live)
+        if self.fixed_bank:
+            q, ck, cv = (x[:n] for x in self.bank)
+        else:
+            q, ck, cv = self.candidates_for(st.step, n)
+        ids = np.asarray(st.live, dtype=np.int32)
+        masks = torch.from_numpy(st.masks).to(self.device, non_blocking=True)
+        out = self.out[:n]
+        ap.apar_decode_attention_spec(h, q, ck, cv, masks, C, ids, out)
+        # accepted rows, thread by thread, each chain root -> accepted node
+        counts = st.accept_bits.sum(axis=1)
+        rep_ids = np.repeat(ids, counts)
+        flat = np.flatnonzero(st.accept_bits.reshape(-1)).astype(np.int64)  # i * C + c, thread-major
+        idx = torch.from_numpy(flat).to(self.device, non_blocking=True)
+        hd = self.w.heads
+        k_acc = ck.reshape(n * C, hd.n_kv_heads, hd.head_dim).index_select(0, idx)
+        v_acc = cv.reshape(n * C, hd.n_kv_heads, hd.head_dim).index_select(0, idx)
+        ap.apar_append_kv_batch(h, rep_ids, k_acc, v_acc)
+        for t in st.finished:
+            ap.apar_free_thread(h, t)
+        kk = vv = None
+        if st.forked:
+            for t, child in zip(st.forked, st.children):
+                assert ap.apar_fork(h, t, 1) == [child]
+            m = len(st.children)
+            if self.fixed_bank:
+                kk, vv = (x[:m] for x in self.child_bank)
+            else:
+                kk, vv = self.child_rows_for(st.step, m)
+            ap.apar_append_kv_batch(h, np.asarray(st.children, dtype=np.int32), kk, vv)
+        self.live = list(self.plan.live)
+        self.step_no += 1
+        return st, q, ck, cv, out, kk, vv
+
+    def close(self) -> None:
+        self.pool.close()

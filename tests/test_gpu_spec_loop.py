@@ -1,0 +1,77 @@
+"""The speculative decode loop (multi-candidate attention + accepted-row appends + fork/release churn)
+against the oracle, through the same driver the benchmark uses (GPU only)."""
+import numpy as np
+import pytest
+
+import paper_2401_06761_amd as ap
+from apar_workloads import build_trace, make_config, node_kv_device
+from oracle import BlockLedger, DenseThreads
+from paper_2401_06761_amd.driver import SpecRun
+
+from harness import books_equal
+
+pytestmark = pytest.mark.gpu
+
+
+def _f64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("n_req,n_steps,p_fork,p_finish", [(4, 12, 0.10, 0.06), (8, 4, 0.02, 0.01)])
+def test_spec_loop_matches_oracle_every_step(n_req, n_steps, p_fork, p_finish):
+    import torch
+
+    w = make_config("spec128", n_requests=n_req)
+    hd = w.heads
+    run = SpecRun(w, n_steps, n_cand=5, p_fork=p_fork, p_finish=p_finish, fixed_bank=False)
+    try:
+        run.build()
+        led = BlockLedger(run.peak_blocks + 64)
+        dense = DenseThreads(hd.n_q_heads, hd.n_kv_heads, hd.head_dim)
+        ops, live, _ = build_trace(w)
+        for op in ops:
+            if op.kind == "create":
+                led.create(), dense.create()
+            elif op.kind == "append":
+                k, v = node_kv_device(w, op.node)
+                led.append(op.tid, op.n_tokens)
+                dense.append(op.tid, _f64(k), _f64(v))
+            elif op.kind == "fork":
+                led.fork(op.tid, len(op.children)), dense.fork(op.tid, len(op.children))
+            else:
+                led.free(op.tid), dense.free(op.tid)
+        books_equal(run.h, led)
+        peak = led.used_blocks()
+        worst = 0.0
+        for s in range(n_steps):
+            st, q, ck, cv, out, kk, vv = run.step()
+            torch.cuda.synchronize()
+            qh, ckh, cvh = _f64(q), _f64(ck), _f64(cv)
+            want = dense.decode_spec(qh, ckh, cvh, st.masks, st.live)
+            err = float(np.abs(_f64(out) - want).max())
+            worst = max(worst, err)
+            assert err <= 2e-2, f"step {s}: max abs err {err}"
+            # the same bookkeeping on the oracle side
+            ids = [t for t, chain in zip(st.live, st.accepted) for _ in chain]
+            led.append_batch(ids)
+            peak = max(peak, led.used_blocks())
+            for i, (t, chain) in enumerate(zip(st.live, st.accepted)):
+                dense.append(t, ckh[i, chain], cvh[i, chain])
+            for t in st.finished:
+                led.free(t), dense.free(t)
+            for t, child in zip(st.forked, st.children):
+                assert led.fork(t, 1) == [child] == dense.fork(t, 1)
+            if st.children:
+                led.append_batch(st.children)
+                kh, vh = _f64(kk), _f64(vv)
+                for i, child in enumerate(st.children):
+                    dense.append(child, kh[i:i + 1], vh[i:i + 1])
+            books_equal(run.h, led)
+            peak = max(peak, led.used_blocks())
+            assert sorted(run.live) == led.live()
+        led.check_invariants()
+        assert peak == run.peak_blocks  # the dry run predicted the peak exactly
+        print(f"spec loop {n_req} requests x {n_steps} steps: worst max abs err {worst:.2e}, "
+              f"{len(run.live)} live threads at the end, peak {peak} blocks")
+    finally:
+        run.close()
