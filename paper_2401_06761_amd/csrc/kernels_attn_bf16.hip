@@ -207,8 +207,14 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
         u32x4 kq1, vq1, kq2 = u32x4{0u, 0u, 0u, 0u}, vq2 = u32x4{0u, 0u, 0u, 0u};
         auto fetch = [&](int t, u32x4& kq, u32x4& vq) {
             const char* tile = head_base + coop[t].blk * block_stride;
-            kq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + my_ofs));
-            vq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + my_ofs));
+            // an open block is row-major: this lane's pieces belong to token row 4*wave + g4; rows past the
+            // fill count are not fetched at all
+            if (4 * wave + g4 < (coop[t].meta >> 16)) {
+                kq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + my_ofs));
+                vq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + my_ofs));
+            } else {
+                kq = vq = u32x4{0u, 0u, 0u, 0u};
+            }
         };
         fetch(0, kq1, vq1);
         if (n_coop > 1) fetch(1, kq2, vq2);
@@ -259,23 +265,34 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
     // apart inside the lane's own 64 bytes of its token's row.  The V half is fetched raw either way.
     Frag k[4], v[4];
     const int k_sealed = lane * 16, k_open = c * 256 + g4 * 64;
-    auto issue_k = [&](const char* tile, bool open) {
+    // Only the filled rows of an open tile are fetched (valid = 16 for sealed tiles: everything is).
+    auto issue_k = [&](const char* tile, int valid) {
+        const bool open = valid < 16;
         const char* p = tile + (open ? k_open : k_sealed);
         const int step = open ? 16 : 1024;
+        if (!open || c < valid) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) k[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + r * step));
+            for (int r = 0; r < 4; ++r)
+                k[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + r * step));
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) k[r].u = u32x4{0u, 0u, 0u, 0u};
+        }
     };
-    auto issue_v = [&](const char* tile) {
+    auto issue_v = [&](const char* tile, int valid) {
         const u32x4* p = reinterpret_cast<const u32x4*>(tile + 4096) + lane;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(p + r * 64);
+        for (int r = 0; r < 4; ++r) {  // raw piece r of this lane is part of token row 4r + g4 when the tile is open
+            if (valid == 16 || 4 * r + g4 < valid) v[r].u = __builtin_nontemporal_load(p + r * 64);
+            else v[r].u = u32x4{0u, 0u, 0u, 0u};
+        }
     };
     int meta = 16 << 16;
     if (wi.n_tiles > 0) {  // (nothing before this point waits on memory when the group has no shared tiles)
         meta = mine[0].meta;
         const char* t0 = head_base + mine[0].blk * block_stride;
-        issue_k(t0, (meta >> 16) < 16);
-        issue_v(t0);
+        issue_k(t0, meta >> 16);
+        issue_v(t0, meta >> 16);
     }
     char* scratch = lds + wave * kOpenScratch;
     for (int t = 0; t < wi.n_tiles; ++t) {
@@ -289,7 +306,7 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
         }
         float sv[4];
         scores(k, st, scale_log2e, valid, my_j >= lo && my_j < hi, g4, sv);
-        if (more) issue_k(tn, (meta_n >> 16) < 16);  // K registers are free again
+        if (more) issue_k(tn, meta_n >> 16);  // K registers are free again
         if (valid < 16) {
             // open block: its V half arrived row-major; turn it into operand order through LDS
 #pragma unroll
@@ -302,7 +319,7 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             __builtin_amdgcn_wave_barrier();
         }
         accumulate(v, st, sv, valid, g4);
-        if (more) issue_v(tn);
+        if (more) issue_v(tn, meta_n >> 16);
         meta = meta_n;
     }
 
