@@ -74,7 +74,7 @@ def cpu_baseline(w_name: str, seed: int, n_req: int, device: str):
 
 def read_traffic(workload: str):
     """HBM bytes per launch of the attention kernel from the committed rocprofv3 counter summary."""
-    path = os.path.join(ROOT, "profiles", f"attention_partial_{workload}_pmc.txt")
+    path = os.path.join(ROOT, "profiles", f"attention_bf16_{workload}_pmc.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
@@ -155,7 +155,7 @@ def main() -> int:
     ap_.add_argument("--requests", type=int, default=None, help="first n requests only (debugging)")
     ap_.add_argument("--chunk", type=int, default=None, help="blocks per work unit")
     ap_.add_argument("--churn", type=float, default=0.01)
-    ap_.add_argument("--cpu-requests", type=int, default=16)
+    ap_.add_argument("--cpu-requests", type=int, default=64)
     ap_.add_argument("--no-cpu-baseline", action="store_true")
     ap_.add_argument("--copy-calibration", action="store_true",
                      help="also run one plain 4 GiB device copy (reference for HBM byte counters)")
@@ -249,7 +249,7 @@ def main() -> int:
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "attention_partial_bf16 (its 1-, 2- and 4-row-tile instantiations, launched back to back)",
+            "kernel": "attention_bf16",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
