@@ -112,7 +112,8 @@ hipError_t launch_seal_blocks(const Shape& s, void* pool, const int32_t* blocks,
 hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src_codes, int n_rows, void* k_out,
                             void* v_out, hipStream_t st);
 hipError_t launch_attention_partial(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
-                                    PartialBuf part, void* out, hipStream_t st);
+                                    PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
+                                    void* out, hipStream_t st);
 hipError_t launch_merge(const Shape& s, const PlanDev& plan, PartialBuf part, const void* q, const void* cand_k,
                         const void* cand_v, const uint8_t* mask, int n_cand, void* out, hipStream_t st);
 

@@ -235,7 +235,7 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     PlanParams prm;
     prm.rows_per_thread = n_cand * p->shape.group;
     prm.max_unit_tiles = p->max_unit_tiles;
-    prm.allow_direct = !spec;  // the merge kernel is where candidates are folded in
+    prm.allow_direct = true;
     prm.fuse = true;
     int rc = build_plan(p->views.data(), n, p->ref.data(), p->seg_of.data(), prm, ph);
     if (rc != APAR_OK) return rc;
@@ -311,9 +311,9 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
             return rc;
         HIP_TRY(hipEventRecord(ev.a, st));
     }
-    HIP_TRY(launch_attention_partial(p->shape, p->kv, q, pd, n_cand, p->part, out, st));
+    HIP_TRY(launch_attention_partial(p->shape, p->kv, q, pd, n_cand, p->part, cand_k, cand_v, mask, out, st));
     if (p->profiling) HIP_TRY(hipEventRecord(ev.b, st));
-    if (ph.any_partial || spec)
+    if (ph.any_partial)
         HIP_TRY(launch_merge(p->shape, pd, p->part, q, cand_k, cand_v, mask, n_cand, out, st));
     if (p->profiling) {
         HIP_TRY(hipEventRecord(ev.c, st));

@@ -75,14 +75,16 @@ struct RowState {
     float m, l;
 };
 
-// S^T = K.Q^T for one tile in base-2 logits; rows outside [lo, hi) and slots >= valid get -inf.
-__device__ __forceinline__ void scores(const Frag (&k)[4], const RowState& st, float scale_log2e, int valid,
-                                       bool row_on, int g4, float (&sv)[4]) {
+// S^T = K.Q^T for one tile in base-2 logits; token slots whose bit is clear in tok_mask get -inf
+// (tok_mask is per lane, i.e. per query row: 0 for a row the tile does not apply to).
+__device__ __forceinline__ void scores(const Frag (&k)[4], const RowState& st, float scale_log2e, uint32_t tok_mask,
+                                       int g4, float (&sv)[4]) {
     f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[kk].b8, st.q[kk].b8, s, 0, 0, 0);
+    const uint32_t mine = tok_mask >> (4 * g4);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) sv[i] = (row_on && 4 * g4 + i < valid) ? s[i] * scale_log2e : -INFINITY;
+    for (int i = 0; i < 4; ++i) sv[i] = ((mine >> i) & 1u) ? s[i] * scale_log2e : -INFINITY;
 }
 
 // Online softmax step and O^T += V^T.P^T for one tile.
@@ -155,6 +157,9 @@ constexpr int kOpenScratch = 16 * kOpenRowStride;   // one wavefront's row-major
 __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ pool, const uint16_t* __restrict__ q,
                                                       PlanDev plan, int n_cand, int n_q, int n_kv, int group,
                                                       float scale_log2e, PartialBuf part,
+                                                      const uint16_t* __restrict__ cand_k,
+                                                      const uint16_t* __restrict__ cand_v,
+                                                      const uint8_t* __restrict__ cand_mask,
                                                       uint16_t* __restrict__ out) {
     // two staged tiles during the shared phase; then one V-transpose scratch per wavefront; last, three
     // wavefronts' row states when a unit is split
@@ -245,7 +250,7 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
                     v_operands_from_rows(sb + 4096, 256, g4, c, vs);
                 }
                 float sv[4];
-                scores(ks, st, scale_log2e, valid, my_jc >= lo && my_jc < hi, g4, sv);
+                scores(ks, st, scale_log2e, (my_jc >= lo && my_jc < hi) ? (1u << valid) - 1u : 0u, g4, sv);
                 accumulate(vs, st, sv, valid, g4);
             }
             if (more) {
@@ -305,7 +310,7 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             meta_n = mine[t + 1].meta;
         }
         float sv[4];
-        scores(k, st, scale_log2e, valid, my_j >= lo && my_j < hi, g4, sv);
+        scores(k, st, scale_log2e, (my_j >= lo && my_j < hi) ? (1u << valid) - 1u : 0u, g4, sv);
         if (more) issue_k(tn, meta_n >> 16);  // K registers are free again
         if (valid < 16) {
             // open block: its V half arrived row-major; turn it into operand order through LDS
@@ -324,11 +329,11 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
     }
 
     // ---- results ------------------------------------------------------------------------------
-    float lt = st.l;
-    lt += __shfl_xor(lt, 16, 64);
-    lt += __shfl_xor(lt, 32, 64);
     if (wi.flags & kWaveSplit) {
         // the four wavefronts hold the same rows over different tiles: fold 1..3 into 0 through LDS
+        float lt = st.l;
+        lt += __shfl_xor(lt, 16, 64);
+        lt += __shfl_xor(lt, 32, 64);
         float* so = reinterpret_cast<float*>(lds);           // [3][16 rows][128]
         float* sml = so + 3 * 16 * 128;                       // [3][16 rows][2]
         __syncthreads();  // every wavefront is done with its transpose scratch, which this area overlaps
@@ -364,7 +369,46 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             for (int jj = 0; jj < 8; ++jj) st.o[jj] += aw * *reinterpret_cast<const f32x4*>(src + 16 * jj);
         }
         st.m = mx;
+        st.l = g4 == 0 ? lt : 0.0f;  // back to one share per lane: the four lanes of a row add up to the sum
+        __builtin_amdgcn_wave_barrier();
     }
+
+    if ((wi.flags & kWaveDirect) && cand_mask != nullptr) {
+        // Multi-candidate call: each thread's candidates are one more tile of at most 8 token rows
+        // (row-major, a row every n_kv * 128 elements), visible to a row only where its mask bit is set.
+        const int rank_lo = wi.grp_lo / n_sl, rank_hi = (wi.grp_lo + wi.n_grp - 1) / n_sl;
+        const int cc_row = row_ok ? rr / group : 0;
+        const int64_t tok_stride = (int64_t)n_kv * 256;  // bytes between candidate rows of one kv head
+        for (int ru = rank_lo; ru <= rank_hi; ++ru) {
+            const int listed_u = plan.dfs_threads[ru];
+            const int64_t base = ((int64_t)listed_u * n_cand * n_kv + kvh) * 256;
+            const char* kb = reinterpret_cast<const char*>(cand_k) + base;
+            const char* vb = reinterpret_cast<const char*>(cand_v) + base;
+            Frag kc[4], vc[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                kc[r].u = u32x4{0u, 0u, 0u, 0u};
+                if (c < n_cand) kc[r].u = *reinterpret_cast<const u32x4*>(kb + c * tok_stride + g4 * 64 + r * 16);
+                u32x4 vr = u32x4{0u, 0u, 0u, 0u};
+                if (4 * r + g4 < n_cand) vr = *reinterpret_cast<const u32x4*>(vb + (4 * r + g4) * tok_stride + c * 16);
+                *reinterpret_cast<u32x4*>(scratch + (4 * r + g4) * kOpenRowStride + c * 16) = vr;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            v_operands_from_rows(scratch, kOpenRowStride, g4, c, vc);
+            __builtin_amdgcn_wave_barrier();
+            uint32_t tm = 0;
+            if (row_ok && rank == ru) tm = cand_mask[(int64_t)listed_u * n_cand + cc_row];
+            float sv[4];
+            scores(kc, st, scale_log2e, tm, g4, sv);
+            accumulate(vc, st, sv, n_cand, g4);
+        }
+    }
+
+    float lt = st.l;
+    lt += __shfl_xor(lt, 16, 64);
+    lt += __shfl_xor(lt, 32, 64);
     if (!row_ok) return;
     if (wi.flags & kWaveDirect) {
         // the row's whole root path was covered here: normalise and write the output row
@@ -392,12 +436,14 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
 }  // namespace
 
 hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
-                                 PartialBuf part, void* out, hipStream_t st) {
+                                 PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
+                                 void* out, hipStream_t st) {
     const int64_t n_wg = (int64_t)plan.n_wg * s.n_kv;
     if (n_wg <= 0) return hipSuccess;
     if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attention_bf16, dim3((unsigned)n_wg), dim3(256), 0, st, (const char*)pool, (const uint16_t*)q,
-                       plan, n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part, (uint16_t*)out);
+                       plan, n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part, (const uint16_t*)cand_k,
+                       (const uint16_t*)cand_v, mask, (uint16_t*)out);
     return hipGetLastError();
 }
 

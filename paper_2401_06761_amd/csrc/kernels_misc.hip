@@ -142,6 +142,9 @@ template <int D>
 __global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ pool, const float* __restrict__ q,
                                                     PlanDev plan, int n_cand, int n_q, int n_kv, int group,
                                                     float scale_log2e, int64_t tile_bytes, PartialBuf part,
+                                                    const float* __restrict__ cand_k,
+                                                    const float* __restrict__ cand_v,
+                                                    const uint8_t* __restrict__ cand_mask,
                                                     float* __restrict__ out) {
     constexpr int E = D / 64;
     const int lane = threadIdx.x;
@@ -190,6 +193,23 @@ __global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ poo
         }
     }
     if (wi.flags & kWaveDirect) {
+        if (cand_mask != nullptr) {  // multi-candidate call: the candidates this row may see
+            const uint32_t bits = cand_mask[(int64_t)listed * n_cand + cc];
+            for (int cp = 0; cp < n_cand; ++cp) {
+                if (!((bits >> cp) & 1u)) continue;
+                const int64_t base = (((int64_t)listed * n_cand + cp) * n_kv + kvh) * D;
+                float dot = 0.0f;
+#pragma unroll
+                for (int e = 0; e < E; ++e) dot += qv[e] * cand_k[base + lane + 64 * e];
+                const float sc = wave_sum(dot) * scale_log2e;
+                const float m_new = fmaxf(m, sc);
+                const float alpha = exp2f(m - m_new), pr = exp2f(sc - m_new);
+                l = l * alpha + pr;
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[e] = acc[e] * alpha + pr * cand_v[base + lane + 64 * e];
+                m = m_new;
+            }
+        }
         const float inv = 1.0f / l;
 #pragma unroll
         for (int e = 0; e < E; ++e) out[qrow * D + lane + 64 * e] = acc[e] * inv;
@@ -219,7 +239,7 @@ __global__ __launch_bounds__(64) void merge_rows(PlanDev plan, PartialBuf part, 
     const int lane = threadIdx.x;
     const int hq = blockIdx.x, c = blockIdx.y, i = blockIdx.z;
     const int p0 = plan.path_ofs[i], p1 = plan.path_ofs[i + 1];
-    if (p0 == p1 && mask == nullptr) return;  // the attention kernel wrote this thread's rows itself
+    if (p0 == p1) return;  // the attention kernel wrote this thread's rows itself (candidates included)
     float m = -INFINITY;
     for (int p = p0; p < p1; ++p) {
         const int64_t slot = ((int64_t)plan.path_ids[p] * n_cand + c) * n_q + hq;
@@ -281,7 +301,8 @@ __global__ __launch_bounds__(64) void merge_rows(PlanDev plan, PartialBuf part, 
 }  // namespace
 
 hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
-                                 PartialBuf part, void* out, hipStream_t st);
+                                 PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
+                                 void* out, hipStream_t st);
 
 hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const void* v, const int32_t* dst_codes,
                               int n_rows, hipStream_t st) {
@@ -338,16 +359,20 @@ hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src
 }
 
 hipError_t launch_attention_partial(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
-                                    PartialBuf part, void* out, hipStream_t st) {
+                                    PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
+                                    void* out, hipStream_t st) {
     if (plan.n_wg <= 0) return hipSuccess;
-    if (s.dtype == APAR_BF16) return launch_attention_bf16(s, pool, q, plan, n_cand, part, out, st);
+    if (s.dtype == APAR_BF16)
+        return launch_attention_bf16(s, pool, q, plan, n_cand, part, cand_k, cand_v, mask, out, st);
     dim3 grid(plan.n_wg, s.n_kv, 64);
     if (s.d == 64)
         hipLaunchKernelGGL(attention_f32<64>, grid, dim3(64), 0, st, (const char*)pool, (const float*)q, plan, n_cand,
-                           s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part, (float*)out);
+                           s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part, (const float*)cand_k,
+                           (const float*)cand_v, mask, (float*)out);
     else
         hipLaunchKernelGGL(attention_f32<128>, grid, dim3(64), 0, st, (const char*)pool, (const float*)q, plan, n_cand,
-                           s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part, (float*)out);
+                           s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part, (const float*)cand_k,
+                           (const float*)cand_v, mask, (float*)out);
     return hipGetLastError();
 }
 

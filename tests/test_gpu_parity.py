@@ -229,14 +229,18 @@ def test_parent_that_keeps_decoding_after_a_fork():
         led.check_invariants()
 
 
-@pytest.mark.parametrize("dtype,d,C", [("f32", 64, 5), ("f32", 128, 1), ("bf16", 128, 5), ("bf16", 128, 3)])
-def test_multi_candidate_step(dtype, d, C):
+@pytest.mark.parametrize("chunk", [None, 2])
+@pytest.mark.parametrize("dtype,d,C", [("f32", 64, 5), ("f32", 128, 1), ("bf16", 128, 5), ("bf16", 128, 3),
+                                       ("bf16", 128, 8)])
+def test_multi_candidate_step(dtype, d, C, chunk):
     t = torch()
     heads = HeadConfig(4, 2, d, dtype)
     w = manual_tree([-1, 0, 0, 2, 2, -1], [30, 16, 9, 1, 25, 3], heads, seed=9, data_scale=0.7)
     N = blocks_upper_bound(w)
     with pool_for(w, N) as pool:
         poison(pool)
+        if chunk:  # small units: partial results and the merge kernel fold the candidates instead
+            ap.apar_set_chunk_blocks(pool.handle, chunk)
         dense = DenseThreads(4, 2, d)
         live, _ = replay_trace(w, pool, None, dense)
         n = len(live)
