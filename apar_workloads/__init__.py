@@ -29,3 +29,4 @@ from .data import (  # noqa: F401
     rows_device,
 )
 from .spec_loop import SpecLoopPlan, SpecStep, draw_candidate_tree, mask_rows_from_parents  # noqa: F401
+from .token_stream import TokenStream  # noqa: F401

@@ -224,6 +224,63 @@ APAR_API int apar_last_plan_export(apar_pool* pool, int which, int32_t* out, int
 APAR_API int apar_read_kv_rows(apar_pool* pool, apar_thread thread, int64_t first, int n, void* k_out_dev,
                       void* v_out_dev, void* hip_stream);
 
+/* ---- decoding controller (Alg. 1) ---------------------------------------
+ * One sequence group per prompt (Sec. 2.3).  The controller keeps each sequence's
+ * tokens, the paragraph tree (Sec. 2.2: a node points at a slice of a sequence and
+ * has a first-child and a next-sibling pointer) and applies one AparDecode step of
+ * Alg. 1 to the tokens the caller sampled.  It samples nothing and runs no model:
+ * per step the caller lists the unfinished sequences (apar_group_unfinished), runs
+ * apar_decode_attention over them, draws one token per sequence and calls
+ * apar_group_step.  Token ids >= 0 are ordinary tokens. */
+typedef struct apar_group apar_group;
+enum { APAR_TOKEN_FORK = -1, APAR_TOKEN_CHILD = -2, APAR_TOKEN_EOS = -3 };
+
+typedef struct apar_group_step_info {
+    int32_t n_forked;        /* sequences whose last token was [Fork]: each spawned one child      */
+    int32_t n_finished;      /* sequences that sampled [EOS] and were released                     */
+    int32_t n_rows_appended; /* K,V rows consumed from k_dev / v_dev                               */
+    int32_t n_unfinished;    /* unfinished sequences after the step (children included)            */
+} apar_group_step_info;
+
+typedef struct apar_group_info {
+    int64_t n_sequences, n_unfinished, n_nodes, steps;
+    int64_t prompt_tokens;
+    int64_t generated_tokens;  /* sampled tokens (injected [Child] tokens not counted)              */
+    int64_t attended_tokens;   /* sum over sampled tokens of the tokens attended to when predicting */
+                               /* them (Sec. 3.4 "Attended tokens")                                 */
+    int64_t cached_tokens;     /* KV slots needed now, in tokens: shared prefixes once, released    */
+                               /* sequences only as far as a live thread still shares them          */
+    int64_t max_cached_tokens; /* maximum of cached_tokens over the steps so far (Sec. 3.4)         */
+} apar_group_info;
+
+/* Starts a group: a root sequence holding the prompt (n_prompt >= 1 rows in k_dev, v_dev:
+ * [n_prompt, Hkv, d]) and the root paragraph node r = PNode(p, p.len).  Errors as
+ * apar_thread_create and apar_append_kv; nothing is left behind on failure. */
+APAR_API int apar_group_create(apar_pool* pool, const int32_t* prompt_tokens, int n_prompt, const void* k_dev,
+                               const void* v_dev, void* hip_stream, apar_group** out);
+/* Releases the sequences that are still unfinished and frees the group.  NULL is accepted. */
+APAR_API int apar_group_destroy(apar_group* group);
+/* Thread ids of the unfinished sequences, in creation order; n_out is always set. */
+APAR_API int apar_group_unfinished(apar_group* group, apar_thread* threads_out, int cap, int* n_out);
+/*
+ * One AparDecode step (Alg. 1).  sampled[i] is the token drawn for the i-th unfinished sequence s
+ * (the order of apar_group_unfinished; n must equal their number).  For each s in order: if
+ * s.last_token is [Fork], s is forked (s' <- s), [Child] is appended to s', two paragraph nodes
+ * are created and s's current node is closed with next_sibling / first_child set; then sampled[i]
+ * is appended to s; if it is [EOS], s is finished and its cache released.  A child joins the
+ * group's list from the next step on.  k_dev, v_dev: one row per appended token, in this order:
+ * for each s in order, the [Child] row of its new thread if it forks, then the row of sampled[i].
+ * Errors: INVALID_ARG (wrong n, a sampled [Child]), THREAD_CAPACITY, OUT_OF_BLOCKS, HIP; on error
+ * the group and the pool are unchanged.
+ */
+APAR_API int apar_group_step(apar_group* group, const int32_t* sampled, int n, const void* k_dev,
+                             const void* v_dev, void* hip_stream, apar_group_step_info* info_out);
+/* Restore(r) of Alg. 1: the generated tokens in root / first-child / next-sibling order
+ * (the prompt and the injected [Child] tokens are not part of any node).  n_out is always set;
+ * INVALID_ARG if cap is too small. */
+APAR_API int apar_group_restore(apar_group* group, int32_t* tokens_out, int64_t cap, int64_t* n_out);
+APAR_API int apar_group_get_info(apar_group* group, apar_group_info* out);
+
 /* ---- measurement -------------------------------------------------------- */
 /* While on, every decode and append call brackets its kernels with HIP events. */
 APAR_API int apar_profile_enable(apar_pool* pool, int on);

@@ -9,9 +9,11 @@ Two independent halves:
                  plain softmax definition.  No blocks, tables or merges.
   * ledger.py  - bookkeeping: an integer-only replay of the allocator policy
                  (block tables, refcounts, free list, copy-on-write count).
+  * controller.py - Algorithm 1 (fork on [Fork], paragraph nodes, Restore) in plain Python.
   * accounting.py - the paper's max-cached-tokens / attended-tokens metrics and
                  the resident-vs-copied-prefix byte counts.
 """
 from .dense import DenseThreads, attend, attend_spec  # noqa: F401
 from .ledger import BlockLedger, OutOfBlocks, InvalidThread  # noqa: F401
 from . import accounting  # noqa: F401
+from . import controller  # noqa: F401

@@ -1,0 +1,114 @@
+"""Algorithm 1 of the APAR paper (decoding with paragraph nodes), plain Python.  TEST INFRASTRUCTURE.
+
+Sequences are private token lists (a fork deep-copies the parent's list, as in dense.py);
+paragraph nodes are objects with first_child / next_sibling pointers (Sec. 2.2 "Paragraph tree");
+one call of step() is one AparDecode of Alg. 1 over the unfinished sequences; restore() is
+Restore(r): root, then first child, then next sibling.  The two savings metrics of Sec. 3.4 are
+counted by brute force: attended tokens = length of the sequence a token was predicted from;
+cached tokens = number of distinct token identities reachable from the unfinished sequences
+(every token carries the identity (sequence that generated it, index), and a fork copies identities).
+
+Readings fixed here (the algorithm listing leaves them open): a child created in a step starts
+decoding in the next step; the prompt is not part of the restored output (the root node starts
+at p.len); the forced [Child] token lies before its node's start, so it is not restored either.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+FORK, CHILD, EOS = -1, -2, -3
+
+
+class PNode:
+    def __init__(self, seq: "Sequence_", start: int):
+        self.seq, self.start, self.end = seq, start, None
+        self.first_child: Optional["PNode"] = None
+        self.next_sibling: Optional["PNode"] = None
+
+
+class Sequence_:
+    def __init__(self, sid: int, tokens: List[int], idents: List[tuple]):
+        self.sid = sid
+        self.tokens = list(tokens)
+        self.idents = list(idents)
+        self.finished = False
+        self.current_node: Optional[PNode] = None
+
+    @property
+    def last_token(self) -> int:
+        return self.tokens[-1]
+
+    def append_token(self, x: int) -> None:
+        self.idents.append((self.sid, len(self.tokens)))
+        self.tokens.append(x)
+
+
+class SequenceGroup:
+    def __init__(self, prompt: List[int]):
+        p = Sequence_(0, [], [])
+        for x in prompt:
+            p.append_token(x)
+        self.root = PNode(p, len(p.tokens))
+        p.current_node = self.root
+        self.G: List[Sequence_] = [p]
+        self.attended = 0
+        self.generated = 0
+        self.max_cached = self.cached_tokens()
+
+    def unfinished(self) -> List[Sequence_]:
+        return [s for s in self.G if not s.finished]
+
+    def is_finished(self) -> bool:
+        return not self.unfinished()
+
+    def cached_tokens(self) -> int:
+        held = set()
+        for s in self.unfinished():
+            held.update(s.idents)
+        return len(held)
+
+    def step(self, sampled: List[int]) -> List[Sequence_]:
+        """One AparDecode.  Returns the sequences whose KV rows were appended, one entry per row, in
+        order ([Child] row of a new thread, then the sampled token's row of its parent)."""
+        todo = self.unfinished()
+        assert len(todo) == len(sampled)
+        rows: List[Sequence_] = []
+        for s, x in zip(todo, sampled):
+            assert x != CHILD
+            self.attended += len(s.tokens)
+            self.generated += 1
+            if s.last_token == FORK:
+                c = Sequence_(len(self.G), s.tokens, s.idents)
+                c.append_token(CHILD)
+                self.G.append(c)
+                rows.append(c)
+                n = PNode(s, len(s.tokens))
+                n2 = PNode(c, len(c.tokens))
+                s.current_node.end = len(s.tokens)
+                s.current_node.next_sibling = n
+                s.current_node.first_child = n2
+                s.current_node = n
+                c.current_node = n2
+            s.append_token(x)
+            rows.append(s)
+            if x == EOS:
+                s.finished = True
+        self.max_cached = max(self.max_cached, self.cached_tokens())
+        return rows
+
+    def restore(self) -> List[int]:
+        out: List[int] = []
+
+        def rec(node: Optional[PNode]) -> None:
+            if node is None:
+                return
+            end = len(node.seq.tokens) if node.end is None else node.end
+            out.extend(node.seq.tokens[node.start:end])
+            rec(node.first_child)
+            rec(node.next_sibling)
+
+        import sys
+
+        sys.setrecursionlimit(max(10000, sys.getrecursionlimit()))
+        rec(self.root)
+        return out

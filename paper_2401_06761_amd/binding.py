@@ -37,6 +37,19 @@ class AparPlanInfo(C.Structure):
                                          "unique_tokens", "path_tokens", "algorithmic_bytes")]
 
 
+class AparGroupStepInfo(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_forked", "n_finished", "n_rows_appended", "n_unfinished")]
+
+
+class AparGroupInfo(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("n_sequences", "n_unfinished", "n_nodes", "steps", "prompt_tokens",
+                                         "generated_tokens", "attended_tokens", "cached_tokens",
+                                         "max_cached_tokens")]
+
+
+APAR_TOKEN_FORK, APAR_TOKEN_CHILD, APAR_TOKEN_EOS = -1, -2, -3
+
+
 class AparProfile(C.Structure):
     _fields_ = [("n_decode_calls", C.c_int64), ("attention_kernel_ms", C.c_double), ("merge_kernel_ms", C.c_double),
                 ("plan_host_ms", C.c_double), ("n_append_calls", C.c_int64), ("append_kernels_ms", C.c_double)]
@@ -78,6 +91,12 @@ def _load() -> C.CDLL:
         "apar_profile_enable": [P, I],
         "apar_profile_read": [P, C.POINTER(AparProfile)],
         "apar_set_chunk_blocks": [P, I],
+        "apar_group_create": [P, I32P, I, V, V, V, C.POINTER(P)],
+        "apar_group_destroy": [P],
+        "apar_group_unfinished": [P, I32P, I, C.POINTER(C.c_int)],
+        "apar_group_step": [P, I32P, I, V, V, V, C.POINTER(AparGroupStepInfo)],
+        "apar_group_restore": [P, I32P, C.c_int64, C.POINTER(C.c_int64)],
+        "apar_group_get_info": [P, C.POINTER(AparGroupInfo)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -272,6 +291,46 @@ def apar_profile_read(pool) -> AparProfile:
 
 def apar_set_chunk_blocks(pool, blocks_per_unit: int) -> None:
     _check(_L().apar_set_chunk_blocks(pool, blocks_per_unit), "apar_set_chunk_blocks")
+
+
+def apar_group_create(pool, prompt_tokens: Sequence[int], k, v, stream=None) -> C.c_void_p:
+    arr, n = _ids(prompt_tokens)
+    out = C.c_void_p()
+    _check(_L().apar_group_create(pool, arr, n, _ptr(k), _ptr(v), _stream(stream), C.byref(out)), "apar_group_create")
+    return out
+
+
+def apar_group_destroy(group) -> None:
+    _check(_L().apar_group_destroy(group), "apar_group_destroy")
+
+
+def apar_group_unfinished(group) -> List[int]:
+    n = C.c_int()
+    _L().apar_group_unfinished(group, None, 0, C.byref(n))
+    buf = (C.c_int32 * max(n.value, 1))()
+    _check(_L().apar_group_unfinished(group, buf, n.value, C.byref(n)), "apar_group_unfinished")
+    return list(buf[: n.value])
+
+
+def apar_group_step(group, sampled: Sequence[int], k, v, stream=None) -> AparGroupStepInfo:
+    arr, n = _ids(sampled)
+    info = AparGroupStepInfo()
+    _check(_L().apar_group_step(group, arr, n, _ptr(k), _ptr(v), _stream(stream), C.byref(info)), "apar_group_step")
+    return info
+
+
+def apar_group_restore(group) -> List[int]:
+    n = C.c_int64()
+    _L().apar_group_restore(group, None, 0, C.byref(n))
+    buf = (C.c_int32 * max(n.value, 1))()
+    _check(_L().apar_group_restore(group, buf, n.value, C.byref(n)), "apar_group_restore")
+    return list(buf[: n.value])
+
+
+def apar_group_get_info(group) -> AparGroupInfo:
+    out = AparGroupInfo()
+    _check(_L().apar_group_get_info(group, C.byref(out)), "apar_group_get_info")
+    return out
 
 
 class Pool:
