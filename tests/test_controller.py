@@ -163,24 +163,28 @@ def test_golden_example_through_the_library():
 
 
 def test_step_that_does_not_fit_changes_nothing():
-    with ap.Pool(2, 2, 64, "f32", 2, dry_run=True) as pool:  # 32 token slots
-        grp = ap.apar_group_create(pool.handle, list(range(20)), None, None)
-        ap.apar_group_step(grp, [FORK], None, None)              # len 21
-        ap.apar_group_step(grp, [5], None, None)                 # fork: child copies the tail block -> 2 blocks used
-        assert ap.apar_pool_stats(pool.handle).free_blocks == 0
-        before = (ap.apar_group_restore(grp), ap.apar_group_unfinished(grp), ap.apar_pool_stats(pool.handle).cow_copies)
-        for _ in range(9):
-            ap.apar_group_step(grp, [FORK if _ == 8 else 1, 2], None, None)
-        # the root's block is now full; its next row needs a fresh block, and so does the fork
-        snap = (ap.apar_group_restore(grp), ap.apar_group_unfinished(grp), ap.apar_pool_stats(pool.handle).threads_issued)
-        with pytest.raises(ap.AparError) as ei:
+    with ap.Pool(2, 2, 64, "f32", 4, dry_run=True) as pool:  # 64 token slots
+        grp = ap.apar_group_create(pool.handle, list(range(20)), None, None)   # blocks 0, 1
+        ap.apar_group_step(grp, [FORK], None, None)              # root: 21 tokens
+        ap.apar_group_step(grp, [5], None, None)                 # fork: the child copies the shared tail -> block 2
+        assert ap.apar_pool_stats(pool.handle).free_blocks == 1
+        for i in range(9):
+            ap.apar_group_step(grp, [100 + i, 200 + i], None, None)
+        ap.apar_group_step(grp, [FORK, 7], None, None)           # both sequences now hold 32 tokens: full tails
+        snap = (ap.apar_group_restore(grp), ap.apar_group_unfinished(grp))
+        st0 = ap.apar_pool_stats(pool.handle)
+        with pytest.raises(ap.AparError) as ei:                  # a [Child] row and two rows at block boundaries
             ap.apar_group_step(grp, [3, 4], None, None)
         assert ei.value.status == -3
-        st = ap.apar_pool_stats(pool.handle)
-        assert (ap.apar_group_restore(grp), ap.apar_group_unfinished(grp)) == snap[:2]
-        assert st.live_threads == 2 and before[2] == 1
+        st1 = ap.apar_pool_stats(pool.handle)
+        assert (ap.apar_group_restore(grp), ap.apar_group_unfinished(grp)) == snap
+        assert (st1.free_blocks, st1.live_threads, st1.cow_copies) == (st0.free_blocks, st0.live_threads, st0.cow_copies)
+        assert st1.threads_issued == st0.threads_issued + 1      # ids are never reused, even after a rollback
+        for b in range(4):
+            assert ap.apar_block_refcount(pool.handle, b) == (2 if b == 0 else 1 if b < 3 else 0)
         with pytest.raises(ap.AparError):
             ap.apar_group_step(grp, [1], None, None)             # wrong count
         with pytest.raises(ap.AparError):
             ap.apar_group_step(grp, [CHILD, 1], None, None)      # [Child] is never sampled
         ap.apar_group_destroy(grp)
+        assert ap.apar_pool_stats(pool.handle).free_blocks == 4
