@@ -204,11 +204,12 @@ APAR_API int apar_last_plan_info(apar_pool* pool, apar_plan_info* out);
  * numbered depth-first along their sharing tree ("rank"); a thread's query rows are cut into
  * `slices` slices of at most 16 rows, and row group = rank * slices + slice.  `which`:
  *   APAR_PLAN_WORKGROUPS  32 ints per workgroup: [0] first shared tile, [1] shared tile count,
- *                         [2] row group the shared tiles' ranges are relative to, [3] unused, then
+ *                         [2] row group the shared tiles' ranges are relative to, [3] 16-row tiles per wavefront (1, 2 or 4;
+ *                         workgroups are stored in the order 4, 2, 1), then
  *                         4 wavefronts x 6: first own tile, own tile count, first row group, row
  *                         group count, first partial-result row (of the thread owning the first
  *                         row group), flags (bit 0: writes output rows directly); [28..31] unused;
- *   APAR_PLAN_TILES       2 ints per tile: block id, lo | hi << 8 | filled_slots << 16, where
+ *   APAR_PLAN_TILES       2 ints per tile: block id, lo | hi << 10 | filled_slots << 20, where
  *                         [lo, hi) are the row groups the block applies to, relative to the
  *                         wavefront's first row group (own tiles) or to [2] (shared tiles);
  *   APAR_PLAN_DFS_THREADS rank -> index into the listed threads;

@@ -47,12 +47,13 @@ __host__ __device__ inline int bf16_v_offset(int token, int dim) {  // byte offs
 // the threads that hold any given block are a contiguous range of ranks.  A
 // thread's query rows (candidates x q heads of one kv group) are cut into
 // `n_slices` slices of at most 16 rows; (thread, slice) is a "row group" with
-// index rank * n_slices + slice.  A wavefront holds up to 16 / rows_per_slice
-// consecutive row groups as the columns of its 16x16 tiles.
+// index rank * n_slices + slice.  A wavefront holds up to row_tiles * (16 / rows_per_slice)
+// consecutive row groups as the columns of its row_tiles 16x16 tiles (a row group
+// never straddles two tiles: group j of the wavefront sits in tile j / (16 / rows_per_slice)).
 // ---------------------------------------------------------------------------
 struct TileRef {     // one block to read, and the row groups it applies to
     int32_t blk;
-    int32_t meta;    // lo | hi << 8 | valid << 16: row groups [lo, hi) relative to the list owner's first
+    int32_t meta;    // lo | hi << 10 | valid << 20: row groups [lo, hi) relative to the list owner's first
                      // row group (the workgroup's for shared lists, the wavefront's for its own list);
                      // valid = filled token slots (1..16)
 };
@@ -71,7 +72,7 @@ constexpr int kSplitMinTiles = 16; // shorter private units are packed four to a
 struct WgDesc {      // one 256-thread workgroup: a shared tile list, then one private list per wavefront
     int32_t coop_ofs, n_coop;   // tiles every wavefront of the group sees (staged once through LDS)
     int32_t grp_base;           // row group that the shared list's ranges are relative to
-    int32_t pad;
+    int32_t row_tiles;          // 16-row tiles per wavefront: 1, 2 or 4
     WaveItem w[4];
     int32_t pad2[4];
 };
@@ -84,6 +85,7 @@ struct PlanDev {              // device pointers of one staged plan
     const int32_t* path_ofs;     // [n_threads + 1], by listed index
     const int32_t* path_ids;     // partial-result rows to merge for each listed thread (none: written directly)
     int32_t n_wg;
+    int32_t n_wg_class[3];       // workgroups with 4, 2 and 1 row tiles per wavefront, stored in that order
     int32_t n_threads;
     int32_t rows_per_thread, rows_per_slice, n_slices;
 };

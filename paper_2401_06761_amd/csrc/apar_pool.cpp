@@ -299,6 +299,8 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     pd.path_ofs = (const int32_t*)(s->dev + ofs[3]);
     pd.path_ids = (const int32_t*)(s->dev + ofs[4]);
     pd.n_wg = (int32_t)ph.wgs.size();
+    for (int k = 0; k < 3; ++k) pd.n_wg_class[k] = ph.n_wg_class[k];
+    if (pd.n_wg_class[0] + pd.n_wg_class[1] + pd.n_wg_class[2] != pd.n_wg) return APAR_ERR_INVALID_ARG;
     pd.n_threads = n;
     pd.rows_per_thread = p->plan_geom[0];
     pd.rows_per_slice = p->plan_geom[1];

@@ -12,7 +12,7 @@
 // S^T (lane = 16*g + c holds tokens 4g..4g+3 of row c) is already the
 // B-operand layout of P^T, so probabilities never move between lanes.
 //
-// A workgroup (4 wavefronts, 16 rows each) is given by the host plan
+// A workgroup (4 wavefronts, 16, 32 or 64 rows each) is given by the host plan
 //   * a shared tile list: blocks whose holders sit in more than one wavefront
 //     (prefixes shared by many sibling threads).  Each wavefront fetches a
 //     quarter of every tile, the tile is staged once in LDS (double buffered,
@@ -154,9 +154,11 @@ __device__ __forceinline__ void v_operands_from_rows(const char* vrows, int stri
 constexpr int kOpenRowStride = 264;                 // padded, so the four token groups hit different LDS banks
 constexpr int kOpenScratch = 16 * kOpenRowStride;   // one wavefront's row-major V half
 
-__global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ pool, const uint16_t* __restrict__ q,
-                                                      PlanDev plan, int n_cand, int n_q, int n_kv, int group,
-                                                      float scale_log2e, PartialBuf part,
+// NT = 16-row tiles per wavefront (1, 2 or 4): a workgroup carries up to 64 * NT query rows.
+template <int NT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3 : NT == 2 ? 2 : 1))) void attention_bf16(const char* __restrict__ pool, const uint16_t* __restrict__ q,
+                                                      PlanDev plan, int wg_first, int n_cand, int n_q, int n_kv,
+                                                      int group, float scale_log2e, PartialBuf part,
                                                       const uint16_t* __restrict__ cand_k,
                                                       const uint16_t* __restrict__ cand_v,
                                                       const uint8_t* __restrict__ cand_mask,
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int g4 = lane >> 4, c = lane & 15;
     const int kvh = blockIdx.x % n_kv;
-    const WgDesc* wg = plan.wgs + blockIdx.x / n_kv;
+    const WgDesc* wg = plan.wgs + wg_first + blockIdx.x / n_kv;
     const WaveItem wi = wg->w[wave];
     const int n_coop = wg->n_coop;
     const TileRef* coop = plan.tiles + wg->coop_ofs;
@@ -177,36 +179,58 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
     const char* head_base = pool + (int64_t)kvh * kTileBytes;
     const int64_t block_stride = (int64_t)n_kv * kTileBytes;
 
-    // Row geometry: column c of this wavefront is row `within` of row group grp_lo + j.
+    // Row geometry: column c of row tile nt is row `within` of the wavefront's row group nt * cap + c / rps.
     const int rps = plan.rows_per_slice, n_sl = plan.n_slices, rpt = plan.rows_per_thread;
-    const int j = c / rps, within = c - j * rps;
-    const int grp = wi.grp_lo + j;
-    const int rank = grp / n_sl, rr = (grp - rank * n_sl) * rps + within;
-    const bool row_ok = j < wi.n_grp && rr < rpt;
-    const int my_j = row_ok ? j : 0x7fff;  // never inside a tile's [lo, hi)
-    RowState st;
-    st.m = -INFINITY;
-    st.l = 0.0f;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) st.q[kk].u = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int jj = 0; jj < 8; ++jj) st.o[jj] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    int64_t qrow = -1, slot = -1;
-    if (row_ok) {
+    const int cap = 16 / rps;
+    const int jc = c / rps, within = c - jc * rps;
+    RowState st[NT];
+    int my_j[NT];       // row group of this lane's row, relative to the wavefront's first; 0x7fff: no row
+    // where the row of tile nt lives: depth-first rank of its thread, row within the thread's rows,
+    // q/output row and partial-result slot (recomputed where needed rather than kept in registers)
+    auto locate = [&](int nt, int& rank, int& rr, int64_t& qrow, int64_t& slot) {
+        const int grp = wi.grp_lo + nt * cap + jc;
+        rank = grp / n_sl;
+        rr = (grp - rank * n_sl) * rps + within;
         const int listed = plan.dfs_threads[rank];
         const int cc = rr / group, hq = kvh * group + (rr - cc * group);
         qrow = ((int64_t)listed * n_cand + cc) * n_q + hq;
         slot = ((int64_t)(wi.part_base + rank - wi.grp_lo / n_sl) * n_cand + cc) * n_q + hq;
-        const u32x4* qp = reinterpret_cast<const u32x4*>(q + qrow * 128 + g4 * 32);
+    };
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) st.q[kk].u = qp[kk];
+    for (int nt = 0; nt < NT; ++nt) {
+        const int j = nt * cap + jc;
+        const int grp = wi.grp_lo + j;
+        const int rank = grp / n_sl, rr = (grp - rank * n_sl) * rps + within;
+        const bool ok = jc < cap && j < wi.n_grp && rr < rpt;
+        my_j[nt] = ok ? j : 0x7fff;
+        st[nt].m = -INFINITY;
+        st[nt].l = 0.0f;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) st[nt].q[kk].u = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) st[nt].o[jj] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (ok) {
+            int rk, r2;
+            int64_t qrow, slot;
+            locate(nt, rk, r2, qrow, slot);
+            const u32x4* qp = reinterpret_cast<const u32x4*>(q + qrow * 128 + g4 * 32);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) st[nt].q[kk].u = qp[kk];
+        }
     }
+    // per-lane token mask of a tile that applies to row groups [lo, hi) of this wavefront
+    auto tok_mask = [&](int nt, int lo, int hi, int valid) -> uint32_t {
+        return (my_j[nt] >= lo && my_j[nt] < hi) ? (1u << valid) - 1u : 0u;
+    };
+    // does a tile touch row tile nt at all?  (wavefront-uniform)
+    auto touches = [&](int nt, int lo, int hi) -> bool {
+        return lo < min((nt + 1) * cap, wi.n_grp) && hi > nt * cap;
+    };
 
     // ---- shared tiles: staged once in LDS for the whole workgroup ---------------------------
     if (n_coop > 0) {
         const int my_ofs = wave * 1024 + lane * 16;  // this wavefront's quarter: K piece `wave`, V piece `wave`
         const int shift = wi.grp_lo - wg->grp_base;  // shared ranges are relative to the group's base
-        const int my_jc = row_ok ? j + shift : 0x7fff;
         // Two tiles are kept in flight: while tile t is consumed from LDS, tile t+1 sits in registers
         // (fetched an iteration ago) on its way into the other LDS buffer and tile t+2 is being fetched.
         u32x4 kq1, vq1, kq2 = u32x4{0u, 0u, 0u, 0u}, vq2 = u32x4{0u, 0u, 0u, 0u};
@@ -214,7 +238,7 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             const char* tile = head_base + coop[t].blk * block_stride;
             // an open block is row-major: this lane's pieces belong to token row 4*wave + g4; rows past the
             // fill count are not fetched at all
-            if (4 * wave + g4 < (coop[t].meta >> 16)) {
+            if (4 * wave + g4 < ((coop[t].meta >> 20) & 31)) {
                 kq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + my_ofs));
                 vq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + my_ofs));
             } else {
@@ -232,9 +256,9 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             const bool more = t + 1 < n_coop;
             if (t + 2 < n_coop) fetch(t + 2, kq2, vq2);
             const int meta = coop[t].meta;
-            const int lo = meta & 0xff, hi = (meta >> 8) & 0xff, valid = meta >> 16;
+            const int lo = (meta & 1023) - shift, hi = ((meta >> 10) & 1023) - shift, valid = (meta >> 20) & 31;
             // does the tile touch any row group of this wavefront?
-            if (wi.n_grp > 0 && lo < shift + wi.n_grp && hi > shift) {
+            if (wi.n_grp > 0 && lo < wi.n_grp && hi > 0) {
                 const char* sb = stage[t & 1];
                 Frag ks[4], vs[4];
                 if (valid == 16) {
@@ -249,9 +273,13 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
                         ks[r].u = *reinterpret_cast<const u32x4*>(sb + c * 256 + g4 * 64 + r * 16);
                     v_operands_from_rows(sb + 4096, 256, g4, c, vs);
                 }
-                float sv[4];
-                scores(ks, st, scale_log2e, (my_jc >= lo && my_jc < hi) ? (1u << valid) - 1u : 0u, g4, sv);
-                accumulate(vs, st, sv, valid, g4);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    if (NT > 1 && !touches(nt, lo, hi)) continue;
+                    float sv[4];
+                    scores(ks, st[nt], scale_log2e, tok_mask(nt, lo, hi, valid), g4, sv);
+                    accumulate(vs, st[nt], sv, valid, g4);
+                }
             }
             if (more) {
                 char* nb = stage[(t + 1) & 1];
@@ -292,26 +320,28 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             else v[r].u = u32x4{0u, 0u, 0u, 0u};
         }
     };
-    int meta = 16 << 16;
+    int meta = 16 << 20;
     if (wi.n_tiles > 0) {  // (nothing before this point waits on memory when the group has no shared tiles)
         meta = mine[0].meta;
         const char* t0 = head_base + mine[0].blk * block_stride;
-        issue_k(t0, meta >> 16);
-        issue_v(t0, meta >> 16);
+        issue_k(t0, (meta >> 20) & 31);
+        issue_v(t0, (meta >> 20) & 31);
     }
     char* scratch = lds + wave * kOpenScratch;
     for (int t = 0; t < wi.n_tiles; ++t) {
         const bool more = t + 1 < wi.n_tiles;
-        const int lo = meta & 0xff, hi = (meta >> 8) & 0xff, valid = meta >> 16;
+        const int lo = meta & 1023, hi = (meta >> 10) & 1023, valid = (meta >> 20) & 31;
         const char* tn = nullptr;
-        int meta_n = 16 << 16;
+        int meta_n = 16 << 20;
         if (more) {
             tn = head_base + mine[t + 1].blk * block_stride;
             meta_n = mine[t + 1].meta;
         }
-        float sv[4];
-        scores(k, st, scale_log2e, (my_j >= lo && my_j < hi) ? (1u << valid) - 1u : 0u, g4, sv);
-        if (more) issue_k(tn, meta_n >> 16);  // K registers are free again
+        float sv[NT][4];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            if (NT == 1 || touches(nt, lo, hi)) scores(k, st[nt], scale_log2e, tok_mask(nt, lo, hi, valid), g4, sv[nt]);
+        if (more) issue_k(tn, (meta_n >> 20) & 31);  // K registers are free again
         if (valid < 16) {
             // open block: its V half arrived row-major; turn it into operand order through LDS
 #pragma unroll
@@ -323,15 +353,18 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             v_operands_from_rows(scratch, kOpenRowStride, g4, c, v);
             __builtin_amdgcn_wave_barrier();
         }
-        accumulate(v, st, sv, valid, g4);
-        if (more) issue_v(tn, meta_n >> 16);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            if (NT == 1 || touches(nt, lo, hi)) accumulate(v, st[nt], sv[nt], valid, g4);
+        if (more) issue_v(tn, (meta_n >> 20) & 31);
         meta = meta_n;
     }
 
     // ---- results ------------------------------------------------------------------------------
-    if (wi.flags & kWaveSplit) {
+    if (NT == 1 && (wi.flags & kWaveSplit)) {
         // the four wavefronts hold the same rows over different tiles: fold 1..3 into 0 through LDS
-        float lt = st.l;
+        RowState& s0 = st[0];
+        float lt = s0.l;
         lt += __shfl_xor(lt, 16, 64);
         lt += __shfl_xor(lt, 32, 64);
         float* so = reinterpret_cast<float*>(lds);           // [3][16 rows][128]
@@ -340,15 +373,15 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
         if (wave > 0) {
             float* dst = so + ((wave - 1) * 16 + c) * 128 + 4 * g4;
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj) *reinterpret_cast<f32x4*>(dst + 16 * jj) = st.o[jj];
+            for (int jj = 0; jj < 8; ++jj) *reinterpret_cast<f32x4*>(dst + 16 * jj) = s0.o[jj];
             if (g4 == 0) {
-                sml[((wave - 1) * 16 + c) * 2] = st.m;
+                sml[((wave - 1) * 16 + c) * 2] = s0.m;
                 sml[((wave - 1) * 16 + c) * 2 + 1] = lt;
             }
         }
         __syncthreads();
         if (wave > 0) return;
-        float mw[3], lw[3], mx = st.m;
+        float mw[3], lw[3], mx = s0.m;
 #pragma unroll
         for (int w2 = 0; w2 < 3; ++w2) {
             mw[w2] = sml[(w2 * 16 + c) * 2];
@@ -356,20 +389,20 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             mx = fmaxf(mx, mw[w2]);
         }
         // a wavefront that saw no tile of a row left m = -inf and sums of zero for it
-        const float a0 = (st.m == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(st.m - mx);
+        const float a0 = (s0.m == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(s0.m - mx);
         lt *= a0;
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) st.o[jj] *= a0;
+        for (int jj = 0; jj < 8; ++jj) s0.o[jj] *= a0;
 #pragma unroll
         for (int w2 = 0; w2 < 3; ++w2) {
             const float aw = (mw[w2] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw[w2] - mx);
             lt += aw * lw[w2];
             const float* src = so + (w2 * 16 + c) * 128 + 4 * g4;
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj) st.o[jj] += aw * *reinterpret_cast<const f32x4*>(src + 16 * jj);
+            for (int jj = 0; jj < 8; ++jj) s0.o[jj] += aw * *reinterpret_cast<const f32x4*>(src + 16 * jj);
         }
-        st.m = mx;
-        st.l = g4 == 0 ? lt : 0.0f;  // back to one share per lane: the four lanes of a row add up to the sum
+        s0.m = mx;
+        s0.l = g4 == 0 ? lt : 0.0f;  // back to one share per lane: the four lanes of a row add up to the sum
         __builtin_amdgcn_wave_barrier();
     }
 
@@ -377,7 +410,6 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
         // Multi-candidate call: each thread's candidates are one more tile of at most 8 token rows
         // (row-major, a row every n_kv * 128 elements), visible to a row only where its mask bit is set.
         const int rank_lo = wi.grp_lo / n_sl, rank_hi = (wi.grp_lo + wi.n_grp - 1) / n_sl;
-        const int cc_row = row_ok ? rr / group : 0;
         const int64_t tok_stride = (int64_t)n_kv * 256;  // bytes between candidate rows of one kv head
         for (int ru = rank_lo; ru <= rank_hi; ++ru) {
             const int listed_u = plan.dfs_threads[ru];
@@ -398,37 +430,52 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             v_operands_from_rows(scratch, kOpenRowStride, g4, c, vc);
             __builtin_amdgcn_wave_barrier();
-            uint32_t tm = 0;
-            if (row_ok && rank == ru) tm = cand_mask[(int64_t)listed_u * n_cand + cc_row];
-            float sv[4];
-            scores(kc, st, scale_log2e, tm, g4, sv);
-            accumulate(vc, st, sv, n_cand, g4);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                uint32_t tm = 0;
+                if (my_j[nt] != 0x7fff) {
+                    const int grp = wi.grp_lo + my_j[nt];
+                    const int rk = grp / n_sl, r2 = (grp - rk * n_sl) * rps + within;
+                    if (rk == ru) tm = cand_mask[(int64_t)listed_u * n_cand + r2 / group];
+                }
+                if (__builtin_amdgcn_ballot_w64(tm != 0) == 0) continue;
+                float sv[4];
+                scores(kc, st[nt], scale_log2e, tm, g4, sv);
+                accumulate(vc, st[nt], sv, n_cand, g4);
+            }
         }
     }
 
-    float lt = st.l;
-    lt += __shfl_xor(lt, 16, 64);
-    lt += __shfl_xor(lt, 32, 64);
-    if (!row_ok) return;
-    if (wi.flags & kWaveDirect) {
-        // the row's whole root path was covered here: normalise and write the output row
-        const float inv = 1.0f / lt;
-        uint16_t* dst = out + qrow * 128 + 4 * g4;
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-            u32x2 pk;
-            pk.x = pack_bf16_rne(st.o[jj][0] * inv, st.o[jj][1] * inv);
-            pk.y = pack_bf16_rne(st.o[jj][2] * inv, st.o[jj][3] * inv);
-            __builtin_nontemporal_store(pk, reinterpret_cast<u32x2*>(dst + 16 * jj));
-        }
-    } else {
-        // streaming stores: a partial result is read once, by the merge kernel
-        float* dst = part.o + slot * 128 + 4 * g4;
+    for (int nt = 0; nt < NT; ++nt) {
+        float lt = st[nt].l;
+        lt += __shfl_xor(lt, 16, 64);
+        lt += __shfl_xor(lt, 32, 64);
+        if (my_j[nt] == 0x7fff) continue;
+        int rk, r2;
+        int64_t qrow, slot;
+        locate(nt, rk, r2, qrow, slot);
+        if (wi.flags & kWaveDirect) {
+            // the row's whole root path was covered here: normalise and write the output row
+            const float inv = 1.0f / lt;
+            uint16_t* dst = out + qrow * 128 + 4 * g4;
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) __builtin_nontemporal_store(st.o[jj], reinterpret_cast<f32x4*>(dst + 16 * jj));
-        if (g4 == 0) {
-            __builtin_nontemporal_store(st.m, part.ml + slot * 2);
-            __builtin_nontemporal_store(lt, part.ml + slot * 2 + 1);
+            for (int jj = 0; jj < 8; ++jj) {
+                u32x2 pk;
+                pk.x = pack_bf16_rne(st[nt].o[jj][0] * inv, st[nt].o[jj][1] * inv);
+                pk.y = pack_bf16_rne(st[nt].o[jj][2] * inv, st[nt].o[jj][3] * inv);
+                __builtin_nontemporal_store(pk, reinterpret_cast<u32x2*>(dst + 16 * jj));
+            }
+        } else {
+            // streaming stores: a partial result is read once, by the merge kernel
+            float* dst = part.o + slot * 128 + 4 * g4;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+                __builtin_nontemporal_store(st[nt].o[jj], reinterpret_cast<f32x4*>(dst + 16 * jj));
+            if (g4 == 0) {
+                __builtin_nontemporal_store(st[nt].m, part.ml + slot * 2);
+                __builtin_nontemporal_store(lt, part.ml + slot * 2 + 1);
+            }
         }
     }
 }
@@ -438,12 +485,24 @@ __global__ __launch_bounds__(256) void attention_bf16(const char* __restrict__ p
 hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
                                  PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
                                  void* out, hipStream_t st) {
-    const int64_t n_wg = (int64_t)plan.n_wg * s.n_kv;
-    if (n_wg <= 0) return hipSuccess;
-    if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(attention_bf16, dim3((unsigned)n_wg), dim3(256), 0, st, (const char*)pool, (const uint16_t*)q,
-                       plan, n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part, (const uint16_t*)cand_k,
-                       (const uint16_t*)cand_v, mask, (uint16_t*)out);
+    // workgroups are sorted by row tiles per wavefront: [4-tile | 2-tile | 1-tile], heaviest first in each
+    int first = 0;
+    for (int cls = 0; cls < 3; ++cls) {
+        const int count = plan.n_wg_class[cls];
+        if (count > 0) {
+            const int64_t n_wg = (int64_t)count * s.n_kv;
+            if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
+#define APAR_LAUNCH(NTV)                                                                                          \
+    hipLaunchKernelGGL((attention_bf16<NTV>), dim3((unsigned)n_wg), dim3(256), 0, st, (const char*)pool,          \
+                       (const uint16_t*)q, plan, first, n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part,       \
+                       (const uint16_t*)cand_k, (const uint16_t*)cand_v, mask, (uint16_t*)out)
+            if (cls == 0) APAR_LAUNCH(4);
+            else if (cls == 1) APAR_LAUNCH(2);
+            else APAR_LAUNCH(1);
+#undef APAR_LAUNCH
+        }
+        first += count;
+    }
     return hipGetLastError();
 }
 

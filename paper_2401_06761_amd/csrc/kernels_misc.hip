@@ -136,7 +136,7 @@ __global__ __launch_bounds__(256) void copy_blocks(char* __restrict__ pool, cons
 // cores' bf16 inputs would not.  Follows the same plan as the bf16 kernel: row c
 // of wavefront k of a workgroup walks the group's shared tiles and wavefront k's
 // own tiles and takes those whose row-group range contains its own.
-// grid = (plan workgroups, kv heads, 64 rows); block = 64 lanes over the head dim.
+// grid = (plan workgroups, kv heads, 4 wavefronts x 4 row tiles x 16 rows); block = 64 lanes over the head dim.
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ pool, const float* __restrict__ q,
@@ -149,14 +149,17 @@ __global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ poo
     constexpr int E = D / 64;
     const int lane = threadIdx.x;
     const int kvh = blockIdx.y;
-    const int wave = blockIdx.z >> 4, c = blockIdx.z & 15;
+    // row c of row tile nt of wavefront `wave`: tile nt holds row groups nt * cap .. of the wavefront
+    const int wave = blockIdx.z >> 6, nt = (blockIdx.z >> 4) & 3, c = blockIdx.z & 15;
     const WgDesc* wg = plan.wgs + blockIdx.x;
+    if (nt >= wg->row_tiles) return;
     const WaveItem wi = wg->w[wave];
     const int rps = plan.rows_per_slice, n_sl = plan.n_slices, rpt = plan.rows_per_thread;
-    const int j = c / rps, within = c - j * rps;
+    const int cap = 16 / rps, jc = c / rps, within = c - jc * rps;
+    const int j = nt * cap + jc;
     const int grp = wi.grp_lo + j;
     const int rank = grp / n_sl, rr = (grp - rank * n_sl) * rps + within;
-    if (j >= wi.n_grp || rr >= rpt) return;
+    if (jc >= cap || j >= wi.n_grp || rr >= rpt) return;
     const int listed = plan.dfs_threads[rank];
     const int cc = rr / group, hq = kvh * group + (rr - cc * group);
     const int64_t qrow = ((int64_t)listed * n_cand + cc) * n_q + hq;
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ poo
         const int my_j = list == 0 ? j + (wi.grp_lo - wg->grp_base) : j;
         for (int t = 0; t < n_tiles; ++t) {
             const int meta = tiles[t].meta;
-            const int lo = meta & 0xff, hi = (meta >> 8) & 0xff, valid = meta >> 16;
+            const int lo = meta & 1023, hi = (meta >> 10) & 1023, valid = (meta >> 20) & 31;
             if (my_j < lo || my_j >= hi) continue;
             const float* tile = reinterpret_cast<const float*>(pool + ((int64_t)tiles[t].blk * n_kv + kvh) * tile_bytes);
             for (int tok = 0; tok < valid; ++tok) {
@@ -364,7 +367,7 @@ hipError_t launch_attention_partial(const Shape& s, const void* pool, const void
     if (plan.n_wg <= 0) return hipSuccess;
     if (s.dtype == APAR_BF16)
         return launch_attention_bf16(s, pool, q, plan, n_cand, part, cand_k, cand_v, mask, out, st);
-    dim3 grid(plan.n_wg, s.n_kv, 64);
+    dim3 grid(plan.n_wg, s.n_kv, 256);
     if (s.d == 64)
         hipLaunchKernelGGL(attention_f32<64>, grid, dim3(64), 0, st, (const char*)pool, (const float*)q, plan, n_cand,
                            s.n_q, s.n_kv, s.group, s.scale_log2e, s.tile_bytes, part, (const float*)cand_k,

@@ -13,7 +13,8 @@
 //
 // Units.  Partial results are expensive: small writes mixed into the streaming
 // reads cost far more than their size.  So a whole subtree of the forest is given
-// to ONE unit whenever its query rows fit one workgroup (4 wavefronts x 16 rows):
+// to ONE unit whenever its query rows fit one workgroup (4 wavefronts x 16, 32 or 64 rows;
+// the fewest rows per wavefront that hold them are chosen):
 // the rows' softmax state then stays in registers from the shared prefix down to
 // each private tail, and threads whose entire path lies inside the unit get their
 // output written directly.  Inside such a unit a block whose holders all sit in one
@@ -42,7 +43,7 @@ namespace {
 
 constexpr int B = kBlockTokens;
 
-inline int32_t make_meta(int lo, int hi, int valid) { return lo | (hi << 8) | (valid << 16); }
+inline int32_t make_meta(int lo, int hi, int valid) { return lo | (hi << 10) | (valid << 20); }
 
 struct Builder {
     PlanHost& ph;
@@ -59,6 +60,9 @@ struct Builder {
     }
 
     int32_t valid_of(const PlanHost::Segment& s, int b) const { return b == s.n_blk - 1 ? s.last_valid : B; }
+
+    // fewest 16-row tiles per wavefront with which one workgroup holds `groups` row groups (4 if none does)
+    int pick_row_tiles(int groups) const { return groups <= 4 * cap ? 1 : groups <= 8 * cap ? 2 : 4; }
 
     // Pre-order walk of the subtree of `root`; f(segment index).
     template <class F>
@@ -103,19 +107,21 @@ struct Builder {
                     ph.tiles.push_back(TileRef{ph.seg_blocks[s.first_block_pos + b], make_meta(0, groups, valid_of(s, b))});
                 emit_narrow(ofs, nb, grp0, groups, pbase, 0);
             } else {
-                for (int g0 = 0; g0 < groups; g0 += 4 * cap) {
-                    const int gn = std::min(4 * cap, groups - g0);
+                const int nt = pick_row_tiles(groups), wcap = nt * cap;
+                for (int g0 = 0; g0 < groups; g0 += 4 * wcap) {
+                    const int gn = std::min(4 * wcap, groups - g0);
                     PlanHost::WideItem wi{};
+                    wi.wg.row_tiles = nt;
                     wi.wg.coop_ofs = (int32_t)ph.tiles.size();
                     wi.wg.n_coop = nb;
                     wi.wg.grp_base = grp0 + g0;
                     for (int b = b0; b < b0 + nb; ++b)
                         ph.tiles.push_back(TileRef{ph.seg_blocks[s.first_block_pos + b], make_meta(0, gn, valid_of(s, b))});
                     for (int k = 0; k < 4; ++k) {
-                        const int lo = k * cap, cnt = std::max(0, std::min(cap, gn - lo));
+                        const int lo = k * wcap, cnt = std::max(0, std::min(wcap, gn - lo));
                         wi.wg.w[k] = WaveItem{0, 0, grp0 + g0 + lo, cnt, pbase + (g0 + lo) / n_sl, 0};
                     }
-                    wi.cost = 2 * nb;
+                    wi.cost = 2 * nb * nt;
                     ph.wide_items.push_back(wi);
                 }
             }
@@ -150,12 +156,13 @@ struct Builder {
         }
         // several wavefronts: give each a contiguous range of row groups, keeping subtrees that fit
         // one wavefront whole where possible
+        const int nt = pick_row_tiles(groups), wcap = nt * cap;
         int wave_lo[4] = {0, 0, 0, 0}, wave_n[4] = {0, 0, 0, 0};
         int cur = 0, fill = 0;
         bool overflow = false;
         auto atom = [&](int lo_rel, int cnt) {
             if (overflow) return;
-            if (fill + cnt > cap) {
+            if (fill + cnt > wcap) {
                 wave_n[cur] = fill;
                 if (++cur >= 4) {
                     overflow = true;
@@ -176,12 +183,12 @@ struct Builder {
                 st.pop_back();
                 const PlanHost::Segment& s = ph.segs[m];
                 const int lo = (s.t_lo - r.t_lo) * n_sl, mg = s.n_shr * n_sl;
-                if (mg <= cap) {
+                if (mg <= wcap) {
                     atom(lo, mg);
                     continue;
                 }
                 for (int e = 0; e < s.n_end; ++e) {  // threads that end here come first in depth-first order
-                    if (n_sl <= cap) atom(lo + e * n_sl, n_sl);
+                    if (n_sl <= wcap) atom(lo + e * n_sl, n_sl);
                     else
                         for (int sl = 0; sl < n_sl; ++sl) atom(lo + e * n_sl + sl, 1);
                 }
@@ -192,10 +199,10 @@ struct Builder {
             st.resize(base);
         }
         if (!overflow) wave_n[cur] = fill;
-        if (overflow) {  // dense packing always fits: groups <= 4 * cap
+        if (overflow) {  // dense packing always fits: groups <= 4 * wcap
             for (int k = 0; k < 4; ++k) {
-                wave_lo[k] = k * cap;
-                wave_n[k] = std::max(0, std::min(cap, groups - k * cap));
+                wave_lo[k] = k * wcap;
+                wave_n[k] = std::max(0, std::min(wcap, groups - k * wcap));
             }
         }
         for (PlanHost::WaveBuild& w : ph.wave_build) w.tiles.clear();
@@ -219,6 +226,7 @@ struct Builder {
         wi.wg.coop_ofs = (int32_t)ph.tiles.size();
         wi.wg.n_coop = (int32_t)ph.coop_build.size();
         wi.wg.grp_base = grp0;
+        wi.wg.row_tiles = nt;
         ph.tiles.insert(ph.tiles.end(), ph.coop_build.begin(), ph.coop_build.end());
         int longest = 0;
         for (int k = 0; k < 4; ++k) {
@@ -228,7 +236,7 @@ struct Builder {
             ph.tiles.insert(ph.tiles.end(), t.begin(), t.end());
             longest = std::max(longest, (int)t.size());
         }
-        wi.cost = 2 * wi.wg.n_coop + longest;
+        wi.cost = nt * (2 * wi.wg.n_coop + longest);
         ph.wide_items.push_back(wi);
     }
 };
@@ -332,7 +340,7 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         }
         s.n_above = par >= 0 ? segs[par].n_above + bld.n_chunks[par] : 0;
         const int groups = s.n_shr * n_sl;
-        const bool fits = groups <= 4 * cap && s.tiles_sub <= (groups <= cap ? 1 : 4) * prm.max_unit_tiles;
+        const bool fits = groups <= 16 * cap && s.tiles_sub <= (groups <= cap ? 1 : 4) * prm.max_unit_tiles;
         if (prm.fuse && fits) {
             s.unit = m;  // a unit is named after its root segment
             bld.emit_fused(m);
@@ -373,11 +381,18 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         }
     }
 
-    // 7. workgroups, heaviest first
+    // 7. workgroups: by row tiles per wavefront (4, 2, 1), heaviest first within a class
     std::stable_sort(ph.wide_items.begin(), ph.wide_items.end(),
-                     [](const PlanHost::WideItem& a, const PlanHost::WideItem& b) { return a.cost > b.cost; });
+                     [](const PlanHost::WideItem& a, const PlanHost::WideItem& b) {
+                         return a.wg.row_tiles != b.wg.row_tiles ? a.wg.row_tiles > b.wg.row_tiles : a.cost > b.cost;
+                     });
     ph.wgs.reserve(ph.wide_items.size() + (ph.narrow_items.size() + 3) / 4);
-    for (const PlanHost::WideItem& w : ph.wide_items) ph.wgs.push_back(w.wg);
+    ph.n_wg_class[0] = ph.n_wg_class[1] = ph.n_wg_class[2] = 0;
+    for (const PlanHost::WideItem& w : ph.wide_items) {
+        ph.wgs.push_back(w.wg);
+        ph.n_wg_class[w.wg.row_tiles == 4 ? 0 : w.wg.row_tiles == 2 ? 1 : 2] += 1;
+    }
+    const size_t n_wide = ph.wgs.size();
     {
         // counting sort by cost, descending
         int32_t max_cost = 0;
@@ -395,6 +410,7 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
             const WaveItem& it = ph.narrow_items[slot[k]].item;
             WgDesc wg{};
             wg.grp_base = it.grp_lo;
+            wg.row_tiles = 1;
             for (int j = 0; j < 4; ++j) {
                 const int32_t b = (int32_t)((int64_t)it.n_tiles * j / 4), e = (int32_t)((int64_t)it.n_tiles * (j + 1) / 4);
                 wg.w[j] = WaveItem{it.tile_ofs + b, e - b, it.grp_lo, it.n_grp, it.part_base, it.flags | kWaveSplit};
@@ -408,9 +424,11 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
                 else wg.w[j] = WaveItem{0, 0, 0, 0, -1, 0};
             }
             wg.grp_base = wg.w[0].grp_lo;
+            wg.row_tiles = 1;
             ph.wgs.push_back(wg);
         }
     }
+    ph.n_wg_class[2] += (int32_t)(ph.wgs.size() - n_wide);
     return APAR_OK;
 }
 

@@ -17,7 +17,8 @@ struct PlanThreadView {  // what the planner needs to know about one listed thre
 
 struct PlanHost {
     // device-format tables
-    std::vector<WgDesc> wgs;            // heaviest first
+    std::vector<WgDesc> wgs;            // by row tiles per wavefront (4, 2, 1), heaviest first within a class
+    int32_t n_wg_class[3] = {0, 0, 0};
     std::vector<TileRef> tiles;
     std::vector<int32_t> dfs_threads;   // listed-thread indices in depth-first order of the sharing tree
     std::vector<int32_t> path_ofs, path_ids;

@@ -108,11 +108,14 @@ def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per
     direct = {}    # rank -> number of direct units
     tile_reads = 0
     for wg_index, wg in enumerate(wgs):
-        coop_ofs, n_coop, grp_base = wg[0], wg[1], wg[2]
+        coop_ofs, n_coop, grp_base, row_tiles = wg[0], wg[1], wg[2], wg[3]
+        assert row_tiles in (1, 2, 4)
+        if wg_index:  # classes are stored 4, 2, 1
+            assert row_tiles <= wgs[wg_index - 1][3]
         tile_reads += n_coop
         for k in range(4):
             t_ofs, n_t, g_lo, n_g, pbase, flags = wg[4 + 6 * k: 10 + 6 * k]
-            assert 0 <= n_g <= cap
+            assert 0 <= n_g <= row_tiles * cap
             tile_reads += n_t
             if n_g == 0:
                 assert n_t == 0
@@ -121,12 +124,12 @@ def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per
                 rank = g // n_sl
                 lst = seen.setdefault(g, [])
                 for blk, meta in tiles[coop_ofs:coop_ofs + n_coop]:
-                    lo, hi, valid = meta & 0xFF, (meta >> 8) & 0xFF, meta >> 16
+                    lo, hi, valid = meta & 1023, (meta >> 10) & 1023, (meta >> 20) & 31
                     assert 1 <= valid <= 16 and lo < hi
                     if lo <= g - grp_base < hi:
                         lst.append((int(blk), int(valid)))
                 for blk, meta in tiles[t_ofs:t_ofs + n_t]:
-                    lo, hi, valid = meta & 0xFF, (meta >> 8) & 0xFF, meta >> 16
+                    lo, hi, valid = meta & 1023, (meta >> 10) & 1023, (meta >> 20) & 31
                     assert 1 <= valid <= 16 and lo < hi <= n_g
                     if lo <= g - g_lo < hi:
                         lst.append((int(blk), int(valid)))

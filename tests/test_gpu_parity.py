@@ -261,3 +261,61 @@ def test_multi_candidate_step(dtype, d, C, chunk):
         e = heads.elem_bytes
         assert info.algorithmic_bytes == info.unique_tokens * heads.kv_bytes_per_token + \
             2 * n * C * 4 * d * e + 2 * n * C * 2 * d * e
+
+
+def _fan_tree(fan, heads, seed):
+    # a root of 40 tokens with `fan` children, every second child with two children of its own
+    parents, lens = [-1], [40]
+    for c in range(fan):
+        parents.append(0)
+        lens.append(5 + (c * 7) % 50)
+        if c % 2:
+            kid = len(parents) - 1
+            parents += [kid, kid]
+            lens += [3 + c % 20, 17]
+    return manual_tree(parents, lens, heads, seed=seed, data_scale=0.5)
+
+
+@pytest.mark.parametrize("dtype,n_q,n_kv,fan", [
+    ("bf16", 2, 2, 40),    # 2 row tiles per wavefront
+    ("bf16", 2, 2, 100),   # 4 row tiles per wavefront
+    ("bf16", 2, 2, 150),   # more rows than one workgroup: stand-alone root, partial results
+    ("bf16", 8, 1, 9),     # 8 rows per thread
+    ("bf16", 8, 1, 20),
+    ("f32", 2, 2, 100),
+    ("f32", 8, 1, 20),
+])
+@pytest.mark.parametrize("chunk", [None, 3])
+def test_wide_sharing_groups(dtype, n_q, n_kv, fan, chunk):
+    w = _fan_tree(fan, HeadConfig(n_q, n_kv, 128, dtype), seed=fan)
+    err, info = run_workload(w, chunk=chunk)
+    print(f"fan {fan}: {info.n_threads} threads, {info.n_partial_rows} partial rows, err {err:.2e}")
+
+
+@pytest.mark.parametrize("dtype,fan,C", [("bf16", 1, 5), ("bf16", 3, 5), ("bf16", 6, 5), ("bf16", 40, 2),
+                                         ("bf16", 11, 8), ("f32", 3, 5)])
+def test_multi_candidate_wide_groups(dtype, fan, C):
+    t = torch()
+    heads = HeadConfig(8, 1, 128, dtype)
+    w = _fan_tree(fan, heads, seed=100 + fan)
+    N = blocks_upper_bound(w)
+    with pool_for(w, N) as pool:
+        poison(pool)
+        dense = DenseThreads(8, 1, 128)
+        live, _ = replay_trace(w, pool, None, dense)
+        n = len(live)
+        rng = np.random.default_rng(fan)
+        q = quantise(0.5 * rng.standard_normal((n, C, 8, 128)).astype(np.float32), dtype)
+        ck = quantise(0.5 * rng.standard_normal((n, C, 1, 128)).astype(np.float32), dtype)
+        cv = quantise(0.5 * rng.standard_normal((n, C, 1, 128)).astype(np.float32), dtype)
+        masks = np.stack([mask_rows_from_parents(draw_candidate_tree(rng, C)) for _ in range(n)])
+        qd = to_dev(q, dtype)
+        out = t.empty_like(qd)
+        ap.apar_decode_attention_spec(pool.handle, qd, to_dev(ck, dtype), to_dev(cv, dtype),
+                                      t.from_numpy(masks).cuda(), C, live, out)
+        t.cuda.synchronize()
+        want = dense.decode_spec(q, ck, cv, masks, live)
+        got = to_host(out)
+        assert np.isfinite(got).all()
+        err = np.abs(got - want).max()
+        assert err <= TOL[dtype], err

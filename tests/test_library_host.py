@@ -184,3 +184,47 @@ def test_error_codes_and_noops():
     with pytest.raises(ap.AparError) as ei:
         ap.apar_pool_create(ap.AparPoolConfig(4, 4, 96, 16, 1, 8, 4, 0.0), None)
     assert ei.value.status == -6
+
+
+@pytest.mark.parametrize("n_q,n_kv,fan,n_cand", [
+    (4, 4, 70, 1),     # 71 rows per kv head share the root: two 16-row tiles per wavefront
+    (4, 4, 130, 1),    # four tiles per wavefront
+    (4, 4, 300, 1),    # more rows than one workgroup holds: the root stands alone, chunks of 256 rows
+    (8, 1, 9, 1),      # 8 rows per thread: 2 threads per tile
+    (8, 1, 30, 1),
+    (8, 1, 40, 1),
+    (8, 1, 3, 5),      # 40 rows per thread: three slices of 14 rows, one row group per tile
+    (8, 1, 6, 5),
+])
+def test_wide_sharing_groups_use_more_row_tiles(n_q, n_kv, fan, n_cand):
+    # a root of 40 tokens with `fan` children, every second child with two children of its own
+    parents, lens = [-1], [40]
+    for c in range(fan):
+        parents.append(0)
+        lens.append(5 + (c * 7) % 50)
+        if c % 2:
+            kid = len(parents) - 1
+            parents += [kid, kid]
+            lens += [3 + c % 20, 17]
+    w = manual_tree(parents, lens, HeadConfig(n_q, n_kv, 128, "bf16"))
+    N = blocks_upper_bound(w)
+    rpt = n_cand * n_q // n_kv
+    with pool_for(w, N, dry_run=True) as pool:
+        live, _ = replay_trace(w, pool, None, dry_run=True)
+        for chunk in (2, 512):
+            ap.apar_set_chunk_blocks(pool.handle, chunk)
+            if n_cand == 1:
+                ap.apar_decode_attention(pool.handle, None, live, None)
+            else:
+                ap.apar_decode_attention_spec(pool.handle, None, None, None, None, n_cand, live, None)
+            res = check_plan_covers_tables(pool.handle, live, n_kv, rpt)
+            wgs = np.array(ap.apar_last_plan_export(pool.handle, ap.APAR_PLAN_WORKGROUPS)).reshape(-1, 32)
+            n_sl = -(-rpt // 16)
+            cap = 16 // -(-rpt // n_sl)
+            groups = len(live) * n_sl
+            if chunk == 512 and groups <= 16 * cap:
+                # the whole tree is one unit with the fewest row tiles that hold it
+                want = 1 if groups <= 4 * cap else 2 if groups <= 8 * cap else 4
+                assert res["partial_rows"] == 0 and len(wgs) == 1 and wgs[0][3] == want
+            if groups > 16 * cap:
+                assert res["partial_rows"] > 0 and wgs[0][3] == 4
