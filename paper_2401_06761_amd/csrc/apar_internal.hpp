@@ -105,6 +105,14 @@ struct PartialBuf {
     float* ml;
 };
 
+// Side streams on which the attention kernels of different row-tile classes run next to each
+// other (each class alone would leave most of the chip idle during its tail).  Created on first
+// use by the launcher, released by the pool; all at the default priority.
+struct ClassStreams {
+    hipStream_t aux[2] = {nullptr, nullptr};
+    hipEvent_t fork = nullptr, join[2] = {nullptr, nullptr};
+};
+
 // ---- launchers (defined next to their kernels) ------------------------------
 hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const void* v, const int32_t* dst_codes,
                               int n_rows, hipStream_t st);
@@ -115,7 +123,7 @@ hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src
                             void* v_out, hipStream_t st);
 hipError_t launch_attention_partial(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
                                     PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
-                                    void* out, hipStream_t st);
+                                    void* out, ClassStreams& cs, hipStream_t st);
 hipError_t launch_merge(const Shape& s, const PlanDev& plan, PartialBuf part, const void* q, const void* cand_k,
                         const void* cand_v, const uint8_t* mask, int n_cand, void* out, hipStream_t st);
 

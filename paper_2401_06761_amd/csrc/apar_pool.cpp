@@ -82,6 +82,7 @@ struct apar_pool {
     int next_slot = 0;
     PartialBuf part{};
     size_t part_slots_cap = 0;
+    ClassStreams class_streams;
 
     bool profiling = false;
     std::vector<EventPair> decode_events, append_events;
@@ -313,7 +314,7 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
             return rc;
         HIP_TRY(hipEventRecord(ev.a, st));
     }
-    HIP_TRY(launch_attention_partial(p->shape, p->kv, q, pd, n_cand, p->part, cand_k, cand_v, mask, out, st));
+    HIP_TRY(launch_attention_partial(p->shape, p->kv, q, pd, n_cand, p->part, cand_k, cand_v, mask, out, p->class_streams, st));
     if (p->profiling) HIP_TRY(hipEventRecord(ev.b, st));
     if (ph.any_partial)
         HIP_TRY(launch_merge(p->shape, pd, p->part, q, cand_k, cand_v, mask, n_cand, out, st));
@@ -409,6 +410,9 @@ int apar_pool_destroy(apar_pool* p) {
     for (EventPair& e : p->decode_events) drop(e.a), drop(e.b), drop(e.c);
     for (EventPair& e : p->append_events) drop(e.a), drop(e.b), drop(e.c);
     for (hipEvent_t e : p->spare_events) drop(e);
+    drop(p->class_streams.fork), drop(p->class_streams.join[0]), drop(p->class_streams.join[1]);
+    for (hipStream_t a : p->class_streams.aux)
+        if (a) (void)hipStreamDestroy(a);
     delete p;
     return rc;
 }

@@ -51,6 +51,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 union Frag {  // 16 bytes seen as a load, as an 8-wide bf16 operand, or as two 4-wide ones
     u32x4 u;
@@ -61,13 +63,6 @@ union Frag {  // 16 bytes seen as a load, as an 8-wide bf16 operand, or as two 4
 constexpr float kSlack = 8.0f;  // a probability may exceed 1 by at most 2^kSlack before the reference moves
 constexpr int kTileBytes = 8192;
 
-__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a += 0x7fffu + ((a >> 16) & 1u);
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xffff0000u);
-}
-
 // The 16 rows of one wavefront: query operands and running softmax state.
 struct RowState {
     Frag q[4];
@@ -75,24 +70,38 @@ struct RowState {
     float m, l;
 };
 
-// S^T = K.Q^T for one tile in base-2 logits; token slots whose bit is clear in tok_mask get -inf
-// (tok_mask is per lane, i.e. per query row: 0 for a row the tile does not apply to).
-__device__ __forceinline__ void scores(const Frag (&k)[4], const RowState& st, float scale_log2e, uint32_t tok_mask,
-                                       int g4, float (&sv)[4]) {
+// S^T = K.Q^T for one tile: raw dot products, tokens 4*g4 .. 4*g4+3 of this lane's row.
+__device__ __forceinline__ f32x4 products(const Frag (&k)[4], const RowState& st) {
     f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[kk].b8, st.q[kk].b8, s, 0, 0, 0);
-    const uint32_t mine = tok_mask >> (4 * g4);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) sv[i] = ((mine >> i) & 1u) ? s[i] * scale_log2e : -INFINITY;
+    return s;
 }
 
-// Online softmax step and O^T += V^T.P^T for one tile.
-__device__ __forceinline__ void accumulate(Frag (&v)[4], RowState& st, const float (&sv)[4], int valid, int g4) {
-    const float top = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+// Token slots whose bit is clear in tok_mask (per lane, i.e. per query row) get a product of -inf and
+// hence probability 0.  Only needed for tiles that are not full and for candidate tiles.
+__device__ __forceinline__ void mask_tokens(f32x4& s, uint32_t tok_mask, int g4) {
+    const uint32_t mine = tok_mask >> (4 * g4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s[i] = ((mine >> i) & 1u) ? s[i] : -INFINITY;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {  // round to nearest even, one instruction
+    const f32x2 x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+}
+
+// Online softmax step and O^T += V^T.P^T for one tile that applies to this lane's row iff in_range.
+// The softmax scale and the reference are folded into one fused multiply-add per logit; rows outside
+// the range, and slots masked to -inf, get probability exp2(-inf) = 0.  V rows of unfilled slots must
+// be finite (the loaders zero them): 0 * V is added for them.
+__device__ __forceinline__ void accumulate(const Frag (&v)[4], RowState& st, const f32x4& s, bool in_range,
+                                           float scale_log2e) {
+    const float top = in_range ? fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])) * scale_log2e : -INFINITY;
     if (__builtin_amdgcn_ballot_w64(top > st.m + kSlack) != 0) {
-        // some row's logits ran away from its reference: move every row's reference to its
-        // running maximum (the four lanes of a row agree on it) and rescale what was summed
+        // some row's logits ran away from its reference (always so for a row's first tile, whose
+        // reference is still -inf): move every row's reference to its running maximum (the four
+        // lanes of a row agree on it) and rescale what was summed
         float mx = fmaxf(top, __shfl_xor(top, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(st.m, mx);
@@ -103,29 +112,17 @@ __device__ __forceinline__ void accumulate(Frag (&v)[4], RowState& st, const flo
         for (int j = 0; j < 8; ++j) st.o[j] *= alpha;
         st.m = m_new;
     }
+    const float bias = (in_range && st.m != -INFINITY) ? -st.m : -INFINITY;
     float p[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) p[i] = (sv[i] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(sv[i] - st.m);
+    for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], scale_log2e, bias));
     st.l += (p[0] + p[1]) + (p[2] + p[3]);
-    if (valid < 16) {
-        // slots past the fill count hold whatever the buffer held: clear their V so that a
-        // zero probability cannot meet a NaN
-        const uint32_t m01 = (4 * g4 + 0 < valid ? 0x0000ffffu : 0u) | (4 * g4 + 1 < valid ? 0xffff0000u : 0u);
-        const uint32_t m23 = (4 * g4 + 2 < valid ? 0x0000ffffu : 0u) | (4 * g4 + 3 < valid ? 0xffff0000u : 0u);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            v[r].u.x &= m01;
-            v[r].u.y &= m23;
-            v[r].u.z &= m01;
-            v[r].u.w &= m23;
-        }
-    }
     union {
         uint32_t w[2];
         s16x4 h;
     } pp;
-    pp.w[0] = pack_bf16_rne(p[0], p[1]);
-    pp.w[1] = pack_bf16_rne(p[2], p[3]);
+    pp.w[0] = pack_bf16_pair(p[0], p[1]);
+    pp.w[1] = pack_bf16_pair(p[2], p[3]);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         st.o[2 * r] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v[r].h4[0], pp.h, st.o[2 * r], 0, 0, 0);
@@ -218,10 +215,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             for (int kk = 0; kk < 4; ++kk) st[nt].q[kk].u = qp[kk];
         }
     }
-    // per-lane token mask of a tile that applies to row groups [lo, hi) of this wavefront
-    auto tok_mask = [&](int nt, int lo, int hi, int valid) -> uint32_t {
-        return (my_j[nt] >= lo && my_j[nt] < hi) ? (1u << valid) - 1u : 0u;
-    };
     // does a tile touch row tile nt at all?  (wavefront-uniform)
     auto touches = [&](int nt, int lo, int hi) -> bool {
         return lo < min((nt + 1) * cap, wi.n_grp) && hi > nt * cap;
@@ -276,9 +269,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
                     if (NT > 1 && !touches(nt, lo, hi)) continue;
-                    float sv[4];
-                    scores(ks, st[nt], scale_log2e, tok_mask(nt, lo, hi, valid), g4, sv);
-                    accumulate(vs, st[nt], sv, valid, g4);
+                    f32x4 s = products(ks, st[nt]);
+                    if (valid < 16) mask_tokens(s, (1u << valid) - 1u, g4);
+                    accumulate(vs, st[nt], s, my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
                 }
             }
             if (more) {
@@ -337,10 +330,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             tn = head_base + mine[t + 1].blk * block_stride;
             meta_n = mine[t + 1].meta;
         }
-        float sv[NT][4];
+        f32x4 s[NT];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-            if (NT == 1 || touches(nt, lo, hi)) scores(k, st[nt], scale_log2e, tok_mask(nt, lo, hi, valid), g4, sv[nt]);
+            if (NT == 1 || touches(nt, lo, hi)) s[nt] = products(k, st[nt]);
         if (more) issue_k(tn, (meta_n >> 20) & 31);  // K registers are free again
         if (valid < 16) {
             // open block: its V half arrived row-major; turn it into operand order through LDS
@@ -354,8 +347,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             __builtin_amdgcn_wave_barrier();
         }
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            if (NT == 1 || touches(nt, lo, hi)) accumulate(v, st[nt], sv[nt], valid, g4);
+        for (int nt = 0; nt < NT; ++nt) {
+            if (NT > 1 && !touches(nt, lo, hi)) continue;
+            if (valid < 16) mask_tokens(s[nt], (1u << valid) - 1u, g4);
+            accumulate(v, st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+        }
         if (more) issue_v(tn, (meta_n >> 20) & 31);
         meta = meta_n;
     }
@@ -439,9 +435,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
                     if (rk == ru) tm = cand_mask[(int64_t)listed_u * n_cand + r2 / group];
                 }
                 if (__builtin_amdgcn_ballot_w64(tm != 0) == 0) continue;
-                float sv[4];
-                scores(kc, st[nt], scale_log2e, tm, g4, sv);
-                accumulate(vc, st[nt], sv, n_cand, g4);
+                f32x4 sc = products(kc, st[nt]);
+                mask_tokens(sc, tm, g4);
+                accumulate(vc, st[nt], sc, tm != 0, scale_log2e);
             }
         }
     }
@@ -462,8 +458,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj) {
                 u32x2 pk;
-                pk.x = pack_bf16_rne(st[nt].o[jj][0] * inv, st[nt].o[jj][1] * inv);
-                pk.y = pack_bf16_rne(st[nt].o[jj][2] * inv, st[nt].o[jj][3] * inv);
+                pk.x = pack_bf16_pair(st[nt].o[jj][0] * inv, st[nt].o[jj][1] * inv);
+                pk.y = pack_bf16_pair(st[nt].o[jj][2] * inv, st[nt].o[jj][3] * inv);
                 __builtin_nontemporal_store(pk, reinterpret_cast<u32x2*>(dst + 16 * jj));
             }
         } else {
@@ -484,26 +480,58 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
 
 hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
                                  PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
-                                 void* out, hipStream_t st) {
-    // workgroups are sorted by row tiles per wavefront: [4-tile | 2-tile | 1-tile], heaviest first in each
-    int first = 0;
+                                 void* out, ClassStreams& cs, hipStream_t st) {
+    // workgroups are sorted by row tiles per wavefront: [4-tile | 2-tile | 1-tile], heaviest first in each.
+    // The last class present runs on the caller's stream; the ones before it run beside it on side
+    // streams that wait for the caller's stream first and that the caller's stream then waits for.
+    int first[3], last = -1, n_present = 0;
+    for (int cls = 0, f = 0; cls < 3; ++cls) {
+        first[cls] = f;
+        f += plan.n_wg_class[cls];
+        if (plan.n_wg_class[cls] > 0) last = cls, ++n_present;
+        if ((int64_t)plan.n_wg_class[cls] * s.n_kv > 0x7fffffff) return hipErrorInvalidValue;
+    }
+    if (last < 0) return hipSuccess;
+    hipError_t e;
+    if (n_present > 1) {
+        if (!cs.fork) {
+            if ((e = hipEventCreateWithFlags(&cs.fork, hipEventDisableTiming)) != hipSuccess) return e;
+        }
+        for (int k = 0; k < 2; ++k) {
+            if (!cs.aux[k] && (e = hipStreamCreateWithFlags(&cs.aux[k], hipStreamNonBlocking)) != hipSuccess) return e;
+            if (!cs.join[k] && (e = hipEventCreateWithFlags(&cs.join[k], hipEventDisableTiming)) != hipSuccess) return e;
+        }
+        if ((e = hipEventRecord(cs.fork, st)) != hipSuccess) return e;
+    }
+    int side = 0;
+    bool used[2] = {false, false};
     for (int cls = 0; cls < 3; ++cls) {
         const int count = plan.n_wg_class[cls];
-        if (count > 0) {
-            const int64_t n_wg = (int64_t)count * s.n_kv;
-            if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
-#define APAR_LAUNCH(NTV)                                                                                          \
-    hipLaunchKernelGGL((attention_bf16<NTV>), dim3((unsigned)n_wg), dim3(256), 0, st, (const char*)pool,          \
-                       (const uint16_t*)q, plan, first, n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part,       \
-                       (const uint16_t*)cand_k, (const uint16_t*)cand_v, mask, (uint16_t*)out)
-            if (cls == 0) APAR_LAUNCH(4);
-            else if (cls == 1) APAR_LAUNCH(2);
-            else APAR_LAUNCH(1);
-#undef APAR_LAUNCH
+        if (count == 0) continue;
+        hipStream_t on = st;
+        if (cls != last) {
+            on = cs.aux[side];
+            if ((e = hipStreamWaitEvent(on, cs.fork, 0)) != hipSuccess) return e;
         }
-        first += count;
+        const unsigned n_wg = (unsigned)count * (unsigned)s.n_kv;
+#define APAR_LAUNCH(NTV)                                                                                          \
+    hipLaunchKernelGGL((attention_bf16<NTV>), dim3(n_wg), dim3(256), 0, on, (const char*)pool, (const uint16_t*)q, \
+                       plan, first[cls], n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part,                      \
+                       (const uint16_t*)cand_k, (const uint16_t*)cand_v, mask, (uint16_t*)out)
+        if (cls == 0) APAR_LAUNCH(4);
+        else if (cls == 1) APAR_LAUNCH(2);
+        else APAR_LAUNCH(1);
+#undef APAR_LAUNCH
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (cls != last) {
+            if ((e = hipEventRecord(cs.join[side], on)) != hipSuccess) return e;
+            used[side] = true;
+            ++side;
+        }
     }
-    return hipGetLastError();
+    for (int k = 0; k < 2; ++k)
+        if (used[k] && (e = hipStreamWaitEvent(st, cs.join[k], 0)) != hipSuccess) return e;
+    return hipSuccess;
 }
 
 }  // namespace apar

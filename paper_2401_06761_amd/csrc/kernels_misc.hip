@@ -305,7 +305,7 @@ __global__ __launch_bounds__(64) void merge_rows(PlanDev plan, PartialBuf part, 
 
 hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
                                  PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
-                                 void* out, hipStream_t st);
+                                 void* out, ClassStreams& cs, hipStream_t st);
 
 hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const void* v, const int32_t* dst_codes,
                               int n_rows, hipStream_t st) {
@@ -363,10 +363,10 @@ hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src
 
 hipError_t launch_attention_partial(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
                                     PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
-                                    void* out, hipStream_t st) {
+                                    void* out, ClassStreams& cs, hipStream_t st) {
     if (plan.n_wg <= 0) return hipSuccess;
     if (s.dtype == APAR_BF16)
-        return launch_attention_bf16(s, pool, q, plan, n_cand, part, cand_k, cand_v, mask, out, st);
+        return launch_attention_bf16(s, pool, q, plan, n_cand, part, cand_k, cand_v, mask, out, cs, st);
     dim3 grid(plan.n_wg, s.n_kv, 256);
     if (s.d == 64)
         hipLaunchKernelGGL(attention_f32<64>, grid, dim3(64), 0, st, (const char*)pool, (const float*)q, plan, n_cand,
