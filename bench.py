@@ -148,8 +148,8 @@ def spec_loop(args, w) -> int:
 def main() -> int:
     ap_ = argparse.ArgumentParser()
     ap_.add_argument("--gpus", type=int, default=1)
-    ap_.add_argument("--steps", type=int, default=20)
-    ap_.add_argument("--warmup", type=int, default=5)
+    ap_.add_argument("--steps", type=int, default=50)
+    ap_.add_argument("--warmup", type=int, default=10)
     ap_.add_argument("--config", default="ht256", choices=["mha64", "ht256", "gqa1024", "spec128"])
     ap_.add_argument("--seed", type=int, default=0)
     ap_.add_argument("--requests", type=int, default=None, help="first n requests only (debugging)")
@@ -215,9 +215,13 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = ap.apar_profile_read(run.h)
+    calls_ms = sorted(ap.apar_profile_attention_calls(run.h))
     ap.apar_profile_enable(run.h, False)
     st1 = ap.apar_pool_stats(run.h)
     info = ap.apar_last_plan_info(run.h)
+
+    def pct(p):
+        return calls_ms[min(len(calls_ms) - 1, int(round(p * (len(calls_ms) - 1))))] if calls_ms else None
 
     K = args.steps
     attn_ms = prof.attention_kernel_ms / K
@@ -257,6 +261,7 @@ def main() -> int:
             "traffic": read_traffic(args.config),
             "algorithmic_bytes_per_launch": alg_bytes / K,
             "kernel_ms_per_launch": attn_ms,
+            "kernel_ms_median_p10_p90": [pct(0.5), pct(0.1), pct(0.9)],
         },
         "breakdown_ms_per_step": {
             "attention_kernel": attn_ms,
@@ -266,6 +271,8 @@ def main() -> int:
             "host_issue": t_host / K * 1e3,
         },
         "attention_call_thread_queries_per_s": (n_queries / K) / ((attn_ms + merge_ms) * 1e-3),
+        "attention_call_end_to_end_thread_queries_per_s":  # plan building on the host counted serially
+            (n_queries / K) / ((attn_ms + merge_ms + prof.plan_host_ms / K) * 1e-3),
         "kv_bytes": {
             "resident": st1.bytes_resident,
             "vanilla_copy_each_prefix": st1.bytes_vanilla,

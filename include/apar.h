@@ -204,11 +204,13 @@ APAR_API int apar_last_plan_info(apar_pool* pool, apar_plan_info* out);
  * numbered depth-first along their sharing tree ("rank"); a thread's query rows are cut into
  * `slices` slices of at most 16 rows, and row group = rank * slices + slice.  `which`:
  *   APAR_PLAN_WORKGROUPS  32 ints per workgroup: [0] first shared tile, [1] shared tile count,
- *                         [2] row group the shared tiles' ranges are relative to, [3] 16-row tiles per wavefront (1, 2 or 4;
- *                         workgroups are stored in the order 4, 2, 1), then
+ *                         [2] row group the shared tiles' ranges are relative to, [3] bits 0-7: 16-row tiles per wavefront
+ *                         (1, 2 or 4; workgroups are stored in the order 4, 2, 1), bits 8-31: how many
+ *                         of the shared tiles are full (every list holds its full tiles first), then
  *                         4 wavefronts x 6: first own tile, own tile count, first row group, row
  *                         group count, first partial-result row (of the thread owning the first
- *                         row group), flags (bit 0: writes output rows directly); [28..31] unused;
+ *                         row group), flags (bit 0: writes output rows directly); [28..31] full tiles at the head
+ *                         of each wavefront's own list;
  *   APAR_PLAN_TILES       2 ints per tile: block id, lo | hi << 10 | filled_slots << 20, where
  *                         [lo, hi) are the row groups the block applies to, relative to the
  *                         wavefront's first row group (own tiles) or to [2] (shared tiles);
@@ -288,6 +290,10 @@ APAR_API int apar_profile_enable(apar_pool* pool, int on);
 /* Waits for the recorded events, adds up the elapsed times since the last
  * read, stores them in out and resets the sums. */
 APAR_API int apar_profile_read(apar_pool* pool, apar_profile* out);
+/* Per-call device times (ms) of the attention kernel for the decode calls that the most recent
+ * apar_profile_read summed, in call order, so that a caller can report a median and percentiles.
+ * Stores the count in n_out; INVALID_ARG if cap is too small (n_out is still set). */
+APAR_API int apar_profile_attention_calls(apar_pool* pool, float* ms_out, int64_t cap, int64_t* n_out);
 /* Tuning knob: the most blocks one wavefront is given in one work unit (1..65536; default 512).
  * Sharing subtrees with more blocks than that are cut into several units whose partial results are
  * merged afterwards; small values exist to exercise that path. */

@@ -90,6 +90,7 @@ def _load() -> C.CDLL:
         "apar_last_plan_export": [P, I, I32P, C.c_int64, C.POINTER(C.c_int64)],
         "apar_profile_enable": [P, I],
         "apar_profile_read": [P, C.POINTER(AparProfile)],
+        "apar_profile_attention_calls": [P, C.POINTER(C.c_float), C.c_int64, C.POINTER(C.c_int64)],
         "apar_set_chunk_blocks": [P, I],
         "apar_group_create": [P, I32P, I, V, V, V, C.POINTER(P)],
         "apar_group_destroy": [P],
@@ -287,6 +288,14 @@ def apar_profile_read(pool) -> AparProfile:
     out = AparProfile()
     _check(_L().apar_profile_read(pool, C.byref(out)), "apar_profile_read")
     return out
+
+
+def apar_profile_attention_calls(pool) -> List[float]:
+    n = C.c_int64()
+    _L().apar_profile_attention_calls(pool, None, 0, C.byref(n))
+    buf = (C.c_float * max(n.value, 1))()
+    _check(_L().apar_profile_attention_calls(pool, buf, n.value, C.byref(n)), "apar_profile_attention_calls")
+    return list(buf[: n.value])
 
 
 def apar_set_chunk_blocks(pool, blocks_per_unit: int) -> None:

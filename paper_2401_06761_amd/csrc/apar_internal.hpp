@@ -69,12 +69,14 @@ constexpr int32_t kWaveSplit = 2;  // the group's four wavefronts hold the SAME 
                                    // their results are combined in LDS and wavefront 0 writes them
 constexpr int kSplitMinTiles = 16; // shorter private units are packed four to a workgroup instead
 
+// Every tile list holds its full tiles (16 filled slots) first and its open ones last, so that
+// the kernels can run the bulk of a list through a loop that knows nothing of open tiles.
 struct WgDesc {      // one 256-thread workgroup: a shared tile list, then one private list per wavefront
     int32_t coop_ofs, n_coop;   // tiles every wavefront of the group sees (staged once through LDS)
     int32_t grp_base;           // row group that the shared list's ranges are relative to
-    int32_t row_tiles;          // 16-row tiles per wavefront: 1, 2 or 4
+    int32_t row_tiles;          // bits 0-7: 16-row tiles per wavefront (1, 2 or 4); bits 8-31: full shared tiles
     WaveItem w[4];
-    int32_t pad2[4];
+    int32_t n_full[4];          // full tiles at the head of each wavefront's own list
 };
 static_assert(sizeof(WgDesc) == 128, "WgDesc is read with aligned scalar loads");
 

@@ -87,6 +87,7 @@ struct apar_pool {
     bool profiling = false;
     std::vector<EventPair> decode_events, append_events;
     std::vector<hipEvent_t> spare_events;
+    std::vector<float> last_attention_ms;  // per call, from the last profile read
     double plan_host_ms = 0.0;
     int64_t n_decode_calls = 0, n_append_calls = 0;
 };
@@ -644,6 +645,7 @@ int apar_profile_enable(apar_pool* p, int on) {
 int apar_profile_read(apar_pool* p, apar_profile* out) {
     if (!p || !out) return APAR_ERR_INVALID_ARG;
     memset(out, 0, sizeof(*out));
+    p->last_attention_ms.clear();
     if (p->dry_run) return APAR_OK;
     DeviceGuard guard(p->device);
     for (EventPair& e : p->decode_events) {
@@ -651,6 +653,7 @@ int apar_profile_read(apar_pool* p, apar_profile* out) {
         HIP_TRY(hipEventSynchronize(e.c));
         HIP_TRY(hipEventElapsedTime(&ms, e.a, e.b));
         out->attention_kernel_ms += ms;
+        p->last_attention_ms.push_back(ms);
         HIP_TRY(hipEventElapsedTime(&ms, e.b, e.c));
         out->merge_kernel_ms += ms;
         p->spare_events.push_back(e.a);
@@ -672,6 +675,15 @@ int apar_profile_read(apar_pool* p, apar_profile* out) {
     p->append_events.clear();
     p->n_decode_calls = p->n_append_calls = 0;
     p->plan_host_ms = 0.0;
+    return APAR_OK;
+}
+
+int apar_profile_attention_calls(apar_pool* p, float* ms_out, int64_t cap, int64_t* n_out) {
+    if (!p || !n_out || cap < 0 || (cap > 0 && !ms_out)) return APAR_ERR_INVALID_ARG;
+    const int64_t n = (int64_t)p->last_attention_ms.size();
+    *n_out = n;
+    if (cap < n) return APAR_ERR_INVALID_ARG;
+    if (n > 0) memcpy(ms_out, p->last_attention_ms.data(), (size_t)n * sizeof(float));
     return APAR_OK;
 }
 

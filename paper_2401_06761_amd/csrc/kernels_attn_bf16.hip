@@ -40,6 +40,8 @@
 // common path.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "apar_internal.hpp"
 
 namespace apar {
@@ -160,9 +162,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
                                                       const uint16_t* __restrict__ cand_v,
                                                       const uint8_t* __restrict__ cand_mask,
                                                       uint16_t* __restrict__ out) {
-    // two staged tiles during the shared phase; then one V-transpose scratch per wavefront; last, three
+    // four staged tiles during the shared phase; then one V-transpose scratch per wavefront; last, three
     // wavefronts' row states when a unit is split
-    __shared__ __attribute__((aligned(16))) char lds[3 * 16 * 130 * 4];
+    __shared__ __attribute__((aligned(16))) char lds[4 * kTileBytes];
+    static_assert(4 * kTileBytes >= 3 * 16 * 130 * 4 && 4 * kTileBytes >= 4 * kOpenScratch, "LDS areas overlap in time");
     char(*stage)[kTileBytes] = reinterpret_cast<char(*)[kTileBytes]>(lds);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -221,107 +224,177 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
     };
 
     // ---- shared tiles: staged once in LDS for the whole workgroup ---------------------------
+    // Tiles go through LDS in groups of four, one whole tile per wavefront: while a group is consumed
+    // from LDS, each wavefront already has its tile of the next group in flight to its registers.
+    // Full tiles come first in every list; as long as the next group is made of full tiles only, the loop
+    // contains no lane-dependent branch around a load (which would make the compiler wait for each load
+    // where it is issued), and the last groups go through a general loop.
     if (n_coop > 0) {
-        const int my_ofs = wave * 1024 + lane * 16;  // this wavefront's quarter: K piece `wave`, V piece `wave`
         const int shift = wi.grp_lo - wg->grp_base;  // shared ranges are relative to the group's base
-        // Two tiles are kept in flight: while tile t is consumed from LDS, tile t+1 sits in registers
-        // (fetched an iteration ago) on its way into the other LDS buffer and tile t+2 is being fetched.
-        u32x4 kq1, vq1, kq2 = u32x4{0u, 0u, 0u, 0u}, vq2 = u32x4{0u, 0u, 0u, 0u};
-        auto fetch = [&](int t, u32x4& kq, u32x4& vq) {
-            const char* tile = head_base + coop[t].blk * block_stride;
-            // an open block is row-major: this lane's pieces belong to token row 4*wave + g4; rows past the
-            // fill count are not fetched at all
-            if (4 * wave + g4 < ((coop[t].meta >> 20) & 31)) {
-                kq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + my_ofs));
-                vq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + my_ofs));
-            } else {
-                kq = vq = u32x4{0u, 0u, 0u, 0u};
+        const int n_coop_full = wg->row_tiles >> 8;
+        u32x4 rk[4], rv[4];
+        auto fetch_full = [&](int t) {
+            const char* tile = head_base + coop[t].blk * block_stride + lane * 16;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                rk[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + r * 1024));
+                rv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + r * 1024));
             }
         };
-        fetch(0, kq1, vq1);
-        if (n_coop > 1) fetch(1, kq2, vq2);
-        *reinterpret_cast<u32x4*>(&stage[0][my_ofs]) = kq1;
-        *reinterpret_cast<u32x4*>(&stage[0][4096 + my_ofs]) = vq1;
-        kq1 = kq2;
-        vq1 = vq2;
-        __syncthreads();
-        for (int t = 0; t < n_coop; ++t) {
-            const bool more = t + 1 < n_coop;
-            if (t + 2 < n_coop) fetch(t + 2, kq2, vq2);
+        auto fetch_any = [&](int t) {
+            if (t >= n_coop) return;
+            const int fill = (coop[t].meta >> 20) & 31;
+            if (fill == 16) {
+                fetch_full(t);
+            } else {
+                // an open block is row-major: piece r of this lane belongs to token row 4r + g4, and rows
+                // past the fill count are not fetched at all (they read as zero)
+                const char* tile = head_base + coop[t].blk * block_stride + lane * 16;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    rk[r] = rv[r] = u32x4{0u, 0u, 0u, 0u};
+                    if (4 * r + g4 < fill) {
+                        rk[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + r * 1024));
+                        rv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + r * 1024));
+                    }
+                }
+            }
+        };
+        auto to_stage = [&]() {
+            char* dst = stage[wave] + lane * 16;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                *reinterpret_cast<u32x4*>(dst + r * 1024) = rk[r];
+                *reinterpret_cast<u32x4*>(dst + 4096 + r * 1024) = rv[r];
+            }
+        };
+        auto consume = [&](int t, const char* sb, auto full_only) {
+            constexpr bool kFull = decltype(full_only)::value;
             const int meta = coop[t].meta;
-            const int lo = (meta & 1023) - shift, hi = ((meta >> 10) & 1023) - shift, valid = (meta >> 20) & 31;
+            const int lo = (meta & 1023) - shift, hi = ((meta >> 10) & 1023) - shift;
+            const int valid = kFull ? 16 : (meta >> 20) & 31;
             // does the tile touch any row group of this wavefront?
-            if (wi.n_grp > 0 && lo < wi.n_grp && hi > 0) {
-                const char* sb = stage[t & 1];
-                Frag ks[4], vs[4];
-                if (valid == 16) {
+            if (wi.n_grp == 0 || lo >= wi.n_grp || hi <= 0) return;
+            Frag ks[4], vs[4];
+            if (kFull || valid == 16) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
+                for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
-                } else {  // an open block: row-major in the stage buffer
+                for (int r = 0; r < 4; ++r) vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
+            } else {  // an open block: row-major in the stage buffer
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        ks[r].u = *reinterpret_cast<const u32x4*>(sb + c * 256 + g4 * 64 + r * 16);
-                    v_operands_from_rows(sb + 4096, 256, g4, c, vs);
-                }
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    if (NT > 1 && !touches(nt, lo, hi)) continue;
-                    f32x4 s = products(ks, st[nt]);
-                    if (valid < 16) mask_tokens(s, (1u << valid) - 1u, g4);
-                    accumulate(vs, st[nt], s, my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
-                }
+                for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + c * 256 + g4 * 64 + r * 16);
+                v_operands_from_rows(sb + 4096, 256, g4, c, vs);
             }
-            if (more) {
-                char* nb = stage[(t + 1) & 1];
-                *reinterpret_cast<u32x4*>(nb + my_ofs) = kq1;
-                *reinterpret_cast<u32x4*>(nb + 4096 + my_ofs) = vq1;
-                kq1 = kq2;
-                vq1 = vq2;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                if (NT > 1 && !touches(nt, lo, hi)) continue;
+                f32x4 s = products(ks, st[nt]);
+                if (!kFull && valid < 16) mask_tokens(s, (1u << valid) - 1u, g4);
+                accumulate(vs, st[nt], s, my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
             }
-            __syncthreads();  // tile t+1 is staged, and everyone is done reading tile t
+        };
+        int t0 = 0;
+        if (n_coop_full >= 8) {
+            fetch_full(wave);
+            for (; t0 + 8 <= n_coop_full; t0 += 4) {  // this group and the next are full tiles
+                if (t0 > 0) __syncthreads();          // everyone is done reading the previous group
+                to_stage();
+                __syncthreads();
+                fetch_full(t0 + 4 + wave);
+                for (int u = 0; u < 4; ++u) consume(t0 + u, stage[u], std::true_type{});
+            }
+        } else {
+            fetch_any(wave);
         }
+        for (; t0 < n_coop; t0 += 4) {
+            if (t0 > 0) __syncthreads();
+            if (t0 + wave < n_coop) to_stage();
+            __syncthreads();
+            fetch_any(t0 + 4 + wave);
+            const int n_here = min(4, n_coop - t0);
+            for (int u = 0; u < n_here; ++u) consume(t0 + u, stage[u], std::false_type{});
+        }
+        __syncthreads();  // the stage buffers are reused below
     }
     if (wi.n_grp == 0) return;  // a wavefront without rows only helped to fetch
 
     // ---- private tiles: straight into operand registers -------------------------------------
     // K pieces of a sealed tile are 1 KiB apart with the lanes side by side; of an open tile, 16 bytes
     // apart inside the lane's own 64 bytes of its token's row.  The V half is fetched raw either way.
+    // K registers are refilled right after the K.Q^T products and V registers after the V^T.P^T products.
     Frag k[4], v[4];
-    const int k_sealed = lane * 16, k_open = c * 256 + g4 * 64;
-    // Only the filled rows of an open tile are fetched (valid = 16 for sealed tiles: everything is).
-    auto issue_k = [&](const char* tile, int valid) {
-        const bool open = valid < 16;
-        const char* p = tile + (open ? k_open : k_sealed);
-        const int step = open ? 16 : 1024;
-        if (!open || c < valid) {
+    auto issue_k_full = [&](const char* tile) {
+        const char* p = tile + lane * 16;
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                k[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + r * step));
+        for (int r = 0; r < 4; ++r) k[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + r * 1024));
+    };
+    auto issue_v_full = [&](const char* tile) {
+        const u32x4* p = reinterpret_cast<const u32x4*>(tile + 4096) + lane;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(p + r * 64);
+    };
+    // Only the filled rows of an open tile are fetched; the others read as zero.
+    auto issue_k = [&](const char* tile, int valid) {
+        if (valid == 16) {
+            issue_k_full(tile);
         } else {
+            const char* p = tile + c * 256 + g4 * 64;
 #pragma unroll
             for (int r = 0; r < 4; ++r) k[r].u = u32x4{0u, 0u, 0u, 0u};
+            if (c < valid) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    k[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + r * 16));
+            }
         }
     };
     auto issue_v = [&](const char* tile, int valid) {
-        const u32x4* p = reinterpret_cast<const u32x4*>(tile + 4096) + lane;
+        if (valid == 16) {
+            issue_v_full(tile);
+        } else {
+            const u32x4* p = reinterpret_cast<const u32x4*>(tile + 4096) + lane;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {  // raw piece r of this lane is part of token row 4r + g4 when the tile is open
-            if (valid == 16 || 4 * r + g4 < valid) v[r].u = __builtin_nontemporal_load(p + r * 64);
-            else v[r].u = u32x4{0u, 0u, 0u, 0u};
+            for (int r = 0; r < 4; ++r) {  // raw piece r of this lane is part of token row 4r + g4
+                v[r].u = u32x4{0u, 0u, 0u, 0u};
+                if (4 * r + g4 < valid) v[r].u = __builtin_nontemporal_load(p + r * 64);
+            }
         }
     };
-    int meta = 16 << 20;
-    if (wi.n_tiles > 0) {  // (nothing before this point waits on memory when the group has no shared tiles)
-        meta = mine[0].meta;
-        const char* t0 = head_base + mine[0].blk * block_stride;
-        issue_k(t0, (meta >> 20) & 31);
-        issue_v(t0, (meta >> 20) & 31);
-    }
     char* scratch = lds + wave * kOpenScratch;
-    for (int t = 0; t < wi.n_tiles; ++t) {
+    const int n_full = min(wg->n_full[wave], wi.n_tiles);
+    int t = 0;
+    int meta = 16 << 20;
+    if (n_full > 0) {
+        // full tiles whose successor is full too: nothing but unconditional loads in this loop
+        meta = mine[0].meta;
+        const char* first = head_base + mine[0].blk * block_stride;
+        issue_k_full(first);
+        issue_v_full(first);
+        for (; t + 1 < n_full; ++t) {
+            const int lo = meta & 1023, hi = (meta >> 10) & 1023;
+            const char* tn = head_base + mine[t + 1].blk * block_stride;
+            const int meta_n = mine[t + 1].meta;
+            f32x4 s[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (NT == 1 || touches(nt, lo, hi)) s[nt] = products(k, st[nt]);
+            issue_k_full(tn);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (NT == 1 || touches(nt, lo, hi))
+                    accumulate(v, st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+            issue_v_full(tn);
+            meta = meta_n;
+        }
+    } else if (wi.n_tiles > 0) {
+        meta = mine[0].meta;
+        const char* first = head_base + mine[0].blk * block_stride;
+        issue_k(first, (meta >> 20) & 31);
+        issue_v(first, (meta >> 20) & 31);
+    }
+    // the last full tile and the open tiles
+    for (; t < wi.n_tiles; ++t) {
         const bool more = t + 1 < wi.n_tiles;
         const int lo = meta & 1023, hi = (meta >> 10) & 1023, valid = (meta >> 20) & 31;
         const char* tn = nullptr;

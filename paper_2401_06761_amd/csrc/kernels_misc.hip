@@ -152,7 +152,7 @@ __global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ poo
     // row c of row tile nt of wavefront `wave`: tile nt holds row groups nt * cap .. of the wavefront
     const int wave = blockIdx.z >> 6, nt = (blockIdx.z >> 4) & 3, c = blockIdx.z & 15;
     const WgDesc* wg = plan.wgs + blockIdx.x;
-    if (nt >= wg->row_tiles) return;
+    if (nt >= (wg->row_tiles & 255)) return;
     const WaveItem wi = wg->w[wave];
     const int rps = plan.rows_per_slice, n_sl = plan.n_slices, rpt = plan.rows_per_thread;
     const int cap = 16 / rps, jc = c / rps, within = c - jc * rps;

@@ -34,7 +34,8 @@ void PlanHost::clear() {
     wgs.clear(), tiles.clear(), dfs_threads.clear(), path_ofs.clear(), path_ids.clear();
     segs.clear(), seg_blocks.clear(), thread_last_seg.clear(), end_threads.clear(), order.clear(), stack.clear();
     path_len.clear(), narrow_items.clear(), wide_items.clear(), coop_build.clear();
-    for (WaveBuild& w : wave_build) w.tiles.clear(), w.thr_lo = w.n_thr = 0;
+    for (WaveBuild& w : wave_build) w.tiles.clear(), w.open.clear(), w.thr_lo = w.n_thr = 0;
+    coop_open.clear(), open_tmp.clear();
     n_partial_rows = n_segments = unique_blocks = unique_tokens = path_tokens = n_direct_threads = 0;
     any_partial = false;
 }
@@ -59,8 +60,6 @@ struct Builder {
         cap = 16 / rps;
     }
 
-    int32_t valid_of(const PlanHost::Segment& s, int b) const { return b == s.n_blk - 1 ? s.last_valid : B; }
-
     // fewest 16-row tiles per wavefront with which one workgroup holds `groups` row groups (4 if none does)
     int pick_row_tiles(int groups) const { return groups <= 4 * cap ? 1 : groups <= 8 * cap ? 2 : 4; }
 
@@ -81,11 +80,27 @@ struct Builder {
         }
     }
 
-    void emit_narrow(int32_t tile_ofs, int32_t n_tiles, int32_t grp_lo, int32_t n_grp, int32_t part_base, int32_t flags) {
+    void emit_narrow(int32_t tile_ofs, int32_t n_tiles, int32_t n_full, int32_t grp_lo, int32_t n_grp,
+                     int32_t part_base, int32_t flags) {
         PlanHost::NarrowItem it;
         it.item = WaveItem{tile_ofs, n_tiles, grp_lo, n_grp, part_base, flags};
         it.cost = n_tiles;
+        it.n_full = n_full;
         ph.narrow_items.push_back(it);
+    }
+
+    // Blocks [b0, b0 + nb) of segment s for row groups [lo, hi): full tiles go to `full`, the open one
+    // (only a segment's last block can be) to `open`.
+    void push_tiles(std::vector<TileRef>& full, std::vector<TileRef>& open, const PlanHost::Segment& s, int b0, int nb,
+                    int lo, int hi) {
+        const int32_t* blk = ph.seg_blocks.data() + s.first_block_pos;
+        int n_plain = nb;
+        if (b0 + nb == s.n_blk && s.last_valid < B) n_plain = nb - 1;
+        const int32_t meta = make_meta(lo, hi, B);
+        const size_t at = full.size();
+        full.resize(at + n_plain);
+        for (int b = 0; b < n_plain; ++b) full[at + b] = TileRef{blk[b0 + b], meta};
+        if (n_plain < nb) open.push_back(TileRef{blk[b0 + nb - 1], make_meta(lo, hi, s.last_valid)});
     }
 
     void emit_standalone(int32_t sid) {
@@ -103,9 +118,11 @@ struct Builder {
             const int32_t pbase = part0[sid] + c * s.n_shr;
             if (groups <= cap) {
                 const int32_t ofs = (int32_t)ph.tiles.size();
-                for (int b = b0; b < b0 + nb; ++b)
-                    ph.tiles.push_back(TileRef{ph.seg_blocks[s.first_block_pos + b], make_meta(0, groups, valid_of(s, b))});
-                emit_narrow(ofs, nb, grp0, groups, pbase, 0);
+                ph.open_tmp.clear();
+                push_tiles(ph.tiles, ph.open_tmp, s, b0, nb, 0, groups);
+                const int32_t n_full = (int32_t)ph.tiles.size() - ofs;
+                ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
+                emit_narrow(ofs, nb, n_full, grp0, groups, pbase, 0);
             } else {
                 const int nt = pick_row_tiles(groups), wcap = nt * cap;
                 for (int g0 = 0; g0 < groups; g0 += 4 * wcap) {
@@ -115,8 +132,10 @@ struct Builder {
                     wi.wg.coop_ofs = (int32_t)ph.tiles.size();
                     wi.wg.n_coop = nb;
                     wi.wg.grp_base = grp0 + g0;
-                    for (int b = b0; b < b0 + nb; ++b)
-                        ph.tiles.push_back(TileRef{ph.seg_blocks[s.first_block_pos + b], make_meta(0, gn, valid_of(s, b))});
+                    ph.open_tmp.clear();
+                    push_tiles(ph.tiles, ph.open_tmp, s, b0, nb, 0, gn);
+                    wi.wg.row_tiles |= ((int32_t)ph.tiles.size() - wi.wg.coop_ofs) << 8;
+                    ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
                     for (int k = 0; k < 4; ++k) {
                         const int lo = k * wcap, cnt = std::max(0, std::min(wcap, gn - lo));
                         wi.wg.w[k] = WaveItem{0, 0, grp0 + g0 + lo, cnt, pbase + (g0 + lo) / n_sl, 0};
@@ -145,13 +164,15 @@ struct Builder {
         const int32_t grp0 = r.t_lo * n_sl;
         if (groups <= cap) {
             const int32_t ofs = (int32_t)ph.tiles.size();
+            ph.open_tmp.clear();
             for_subtree(rid, [&](int32_t m) {
                 const PlanHost::Segment& s = ph.segs[m];
                 const int lo = (s.t_lo - r.t_lo) * n_sl, hi = lo + s.n_shr * n_sl;
-                for (int b = 0; b < s.n_blk; ++b)
-                    ph.tiles.push_back(TileRef{ph.seg_blocks[s.first_block_pos + b], make_meta(lo, hi, valid_of(s, b))});
+                push_tiles(ph.tiles, ph.open_tmp, s, 0, s.n_blk, lo, hi);
             });
-            emit_narrow(ofs, (int32_t)ph.tiles.size() - ofs, grp0, groups, pbase, flags);
+            const int32_t n_full = (int32_t)ph.tiles.size() - ofs;
+            ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
+            emit_narrow(ofs, (int32_t)ph.tiles.size() - ofs, n_full, grp0, groups, pbase, flags);
             return;
         }
         // several wavefronts: give each a contiguous range of row groups, keeping subtrees that fit
@@ -205,36 +226,38 @@ struct Builder {
                 wave_n[k] = std::max(0, std::min(wcap, groups - k * wcap));
             }
         }
-        for (PlanHost::WaveBuild& w : ph.wave_build) w.tiles.clear();
-        ph.coop_build.clear();
+        for (PlanHost::WaveBuild& w : ph.wave_build) w.tiles.clear(), w.open.clear();
+        ph.coop_build.clear(), ph.coop_open.clear();
         for_subtree(rid, [&](int32_t m) {
             const PlanHost::Segment& s = ph.segs[m];
             const int lo = (s.t_lo - r.t_lo) * n_sl, hi = lo + s.n_shr * n_sl;
             int owner = -1;
             for (int k = 0; k < 4; ++k)
                 if (wave_n[k] > 0 && lo >= wave_lo[k] && hi <= wave_lo[k] + wave_n[k]) owner = k;
-            for (int b = 0; b < s.n_blk; ++b) {
-                const int32_t blk = ph.seg_blocks[s.first_block_pos + b];
-                const int v = valid_of(s, b);
-                if (owner >= 0)
-                    ph.wave_build[owner].tiles.push_back(TileRef{blk, make_meta(lo - wave_lo[owner], hi - wave_lo[owner], v)});
-                else
-                    ph.coop_build.push_back(TileRef{blk, make_meta(lo, hi, v)});
-            }
+            if (owner >= 0)
+                push_tiles(ph.wave_build[owner].tiles, ph.wave_build[owner].open, s, 0, s.n_blk, lo - wave_lo[owner],
+                           hi - wave_lo[owner]);
+            else
+                push_tiles(ph.coop_build, ph.coop_open, s, 0, s.n_blk, lo, hi);
         });
         PlanHost::WideItem wi{};
         wi.wg.coop_ofs = (int32_t)ph.tiles.size();
-        wi.wg.n_coop = (int32_t)ph.coop_build.size();
+        wi.wg.n_coop = (int32_t)(ph.coop_build.size() + ph.coop_open.size());
         wi.wg.grp_base = grp0;
-        wi.wg.row_tiles = nt;
+        wi.wg.row_tiles = nt | ((int32_t)ph.coop_build.size() << 8);
         ph.tiles.insert(ph.tiles.end(), ph.coop_build.begin(), ph.coop_build.end());
+        ph.tiles.insert(ph.tiles.end(), ph.coop_open.begin(), ph.coop_open.end());
         int longest = 0;
         for (int k = 0; k < 4; ++k) {
             const std::vector<TileRef>& t = ph.wave_build[k].tiles;
-            wi.wg.w[k] = WaveItem{(int32_t)ph.tiles.size(), (int32_t)t.size(), grp0 + wave_lo[k], wave_n[k],
+            const std::vector<TileRef>& o = ph.wave_build[k].open;
+            const int32_t cnt = (int32_t)(t.size() + o.size());
+            wi.wg.w[k] = WaveItem{(int32_t)ph.tiles.size(), cnt, grp0 + wave_lo[k], wave_n[k],
                                   direct ? -1 : pbase + wave_lo[k] / n_sl, flags};
+            wi.wg.n_full[k] = (int32_t)t.size();
             ph.tiles.insert(ph.tiles.end(), t.begin(), t.end());
-            longest = std::max(longest, (int)t.size());
+            ph.tiles.insert(ph.tiles.end(), o.begin(), o.end());
+            longest = std::max(longest, (int)cnt);
         }
         wi.cost = nt * (2 * wi.wg.n_coop + longest);
         ph.wide_items.push_back(wi);
@@ -384,13 +407,14 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
     // 7. workgroups: by row tiles per wavefront (4, 2, 1), heaviest first within a class
     std::stable_sort(ph.wide_items.begin(), ph.wide_items.end(),
                      [](const PlanHost::WideItem& a, const PlanHost::WideItem& b) {
-                         return a.wg.row_tiles != b.wg.row_tiles ? a.wg.row_tiles > b.wg.row_tiles : a.cost > b.cost;
+                         const int ta = a.wg.row_tiles & 255, tb = b.wg.row_tiles & 255;
+                         return ta != tb ? ta > tb : a.cost > b.cost;
                      });
     ph.wgs.reserve(ph.wide_items.size() + (ph.narrow_items.size() + 3) / 4);
     ph.n_wg_class[0] = ph.n_wg_class[1] = ph.n_wg_class[2] = 0;
     for (const PlanHost::WideItem& w : ph.wide_items) {
         ph.wgs.push_back(w.wg);
-        ph.n_wg_class[w.wg.row_tiles == 4 ? 0 : w.wg.row_tiles == 2 ? 1 : 2] += 1;
+        ph.n_wg_class[(w.wg.row_tiles & 255) == 4 ? 0 : (w.wg.row_tiles & 255) == 2 ? 1 : 2] += 1;
     }
     const size_t n_wide = ph.wgs.size();
     {
@@ -408,20 +432,26 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         size_t k = 0;
         for (; k < slot.size() && ph.narrow_items[slot[k]].cost >= kSplitMinTiles; ++k) {
             const WaveItem& it = ph.narrow_items[slot[k]].item;
+            const int32_t item_full = ph.narrow_items[slot[k]].n_full;
             WgDesc wg{};
             wg.grp_base = it.grp_lo;
             wg.row_tiles = 1;
             for (int j = 0; j < 4; ++j) {
                 const int32_t b = (int32_t)((int64_t)it.n_tiles * j / 4), e = (int32_t)((int64_t)it.n_tiles * (j + 1) / 4);
                 wg.w[j] = WaveItem{it.tile_ofs + b, e - b, it.grp_lo, it.n_grp, it.part_base, it.flags | kWaveSplit};
+                wg.n_full[j] = std::max(0, std::min(e, item_full) - b);
             }
             ph.wgs.push_back(wg);
         }
         for (; k < slot.size(); k += 4) {
             WgDesc wg{};
             for (int j = 0; j < 4; ++j) {
-                if (k + j < slot.size()) wg.w[j] = ph.narrow_items[slot[k + j]].item;
-                else wg.w[j] = WaveItem{0, 0, 0, 0, -1, 0};
+                if (k + j < slot.size()) {
+                    wg.w[j] = ph.narrow_items[slot[k + j]].item;
+                    wg.n_full[j] = ph.narrow_items[slot[k + j]].n_full;
+                } else {
+                    wg.w[j] = WaveItem{0, 0, 0, 0, -1, 0};
+                }
             }
             wg.grp_base = wg.w[0].grp_lo;
             wg.row_tiles = 1;

@@ -42,14 +42,15 @@ struct PlanHost {
     std::vector<int32_t> seg_blocks, thread_last_seg, end_threads, order, stack;
     std::vector<int32_t> path_len;
     struct WaveBuild {
-        std::vector<TileRef> tiles;
+        std::vector<TileRef> tiles, open;  // full tiles; open tiles (appended after them)
         int32_t thr_lo = 0, n_thr = 0;  // pseudo-thread range (global depth-first rank * slices)
     };
     WaveBuild wave_build[4];
-    std::vector<TileRef> coop_build;
+    std::vector<TileRef> coop_build, coop_open, open_tmp;
     struct NarrowItem {
         WaveItem item;
         int32_t cost;
+        int32_t n_full;  // full tiles at the head of the item's list
     };
     std::vector<NarrowItem> narrow_items;
     struct WideItem {

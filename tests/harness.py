@@ -108,14 +108,21 @@ def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per
     direct = {}    # rank -> number of direct units
     tile_reads = 0
     for wg_index, wg in enumerate(wgs):
-        coop_ofs, n_coop, grp_base, row_tiles = wg[0], wg[1], wg[2], wg[3]
+        coop_ofs, n_coop, grp_base, row_tiles, coop_full = wg[0], wg[1], wg[2], wg[3] & 255, wg[3] >> 8
         assert row_tiles in (1, 2, 4)
         if wg_index:  # classes are stored 4, 2, 1
-            assert row_tiles <= wgs[wg_index - 1][3]
+            assert row_tiles <= wgs[wg_index - 1][3] & 255
+        # every list holds its full tiles first, then its open ones, and says how many are full
+        assert 0 <= coop_full <= n_coop
+        fills = (tiles[coop_ofs:coop_ofs + n_coop, 1] >> 20) & 31
+        assert (fills[:coop_full] == 16).all() and (fills[coop_full:] < 16).all()
         tile_reads += n_coop
         for k in range(4):
             t_ofs, n_t, g_lo, n_g, pbase, flags = wg[4 + 6 * k: 10 + 6 * k]
             assert 0 <= n_g <= row_tiles * cap
+            fills = (tiles[t_ofs:t_ofs + n_t, 1] >> 20) & 31
+            assert 0 <= wg[28 + k] <= n_t
+            assert (fills[:wg[28 + k]] == 16).all() and (fills[wg[28 + k]:] < 16).all()
             tile_reads += n_t
             if n_g == 0:
                 assert n_t == 0

@@ -225,6 +225,6 @@ def test_wide_sharing_groups_use_more_row_tiles(n_q, n_kv, fan, n_cand):
             if chunk == 512 and groups <= 16 * cap:
                 # the whole tree is one unit with the fewest row tiles that hold it
                 want = 1 if groups <= 4 * cap else 2 if groups <= 8 * cap else 4
-                assert res["partial_rows"] == 0 and len(wgs) == 1 and wgs[0][3] == want
+                assert res["partial_rows"] == 0 and len(wgs) == 1 and wgs[0][3] & 255 == want
             if groups > 16 * cap:
-                assert res["partial_rows"] > 0 and wgs[0][3] == 4
+                assert res["partial_rows"] > 0 and wgs[0][3] & 255 == 4
