@@ -134,8 +134,8 @@ def spec_loop(args, w) -> int:
                      "algorithmic_bytes_per_launch": alg / K, "kernel_ms_per_launch": attn_ms},
         "breakdown_ms_per_step": {"attention_kernel": attn_ms, "merge_kernel": prof.merge_kernel_ms / K,
                                   "append_kernels": prof.append_kernels_ms / K, "plan_host": prof.plan_host_ms / K,
-                                  "host_issue": t_host / K * 1e3},
-        "host_share_of_wall": t_host / elapsed,
+                                  "host_issue": t_host / K * 1e3, "host_waiting_for_gpu": prof.host_wait_ms / K},
+        "host_share_of_wall": (t_host - prof.host_wait_ms * 1e-3) / elapsed,
         "peak_blocks": run.peak_blocks, "peak_threads": run.peak_threads, "dry_run_s": t_dry,
         "kv_bytes": {"resident": st1.bytes_resident, "vanilla_copy_each_prefix": st1.bytes_vanilla,
                      "ratio": st1.bytes_vanilla / max(st1.bytes_resident, 1)},
@@ -269,6 +269,7 @@ def main() -> int:
             "append_kernels": append_ms,
             "plan_host": prof.plan_host_ms / K,
             "host_issue": t_host / K * 1e3,
+            "host_waiting_for_gpu": prof.host_wait_ms / K,
         },
         "attention_call_thread_queries_per_s": (n_queries / K) / ((attn_ms + merge_ms) * 1e-3),
         "attention_call_end_to_end_thread_queries_per_s":  # plan building on the host counted serially

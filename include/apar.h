@@ -101,9 +101,13 @@ typedef struct apar_profile {
     int64_t n_decode_calls;
     double attention_kernel_ms; /* sum over calls: the partial-attention kernel           */
     double merge_kernel_ms;     /* sum over calls: the merge / normalise kernel            */
-    double plan_host_ms;        /* sum over calls: host time building + staging the plan   */
+    double plan_host_ms;        /* sum over calls: host time building + staging the plan,
+                                   without the waits counted in host_wait_ms               */
     int64_t n_append_calls;
     double append_kernels_ms;   /* sum over calls: copy-on-write copies + row writes       */
+    double host_wait_ms;        /* sum over decode and append calls: host time spent waiting
+                                   for a staging buffer that the GPU had not consumed yet,
+                                   i.e. the GPU was the slower side                        */
 } apar_profile;
 
 /*

@@ -52,7 +52,8 @@ APAR_TOKEN_FORK, APAR_TOKEN_CHILD, APAR_TOKEN_EOS = -1, -2, -3
 
 class AparProfile(C.Structure):
     _fields_ = [("n_decode_calls", C.c_int64), ("attention_kernel_ms", C.c_double), ("merge_kernel_ms", C.c_double),
-                ("plan_host_ms", C.c_double), ("n_append_calls", C.c_int64), ("append_kernels_ms", C.c_double)]
+                ("plan_host_ms", C.c_double), ("n_append_calls", C.c_int64), ("append_kernels_ms", C.c_double),
+                ("host_wait_ms", C.c_double)]
 
 
 def library_path() -> str:

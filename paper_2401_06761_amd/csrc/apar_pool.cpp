@@ -88,7 +88,7 @@ struct apar_pool {
     std::vector<EventPair> decode_events, append_events;
     std::vector<hipEvent_t> spare_events;
     std::vector<float> last_attention_ms;  // per call, from the last profile read
-    double plan_host_ms = 0.0;
+    double plan_host_ms = 0.0, host_wait_ms = 0.0, wait_in_call_ms = 0.0;
     int64_t n_decode_calls = 0, n_append_calls = 0;
 };
 
@@ -121,8 +121,11 @@ int acquire_stage(apar_pool* p, size_t bytes, StageSlot** out) {
     StageSlot& s = p->stage[p->next_slot];
     p->next_slot = (p->next_slot + 1) % kStageSlots;
     if (s.pending) {
+        const auto w0 = std::chrono::steady_clock::now();
         HIP_TRY(hipEventSynchronize(s.ev));
         s.pending = false;
+        p->wait_in_call_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - w0).count();
+        if (p->profiling) p->host_wait_ms += p->wait_in_call_ms;
     }
     if (!s.ev) HIP_TRY(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
     if (s.cap < bytes) {
@@ -222,6 +225,7 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
         if (spec && (!cand_k || !cand_v || !mask)) return APAR_ERR_INVALID_ARG;
     }
     const auto t0 = std::chrono::steady_clock::now();
+    p->wait_in_call_ms = 0.0;
 
     for (int i = 0; i < n; ++i) {
         Thread* t = live_thread(p, ids[i]);
@@ -328,7 +332,8 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     s->pending = true;
     p->last_plan = info;
     if (p->profiling)
-        p->plan_host_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+        p->plan_host_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count() -
+                           p->wait_in_call_ms;
     return APAR_OK;
 }
 
@@ -671,10 +676,11 @@ int apar_profile_read(apar_pool* p, apar_profile* out) {
     out->n_decode_calls = p->n_decode_calls;
     out->n_append_calls = p->n_append_calls;
     out->plan_host_ms = p->plan_host_ms;
+    out->host_wait_ms = p->host_wait_ms;
     p->decode_events.clear();
     p->append_events.clear();
     p->n_decode_calls = p->n_append_calls = 0;
-    p->plan_host_ms = 0.0;
+    p->plan_host_ms = p->host_wait_ms = 0.0;
     return APAR_OK;
 }
 

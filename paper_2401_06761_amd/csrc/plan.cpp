@@ -32,10 +32,8 @@ namespace apar {
 
 void PlanHost::clear() {
     wgs.clear(), tiles.clear(), dfs_threads.clear(), path_ofs.clear(), path_ids.clear();
-    segs.clear(), seg_blocks.clear(), thread_last_seg.clear(), end_threads.clear(), order.clear(), stack.clear();
-    path_len.clear(), narrow_items.clear(), wide_items.clear(), coop_build.clear();
-    for (WaveBuild& w : wave_build) w.tiles.clear(), w.open.clear(), w.thr_lo = w.n_thr = 0;
-    coop_open.clear(), open_tmp.clear();
+    segs.clear(), thread_last_seg.clear(), end_threads.clear(), order.clear(), stack.clear();
+    path_len.clear(), narrow_items.clear(), wide_items.clear(), open_tmp.clear();
     n_partial_rows = n_segments = unique_blocks = unique_tokens = path_tokens = n_direct_threads = 0;
     any_partial = false;
 }
@@ -93,7 +91,7 @@ struct Builder {
     // (only a segment's last block can be) to `open`.
     void push_tiles(std::vector<TileRef>& full, std::vector<TileRef>& open, const PlanHost::Segment& s, int b0, int nb,
                     int lo, int hi) {
-        const int32_t* blk = ph.seg_blocks.data() + s.first_block_pos;
+        const int32_t* blk = s.blocks;
         int n_plain = nb;
         if (b0 + nb == s.n_blk && s.last_valid < B) n_plain = nb - 1;
         const int32_t meta = make_meta(lo, hi, B);
@@ -226,37 +224,60 @@ struct Builder {
                 wave_n[k] = std::max(0, std::min(wcap, groups - k * wcap));
             }
         }
-        for (PlanHost::WaveBuild& w : ph.wave_build) w.tiles.clear(), w.open.clear();
-        ph.coop_build.clear(), ph.coop_open.clear();
+        // first pass: who owns each segment of the subtree (a wavefront whose row groups contain all its
+        // holders, else the shared list), and how long the lists get; second pass: write the tiles in place
+        int n_plain[5] = {0, 0, 0, 0, 0}, n_open[5] = {0, 0, 0, 0, 0};  // [0]: shared list, [1 + k]: wavefront k
+        std::vector<int32_t>& visit = ph.order;
+        visit.clear();
         for_subtree(rid, [&](int32_t m) {
             const PlanHost::Segment& s = ph.segs[m];
             const int lo = (s.t_lo - r.t_lo) * n_sl, hi = lo + s.n_shr * n_sl;
             int owner = -1;
             for (int k = 0; k < 4; ++k)
                 if (wave_n[k] > 0 && lo >= wave_lo[k] && hi <= wave_lo[k] + wave_n[k]) owner = k;
-            if (owner >= 0)
-                push_tiles(ph.wave_build[owner].tiles, ph.wave_build[owner].open, s, 0, s.n_blk, lo - wave_lo[owner],
-                           hi - wave_lo[owner]);
-            else
-                push_tiles(ph.coop_build, ph.coop_open, s, 0, s.n_blk, lo, hi);
+            visit.push_back(m);
+            visit.push_back(owner);
+            const bool open = s.last_valid < B;
+            n_plain[owner + 1] += s.n_blk - (open ? 1 : 0);
+            n_open[owner + 1] += open ? 1 : 0;
         });
+        const size_t base = ph.tiles.size();
+        size_t total = 0;
+        TileRef *plain_at[5], *open_at[5];
+        size_t list_ofs[5];
+        for (int l = 0; l < 5; ++l) {
+            list_ofs[l] = base + total;
+            total += (size_t)n_plain[l] + n_open[l];
+        }
+        ph.tiles.resize(base + total);
+        for (int l = 0; l < 5; ++l) {
+            plain_at[l] = ph.tiles.data() + list_ofs[l];
+            open_at[l] = plain_at[l] + n_plain[l];
+        }
+        for (size_t i = 0; i < visit.size(); i += 2) {
+            const PlanHost::Segment& s = ph.segs[visit[i]];
+            const int owner = visit[i + 1];
+            const int rel = owner >= 0 ? wave_lo[owner] : 0;
+            const int lo = (s.t_lo - r.t_lo) * n_sl - rel, hi = lo + s.n_shr * n_sl;
+            const bool open = s.last_valid < B;
+            const int np = s.n_blk - (open ? 1 : 0);
+            const int32_t meta = make_meta(lo, hi, B);
+            TileRef* dst = plain_at[owner + 1];
+            for (int b2 = 0; b2 < np; ++b2) dst[b2] = TileRef{s.blocks[b2], meta};
+            plain_at[owner + 1] += np;
+            if (open) *open_at[owner + 1]++ = TileRef{s.blocks[np], make_meta(lo, hi, s.last_valid)};
+        }
         PlanHost::WideItem wi{};
-        wi.wg.coop_ofs = (int32_t)ph.tiles.size();
-        wi.wg.n_coop = (int32_t)(ph.coop_build.size() + ph.coop_open.size());
+        wi.wg.coop_ofs = (int32_t)list_ofs[0];
+        wi.wg.n_coop = n_plain[0] + n_open[0];
         wi.wg.grp_base = grp0;
-        wi.wg.row_tiles = nt | ((int32_t)ph.coop_build.size() << 8);
-        ph.tiles.insert(ph.tiles.end(), ph.coop_build.begin(), ph.coop_build.end());
-        ph.tiles.insert(ph.tiles.end(), ph.coop_open.begin(), ph.coop_open.end());
+        wi.wg.row_tiles = nt | (n_plain[0] << 8);
         int longest = 0;
         for (int k = 0; k < 4; ++k) {
-            const std::vector<TileRef>& t = ph.wave_build[k].tiles;
-            const std::vector<TileRef>& o = ph.wave_build[k].open;
-            const int32_t cnt = (int32_t)(t.size() + o.size());
-            wi.wg.w[k] = WaveItem{(int32_t)ph.tiles.size(), cnt, grp0 + wave_lo[k], wave_n[k],
+            const int32_t cnt = n_plain[k + 1] + n_open[k + 1];
+            wi.wg.w[k] = WaveItem{(int32_t)list_ofs[k + 1], cnt, grp0 + wave_lo[k], wave_n[k],
                                   direct ? -1 : pbase + wave_lo[k] / n_sl, flags};
-            wi.wg.n_full[k] = (int32_t)t.size();
-            ph.tiles.insert(ph.tiles.end(), t.begin(), t.end());
-            ph.tiles.insert(ph.tiles.end(), o.begin(), o.end());
+            wi.wg.n_full[k] = n_plain[k + 1];
             longest = std::max(longest, (int)cnt);
         }
         wi.cost = nt * (2 * wi.wg.n_coop + longest);
@@ -276,6 +297,14 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
     // 1. segments and their forest
     ph.thread_last_seg.resize(n);
     for (int i = 0; i < n; ++i) {
+        // the walk below hops between a thread's table, the segment marks and the refcounts of its first
+        // block, all cold: fetch them a few threads ahead
+        if (i + 16 < n) __builtin_prefetch(threads[i + 16].table);
+        if (i + 8 < n) {
+            const int32_t b0 = threads[i + 8].table[0];
+            __builtin_prefetch(seg_of + b0);
+            __builtin_prefetch(refcount + b0);
+        }
         const PlanThreadView& t = threads[i];
         ph.path_tokens += t.len;
         int pos = 0;
@@ -284,19 +313,33 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
             const int32_t first = t.table[pos];
             int32_t sid = seg_of[first];
             if (sid < 0) {
+                // refcounts never grow along a table (holders only drop out), so the run of equal
+                // refcounts ends where a galloping search says it does
                 const int32_t r = refcount[first];
                 int end = pos + 1;
-                while (end < t.n_blocks && refcount[t.table[end]] == r) ++end;
+                if (end < t.n_blocks && refcount[t.table[end]] == r) {
+                    int step = 1, good = end;  // table[good] is known to be in the run
+                    while (good + step < t.n_blocks && refcount[t.table[good + step]] == r) {
+                        good += step;
+                        step *= 2;
+                    }
+                    int bad = std::min(good + step, (int)t.n_blocks);  // first position known to be outside (or the end)
+                    while (bad - good > 1) {
+                        const int mid = good + (bad - good) / 2;
+                        if (refcount[t.table[mid]] == r) good = mid;
+                        else bad = mid;
+                    }
+                    end = good + 1;
+                }
                 sid = (int32_t)segs.size();
                 seg_of[first] = sid;
                 PlanHost::Segment s{};
-                s.first_block_pos = (int32_t)ph.seg_blocks.size();
+                s.blocks = t.table + pos;
                 s.n_blk = end - pos;
                 s.last_valid = (end == t.n_blocks) ? (int32_t)(t.len - (int64_t)(t.n_blocks - 1) * B) : B;
                 s.parent = prev;
                 s.first_child = s.last_child = s.next_sibling = -1;
                 s.unit = -1;
-                ph.seg_blocks.insert(ph.seg_blocks.end(), t.table + pos, t.table + end);
                 segs.push_back(s);
                 if (prev >= 0) {
                     if (segs[prev].last_child >= 0) segs[segs[prev].last_child].next_sibling = sid;
@@ -311,7 +354,7 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         ph.thread_last_seg[i] = prev;
         segs[prev].n_end += 1;
     }
-    for (const PlanHost::Segment& s : segs) seg_of[ph.seg_blocks[s.first_block_pos]] = -1;  // scratch left clean
+    for (const PlanHost::Segment& s : segs) seg_of[s.blocks[0]] = -1;  // scratch left clean
     const int32_t n_seg = (int32_t)segs.size();
     ph.n_segments = n_seg;
 

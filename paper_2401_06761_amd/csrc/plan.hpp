@@ -29,7 +29,7 @@ struct PlanHost {
 
     // scratch kept between calls so that steady-state planning does not allocate
     struct Segment {
-        int32_t first_block_pos;  // index into seg_blocks
+        const int32_t* blocks;    // the run inside the table of the first listed holder (tables outlive the plan build)
         int32_t n_blk, last_valid, n_shr;
         int32_t parent, first_child, last_child, next_sibling;
         int32_t n_end, end_ofs;   // listed threads whose table ends with this segment
@@ -39,14 +39,9 @@ struct PlanHost {
         int32_t n_above;          // partial results produced above it on the path (same for all its threads)
     };
     std::vector<Segment> segs;
-    std::vector<int32_t> seg_blocks, thread_last_seg, end_threads, order, stack;
+    std::vector<int32_t> thread_last_seg, end_threads, order, stack;
     std::vector<int32_t> path_len;
-    struct WaveBuild {
-        std::vector<TileRef> tiles, open;  // full tiles; open tiles (appended after them)
-        int32_t thr_lo = 0, n_thr = 0;  // pseudo-thread range (global depth-first rank * slices)
-    };
-    WaveBuild wave_build[4];
-    std::vector<TileRef> coop_build, coop_open, open_tmp;
+    std::vector<TileRef> open_tmp;
     struct NarrowItem {
         WaveItem item;
         int32_t cost;
