@@ -53,6 +53,7 @@ class SpecStep:
     forked: List[int]  # surviving thread ids that fork one child
     children: List[int]  # the children's ids, same order as `forked`
     accept_bits: np.ndarray = None  # [n, C] bool: the same accepted sets as a matrix
+    accept_masks: np.ndarray = None  # [n] uint8: the same again, bit c of byte i = candidate c of thread i
 
 
 class SpecLoopPlan:
@@ -94,6 +95,7 @@ class SpecLoopPlan:
         self.live = sorted(survivors.tolist() + children)
         st = SpecStep(self.step, live, parents, masks, accepted, finished, forked, children)
         st.accept_bits = bits
+        st.accept_masks = chain_bits.astype(np.uint8)
         self.step += 1
         return st
 

@@ -95,7 +95,7 @@ def spec_loop(args, w) -> int:
     hd = w.heads
     K = args.steps
     t0 = time.perf_counter()
-    run = SpecRun(w, K + args.warmup, n_cand=5)
+    run = SpecRun(w, K + args.warmup, n_cand=5, commit=not args.two_pass)
     t_dry = time.perf_counter() - t0
     run.build()
     if args.chunk:
@@ -126,7 +126,9 @@ def spec_loop(args, w) -> int:
         "dtype": hd.dtype, "data": "synthetic",
         "config": {"workload": f"spec128: {w.n_requests} requests, depth-2 fork trees, then a {K}-step speculative "
                                f"loop with 5 candidates per thread (fork 0.02, finish 0.01 per step); "
-                               f"{n0} -> {len(run.live)} live threads, seed {args.seed}"},
+                               f"{n0} -> {len(run.live)} live threads, seed {args.seed}",
+                   "accepted_rows": "gathered and appended in a second pass" if args.two_pass
+                   else "committed straight from the candidate arrays"},
         "candidate_queries_per_s": 5 * n_q / elapsed,
         "roofline": {"bound": "hbm", "kernel": "attention_bf16 (multi-candidate call)",
                      "achieved": (alg / K) / (attn_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -157,6 +159,9 @@ def main() -> int:
     ap_.add_argument("--churn", type=float, default=0.01)
     ap_.add_argument("--cpu-requests", type=int, default=64)
     ap_.add_argument("--no-cpu-baseline", action="store_true")
+    ap_.add_argument("--two-pass", action="store_true",
+                     help="spec128: gather the accepted rows on the caller's side and append them with "
+                          "apar_append_kv_batch instead of apar_commit_candidates")
     ap_.add_argument("--copy-calibration", action="store_true",
                      help="also run one plain 4 GiB device copy (reference for HBM byte counters)")
     args = ap_.parse_args()

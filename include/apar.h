@@ -190,6 +190,25 @@ APAR_API int apar_decode_attention(apar_pool* pool, const void* q_dev, const apa
 APAR_API int apar_decode_attention_spec(apar_pool* pool, const void* q_dev, const void* cand_k_dev,
                                const void* cand_v_dev, const uint8_t* mask_dev, int n_cand,
                                const apar_thread* threads, int n, void* out_dev, void* hip_stream);
+/*
+ * Commit of a multi-candidate step: the accepted candidates become part of each thread's
+ * sequence (Sec. 3.2, the Medusa-APAR setting: a predict-verify step keeps one root path of
+ * its candidate tree; App. C.1: sequences accept different numbers of tokens and mis-predicted
+ * slots do not count).
+ * For every listed thread i, in listed order, the candidates c whose bit is set in
+ * accept_masks[i] are appended in ascending c (a candidate's ancestors have smaller indices,
+ * so this is root -> accepted node order), their rows taken straight from
+ *   cand_k_dev, cand_v_dev : [n, n_cand, Hkv, d], device, pool dtype
+ * - the arrays the preceding apar_decode_attention_spec call was given - with no gather on
+ * the caller's side and no second pass.  Tables, refcounts and the free list end up exactly as
+ * after apar_append_kv_batch with thread i repeated once per accepted candidate.
+ *   accept_masks : [n] bytes, HOST memory (the host books need them); bits >= n_cand must be 0.
+ * A thread may be listed more than once and a mask may be 0.  All or nothing.
+ * Errors: INVALID_ARG (null pointers, n_cand outside 1..8, a bit for a missing candidate),
+ * INVALID_THREAD, OUT_OF_BLOCKS, HIP.
+ */
+APAR_API int apar_commit_candidates(apar_pool* pool, const apar_thread* threads, int n, const void* cand_k_dev,
+                           const void* cand_v_dev, int n_cand, const uint8_t* accept_masks, void* hip_stream);
 
 /* Release (Alg. 1 ReleaseCache): walks the table from its last block to its
  * first, drops one reference from each and returns a block to the pool when no

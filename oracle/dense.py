@@ -113,6 +113,16 @@ class DenseThreads:
         self._k[t] = np.concatenate([K, k], axis=0)
         self._v[t] = np.concatenate([V, v], axis=0)
 
+    def commit_candidates(self, threads: Sequence[int], cand_k: np.ndarray, cand_v: np.ndarray,
+                          accept_masks: Sequence[int]) -> None:
+        """Commit of a multi-candidate step (Sec. 3.2 Medusa-APAR; App. C.1): thread threads[i] gains the
+        candidates c with bit c of accept_masks[i] set, in ascending c, taken from cand_k[i, c], cand_v[i, c]
+        ([n, C, Hkv, d]); the others are dropped."""
+        for i, t in enumerate(threads):
+            for c in range(cand_k.shape[1]):
+                if (int(accept_masks[i]) >> c) & 1:
+                    self.append(t, cand_k[i, c], cand_v[i, c])
+
     def free(self, t: int) -> None:
         self._get(t)
         del self._k[t], self._v[t]

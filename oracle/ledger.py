@@ -159,6 +159,15 @@ class BlockLedger:
         for t in threads:
             self._append_one(t)
 
+    def commit_candidates(self, threads: Sequence[int], accept_masks: Sequence[int]) -> None:
+        """Books of a multi-candidate commit: one appended row per accepted candidate, thread by thread in
+        listed order (the same allocator walk as append_batch with each thread repeated)."""
+        rows = []
+        for t, m in zip(threads, accept_masks):
+            rows += [t] * bin(int(m)).count("1")
+        if rows:
+            self.append_batch(rows)
+
     def free(self, t: int) -> None:
         self._need(t)
         for b in reversed(self.table[t]):

@@ -81,6 +81,7 @@ def _load() -> C.CDLL:
         "apar_append_kv_batch": [P, I32P, I, V, V, V],
         "apar_decode_attention": [P, V, I32P, I, V, V],
         "apar_decode_attention_spec": [P, V, V, V, V, I, I32P, I, V, V],
+        "apar_commit_candidates": [P, I32P, I, V, V, I, C.POINTER(C.c_uint8), V],
         "apar_free_thread": [P, C.c_int32],
         "apar_thread_len": [P, C.c_int32, C.POINTER(C.c_int64)],
         "apar_thread_block_table": [P, C.c_int32, I32P, I, C.POINTER(C.c_int)],
@@ -222,6 +223,19 @@ def apar_decode_attention_spec(pool, q, cand_k, cand_v, mask, n_cand: int, threa
     arr, n = _ids(threads)
     _check(_L().apar_decode_attention_spec(pool, _ptr(q), _ptr(cand_k), _ptr(cand_v), _ptr(mask), n_cand, arr, n,
                                            _ptr(out), _stream(stream)), "apar_decode_attention_spec")
+
+
+def apar_commit_candidates(pool, threads: Sequence[int], cand_k, cand_v, n_cand: int, accept_masks, stream=None) -> None:
+    """accept_masks: one byte per listed thread (host), bit c set iff candidate c is accepted."""
+    import numpy as np
+
+    arr, n = _ids(threads)
+    masks = np.ascontiguousarray(accept_masks, dtype=np.uint8)
+    if masks.shape != (n,):
+        raise ValueError("accept_masks must hold one byte per listed thread")
+    _check(_L().apar_commit_candidates(pool, arr, n, _ptr(cand_k), _ptr(cand_v), n_cand,
+                                       masks.ctypes.data_as(C.POINTER(C.c_uint8)), _stream(stream)),
+           "apar_commit_candidates")
 
 
 def apar_free_thread(pool, thread: int) -> None:

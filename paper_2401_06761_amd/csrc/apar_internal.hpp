@@ -117,7 +117,7 @@ struct ClassStreams {
 
 // ---- launchers (defined next to their kernels) ------------------------------
 hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const void* v, const int32_t* dst_codes,
-                              int n_rows, hipStream_t st);
+                              const int32_t* src_rows, int n_rows, hipStream_t st);
 hipError_t launch_block_copies(const Shape& s, void* pool, const int32_t* src_dst_pairs, int n_pairs,
                                hipStream_t st);
 hipError_t launch_seal_blocks(const Shape& s, void* pool, const int32_t* blocks, int n_blocks, hipStream_t st);

@@ -73,7 +73,8 @@ struct apar_pool {
     std::vector<int32_t> seg_of;  // segment that starts at each block, -1 if none
     int max_unit_tiles = 512;  // longest tile list given to one wavefront
     std::vector<PlanThreadView> views;
-    std::vector<int32_t> scratch_codes, scratch_copies, scratch_seals;
+    std::vector<int32_t> scratch_codes, scratch_copies, scratch_seals, scratch_commit_src;
+    std::vector<apar_thread> scratch_commit_ids;
     apar_plan_info last_plan{};
     PlanHost plan;  // the last plan, kept for reuse of its storage and for inspection
     int32_t plan_geom[3] = {1, 1, 1};  // rows per thread, rows per slice, slices of the last plan
@@ -180,18 +181,23 @@ inline int32_t append_one(apar_pool* p, Thread& t, std::vector<int32_t>& copies,
     return code;
 }
 
+// src_rows (may be null): which row of k, v each appended row is taken from.
 int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vector<int32_t>& copies,
-               const std::vector<int32_t>& seals, const void* k, const void* v, hipStream_t st) {
+               const std::vector<int32_t>& seals, const std::vector<int32_t>* src_rows, const void* k, const void* v,
+               hipStream_t st) {
     const size_t copy_bytes = align_up(copies.size() * sizeof(int32_t), 256);
     const size_t code_bytes = align_up(codes.size() * sizeof(int32_t), 256);
-    const size_t seal_bytes = seals.size() * sizeof(int32_t);
+    const size_t seal_bytes = align_up(seals.size() * sizeof(int32_t), 256);
+    const size_t src_bytes = src_rows ? src_rows->size() * sizeof(int32_t) : 0;
+    const size_t total = copy_bytes + code_bytes + seal_bytes + src_bytes;
     StageSlot* s = nullptr;
-    int rc = acquire_stage(p, copy_bytes + code_bytes + seal_bytes, &s);
+    int rc = acquire_stage(p, total, &s);
     if (rc != APAR_OK) return rc;
     if (!copies.empty()) memcpy(s->host, copies.data(), copies.size() * sizeof(int32_t));
     memcpy(s->host + copy_bytes, codes.data(), codes.size() * sizeof(int32_t));
-    if (!seals.empty()) memcpy(s->host + copy_bytes + code_bytes, seals.data(), seal_bytes);
-    HIP_TRY(hipMemcpyAsync(s->dev, s->host, copy_bytes + code_bytes + seal_bytes, hipMemcpyHostToDevice, st));
+    if (!seals.empty()) memcpy(s->host + copy_bytes + code_bytes, seals.data(), seals.size() * sizeof(int32_t));
+    if (src_bytes) memcpy(s->host + copy_bytes + code_bytes + seal_bytes, src_rows->data(), src_bytes);
+    HIP_TRY(hipMemcpyAsync(s->dev, s->host, total, hipMemcpyHostToDevice, st));
     EventPair ev;
     if (p->profiling) {
         if ((rc = new_event(p, &ev.a)) != APAR_OK || (rc = new_event(p, &ev.b)) != APAR_OK) return rc;
@@ -199,7 +205,9 @@ int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vecto
     }
     if (!copies.empty())
         HIP_TRY(launch_block_copies(p->shape, p->kv, (const int32_t*)s->dev, (int)(copies.size() / 2), st));
-    HIP_TRY(launch_append_rows(p->shape, p->kv, k, v, (const int32_t*)(s->dev + copy_bytes), (int)codes.size(), st));
+    HIP_TRY(launch_append_rows(p->shape, p->kv, k, v, (const int32_t*)(s->dev + copy_bytes),
+                               src_bytes ? (const int32_t*)(s->dev + copy_bytes + code_bytes + seal_bytes) : nullptr,
+                               (int)codes.size(), st));
     if (!seals.empty())
         HIP_TRY(launch_seal_blocks(p->shape, p->kv, (const int32_t*)(s->dev + copy_bytes + code_bytes), (int)seals.size(), st));
     if (p->profiling) {
@@ -468,17 +476,13 @@ int apar_append_kv(apar_pool* p, apar_thread thread, const void* k_dev, const vo
     for (int i = 0; i < n_tokens; ++i) codes[i] = append_one(p, *t, copies, seals);
     if (p->dry_run) return APAR_OK;
     DeviceGuard guard(p->device);
-    return run_append(p, codes, copies, seals, k_dev, v_dev, (hipStream_t)hip_stream);
+    return run_append(p, codes, copies, seals, nullptr, k_dev, v_dev, (hipStream_t)hip_stream);
 }
 
-int apar_append_kv_batch(apar_pool* p, const apar_thread* threads, int n, const void* k_dev, const void* v_dev,
-                         void* hip_stream) {
-    if (!p || n < 0) return APAR_ERR_INVALID_ARG;
-    if (n == 0) return APAR_OK;
-    if (!threads) return APAR_ERR_INVALID_ARG;
-    if (p->dry_run ? (k_dev || v_dev) : (!k_dev || !v_dev)) return APAR_ERR_INVALID_ARG;
-    for (int i = 0; i < n; ++i)
-        if (!live_thread(p, threads[i])) return APAR_ERR_INVALID_THREAD;
+// One row per entry of `threads` (a thread may repeat), row i taken from row src_rows[i] of k_dev, v_dev
+// (row i if src_rows is null).  All or nothing.
+static int append_rows_of(apar_pool* p, const apar_thread* threads, int n, const std::vector<int32_t>* src_rows,
+                          const void* k_dev, const void* v_dev, void* hip_stream) {
     if ((int64_t)p->free_stack.size() < n) {
         // Each row takes at most one block, so only a nearly full pool needs the
         // exact count: replay the policy on scratch copies of what it reads.
@@ -519,7 +523,43 @@ int apar_append_kv_batch(apar_pool* p, const apar_thread* threads, int n, const 
     for (int i = 0; i < n; ++i) codes[i] = append_one(p, p->threads[threads[i]], copies, seals);
     if (p->dry_run) return APAR_OK;
     DeviceGuard guard(p->device);
-    return run_append(p, codes, copies, seals, k_dev, v_dev, (hipStream_t)hip_stream);
+    return run_append(p, codes, copies, seals, src_rows, k_dev, v_dev, (hipStream_t)hip_stream);
+}
+
+int apar_append_kv_batch(apar_pool* p, const apar_thread* threads, int n, const void* k_dev, const void* v_dev,
+                         void* hip_stream) {
+    if (!p || n < 0) return APAR_ERR_INVALID_ARG;
+    if (n == 0) return APAR_OK;
+    if (!threads) return APAR_ERR_INVALID_ARG;
+    if (p->dry_run ? (k_dev || v_dev) : (!k_dev || !v_dev)) return APAR_ERR_INVALID_ARG;
+    for (int i = 0; i < n; ++i)
+        if (!live_thread(p, threads[i])) return APAR_ERR_INVALID_THREAD;
+    return append_rows_of(p, threads, n, nullptr, k_dev, v_dev, hip_stream);
+}
+
+int apar_commit_candidates(apar_pool* p, const apar_thread* threads, int n, const void* cand_k_dev,
+                           const void* cand_v_dev, int n_cand, const uint8_t* accept_masks, void* hip_stream) {
+    if (!p || n < 0 || n_cand < 1 || n_cand > 8) return APAR_ERR_INVALID_ARG;
+    if (n == 0) return APAR_OK;
+    if (!threads || !accept_masks) return APAR_ERR_INVALID_ARG;
+    if (p->dry_run ? (cand_k_dev || cand_v_dev) : (!cand_k_dev || !cand_v_dev)) return APAR_ERR_INVALID_ARG;
+    if ((int64_t)n * n_cand > INT32_MAX) return APAR_ERR_INVALID_ARG;
+    std::vector<apar_thread>& ids = p->scratch_commit_ids;
+    std::vector<int32_t>& src = p->scratch_commit_src;
+    ids.clear();
+    src.clear();
+    for (int i = 0; i < n; ++i) {
+        if (!live_thread(p, threads[i])) return APAR_ERR_INVALID_THREAD;
+        const uint32_t bits = accept_masks[i];
+        if (bits >> n_cand) return APAR_ERR_INVALID_ARG;  // a candidate that does not exist
+        for (int c = 0; c < n_cand; ++c)
+            if ((bits >> c) & 1u) {
+                ids.push_back(threads[i]);
+                src.push_back(i * n_cand + c);
+            }
+    }
+    if (ids.empty()) return APAR_OK;
+    return append_rows_of(p, ids.data(), (int)ids.size(), &src, cand_k_dev, cand_v_dev, hip_stream);
 }
 
 int apar_decode_attention(apar_pool* p, const void* q_dev, const apar_thread* threads, int n, void* out_dev,

@@ -24,7 +24,8 @@ __device__ __forceinline__ float wave_sum(float x) {
 }
 
 // ---------------------------------------------------------------------------
-// Row writes.  One wavefront per (row, kv head).
+// Row writes.  One wavefront per (row, kv head).  Row i of the call is taken from
+// row src_rows[i] of k and v (from row i when src_rows is null).
 // bf16 pools keep a block that is still filling in plain row-major form (K rows
 // then V rows, 256 contiguous bytes each), so an appended row is two full-line
 // writes per half; seal_blocks_bf16 rewrites a block into matrix-core order once
@@ -32,14 +33,16 @@ __device__ __forceinline__ float wave_sum(float x) {
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void append_rows_bf16(char* __restrict__ pool, const uint16_t* __restrict__ k,
                                                        const uint16_t* __restrict__ v,
-                                                       const int32_t* __restrict__ codes, int n_kv,
+                                                       const int32_t* __restrict__ codes,
+                                                       const int32_t* __restrict__ src_rows, int n_kv,
                                                        int64_t tile_bytes) {
     const int row = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
     if (lane >= 32) return;
     const int32_t code = codes[row];
     const int slot = code & 15;
     char* tile = pool + ((int64_t)(code >> 4) * n_kv + h) * tile_bytes;
-    const uint16_t* src = (lane < 16 ? k : v) + ((int64_t)row * n_kv + h) * 128 + (lane & 15) * 8;
+    const int64_t from = src_rows ? src_rows[row] : row;
+    const uint16_t* src = (lane < 16 ? k : v) + (from * n_kv + h) * 128 + (lane & 15) * 8;
     *reinterpret_cast<uint4*>(tile + (lane < 16 ? 0 : 4096) + slot * 256 + (lane & 15) * 16) =
         *reinterpret_cast<const uint4*>(src);
 }
@@ -73,13 +76,15 @@ __global__ __launch_bounds__(256) void seal_blocks_bf16(char* __restrict__ pool,
 
 __global__ __launch_bounds__(64) void append_rows_f32(char* __restrict__ pool, const float* __restrict__ k,
                                                       const float* __restrict__ v, const int32_t* __restrict__ codes,
-                                                      int n_kv, int d, int64_t tile_bytes) {
+                                                      const int32_t* __restrict__ src_rows, int n_kv, int d,
+                                                      int64_t tile_bytes) {
     const int row = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
     const int32_t code = codes[row];
     const int slot = code & 15;
     float* tile = reinterpret_cast<float*>(pool + ((int64_t)(code >> 4) * n_kv + h) * tile_bytes);
-    const float* ksrc = k + ((int64_t)row * n_kv + h) * d;
-    const float* vsrc = v + ((int64_t)row * n_kv + h) * d;
+    const int64_t from = src_rows ? src_rows[row] : row;
+    const float* ksrc = k + (from * n_kv + h) * d;
+    const float* vsrc = v + (from * n_kv + h) * d;
     for (int x = lane; x < d; x += 64) {
         tile[slot * d + x] = ksrc[x];
         tile[16 * d + slot * d + x] = vsrc[x];
@@ -308,21 +313,23 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
                                  void* out, ClassStreams& cs, hipStream_t st);
 
 hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const void* v, const int32_t* dst_codes,
-                              int n_rows, hipStream_t st) {
+                              const int32_t* src_rows, int n_rows, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;
     // grid.x carries the rows: go through them in slices that fit the grid limits
     const int kMaxRows = 1 << 20;
     for (int r0 = 0; r0 < n_rows; r0 += kMaxRows) {
         const int nr = n_rows - r0 < kMaxRows ? n_rows - r0 : kMaxRows;
         dim3 grid(nr, s.n_kv);
-        const int64_t row_elems = (int64_t)s.n_kv * s.d;
+        // with a source index the rows are addressed from the arrays' start; without, slice by slice
+        const int64_t row_elems = src_rows ? 0 : (int64_t)s.n_kv * s.d;
+        const int32_t* from = src_rows ? src_rows + r0 : nullptr;
         if (s.dtype == APAR_BF16) {
             hipLaunchKernelGGL(append_rows_bf16, grid, dim3(64), 0, st, (char*)pool,
                                (const uint16_t*)k + r0 * row_elems, (const uint16_t*)v + r0 * row_elems,
-                               dst_codes + r0, s.n_kv, s.tile_bytes);
+                               dst_codes + r0, from, s.n_kv, s.tile_bytes);
         } else {
             hipLaunchKernelGGL(append_rows_f32, grid, dim3(64), 0, st, (char*)pool, (const float*)k + r0 * row_elems,
-                               (const float*)v + r0 * row_elems, dst_codes + r0, s.n_kv, s.d, s.tile_bytes);
+                               (const float*)v + r0 * row_elems, dst_codes + r0, from, s.n_kv, s.d, s.tile_bytes);
         }
     }
     return hipGetLastError();

@@ -130,7 +130,7 @@ class SpecRun:
     TAG_CQ, TAG_CK, TAG_CV, TAG_CHILD_K, TAG_CHILD_V = 11, 12, 13, 14, 15
 
     def __init__(self, w: Workload, n_steps: int, n_cand: int = 5, p_fork: float = 0.02, p_finish: float = 0.01,
-                 device: str = "cuda:0", fixed_bank: bool = True):
+                 device: str = "cuda:0", fixed_bank: bool = True, commit: bool = True):
         import torch
 
         from apar_workloads import SpecLoopPlan
@@ -139,6 +139,7 @@ class SpecRun:
         self.w, self.n_steps, self.C, self.device = w, n_steps, n_cand, device
         self.p_fork, self.p_finish = p_fork, p_finish
         self.fixed_bank = fixed_bank
+        self.commit = commit  # False: gather the accepted rows here and append them in a second pass
         self._Plan = SpecLoopPlan
         hd = w.heads
         # dry run: same ops, no device memory
@@ -230,14 +231,17 @@ class SpecRun:
         out = self.out[:n]
         ap.apar_decode_attention_spec(h, q, ck, cv, masks, C, ids, out)
         # accepted rows, thread by thread, each chain root -> accepted node
-        counts = st.accept_bits.sum(axis=1)
-        rep_ids = np.repeat(ids, counts)
-        flat = np.flatnonzero(st.accept_bits.reshape(-1)).astype(np.int64)  # i * C + c, thread-major
-        idx = torch.from_numpy(flat).to(self.device, non_blocking=True)
-        hd = self.w.heads
-        k_acc = ck.reshape(n * C, hd.n_kv_heads, hd.head_dim).index_select(0, idx)
-        v_acc = cv.reshape(n * C, hd.n_kv_heads, hd.head_dim).index_select(0, idx)
-        ap.apar_append_kv_batch(h, rep_ids, k_acc, v_acc)
+        if self.commit:
+            ap.apar_commit_candidates(h, ids, ck, cv, C, st.accept_masks)
+        else:
+            counts = st.accept_bits.sum(axis=1)
+            rep_ids = np.repeat(ids, counts)
+            flat = np.flatnonzero(st.accept_bits.reshape(-1)).astype(np.int64)  # i * C + c, thread-major
+            idx = torch.from_numpy(flat).to(self.device, non_blocking=True)
+            hd = self.w.heads
+            k_acc = ck.reshape(n * C, hd.n_kv_heads, hd.head_dim).index_select(0, idx)
+            v_acc = cv.reshape(n * C, hd.n_kv_heads, hd.head_dim).index_select(0, idx)
+            ap.apar_append_kv_batch(h, rep_ids, k_acc, v_acc)
         for t in st.finished:
             ap.apar_free_thread(h, t)
         kk = vv = None

@@ -319,3 +319,43 @@ def test_multi_candidate_wide_groups(dtype, fan, C):
         assert np.isfinite(got).all()
         err = np.abs(got - want).max()
         assert err <= TOL[dtype], err
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_commit_candidates_rows_tables_and_next_decode(dtype, d):
+    # several commit rounds over forked threads: rows cross block boundaries (blocks get sealed), shared
+    # tails are copied on write; afterwards every row reads back exactly and a decode sees the new rows
+    t = torch()
+    heads = HeadConfig(4, 2, d, dtype)
+    w = manual_tree([-1, 0, 0, 1, 1, 2, -1, 6], [21, 3, 30, 1, 17, 16, 5, 40], heads, seed=3, data_scale=0.5)
+    N = blocks_upper_bound(w) + 32
+    with pool_for(w, N) as pool:
+        poison(pool)
+        led = BlockLedger(N)
+        dense = DenseThreads(4, 2, d)
+        live, _ = replay_trace(w, pool, led, dense)
+        rng = np.random.default_rng(77)
+        for rnd, C in enumerate((5, 8, 1, 5, 5, 8)):
+            n = len(live)
+            ck = quantise(0.5 * rng.standard_normal((n, C, 2, d)).astype(np.float32), dtype)
+            cv = quantise(0.5 * rng.standard_normal((n, C, 2, d)).astype(np.float32), dtype)
+            masks = rng.integers(0, 1 << C, size=n).astype(np.uint8)
+            if rnd == 1:
+                masks[:] = (1 << C) - 1  # everything accepted
+            if rnd == 2:
+                masks[0] = 0
+            ap.apar_commit_candidates(pool.handle, live, to_dev(ck, dtype), to_dev(cv, dtype), C, masks)
+            led.commit_candidates(live, masks)
+            dense.commit_candidates(live, ck, cv, masks)
+            books_equal(pool.handle, led)
+        for th in live:
+            L = dense.length(th)
+            k = t.empty((L, 2, d), dtype=pool.torch_dtype, device="cuda:0")
+            v = t.empty_like(k)
+            ap.apar_read_kv_rows(pool.handle, th, 0, L, k, v)
+            t.cuda.synchronize()
+            K, V = dense.rows(th)
+            assert np.array_equal(to_host(k), K) and np.array_equal(to_host(v), V)
+        got, want = decode_both(w, pool, dense, live, step=9)
+        assert np.abs(got - want).max() <= TOL[dtype]
+        led.check_invariants()

@@ -17,13 +17,14 @@ def _f64(t):
     return t.float().cpu().numpy().astype(np.float64)
 
 
+@pytest.mark.parametrize("commit", [True, False])
 @pytest.mark.parametrize("n_req,n_steps,p_fork,p_finish", [(4, 12, 0.10, 0.06), (8, 4, 0.02, 0.01)])
-def test_spec_loop_matches_oracle_every_step(n_req, n_steps, p_fork, p_finish):
+def test_spec_loop_matches_oracle_every_step(n_req, n_steps, p_fork, p_finish, commit):
     import torch
 
     w = make_config("spec128", n_requests=n_req)
     hd = w.heads
-    run = SpecRun(w, n_steps, n_cand=5, p_fork=p_fork, p_finish=p_finish, fixed_bank=False)
+    run = SpecRun(w, n_steps, n_cand=5, p_fork=p_fork, p_finish=p_finish, fixed_bank=False, commit=commit)
     try:
         run.build()
         led = BlockLedger(run.peak_blocks + 64)
@@ -52,11 +53,15 @@ def test_spec_loop_matches_oracle_every_step(n_req, n_steps, p_fork, p_finish):
             worst = max(worst, err)
             assert err <= 2e-2, f"step {s}: max abs err {err}"
             # the same bookkeeping on the oracle side
-            ids = [t for t, chain in zip(st.live, st.accepted) for _ in chain]
-            led.append_batch(ids)
+            if commit:
+                led.commit_candidates(st.live, st.accept_masks)
+                dense.commit_candidates(st.live, ckh, cvh, st.accept_masks)
+            else:
+                ids = [t for t, chain in zip(st.live, st.accepted) for _ in chain]
+                led.append_batch(ids)
+                for i, (t, chain) in enumerate(zip(st.live, st.accepted)):
+                    dense.append(t, ckh[i, chain], cvh[i, chain])
             peak = max(peak, led.used_blocks())
-            for i, (t, chain) in enumerate(zip(st.live, st.accepted)):
-                dense.append(t, ckh[i, chain], cvh[i, chain])
             for t in st.finished:
                 led.free(t), dense.free(t)
             for t, child in zip(st.forked, st.children):

@@ -228,3 +228,51 @@ def test_wide_sharing_groups_use_more_row_tiles(n_q, n_kv, fan, n_cand):
                 assert res["partial_rows"] == 0 and len(wgs) == 1 and wgs[0][3] & 255 == want
             if groups > 16 * cap:
                 assert res["partial_rows"] > 0 and wgs[0][3] & 255 == 4
+
+
+def test_commit_candidates_books_and_errors():
+    # dry-run pools: the commit leaves the same books as one batched append per accepted candidate
+    heads = HeadConfig(4, 2, 64, "f32")
+    w = manual_tree([-1, 0, 0, 2, 2, -1], [30, 16, 9, 1, 25, 3], heads)
+    N = blocks_upper_bound(w) + 8
+    rng = np.random.default_rng(5)
+    with pool_for(w, N, dry_run=True) as pool:
+        led = BlockLedger(N)
+        live, _ = replay_trace(w, pool, led, dry_run=True)
+        for C in (1, 5, 8):
+            masks = rng.integers(0, 1 << C, size=len(live)).astype(np.uint8)
+            masks[0] = 0
+            ap.apar_commit_candidates(pool.handle, live, None, None, C, masks)
+            led.commit_candidates(live, masks)
+            books_equal(pool.handle, led)
+        # a thread may repeat
+        ap.apar_commit_candidates(pool.handle, [live[1], live[1]], None, None, 3, [0b101, 0b010])
+        led.commit_candidates([live[1], live[1]], [0b101, 0b010])
+        books_equal(pool.handle, led)
+        for bad in (lambda: ap.apar_commit_candidates(pool.handle, live[:1], None, None, 3, [0b1000]),
+                    lambda: ap.apar_commit_candidates(pool.handle, live[:1], None, None, 9, [1]),
+                    lambda: ap.apar_commit_candidates(pool.handle, live[:1], None, None, 0, [0])):
+            with pytest.raises(ap.AparError) as e:
+                bad()
+            assert e.value.status == -1
+        with pytest.raises(ap.AparError) as e:
+            ap.apar_commit_candidates(pool.handle, [10 ** 6], None, None, 2, [1])
+        assert e.value.status == -2
+        books_equal(pool.handle, led)
+    # all or nothing when the pool runs out
+    with ap.Pool(4, 2, 64, "f32", 3, dry_run=True) as pool:
+        led = BlockLedger(3)
+        t = ap.apar_thread_create(pool.handle)
+        led.create()
+        ap.apar_append_kv(pool.handle, t, None, None, 30)
+        led.append(t, 30)
+        kid = ap.apar_fork(pool.handle, t, 1)[0]
+        led.fork(t, 1)
+        # t needs a copy of the shared tail (1 block) and kid another copy plus a new block: 3 > 1 free
+        with pytest.raises(ap.AparError) as e:
+            ap.apar_commit_candidates(pool.handle, [t, kid], None, None, 5, [0b00001, 0b11111])
+        assert e.value.status == -3
+        books_equal(pool.handle, led)
+        ap.apar_commit_candidates(pool.handle, [t, kid], None, None, 5, [0b00001, 0b00000])
+        led.commit_candidates([t, kid], [1, 0])
+        books_equal(pool.handle, led)

@@ -301,3 +301,23 @@ def test_ledger_tokens_equal_dense_rows_on_random_traces():
             led.check_invariants()
             for x in led.live():
                 assert store.read(led, x) == [int(v) for v in dense.rows(x)[0][:, 0, 0]]
+
+
+def test_commit_candidates_books_equal_one_append_per_accepted_candidate():
+    import copy
+
+    led = BlockLedger(64)
+    a = led.create()
+    led.append(a, 21)
+    kids = led.fork(a, 3)
+    led.append(kids[0], 11)  # tail at slot 0 of a new block afterwards (21 + 11 = 32)
+    one = copy.deepcopy(led)
+    masks = [0b10110, 0b00000, 0b11111, 0b00001]
+    led.commit_candidates([a] + kids, masks)
+    for t, m in zip([a] + kids, masks):
+        for _ in range(bin(m).count("1")):
+            one.append(t, 1)
+    assert led.table == one.table and led.len == one.len and led.ref == one.ref
+    assert led.free_stack == one.free_stack and led.cow_copies == one.cow_copies
+    assert [led.len[t] for t in [a] + kids] == [24, 32, 26, 22]
+    led.check_invariants()

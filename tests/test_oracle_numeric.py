@@ -286,3 +286,39 @@ def test_empty_thread_is_rejected():
     t = o.create()
     with pytest.raises(ValueError):
         o.decode(np.zeros((1, 1, 2)), [t])
+
+
+# commit of a multi-candidate step -------------------------------------------------
+def test_commit_keeps_exactly_the_accepted_rows_in_candidate_order():
+    # values reveal which rows were kept: candidate c of thread i carries the number 100*i + c
+    n_kv, d, C = 1, 2, 5
+    o = DenseThreads(1, n_kv, d)
+    a, b = o.create(), o.create()
+    o.append(a, np.full((3, n_kv, d), -1.0), np.full((3, n_kv, d), -1.0))
+    o.append(b, np.full((1, n_kv, d), -2.0), np.full((1, n_kv, d), -2.0))
+    ck = np.array([[[[100.0 * i + c] * d] for c in range(C)] for i in range(2)])
+    cv = -ck
+    o.commit_candidates([a, b], ck, cv, [0b01101, 0b00000])
+    Ka, Va = o.rows(a)
+    assert Ka[:, 0, 0].tolist() == [-1.0, -1.0, -1.0, 0.0, 2.0, 3.0] and Va[3:, 0, 1].tolist() == [-0.0, -2.0, -3.0]
+    assert o.length(b) == 1  # nothing accepted: nothing changes
+    # a thread listed twice gains both selections, in listed order
+    o.commit_candidates([b, b], ck, cv, [0b10000, 0b00001])
+    assert o.rows(b)[0][:, 0, 0].tolist() == [-2.0, 4.0, 100.0]
+
+
+def test_commit_then_decode_equals_the_verified_candidate_row():
+    # a chain of candidates, a prefix of it accepted: the decode output the accepted node's row got in
+    # the multi-candidate step is the output of an ordinary decode after the commit
+    n_q, n_kv, d, C = 2, 1, 4, 5
+    r = _rng(23)
+    o = DenseThreads(n_q, n_kv, d)
+    t = o.create()
+    o.append(t, r.standard_normal((9, n_kv, d)), r.standard_normal((9, n_kv, d)))
+    q = r.standard_normal((1, C, n_q, d))
+    ck, cv = r.standard_normal((1, C, n_kv, d)), r.standard_normal((1, C, n_kv, d))
+    chain = np.array([[(1 << (c + 1)) - 1 for c in range(C)]], dtype=np.uint8)
+    spec = o.decode_spec(q, ck, cv, chain, [t])[0]
+    o.commit_candidates([t], ck, cv, [0b00111])
+    assert o.length(t) == 12
+    np.testing.assert_allclose(o.decode(q[0, 2][None], [t])[0], spec[2], atol=1e-14)
