@@ -14,7 +14,9 @@ Readings fixed here (the paper is silent on them):
   * grouped-query attention: q head h reads kv head h // (Hq / Hkv);
   * multi-candidate step (Medusa-style verification, Sec. 3.2 / App. C.1):
     candidate c attends to all cached rows, then to candidate c' iff bit c' of
-    mask row c is set; candidates' K,V are passed alongside and are not cached.
+    mask row c is set; candidates' K,V are passed alongside and are not cached;
+  * segment prefill / training mask: the queries of a segment are the thread's
+    last m positions, whose rows are already cached; a query sees its own row.
 
 Parity pins for every function here live in tests/test_oracle_numeric.py.
 """
@@ -151,6 +153,29 @@ class DenseThreads:
         for i, t in enumerate(threads):
             K, V = self._get(t)
             out[i] = attend(q[i], K, V, self.scale)
+        return out
+
+    def prefill(self, q: np.ndarray, threads: Sequence[int], m: Sequence[int]) -> np.ndarray:
+        """Tree-masked attention for whole segments (Sec. 2.2 "Training attention": a token attends only to
+        the tokens on its path to the root, causally; the same mask serves the prompt / segment prefill).
+
+        The last m[i] rows of thread threads[i] are the query tokens' own rows: query r of thread i sits at
+        position len_i - m[i] + r and attends to rows 0 .. that position of the thread (its ancestors' rows
+        up to each fork point, then its own rows up to and including itself).
+        q: [sum(m), Hq, d], thread 0's m[0] queries first.  Returns the same shape.
+        """
+        q = np.asarray(q, dtype=np.float64)
+        out = np.empty(q.shape, dtype=np.float64)
+        row = 0
+        for t, mi in zip(threads, m):
+            K, V = self._get(t)
+            L = K.shape[0]
+            if mi < 1 or mi > L:
+                raise ValueError("m must be in 1..len")
+            for r in range(mi):
+                last = L - mi + r
+                out[row] = attend(q[row], K[: last + 1], V[: last + 1], self.scale)
+                row += 1
         return out
 
     def decode_spec(self, q: np.ndarray, cand_k: np.ndarray, cand_v: np.ndarray,

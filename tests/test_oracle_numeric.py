@@ -322,3 +322,84 @@ def test_commit_then_decode_equals_the_verified_candidate_row():
     o.commit_candidates([t], ck, cv, [0b00111])
     assert o.length(t) == 12
     np.testing.assert_allclose(o.decode(q[0, 2][None], [t])[0], spec[2], atol=1e-14)
+
+
+# prefill: the tree mask over whole segments -----------------------------------------
+def test_prefill_of_an_unforked_thread_is_causal_sdpa():
+    n_q, n_kv, d, T = 4, 2, 8, 37
+    r = _rng(31)
+    o = DenseThreads(n_q, n_kv, d)
+    t = o.create()
+    K, V = r.standard_normal((T, n_kv, d)), r.standard_normal((T, n_kv, d))
+    o.append(t, K, V)
+    q = r.standard_normal((T, n_q, d))
+    got = o.prefill(q, [t], [T])
+    qt = torch.from_numpy(q).permute(1, 0, 2)[None]                          # [1, Hq, T, d]
+    kt = torch.from_numpy(np.repeat(K, n_q // n_kv, axis=1)).permute(1, 0, 2)[None]
+    vt = torch.from_numpy(np.repeat(V, n_q // n_kv, axis=1)).permute(1, 0, 2)[None]
+    want = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, is_causal=True)[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(got, want, atol=1e-12)
+    # the last m queries only: the same rows of the full result
+    np.testing.assert_allclose(o.prefill(q[-5:], [t], [5]), want[-5:], atol=1e-12)
+    # m = 1 is the decode step
+    np.testing.assert_allclose(o.prefill(q[-1:], [t], [1])[0], o.decode(q[-1:], [t])[0], atol=1e-14)
+
+
+def test_prefill_of_a_tree_equals_sdpa_under_the_explicit_tree_mask():
+    # nodes in creation order; every node's segment is prefetched as one thread.  The reference lays all
+    # tokens of the tree side by side and masks token i -> token j by the definition: j's node is i's node
+    # or an ancestor of it, and j comes no later than i where they share a node.
+    parents = [-1, 0, 0, 1, 1, 2]
+    seg = [5, 3, 4, 2, 6, 1]
+    n_q, n_kv, d = 2, 1, 4
+    r = _rng(37)
+    o = DenseThreads(n_q, n_kv, d)
+    tid = {}
+    Kn = [r.standard_normal((s, n_kv, d)) for s in seg]
+    Vn = [r.standard_normal((s, n_kv, d)) for s in seg]
+    Qn = [r.standard_normal((s, n_q, d)) for s in seg]
+    kids = {i: [j for j, p in enumerate(parents) if p == i] for i in range(len(parents))}
+    order = []
+
+    def visit(i):
+        o.append(tid[i], Kn[i], Vn[i])
+        order.append(i)
+        if kids[i]:
+            for j, t in zip(kids[i], o.fork(tid[i], len(kids[i]))):
+                tid[j] = t
+            for j in kids[i]:
+                visit(j)
+
+    tid[0] = o.create()
+    visit(0)
+    got = o.prefill(np.concatenate([Qn[i] for i in order]), [tid[i] for i in order], [seg[i] for i in order])
+    # explicit mask over the concatenated tokens
+    node_of = np.concatenate([[i] * seg[i] for i in order])
+    pos_in = np.concatenate([np.arange(seg[i]) for i in order])
+    anc = {i: set() for i in range(len(parents))}
+    for i in range(len(parents)):
+        a = parents[i]
+        while a >= 0:
+            anc[i].add(a)
+            a = parents[a]
+    N = len(node_of)
+    mask = np.zeros((N, N), dtype=bool)
+    for i in range(N):
+        for j in range(N):
+            mask[i, j] = (node_of[j] in anc[node_of[i]]) or (node_of[j] == node_of[i] and pos_in[j] <= pos_in[i])
+    qt = torch.from_numpy(np.concatenate([Qn[i] for i in order])).permute(1, 0, 2)[None]
+    kt = torch.from_numpy(np.repeat(np.concatenate([Kn[i] for i in order]), n_q, axis=1)).permute(1, 0, 2)[None]
+    vt = torch.from_numpy(np.repeat(np.concatenate([Vn[i] for i in order]), n_q, axis=1)).permute(1, 0, 2)[None]
+    want = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, attn_mask=torch.from_numpy(mask))[0]
+    np.testing.assert_allclose(got, want.permute(1, 0, 2).numpy(), atol=1e-12)
+    # a sibling's tokens are invisible: changing node 1's values leaves node 2's rows alone
+    assert not mask[node_of == 2][:, node_of == 1].any()
+
+
+def test_prefill_rejects_bad_lengths():
+    o = DenseThreads(1, 1, 2)
+    t = o.create()
+    o.append(t, np.ones((3, 1, 2)), np.ones((3, 1, 2)))
+    for m in (0, 4):
+        with pytest.raises(ValueError):
+            o.prefill(np.ones((max(m, 1), 1, 2)), [t], [m])
