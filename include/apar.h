@@ -210,6 +210,23 @@ APAR_API int apar_decode_attention_spec(apar_pool* pool, const void* q_dev, cons
 APAR_API int apar_commit_candidates(apar_pool* pool, const apar_thread* threads, int n, const void* cand_k_dev,
                            const void* cand_v_dev, int n_cand, const uint8_t* accept_masks, void* hip_stream);
 
+/*
+ * Prefill attention under the paragraph-tree mask (Sec. 2.2 "Training attention", Fig. 2: a token
+ * attends only to the tokens on its path to the root, causally; the same mask serves the prefill of
+ * a prompt or of a whole segment at inference).  The last m[i] cached rows of listed thread i are
+ * its query tokens' own rows - append them first -: query r (0 <= r < m[i]) sits at position
+ * len_i - m[i] + r and attends to rows 0 .. that position of the thread, i.e. to its ancestors'
+ * rows up to each fork point and to its own rows up to and including itself.  Listing every node
+ * of a paragraph tree, each with its own segment length as m, computes the attention of the whole
+ * tree in one call; m[i] = 1 is the decode step.
+ *   q_dev, out_dev : [sum(m), Hq, d], pool dtype, device; thread 0's m[0] query tokens first.
+ *   threads, m     : host arrays of n entries (a thread may be listed more than once).
+ * Only pools whose Hq / Hkv divides 16 are supported.  Nothing is written but out_dev.
+ * Errors: INVALID_THREAD, INVALID_ARG (null pointers, m[i] outside 1..len_i), UNSUPPORTED, HIP.
+ */
+APAR_API int apar_prefill_attention(apar_pool* pool, const void* q_dev, const apar_thread* threads, const int32_t* m,
+                           int n, void* out_dev, void* hip_stream);
+
 /* Release (Alg. 1 ReleaseCache): walks the table from its last block to its
  * first, drops one reference from each and returns a block to the pool when no
  * thread holds it any more.  Errors: INVALID_THREAD. */

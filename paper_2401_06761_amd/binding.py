@@ -82,6 +82,7 @@ def _load() -> C.CDLL:
         "apar_decode_attention": [P, V, I32P, I, V, V],
         "apar_decode_attention_spec": [P, V, V, V, V, I, I32P, I, V, V],
         "apar_commit_candidates": [P, I32P, I, V, V, I, C.POINTER(C.c_uint8), V],
+        "apar_prefill_attention": [P, V, I32P, I32P, I, V, V],
         "apar_free_thread": [P, C.c_int32],
         "apar_thread_len": [P, C.c_int32, C.POINTER(C.c_int64)],
         "apar_thread_block_table": [P, C.c_int32, I32P, I, C.POINTER(C.c_int)],
@@ -236,6 +237,15 @@ def apar_commit_candidates(pool, threads: Sequence[int], cand_k, cand_v, n_cand:
     _check(_L().apar_commit_candidates(pool, arr, n, _ptr(cand_k), _ptr(cand_v), n_cand,
                                        masks.ctypes.data_as(C.POINTER(C.c_uint8)), _stream(stream)),
            "apar_commit_candidates")
+
+
+def apar_prefill_attention(pool, q, threads: Sequence[int], m: Sequence[int], out, stream=None) -> None:
+    arr, n = _ids(threads)
+    marr, nm = _ids(m)
+    if nm != n:
+        raise ValueError("one m per listed thread")
+    _check(_L().apar_prefill_attention(pool, _ptr(q), arr, marr, n, _ptr(out), _stream(stream)),
+           "apar_prefill_attention")
 
 
 def apar_free_thread(pool, thread: int) -> None:

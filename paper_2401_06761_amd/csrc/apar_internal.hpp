@@ -55,7 +55,9 @@ struct TileRef {     // one block to read, and the row groups it applies to
     int32_t blk;
     int32_t meta;    // lo | hi << 10 | valid << 20: row groups [lo, hi) relative to the list owner's first
                      // row group (the workgroup's for shared lists, the wavefront's for its own list);
-                     // valid = filled token slots (1..16)
+                     // valid = filled token slots (1..16).  Bit 30 marks a causal tile (prefill): row
+                     // group lo sees only the first `first` slots (bits 25-29, 1..16), group lo + 1 one
+                     // more, and so on up to valid.  Causal tiles count as open when lists are ordered.
 };
 
 struct WaveItem {    // what one wavefront computes
@@ -83,7 +85,7 @@ static_assert(sizeof(WgDesc) == 128, "WgDesc is read with aligned scalar loads")
 struct PlanDev {              // device pointers of one staged plan
     const WgDesc* wgs;
     const TileRef* tiles;
-    const int32_t* dfs_threads;  // rank -> index into the listed threads
+    const int32_t* dfs_threads;  // rank -> index into the listed threads (null: the identity)
     const int32_t* path_ofs;     // [n_threads + 1], by listed index
     const int32_t* path_ids;     // partial-result rows to merge for each listed thread (none: written directly)
     int32_t n_wg;

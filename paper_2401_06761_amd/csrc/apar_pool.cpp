@@ -73,6 +73,7 @@ struct apar_pool {
     std::vector<int32_t> seg_of;  // segment that starts at each block, -1 if none
     int max_unit_tiles = 512;  // longest tile list given to one wavefront
     std::vector<PlanThreadView> views;
+    std::vector<PrefillThreadView> prefill_views;
     std::vector<int32_t> scratch_codes, scratch_copies, scratch_seals, scratch_commit_src;
     std::vector<apar_thread> scratch_commit_ids;
     apar_plan_info last_plan{};
@@ -345,6 +346,81 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     return APAR_OK;
 }
 
+int prefill_common(apar_pool* p, const void* q, const apar_thread* ids, const int32_t* m, int n, void* out,
+                   void* stream) {
+    if (!p || n < 0) return APAR_ERR_INVALID_ARG;
+    if (n == 0) return APAR_OK;
+    if (!ids || !m) return APAR_ERR_INVALID_ARG;
+    if (p->dry_run ? (q || out) : (!q || !out)) return APAR_ERR_INVALID_ARG;
+    const auto t0 = std::chrono::steady_clock::now();
+    p->wait_in_call_ms = 0.0;
+    std::vector<PrefillThreadView>& views = p->prefill_views;
+    views.resize(n);
+    int64_t rows = 0, attended = 0;
+    for (int i = 0; i < n; ++i) {
+        Thread* t = live_thread(p, ids[i]);
+        if (!t) return APAR_ERR_INVALID_THREAD;
+        if (m[i] < 1 || m[i] > t->len) return APAR_ERR_INVALID_ARG;
+        views[i] = PrefillThreadView{t->table.data(), (int32_t)t->table.size(), t->len, m[i], rows};
+        rows += m[i];
+        attended += (int64_t)m[i] * (t->len - m[i]) + (int64_t)m[i] * (m[i] + 1) / 2;
+    }
+    if (rows > INT32_MAX / 2) return APAR_ERR_UNSUPPORTED;
+    PlanHost& ph = p->plan;
+    int rc = build_prefill_plan(views.data(), n, p->shape.group, ph);
+    if (rc != APAR_OK) return rc;
+    apar_plan_info info{};
+    info.n_threads = n;
+    info.n_units = (int64_t)ph.wgs.size() * p->shape.n_kv;
+    info.path_tokens = attended;  // (query token, attended row) pairs
+    const int64_t e = p->shape.dtype == APAR_F32 ? 4 : 2;
+    info.algorithmic_bytes = 2 * rows * p->shape.n_q * p->shape.d * e;  // queries in, outputs out; K,V reads depend on caching
+    p->plan_geom[0] = p->plan_geom[1] = p->shape.group;
+    p->plan_geom[2] = 1;
+    p->last_plan = info;
+    if (p->dry_run) return APAR_OK;
+    DeviceGuard guard(p->device);
+    hipStream_t st = (hipStream_t)stream;
+    const size_t wg_bytes = align_up(ph.wgs.size() * sizeof(WgDesc), 256);
+    const size_t tile_bytes = ph.tiles.size() * sizeof(TileRef);
+    StageSlot* s = nullptr;
+    if ((rc = acquire_stage(p, wg_bytes + tile_bytes, &s)) != APAR_OK) return rc;
+    memcpy(s->host, ph.wgs.data(), ph.wgs.size() * sizeof(WgDesc));
+    if (tile_bytes) memcpy(s->host + wg_bytes, ph.tiles.data(), tile_bytes);
+    HIP_TRY(hipMemcpyAsync(s->dev, s->host, wg_bytes + tile_bytes, hipMemcpyHostToDevice, st));
+    PlanDev pd{};
+    pd.wgs = (const WgDesc*)s->dev;
+    pd.tiles = (const TileRef*)(s->dev + wg_bytes);
+    pd.dfs_threads = nullptr;  // a row group is a query token, numbered as q_dev's rows are
+    pd.path_ofs = pd.path_ids = nullptr;
+    pd.n_wg = (int32_t)ph.wgs.size();
+    for (int k = 0; k < 3; ++k) pd.n_wg_class[k] = ph.n_wg_class[k];
+    pd.n_threads = (int32_t)rows;
+    pd.rows_per_thread = pd.rows_per_slice = p->shape.group;
+    pd.n_slices = 1;
+    EventPair ev;
+    if (p->profiling) {
+        if ((rc = new_event(p, &ev.a)) != APAR_OK || (rc = new_event(p, &ev.b)) != APAR_OK ||
+            (rc = new_event(p, &ev.c)) != APAR_OK)
+            return rc;
+        HIP_TRY(hipEventRecord(ev.a, st));
+    }
+    HIP_TRY(launch_attention_partial(p->shape, p->kv, q, pd, 1, p->part, nullptr, nullptr, nullptr, out,
+                                     p->class_streams, st));
+    if (p->profiling) {
+        HIP_TRY(hipEventRecord(ev.b, st));
+        HIP_TRY(hipEventRecord(ev.c, st));
+        p->decode_events.push_back(ev);
+        p->n_decode_calls += 1;
+    }
+    HIP_TRY(hipEventRecord(s->ev, st));
+    s->pending = true;
+    if (p->profiling)
+        p->plan_host_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count() -
+                           p->wait_in_call_ms;
+    return APAR_OK;
+}
+
 }  // namespace
 
 // ===========================================================================
@@ -571,6 +647,11 @@ int apar_decode_attention_spec(apar_pool* p, const void* q_dev, const void* cand
                                const uint8_t* mask_dev, int n_cand, const apar_thread* threads, int n, void* out_dev,
                                void* hip_stream) {
     return decode_common(p, q_dev, cand_k_dev, cand_v_dev, mask_dev, n_cand, threads, n, out_dev, hip_stream, true);
+}
+
+int apar_prefill_attention(apar_pool* p, const void* q_dev, const apar_thread* threads, const int32_t* m, int n,
+                           void* out_dev, void* hip_stream) {
+    return prefill_common(p, q_dev, threads, m, n, out_dev, hip_stream);
 }
 
 int apar_free_thread(apar_pool* p, apar_thread thread) {

@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         const int grp = wi.grp_lo + nt * cap + jc;
         rank = grp / n_sl;
         rr = (grp - rank * n_sl) * rps + within;
-        const int listed = plan.dfs_threads[rank];
+        const int listed = plan.dfs_threads ? plan.dfs_threads[rank] : rank;
         const int cc = rr / group, hq = kvh * group + (rr - cc * group);
         qrow = ((int64_t)listed * n_cand + cc) * n_q + hq;
         slot = ((int64_t)(wi.part_base + rank - wi.grp_lo / n_sl) * n_cand + cc) * n_q + hq;
@@ -218,6 +218,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             for (int kk = 0; kk < 4; ++kk) st[nt].q[kk].u = qp[kk];
         }
     }
+    // token slots of a tile that the row `ahead` row groups past the tile's first one may see: the filled
+    // ones; of a causal tile (bit 30) `first` slots (bits 25-29) for the first row group and one more for
+    // every further one
+    auto visible = [](int meta, int ahead) -> uint32_t {
+        const int fill = (meta >> 20) & 31;
+        const int limit = (meta >> 30) ? min(fill, max(0, ((meta >> 25) & 31) + ahead)) : fill;
+        return (1u << limit) - 1u;
+    };
     // does a tile touch row tile nt at all?  (wavefront-uniform)
     auto touches = [&](int nt, int lo, int hi) -> bool {
         return lo < min((nt + 1) * cap, wi.n_grp) && hi > nt * cap;
@@ -290,7 +298,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             for (int nt = 0; nt < NT; ++nt) {
                 if (NT > 1 && !touches(nt, lo, hi)) continue;
                 f32x4 s = products(ks, st[nt]);
-                if (!kFull && valid < 16) mask_tokens(s, (1u << valid) - 1u, g4);
+                if (!kFull && (valid < 16 || (meta >> 30))) mask_tokens(s, visible(meta, my_j[nt] - lo), g4);
                 accumulate(vs, st[nt], s, my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
             }
         };
@@ -422,7 +430,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             if (NT > 1 && !touches(nt, lo, hi)) continue;
-            if (valid < 16) mask_tokens(s[nt], (1u << valid) - 1u, g4);
+            if (valid < 16 || (meta >> 30)) mask_tokens(s[nt], visible(meta, my_j[nt] - lo), g4);
             accumulate(v, st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
         }
         if (more) issue_v(tn, (meta_n >> 20) & 31);
@@ -481,7 +489,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         const int rank_lo = wi.grp_lo / n_sl, rank_hi = (wi.grp_lo + wi.n_grp - 1) / n_sl;
         const int64_t tok_stride = (int64_t)n_kv * 256;  // bytes between candidate rows of one kv head
         for (int ru = rank_lo; ru <= rank_hi; ++ru) {
-            const int listed_u = plan.dfs_threads[ru];
+            const int listed_u = plan.dfs_threads ? plan.dfs_threads[ru] : ru;
             const int64_t base = ((int64_t)listed_u * n_cand * n_kv + kvh) * 256;
             const char* kb = reinterpret_cast<const char*>(cand_k) + base;
             const char* vb = reinterpret_cast<const char*>(cand_v) + base;

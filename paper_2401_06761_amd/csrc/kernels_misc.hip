@@ -165,7 +165,7 @@ __global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ poo
     const int grp = wi.grp_lo + j;
     const int rank = grp / n_sl, rr = (grp - rank * n_sl) * rps + within;
     if (jc >= cap || j >= wi.n_grp || rr >= rpt) return;
-    const int listed = plan.dfs_threads[rank];
+    const int listed = plan.dfs_threads ? plan.dfs_threads[rank] : rank;
     const int cc = rr / group, hq = kvh * group + (rr - cc * group);
     const int64_t qrow = ((int64_t)listed * n_cand + cc) * n_q + hq;
     float qv[E], acc[E];
@@ -183,8 +183,11 @@ __global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ poo
         const int my_j = list == 0 ? j + (wi.grp_lo - wg->grp_base) : j;
         for (int t = 0; t < n_tiles; ++t) {
             const int meta = tiles[t].meta;
-            const int lo = meta & 1023, hi = (meta >> 10) & 1023, valid = (meta >> 20) & 31;
+            const int lo = meta & 1023, hi = (meta >> 10) & 1023;
             if (my_j < lo || my_j >= hi) continue;
+            // a causal tile (bit 30) shows its first row group `first` slots (bits 25-29), every further one one more
+            int valid = (meta >> 20) & 31;
+            if (meta >> 30) valid = min(valid, ((meta >> 25) & 31) + (my_j - lo));
             const float* tile = reinterpret_cast<const float*>(pool + ((int64_t)tiles[t].blk * n_kv + kvh) * tile_bytes);
             for (int tok = 0; tok < valid; ++tok) {
                 float dot = 0.0f;

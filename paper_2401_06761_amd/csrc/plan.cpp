@@ -505,4 +505,73 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
     return APAR_OK;
 }
 
+int build_prefill_plan(const PrefillThreadView* threads, int n, int group, PlanHost& ph) {
+    ph.clear();
+    if (group < 1 || group > 16 || 16 % group != 0) return APAR_ERR_UNSUPPORTED;
+    const int cap = 16 / group;  // query tokens per 16-row tile
+    for (int i = 0; i < n; ++i) {
+        const PrefillThreadView& t = threads[i];
+        const int64_t L = t.len;
+        for (int64_t r0 = 0; r0 < t.m;) {
+            const int64_t left = t.m - r0;
+            const int nt = left <= 4 * cap ? 1 : left <= 8 * cap ? 2 : 4;
+            const int chunk = (int)std::min<int64_t>(left, 4 * nt * cap);
+            const int W = (chunk + 3) / 4;            // tokens per wavefront (<= nt * cap)
+            const int64_t p0 = L - t.m + r0;          // position of the workgroup's first query token
+            const int n_sh = (int)((p0 + 1) / kBlockTokens);  // blocks wholly at or below that position: full
+            PlanHost::WideItem wi{};
+            wi.wg.coop_ofs = (int32_t)ph.tiles.size();
+            wi.wg.n_coop = n_sh;
+            wi.wg.grp_base = (int32_t)(t.q_base + r0);
+            wi.wg.row_tiles = nt | (n_sh << 8);
+            {
+                const size_t at = ph.tiles.size();
+                ph.tiles.resize(at + n_sh);
+                const int32_t meta = make_meta(0, chunk, B);
+                for (int b = 0; b < n_sh; ++b) ph.tiles[at + b] = TileRef{t.table[b], meta};
+            }
+            int longest = 0;
+            for (int k = 0; k < 4; ++k) {
+                const int w0 = k * W, cnt = std::max(0, std::min(W, chunk - w0));
+                if (cnt == 0) {
+                    wi.wg.w[k] = WaveItem{0, 0, wi.wg.grp_base, 0, -1, 0};
+                    continue;
+                }
+                const int64_t pw0 = p0 + w0, p_last = pw0 + cnt - 1;
+                const int32_t ofs = (int32_t)ph.tiles.size();
+                int n_plain = 0;
+                for (int64_t b = n_sh; b <= p_last / kBlockTokens; ++b) {
+                    const int lo = (int)std::max<int64_t>(0, b * kBlockTokens - pw0);  // first token that sees slot 0
+                    const int fill = (int)std::min<int64_t>(kBlockTokens, L - b * kBlockTokens);
+                    const int64_t first = pw0 + lo - b * kBlockTokens + 1;             // slots that token sees
+                    int32_t meta = make_meta(lo, cnt, fill);
+                    if (first < fill) meta |= ((int32_t)first << 25) | (1 << 30);      // causal
+                    else if (fill == kBlockTokens) ++n_plain;                          // (these come first)
+                    ph.tiles.push_back(TileRef{t.table[b], meta});
+                }
+                const int32_t n_tiles = (int32_t)ph.tiles.size() - ofs;
+                wi.wg.w[k] = WaveItem{ofs, n_tiles, wi.wg.grp_base + w0, cnt, -1, kWaveDirect};
+                wi.wg.n_full[k] = n_plain;
+                longest = std::max(longest, (int)n_tiles);
+            }
+            wi.cost = nt * (2 * n_sh + longest);
+            ph.wide_items.push_back(wi);
+            r0 += chunk;
+        }
+    }
+    if (ph.tiles.size() > (size_t)INT32_MAX / 2) return APAR_ERR_UNSUPPORTED;
+    std::stable_sort(ph.wide_items.begin(), ph.wide_items.end(),
+                     [](const PlanHost::WideItem& a, const PlanHost::WideItem& b) {
+                         const int ta = a.wg.row_tiles & 255, tb = b.wg.row_tiles & 255;
+                         return ta != tb ? ta > tb : a.cost > b.cost;
+                     });
+    ph.n_wg_class[0] = ph.n_wg_class[1] = ph.n_wg_class[2] = 0;
+    ph.wgs.reserve(ph.wide_items.size());
+    for (const PlanHost::WideItem& w : ph.wide_items) {
+        ph.wgs.push_back(w.wg);
+        ph.n_wg_class[(w.wg.row_tiles & 255) == 4 ? 0 : (w.wg.row_tiles & 255) == 2 ? 1 : 2] += 1;
+    }
+    return APAR_OK;
+}
+
 }  // namespace apar

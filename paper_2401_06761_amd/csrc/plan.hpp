@@ -65,6 +65,20 @@ struct PlanParams {
     bool fuse;                // build tree-fused units (false: every segment stands alone)
 };
 
+struct PrefillThreadView {  // one listed thread of a prefill call
+    const int32_t* table;
+    int32_t n_blocks;
+    int64_t len;
+    int32_t m;        // its last m rows are the query tokens
+    int64_t q_base;   // index of its first query token among all query tokens of the call
+};
+
+// Plan of a prefill call: the query tokens take the place of the listed threads of a decode plan (row
+// group = query token, numbered across the call), a workgroup holds up to 256 / group consecutive tokens
+// of one thread, the tiles below its first token go on its shared list and the tiles on the diagonal
+// on the wavefronts' own lists, marked causal.  group = q heads per kv head, a divisor of 16.
+int build_prefill_plan(const PrefillThreadView* threads, int n, int group, PlanHost& ph);
+
 // seg_of: pool-sized scratch, all -1 on entry and on exit.  refcount: the pool's refcounts.
 // Returns 0, or a negative apar_status.
 int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, int32_t* seg_of, const PlanParams& prm,

@@ -173,3 +173,60 @@ def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per
     assert info.path_tokens == sum(ap.apar_thread_len(handle, t) for t in threads)
     return {"unit_block_reads": tile_reads, "unique_blocks": len(uniq), "partial_rows": len(all_parts),
             "direct_threads": len(direct)}
+
+
+def check_prefill_plan(handle, threads: Sequence[int], m: Sequence[int], group: int) -> int:
+    """The exported plan of a prefill call must show every query token exactly the token slots of its
+    thread's table up to and including its own position, each once.  Returns the number of tile reads."""
+    wgs = np.array(ap.apar_last_plan_export(handle, ap.APAR_PLAN_WORKGROUPS), dtype=np.int64).reshape(-1, 32)
+    tiles = np.array(ap.apar_last_plan_export(handle, ap.APAR_PLAN_TILES), dtype=np.int64).reshape(-1, 2)
+    rpt, rps, n_sl = ap.apar_last_plan_export(handle, ap.APAR_PLAN_GEOMETRY)
+    assert (rpt, rps, n_sl) == (group, group, 1)
+    cap = 16 // group
+    seen = {}  # query token -> list of (block, slot)
+    reads = 0
+
+    def show(lst, blk, meta, ahead):
+        fill = (meta >> 20) & 31
+        limit = min(fill, ((meta >> 25) & 31) + ahead) if meta >> 30 else fill
+        assert 1 <= fill <= 16 and limit >= 1
+        lst += [(int(blk), s) for s in range(limit)]
+
+    for wi, wg in enumerate(wgs):
+        coop_ofs, n_coop, grp_base, row_tiles, coop_full = wg[0], wg[1], wg[2], wg[3] & 255, wg[3] >> 8
+        assert row_tiles in (1, 2, 4) and (wi == 0 or row_tiles <= wgs[wi - 1][3] & 255)
+        reads += n_coop
+        for k in range(4):
+            t_ofs, n_t, g_lo, n_g, _, flags = wg[4 + 6 * k: 10 + 6 * k]
+            assert 0 <= n_g <= row_tiles * cap
+            if n_g == 0:
+                assert n_t == 0
+                continue
+            assert flags & 1
+            reads += n_t
+            own = tiles[t_ofs:t_ofs + n_t]
+            plain = [((mt >> 20) & 31) == 16 and not (mt >> 30) for mt in own[:, 1]]
+            assert all(plain[:wg[28 + k]]) and not any(plain[wg[28 + k]:])
+            for g in range(g_lo, g_lo + n_g):
+                lst = seen.setdefault(int(g), [])
+                for blk, meta in tiles[coop_ofs:coop_ofs + n_coop]:
+                    lo, hi = meta & 1023, (meta >> 10) & 1023
+                    assert ((meta >> 20) & 31) == 16 and not meta >> 30
+                    if lo <= g - grp_base < hi:
+                        show(lst, blk, meta, g - grp_base - lo)
+                for blk, meta in own:
+                    lo, hi = meta & 1023, (meta >> 10) & 1023
+                    assert lo < hi <= n_g
+                    if lo <= g - g_lo < hi:
+                        show(lst, blk, meta, g - g_lo - lo)
+    row = 0
+    for t, mi in zip(threads, m):
+        table = ap.apar_thread_block_table(handle, t)
+        L = ap.apar_thread_len(handle, t)
+        for r in range(mi):
+            pos = L - mi + r
+            want = [(table[x // 16], x % 16) for x in range(pos + 1)]
+            assert sorted(seen[row]) == want, f"query token {row} (thread {t}, position {pos})"
+            row += 1
+    assert sorted(seen) == list(range(row))
+    return reads

@@ -359,3 +359,40 @@ def test_commit_candidates_rows_tables_and_next_decode(dtype, d):
         got, want = decode_both(w, pool, dense, live, step=9)
         assert np.abs(got - want).max() <= TOL[dtype]
         led.check_invariants()
+
+
+@pytest.mark.parametrize("dtype,n_q,n_kv,d", [("bf16", 4, 4, 128), ("bf16", 8, 2, 128), ("bf16", 8, 1, 128),
+                                              ("bf16", 16, 1, 128), ("f32", 2, 2, 64), ("f32", 4, 1, 128)])
+def test_prefill_attention_over_tree_segments(dtype, n_q, n_kv, d):
+    t = torch()
+    heads = HeadConfig(n_q, n_kv, d, dtype)
+    parents = [-1, 0, 0, 1, 1, 2, -1, 6, 6]
+    segs = [300, 15, 16, 17, 1, 33, 70, 130, 2]
+    w = manual_tree(parents, segs, heads, seed=21, data_scale=0.5)
+    N = blocks_upper_bound(w)
+    with pool_for(w, N) as pool:
+        poison(pool)
+        dense = DenseThreads(n_q, n_kv, d)
+        live, nodes = replay_trace(w, pool, None, dense)
+        lens = [dense.length(th) for th in live]
+        rng = np.random.default_rng(3)
+        cases = [[w.nodes[i].seg_len for i in nodes], lens, [1] * len(live), [min(L, 20) for L in lens]]
+        for m in cases:
+            q = quantise(0.5 * rng.standard_normal((sum(m), n_q, d)).astype(np.float32), dtype)
+            qd = to_dev(q, dtype)
+            out = t.empty_like(qd)
+            ap.apar_prefill_attention(pool.handle, qd, live, m, out)
+            t.cuda.synchronize()
+            got = to_host(out)
+            want = dense.prefill(q, live, m)
+            assert np.isfinite(got).all()
+            err = np.abs(got - want).max()
+            assert err <= TOL[dtype], f"m = {m}: max abs err {err}"
+        # m = 1 is the decode step
+        q = quantise(0.5 * rng.standard_normal((len(live), n_q, d)).astype(np.float32), dtype)
+        qd = to_dev(q, dtype)
+        a, b = t.empty_like(qd), t.empty_like(qd)
+        ap.apar_prefill_attention(pool.handle, qd, live, [1] * len(live), a)
+        ap.apar_decode_attention(pool.handle, qd, live, b)
+        t.cuda.synchronize()
+        assert np.abs(to_host(a) - to_host(b)).max() <= TOL[dtype]

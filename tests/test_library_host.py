@@ -276,3 +276,43 @@ def test_commit_candidates_books_and_errors():
         ap.apar_commit_candidates(pool.handle, [t, kid], None, None, 5, [0b00001, 0b00000])
         led.commit_candidates([t, kid], [1, 0])
         books_equal(pool.handle, led)
+
+
+@pytest.mark.parametrize("n_q,n_kv", [(4, 4), (8, 2), (8, 1), (16, 1)])
+def test_prefill_plans_show_every_query_its_causal_path(n_q, n_kv):
+    from harness import check_prefill_plan
+
+    heads = HeadConfig(n_q, n_kv, 128, "bf16")
+    # segment lengths around every block boundary, a long root (several workgroups), nested forks
+    parents = [-1, 0, 0, 1, 1, 2, -1, 6, 6]
+    segs = [300, 15, 16, 17, 1, 33, 70, 130, 2]
+    w = manual_tree(parents, segs, heads)
+    N = blocks_upper_bound(w)
+    with pool_for(w, N, dry_run=True) as pool:
+        live, nodes = replay_trace(w, pool, None, dry_run=True)
+        lens = [ap.apar_thread_len(pool.handle, t) for t in live]
+        # every live thread's own segment
+        m = [w.nodes[i].seg_len for i in nodes]
+        ap.apar_prefill_attention(pool.handle, None, live, m, None)
+        check_prefill_plan(pool.handle, live, m, n_q // n_kv)
+        info = ap.apar_last_plan_info(pool.handle)
+        assert info.path_tokens == sum(mi * (L - mi) + mi * (mi + 1) // 2 for mi, L in zip(m, lens))
+        # whole paths, single tokens, a thread listed twice
+        for m2 in (lens, [1] * len(live), [min(L, 20) for L in lens]):
+            ap.apar_prefill_attention(pool.handle, None, live, m2, None)
+            check_prefill_plan(pool.handle, live, m2, n_q // n_kv)
+        ap.apar_prefill_attention(pool.handle, None, [live[0], live[0]], [3, lens[0]], None)
+        check_prefill_plan(pool.handle, [live[0], live[0]], [3, lens[0]], n_q // n_kv)
+        for bad_m in ([0] + [1] * (len(live) - 1), [lens[0] + 1] + [1] * (len(live) - 1)):
+            with pytest.raises(ap.AparError) as e:
+                ap.apar_prefill_attention(pool.handle, None, live, bad_m, None)
+            assert e.value.status == -1
+
+
+def test_prefill_needs_a_group_size_that_divides_16():
+    with ap.Pool(6, 2, 128, "bf16", 8, dry_run=True) as pool:
+        t = ap.apar_thread_create(pool.handle)
+        ap.apar_append_kv(pool.handle, t, None, None, 5)
+        with pytest.raises(ap.AparError) as e:
+            ap.apar_prefill_attention(pool.handle, None, [t], [5], None)
+        assert e.value.status == -6
