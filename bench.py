@@ -147,6 +147,67 @@ def spec_loop(args, w) -> int:
     return 0
 
 
+def prefill_bench(args, w) -> int:
+    """Secondary measurement: tree-masked prefill attention (apar_prefill_attention) over the segments of a
+    resident fork-tree workload.  MFMA-bound, so the roofline is the dense bf16 matrix-core peak."""
+    import numpy as np
+    import torch
+
+    import paper_2401_06761_amd as ap
+    from apar_workloads import rows_device
+    from paper_2401_06761_amd.driver import TreeRun
+
+    hd = w.heads
+    run = TreeRun(w, headroom_steps=8, device="cuda:0")
+    run.build()
+    live = np.asarray(run.live, dtype=np.int32)
+    lens = np.array([ap.apar_thread_len(run.h, int(t)) for t in live], dtype=np.int64)
+    own = np.array([w.nodes[run.node_of[int(t)]].seg_len for t in live], dtype=np.int64)
+    results = {}
+    for name, m in (("own_segments", own), ("whole_paths", lens)):
+        if name == "whole_paths" and int(m.sum()) > 4_000_000:
+            continue  # (the q and out rows alone would take tens of GB)
+        rows = int(m.sum())
+        q = rows_device(w, 21, 0, (rows, hd.n_q_heads, hd.head_dim), "cuda:0")
+        out = torch.empty_like(q)
+        m32 = m.astype(np.int32)
+        for _ in range(args.warmup):
+            ap.apar_prefill_attention(run.h, q, live, m32, out)
+        torch.cuda.synchronize()
+        ap.apar_profile_read(run.h)
+        ap.apar_profile_enable(run.h, True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            ap.apar_prefill_attention(run.h, q, live, m32, out)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        prof = ap.apar_profile_read(run.h)
+        ap.apar_profile_enable(run.h, False)
+        info = ap.apar_last_plan_info(run.h)
+        flops = 4.0 * hd.head_dim * hd.n_q_heads * info.path_tokens
+        ms = prof.attention_kernel_ms / args.steps
+        results[name] = {"query_tokens": rows, "attended_pairs": int(info.path_tokens), "flop_per_call": flops,
+                         "kernel_ms_per_call": ms, "wall_ms_per_call": wall / args.steps * 1e3,
+                         "plan_host_ms_per_call": prof.plan_host_ms / args.steps,
+                         "tflops": flops / (ms * 1e-3) / 1e12, "workgroups": int(info.n_units)}
+        del q, out
+    main_r = results["own_segments"]
+    line = {
+        "metric": "tree-masked prefill attention, query tokens/s (secondary; the headline is the decode step)",
+        "value": main_r["query_tokens"] / (main_r["wall_ms_per_call"] * 1e-3), "unit": "query-tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_r["wall_ms_per_call"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": hd.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.config} forest resident in the pool ({len(live)} live threads); one call = "
+                               f"prefill attention of every live thread's own segment under the tree mask"},
+        "roofline": {"bound": "mfma", "kernel": "attention_bf16 (prefill plan)", "achieved": main_r["tflops"],
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": main_r["tflops"] / 2500.0, "traffic": None},
+        "cases": results,
+    }
+    run.close()
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap_ = argparse.ArgumentParser()
     ap_.add_argument("--gpus", type=int, default=1)
@@ -159,6 +220,8 @@ def main() -> int:
     ap_.add_argument("--churn", type=float, default=0.01)
     ap_.add_argument("--cpu-requests", type=int, default=64)
     ap_.add_argument("--no-cpu-baseline", action="store_true")
+    ap_.add_argument("--prefill", action="store_true",
+                     help="measure apar_prefill_attention over the workload's segments instead of the decode step")
     ap_.add_argument("--two-pass", action="store_true",
                      help="spec128: gather the accepted rows on the caller's side and append them with "
                           "apar_append_kv_batch instead of apar_commit_candidates")
@@ -182,6 +245,8 @@ def main() -> int:
     dev = "cuda:0"
     w = make_config(args.config, seed=args.seed, n_requests=args.requests)
     hd = w.heads
+    if args.prefill:
+        return prefill_bench(args, w)
     if args.config == "spec128":
         return spec_loop(args, w)
     t_build = time.perf_counter()

@@ -57,8 +57,14 @@ struct TileRef {     // one block to read, and the row groups it applies to
                      // row group (the workgroup's for shared lists, the wavefront's for its own list);
                      // valid = filled token slots (1..16).  Bit 30 marks a causal tile (prefill): row
                      // group lo sees only the first `first` slots (bits 25-29, 1..16), group lo + 1 one
-                     // more, and so on up to valid.  Causal tiles count as open when lists are ordered.
+                     // more, and so on up to valid.
 };
+
+// Most 16-row tiles one wavefront is given.  The kernels take 4 as well, but with 64 rows of state a
+// wavefront runs out of the 256 architectural registers and the compiler shuttles accumulators to and
+// from the accumulation registers around every use: measured slower than two tiles plus partial results
+// (decode) or more workgroups (prefill), so the plans stop at 2.
+constexpr int kMaxRowTiles = 2;
 
 struct WaveItem {    // what one wavefront computes
     int32_t tile_ofs, n_tiles;  // its own tile list
@@ -76,7 +82,8 @@ constexpr int kSplitMinTiles = 16; // shorter private units are packed four to a
 struct WgDesc {      // one 256-thread workgroup: a shared tile list, then one private list per wavefront
     int32_t coop_ofs, n_coop;   // tiles every wavefront of the group sees (staged once through LDS)
     int32_t grp_base;           // row group that the shared list's ranges are relative to
-    int32_t row_tiles;          // bits 0-7: 16-row tiles per wavefront (1, 2 or 4); bits 8-31: full shared tiles
+    int32_t row_tiles;          // bits 0-7: 16-row tiles per wavefront (1 or 2; the f32 kernel also takes 4);
+                                // bits 8-31: full shared tiles
     WaveItem w[4];
     int32_t n_full[4];          // full tiles at the head of each wavefront's own list
 };

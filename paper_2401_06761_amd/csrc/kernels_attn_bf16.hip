@@ -12,19 +12,22 @@
 // S^T (lane = 16*g + c holds tokens 4g..4g+3 of row c) is already the
 // B-operand layout of P^T, so probabilities never move between lanes.
 //
-// A workgroup (4 wavefronts, 16, 32 or 64 rows each) is given by the host plan
+// A workgroup (4 wavefronts, 16 or 32 rows each) is given by the host plan
 //   * a shared tile list: blocks whose holders sit in more than one wavefront
-//     (prefixes shared by many sibling threads).  Each wavefront fetches a
-//     quarter of every tile, the tile is staged once in LDS (double buffered,
-//     one barrier per tile) and every wavefront applies it to those of its rows
-//     that hold the block;
+//     (prefixes shared by many sibling threads).  They go through LDS in groups
+//     of four, one whole tile per wavefront, the next group in flight to
+//     registers while the current one is consumed (two barriers per group), and
+//     every wavefront applies each tile to those of its rows that hold the block;
 //   * one private tile list per wavefront: blocks held only by rows of that
 //     wavefront (private tails, small sibling groups), loaded straight from HBM
 //     into operand registers with no barrier.  K registers are refilled right
 //     after the K.Q^T products and V registers after the V^T.P^T products, so
 //     the next tile is in flight while the current one is consumed.
+// Every list holds its full tiles first: they run through loops with nothing
+// but unconditional loads; the open tiles after them through general loops.
 // Every tile names the range of row groups it applies to; other rows see -inf
-// logits.  A row's softmax state stays in registers across all the blocks of
+// logits.  A causal tile (prefill: the query tokens are the row groups) shows
+// each further row group one more of its token slots.  A row's softmax state stays in registers across all the blocks of
 // its root path that the unit covers; attention is a set operation, so the
 // order in which a unit visits them does not matter.  Rows whose whole path
 // lies in the unit are normalised and written out here; the others leave a
@@ -153,9 +156,9 @@ __device__ __forceinline__ void v_operands_from_rows(const char* vrows, int stri
 constexpr int kOpenRowStride = 264;                 // padded, so the four token groups hit different LDS banks
 constexpr int kOpenScratch = 16 * kOpenRowStride;   // one wavefront's row-major V half
 
-// NT = 16-row tiles per wavefront (1, 2 or 4): a workgroup carries up to 64 * NT query rows.
+// NT = 16-row tiles per wavefront (1 or 2 are instantiated): a workgroup carries up to 64 * NT query rows.
 template <int NT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3 : NT == 2 ? 2 : 1))) void attention_bf16(const char* __restrict__ pool, const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3 : 2))) void attention_bf16(const char* __restrict__ pool, const uint16_t* __restrict__ q,
                                                       PlanDev plan, int wg_first, int n_cand, int n_q, int n_kv,
                                                       int group, float scale_log2e, PartialBuf part,
                                                       const uint16_t* __restrict__ cand_k,
@@ -234,9 +237,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
     // ---- shared tiles: staged once in LDS for the whole workgroup ---------------------------
     // Tiles go through LDS in groups of four, one whole tile per wavefront: while a group is consumed
     // from LDS, each wavefront already has its tile of the next group in flight to its registers.
-    // Full tiles come first in every list; as long as the next group is made of full tiles only, the loop
-    // contains no lane-dependent branch around a load (which would make the compiler wait for each load
-    // where it is issued), and the last groups go through a general loop.
+    // Full tiles (16 filled slots) come first in every list and go through a loop that contains no
+    // lane-dependent branch around a load (which would make the compiler wait for each load where it is
+    // issued); the open tiles after them go through a general loop.
     if (n_coop > 0) {
         const int shift = wi.grp_lo - wg->grp_base;  // shared ranges are relative to the group's base
         const int n_coop_full = wg->row_tiles >> 8;
@@ -298,30 +301,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             for (int nt = 0; nt < NT; ++nt) {
                 if (NT > 1 && !touches(nt, lo, hi)) continue;
                 f32x4 s = products(ks, st[nt]);
-                if (!kFull && (valid < 16 || (meta >> 30))) mask_tokens(s, visible(meta, my_j[nt] - lo), g4);
+                if ((!kFull && valid < 16) || (meta >> 30)) mask_tokens(s, visible(meta, my_j[nt] - lo), g4);
                 accumulate(vs, st[nt], s, my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
             }
         };
-        int t0 = 0;
-        if (n_coop_full >= 8) {
-            fetch_full(wave);
-            for (; t0 + 8 <= n_coop_full; t0 += 4) {  // this group and the next are full tiles
-                if (t0 > 0) __syncthreads();          // everyone is done reading the previous group
-                to_stage();
+        if (n_coop_full > 0) {  // the full tiles; which wavefront fetches is a scalar decision
+            if (wave < n_coop_full) fetch_full(wave);
+            for (int t0 = 0; t0 < n_coop_full; t0 += 4) {
+                if (t0 > 0) __syncthreads();  // everyone is done reading the previous group
+                if (t0 + wave < n_coop_full) to_stage();
                 __syncthreads();
-                fetch_full(t0 + 4 + wave);
-                for (int u = 0; u < 4; ++u) consume(t0 + u, stage[u], std::true_type{});
+                if (t0 + 4 + wave < n_coop_full) fetch_full(t0 + 4 + wave);
+                const int n_here = min(4, n_coop_full - t0);
+                for (int u = 0; u < n_here; ++u) consume(t0 + u, stage[u], std::true_type{});
             }
-        } else {
-            fetch_any(wave);
         }
-        for (; t0 < n_coop; t0 += 4) {
-            if (t0 > 0) __syncthreads();
-            if (t0 + wave < n_coop) to_stage();
-            __syncthreads();
-            fetch_any(t0 + 4 + wave);
-            const int n_here = min(4, n_coop - t0);
-            for (int u = 0; u < n_here; ++u) consume(t0 + u, stage[u], std::false_type{});
+        if (n_coop_full < n_coop) {  // the open tiles
+            if (n_coop_full > 0) __syncthreads();
+            fetch_any(n_coop_full + wave);
+            for (int t0 = n_coop_full; t0 < n_coop; t0 += 4) {
+                if (t0 > n_coop_full) __syncthreads();
+                if (t0 + wave < n_coop) to_stage();
+                __syncthreads();
+                fetch_any(t0 + 4 + wave);
+                const int n_here = min(4, n_coop - t0);
+                for (int u = 0; u < n_here; ++u) consume(t0 + u, stage[u], std::false_type{});
+            }
         }
         __syncthreads();  // the stage buffers are reused below
     }
@@ -389,9 +394,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
                 if (NT == 1 || touches(nt, lo, hi)) s[nt] = products(k, st[nt]);
             issue_k_full(tn);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                if (NT == 1 || touches(nt, lo, hi))
-                    accumulate(v, st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+            for (int nt = 0; nt < NT; ++nt) {
+                if (NT > 1 && !touches(nt, lo, hi)) continue;
+                if (meta >> 30) mask_tokens(s[nt], visible(meta, my_j[nt] - lo), g4);
+                accumulate(v, st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+            }
             issue_v_full(tn);
             meta = meta_n;
         }
@@ -599,7 +606,7 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
     hipLaunchKernelGGL((attention_bf16<NTV>), dim3(n_wg), dim3(256), 0, on, (const char*)pool, (const uint16_t*)q, \
                        plan, first[cls], n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part,                      \
                        (const uint16_t*)cand_k, (const uint16_t*)cand_v, mask, (uint16_t*)out)
-        if (cls == 0) APAR_LAUNCH(4);
+        if (cls == 0) return hipErrorInvalidValue;  // four row tiles per wavefront: not built (see kMaxRowTiles)
         else if (cls == 1) APAR_LAUNCH(2);
         else APAR_LAUNCH(1);
 #undef APAR_LAUNCH

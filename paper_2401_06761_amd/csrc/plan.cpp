@@ -13,7 +13,7 @@
 //
 // Units.  Partial results are expensive: small writes mixed into the streaming
 // reads cost far more than their size.  So a whole subtree of the forest is given
-// to ONE unit whenever its query rows fit one workgroup (4 wavefronts x 16, 32 or 64 rows;
+// to ONE unit whenever its query rows fit one workgroup (4 wavefronts x 16 or 32 rows;
 // the fewest rows per wavefront that hold them are chosen):
 // the rows' softmax state then stays in registers from the shared prefix down to
 // each private tail, and threads whose entire path lies inside the unit get their
@@ -58,8 +58,12 @@ struct Builder {
         cap = 16 / rps;
     }
 
-    // fewest 16-row tiles per wavefront with which one workgroup holds `groups` row groups (4 if none does)
-    int pick_row_tiles(int groups) const { return groups <= 4 * cap ? 1 : groups <= 8 * cap ? 2 : 4; }
+    // fewest 16-row tiles per wavefront with which one workgroup holds `groups` row groups (the most if none does)
+    int pick_row_tiles(int groups) const {
+        int nt = 1;
+        while (nt < kMaxRowTiles && groups > 4 * nt * cap) nt *= 2;
+        return nt;
+    }
 
     // Pre-order walk of the subtree of `root`; f(segment index).
     template <class F>
@@ -406,7 +410,7 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         }
         s.n_above = par >= 0 ? segs[par].n_above + bld.n_chunks[par] : 0;
         const int groups = s.n_shr * n_sl;
-        const bool fits = groups <= 16 * cap && s.tiles_sub <= (groups <= cap ? 1 : 4) * prm.max_unit_tiles;
+        const bool fits = groups <= 4 * kMaxRowTiles * cap && s.tiles_sub <= (groups <= cap ? 1 : 4) * prm.max_unit_tiles;
         if (prm.fuse && fits) {
             s.unit = m;  // a unit is named after its root segment
             bld.emit_fused(m);
@@ -514,7 +518,7 @@ int build_prefill_plan(const PrefillThreadView* threads, int n, int group, PlanH
         const int64_t L = t.len;
         for (int64_t r0 = 0; r0 < t.m;) {
             const int64_t left = t.m - r0;
-            const int nt = left <= 4 * cap ? 1 : left <= 8 * cap ? 2 : 4;
+            const int nt = left <= 4 * cap ? 1 : kMaxRowTiles;
             const int chunk = (int)std::min<int64_t>(left, 4 * nt * cap);
             const int W = (chunk + 3) / 4;            // tokens per wavefront (<= nt * cap)
             const int64_t p0 = L - t.m + r0;          // position of the workgroup's first query token
@@ -546,7 +550,7 @@ int build_prefill_plan(const PrefillThreadView* threads, int n, int group, PlanH
                     const int64_t first = pw0 + lo - b * kBlockTokens + 1;             // slots that token sees
                     int32_t meta = make_meta(lo, cnt, fill);
                     if (first < fill) meta |= ((int32_t)first << 25) | (1 << 30);      // causal
-                    else if (fill == kBlockTokens) ++n_plain;                          // (these come first)
+                    if (fill == kBlockTokens) ++n_plain;  // (only a thread's last block can be open: full ones come first)
                     ph.tiles.push_back(TileRef{t.table[b], meta});
                 }
                 const int32_t n_tiles = (int32_t)ph.tiles.size() - ofs;

@@ -109,7 +109,7 @@ def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per
     tile_reads = 0
     for wg_index, wg in enumerate(wgs):
         coop_ofs, n_coop, grp_base, row_tiles, coop_full = wg[0], wg[1], wg[2], wg[3] & 255, wg[3] >> 8
-        assert row_tiles in (1, 2, 4)
+        assert row_tiles in (1, 2)
         if wg_index:  # classes are stored 4, 2, 1
             assert row_tiles <= wgs[wg_index - 1][3] & 255
         # every list holds its full tiles first, then its open ones, and says how many are full
@@ -194,7 +194,7 @@ def check_prefill_plan(handle, threads: Sequence[int], m: Sequence[int], group: 
 
     for wi, wg in enumerate(wgs):
         coop_ofs, n_coop, grp_base, row_tiles, coop_full = wg[0], wg[1], wg[2], wg[3] & 255, wg[3] >> 8
-        assert row_tiles in (1, 2, 4) and (wi == 0 or row_tiles <= wgs[wi - 1][3] & 255)
+        assert row_tiles in (1, 2) and (wi == 0 or row_tiles <= wgs[wi - 1][3] & 255)
         reads += n_coop
         for k in range(4):
             t_ofs, n_t, g_lo, n_g, _, flags = wg[4 + 6 * k: 10 + 6 * k]
@@ -205,7 +205,7 @@ def check_prefill_plan(handle, threads: Sequence[int], m: Sequence[int], group: 
             assert flags & 1
             reads += n_t
             own = tiles[t_ofs:t_ofs + n_t]
-            plain = [((mt >> 20) & 31) == 16 and not (mt >> 30) for mt in own[:, 1]]
+            plain = [((mt >> 20) & 31) == 16 for mt in own[:, 1]]
             assert all(plain[:wg[28 + k]]) and not any(plain[wg[28 + k]:])
             for g in range(g_lo, g_lo + n_g):
                 lst = seen.setdefault(int(g), [])

@@ -188,8 +188,8 @@ def test_error_codes_and_noops():
 
 @pytest.mark.parametrize("n_q,n_kv,fan,n_cand", [
     (4, 4, 70, 1),     # 71 rows per kv head share the root: two 16-row tiles per wavefront
-    (4, 4, 130, 1),    # four tiles per wavefront
-    (4, 4, 300, 1),    # more rows than one workgroup holds: the root stands alone, chunks of 256 rows
+    (4, 4, 130, 1),    # more rows than one workgroup holds: the root stands alone, chunks of 128 rows
+    (4, 4, 300, 1),
     (8, 1, 9, 1),      # 8 rows per thread: 2 threads per tile
     (8, 1, 30, 1),
     (8, 1, 40, 1),
@@ -222,12 +222,12 @@ def test_wide_sharing_groups_use_more_row_tiles(n_q, n_kv, fan, n_cand):
             n_sl = -(-rpt // 16)
             cap = 16 // -(-rpt // n_sl)
             groups = len(live) * n_sl
-            if chunk == 512 and groups <= 16 * cap:
+            if chunk == 512 and groups <= 8 * cap:
                 # the whole tree is one unit with the fewest row tiles that hold it
-                want = 1 if groups <= 4 * cap else 2 if groups <= 8 * cap else 4
+                want = 1 if groups <= 4 * cap else 2
                 assert res["partial_rows"] == 0 and len(wgs) == 1 and wgs[0][3] & 255 == want
-            if groups > 16 * cap:
-                assert res["partial_rows"] > 0 and wgs[0][3] & 255 == 4
+            if groups > 8 * cap:
+                assert res["partial_rows"] > 0 and wgs[0][3] & 255 == 2
 
 
 def test_commit_candidates_books_and_errors():
