@@ -30,3 +30,4 @@ from .data import (  # noqa: F401
 )
 from .spec_loop import SpecLoopPlan, SpecStep, draw_candidate_tree, mask_rows_from_parents  # noqa: F401
 from .token_stream import TokenStream  # noqa: F401
+from .serving import Request, SamplerConfig, make_requests, sample_flat, sample_tokens  # noqa: F401

@@ -190,6 +190,12 @@ APAR_API int apar_decode_attention(apar_pool* pool, const void* q_dev, const apa
 APAR_API int apar_decode_attention_spec(apar_pool* pool, const void* q_dev, const void* cand_k_dev,
                                const void* cand_v_dev, const uint8_t* mask_dev, int n_cand,
                                const apar_thread* threads, int n, void* out_dev, void* hip_stream);
+/* As apar_append_kv_batch, but row i of the call is read from row src_rows[i] (>= 0, host array) of
+ * k_dev, v_dev, so that a caller can append a subset of a larger array of rows without gathering it
+ * first (Alg. 1 batches the rows of many sequence groups; a scheduler may have dropped some). */
+APAR_API int apar_append_kv_gather(apar_pool* pool, const apar_thread* threads, const int32_t* src_rows, int n,
+                          const void* k_dev, const void* v_dev, void* hip_stream);
+
 /*
  * Commit of a multi-candidate step: the accepted candidates become part of each thread's
  * sequence (Sec. 3.2, the Medusa-APAR setting: a predict-verify step keeps one root path of
@@ -323,6 +329,67 @@ APAR_API int apar_group_step(apar_group* group, const int32_t* sampled, int n, c
  * INVALID_ARG if cap is too small. */
 APAR_API int apar_group_restore(apar_group* group, int32_t* tokens_out, int64_t cap, int64_t* n_out);
 APAR_API int apar_group_get_info(apar_group* group, apar_group_info* out);
+
+/* ---- serving loop (Sec. 3.3 "Results in High-Throughput Scenarios", App. C.2) -------------
+ * Requests wait in a first-come-first-served queue over one pool.  Per decode step the caller
+ * admits (apar_server_admit), lists the batch (apar_server_batch), runs apar_decode_attention
+ * over its threads, samples one token per entry and applies one AparDecode step to every running
+ * request at once (apar_server_step): forks, one batched append of all rows, early release of
+ * every sequence that drew [EOS] (Sec. 2.4 feature 2) and collection of completed requests.  The
+ * paper serves through an existing paged-attention engine and says only that concurrency is
+ * capped and that over-admission leads to swapping or recomputation of KV cache; the policy here:
+ *   admission  - head of the queue only, while fewer than max_running requests run and
+ *                free_blocks - ceil(prompt / 16) >= watermark_blocks;
+ *   preemption - when a step's rows do not fit, the most recently admitted running request is
+ *                released and goes back to the head of the queue (it restarts from its prompt:
+ *                recomputation), and the step is retried without it until it fits. */
+typedef struct apar_server apar_server;
+typedef struct apar_server_config {
+    int32_t max_running;
+    int32_t watermark_blocks;
+} apar_server_config;
+typedef struct apar_server_seq {   /* one unfinished sequence of the batch */
+    int32_t request_id;
+    apar_thread thread;
+    int32_t seq_index;    /* index of the sequence in its group, creation order (0: the prompt's)  */
+    int32_t last_token;
+    int64_t length;       /* tokens so far, prompt included                                          */
+    int64_t start_len;    /* length it began with: the prompt (root) or parent's tokens + [Child]    */
+    int32_t group_size;   /* sequences its group has issued so far                                   */
+    int32_t reserved;
+} apar_server_seq;
+typedef struct apar_server_step_info {
+    int32_t n_preempted, n_forked, n_finished_sequences, n_finished_requests, n_rows_appended, n_running;
+} apar_server_step_info;
+typedef struct apar_server_stats {
+    int64_t steps, n_submitted, n_waiting, n_running, n_finished, n_admissions, n_preemptions;
+    int64_t generated_tokens;        /* sampled tokens of steps that were applied (a preempted request's count again) */
+    int64_t batch_sequences_total;   /* sum over steps of the sequences decoded                      */
+    int64_t peak_used_blocks, peak_running, peak_threads;
+} apar_server_stats;
+APAR_API int apar_server_create(apar_pool* pool, const apar_server_config* cfg, apar_server** out);
+/* Releases whatever still runs.  NULL is accepted. */
+APAR_API int apar_server_destroy(apar_server* server);
+APAR_API int apar_server_submit(apar_server* server, int32_t request_id, const int32_t* prompt_tokens, int n_prompt);
+/* Admits from the head of the queue.  The j-th request admitted by the call takes its prompt's rows
+ * from k_dev, v_dev ([rows_available, Hkv, d]) right after those of the (j-1)-th; admission also stops
+ * before a prompt that no longer fits in rows_available.  Both NULL on a dry-run pool. */
+APAR_API int apar_server_admit(apar_server* server, const void* k_dev, const void* v_dev, int64_t rows_available,
+                               void* hip_stream, int32_t* n_admitted_out, int64_t* rows_used_out);
+/* The unfinished sequences of all running requests: requests in admission order, sequences in
+ * creation order.  n_out is always set; INVALID_ARG if cap is too small. */
+APAR_API int apar_server_batch(apar_server* server, apar_server_seq* out, int cap, int* n_out);
+/* sampled[i]: the token drawn for batch entry i (n = batch size).  k_dev, v_dev: the rows of the
+ * step, request by request in batch order, each request's rows as in apar_group_step.  The entries
+ * and rows of a request preempted by this call are skipped.  Errors: INVALID_ARG, THREAD_CAPACITY,
+ * HIP; then no step was applied (requests preempted before the error stay preempted). */
+APAR_API int apar_server_step(apar_server* server, const int32_t* sampled, int n, const void* k_dev, const void* v_dev,
+                              void* hip_stream, apar_server_step_info* info_out);
+/* The oldest completed request: its id (-1 if none), its tokens in Restore order (Alg. 1) and its
+ * Sec. 3.4 counters.  INVALID_ARG with n_tokens_out set if cap is too small (the request stays). */
+APAR_API int apar_server_pop_finished(apar_server* server, int32_t* request_id_out, int32_t* tokens_out, int64_t cap,
+                                      int64_t* n_tokens_out, apar_group_info* info_out);
+APAR_API int apar_server_get_stats(apar_server* server, apar_server_stats* out);
 
 /* ---- measurement -------------------------------------------------------- */
 /* While on, every decode and append call brackets its kernels with HIP events. */

@@ -10,6 +10,7 @@ Two independent halves:
   * ledger.py  - bookkeeping: an integer-only replay of the allocator policy
                  (block tables, refcounts, free list, copy-on-write count).
   * controller.py - Algorithm 1 (fork on [Fork], paragraph nodes, Restore) in plain Python.
+  * serving.py - the serving loop (queue, admission, preemption) over controller + ledger.
   * accounting.py - the paper's max-cached-tokens / attended-tokens metrics and
                  the resident-vs-copied-prefix byte counts.
 """
@@ -17,3 +18,4 @@ from .dense import DenseThreads, attend, attend_spec  # noqa: F401
 from .ledger import BlockLedger, OutOfBlocks, InvalidThread  # noqa: F401
 from . import accounting  # noqa: F401
 from . import controller  # noqa: F401
+from . import serving  # noqa: F401

@@ -50,6 +50,26 @@ class AparGroupInfo(C.Structure):
 APAR_TOKEN_FORK, APAR_TOKEN_CHILD, APAR_TOKEN_EOS = -1, -2, -3
 
 
+class AparServerConfig(C.Structure):
+    _fields_ = [("max_running", C.c_int32), ("watermark_blocks", C.c_int32)]
+
+
+class AparServerSeq(C.Structure):
+    _fields_ = [("request_id", C.c_int32), ("thread", C.c_int32), ("seq_index", C.c_int32), ("last_token", C.c_int32),
+                ("length", C.c_int64), ("start_len", C.c_int64), ("group_size", C.c_int32), ("reserved", C.c_int32)]
+
+
+class AparServerStepInfo(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("n_preempted", "n_forked", "n_finished_sequences", "n_finished_requests",
+                                         "n_rows_appended", "n_running")]
+
+
+class AparServerStats(C.Structure):
+    _fields_ = [(k, C.c_int64) for k in ("steps", "n_submitted", "n_waiting", "n_running", "n_finished",
+                                         "n_admissions", "n_preemptions", "generated_tokens",
+                                         "batch_sequences_total", "peak_used_blocks", "peak_running", "peak_threads")]
+
+
 class AparProfile(C.Structure):
     _fields_ = [("n_decode_calls", C.c_int64), ("attention_kernel_ms", C.c_double), ("merge_kernel_ms", C.c_double),
                 ("plan_host_ms", C.c_double), ("n_append_calls", C.c_int64), ("append_kernels_ms", C.c_double),
@@ -95,6 +115,16 @@ def _load() -> C.CDLL:
         "apar_profile_read": [P, C.POINTER(AparProfile)],
         "apar_profile_attention_calls": [P, C.POINTER(C.c_float), C.c_int64, C.POINTER(C.c_int64)],
         "apar_set_chunk_blocks": [P, I],
+        "apar_append_kv_gather": [P, I32P, I32P, I, V, V, V],
+        "apar_server_create": [P, C.POINTER(AparServerConfig), C.POINTER(P)],
+        "apar_server_destroy": [P],
+        "apar_server_submit": [P, C.c_int32, I32P, I],
+        "apar_server_admit": [P, V, V, C.c_int64, V, C.POINTER(C.c_int32), C.POINTER(C.c_int64)],
+        "apar_server_batch": [P, C.POINTER(AparServerSeq), I, C.POINTER(C.c_int)],
+        "apar_server_step": [P, I32P, I, V, V, V, C.POINTER(AparServerStepInfo)],
+        "apar_server_pop_finished": [P, C.POINTER(C.c_int32), I32P, C.c_int64, C.POINTER(C.c_int64),
+                                     C.POINTER(AparGroupInfo)],
+        "apar_server_get_stats": [P, C.POINTER(AparServerStats)],
         "apar_group_create": [P, I32P, I, V, V, V, C.POINTER(P)],
         "apar_group_destroy": [P],
         "apar_group_unfinished": [P, I32P, I, C.POINTER(C.c_int)],
@@ -364,6 +394,78 @@ def apar_group_restore(group) -> List[int]:
 def apar_group_get_info(group) -> AparGroupInfo:
     out = AparGroupInfo()
     _check(_L().apar_group_get_info(group, C.byref(out)), "apar_group_get_info")
+    return out
+
+
+def apar_append_kv_gather(pool, threads: Sequence[int], src_rows: Sequence[int], k, v, stream=None) -> None:
+    arr, n = _ids(threads)
+    src, ns = _ids(src_rows)
+    if ns != n:
+        raise ValueError("one source row per listed thread")
+    _check(_L().apar_append_kv_gather(pool, arr, src, n, _ptr(k), _ptr(v), _stream(stream)), "apar_append_kv_gather")
+
+
+def apar_server_create(pool, max_running: int, watermark_blocks: int) -> C.c_void_p:
+    cfg = AparServerConfig(max_running, watermark_blocks)
+    out = C.c_void_p()
+    _check(_L().apar_server_create(pool, C.byref(cfg), C.byref(out)), "apar_server_create")
+    return out
+
+
+def apar_server_destroy(server) -> None:
+    _check(_L().apar_server_destroy(server), "apar_server_destroy")
+
+
+def apar_server_submit(server, request_id: int, prompt_tokens: Sequence[int]) -> None:
+    arr, n = _ids(prompt_tokens)
+    _check(_L().apar_server_submit(server, request_id, arr, n), "apar_server_submit")
+
+
+def apar_server_admit(server, k, v, rows_available: int, stream=None):
+    """Returns (requests admitted, prompt rows consumed from k, v)."""
+    n, used = C.c_int32(), C.c_int64()
+    _check(_L().apar_server_admit(server, _ptr(k), _ptr(v), rows_available, _stream(stream), C.byref(n), C.byref(used)),
+           "apar_server_admit")
+    return n.value, used.value
+
+
+def apar_server_batch(server):
+    """The batch as a numpy structured array (fields as apar_server_seq)."""
+    import numpy as np
+
+    n = C.c_int()
+    _L().apar_server_batch(server, None, 0, C.byref(n))
+    buf = (AparServerSeq * max(n.value, 1))()
+    _check(_L().apar_server_batch(server, buf, n.value, C.byref(n)), "apar_server_batch")
+    dt = np.dtype([("request_id", "<i4"), ("thread", "<i4"), ("seq_index", "<i4"), ("last_token", "<i4"),
+                   ("length", "<i8"), ("start_len", "<i8"), ("group_size", "<i4"), ("reserved", "<i4")])
+    return np.frombuffer(buf, dtype=dt, count=n.value).copy()
+
+
+def apar_server_step(server, sampled, k, v, stream=None) -> AparServerStepInfo:
+    arr, n = _ids(sampled)
+    info = AparServerStepInfo()
+    _check(_L().apar_server_step(server, arr, n, _ptr(k), _ptr(v), _stream(stream), C.byref(info)), "apar_server_step")
+    return info
+
+
+def apar_server_pop_finished(server):
+    """(request id, tokens in Restore order, AparGroupInfo) of the oldest completed request, or None."""
+    rid, n = C.c_int32(), C.c_int64()
+    rc = _L().apar_server_pop_finished(server, C.byref(rid), None, 0, C.byref(n), None)
+    if rid.value < 0:
+        _check(rc, "apar_server_pop_finished")
+        return None
+    buf = (C.c_int32 * max(n.value, 1))()
+    info = AparGroupInfo()
+    _check(_L().apar_server_pop_finished(server, C.byref(rid), buf, n.value, C.byref(n), C.byref(info)),
+           "apar_server_pop_finished")
+    return rid.value, list(buf[: n.value]), info
+
+
+def apar_server_get_stats(server) -> AparServerStats:
+    out = AparServerStats()
+    _check(_L().apar_server_get_stats(server, C.byref(out)), "apar_server_get_stats")
     return out
 
 

@@ -613,6 +613,21 @@ int apar_append_kv_batch(apar_pool* p, const apar_thread* threads, int n, const 
     return append_rows_of(p, threads, n, nullptr, k_dev, v_dev, hip_stream);
 }
 
+int apar_append_kv_gather(apar_pool* p, const apar_thread* threads, const int32_t* src_rows, int n, const void* k_dev,
+                          const void* v_dev, void* hip_stream) {
+    if (!p || n < 0) return APAR_ERR_INVALID_ARG;
+    if (n == 0) return APAR_OK;
+    if (!threads || !src_rows) return APAR_ERR_INVALID_ARG;
+    if (p->dry_run ? (k_dev || v_dev) : (!k_dev || !v_dev)) return APAR_ERR_INVALID_ARG;
+    for (int i = 0; i < n; ++i) {
+        if (!live_thread(p, threads[i])) return APAR_ERR_INVALID_THREAD;
+        if (src_rows[i] < 0) return APAR_ERR_INVALID_ARG;
+    }
+    std::vector<int32_t>& src = p->scratch_commit_src;
+    src.assign(src_rows, src_rows + n);
+    return append_rows_of(p, threads, n, &src, k_dev, v_dev, hip_stream);
+}
+
 int apar_commit_candidates(apar_pool* p, const apar_thread* threads, int n, const void* cand_k_dev,
                            const void* cand_v_dev, int n_cand, const uint8_t* accept_masks, void* hip_stream) {
     if (!p || n < 0 || n_cand < 1 || n_cand > 8) return APAR_ERR_INVALID_ARG;

@@ -6,6 +6,7 @@
 // Everything here goes through the public calls of apar.h.
 #include <algorithm>
 #include <cstring>
+#include <deque>
 #include <new>
 #include <vector>
 
@@ -37,8 +38,6 @@ struct apar_group {
     std::vector<PNode> nodes;
     int64_t prompt_len = 0;
     int64_t attended = 0, generated = 0, max_cached = 0, cached_now = 0, steps = 0;
-    std::vector<apar_thread> batch;
-    std::vector<int32_t> forking;
 };
 
 namespace {
@@ -71,6 +70,129 @@ int64_t cached_tokens(const apar_group* g) {
         }
     }
     return total;
+}
+
+// One AparDecode step of a group in three parts, so that several groups can share one batched append:
+// prepare forks the sequences whose last token is [Fork] and lists the threads of the rows to append
+// ([Child] row of a new thread, then the sampled token's row of its parent); commit does the bookkeeping
+// of Alg. 1 once the rows are in; rollback releases the forked children when they are not.
+struct StepPlan {
+    std::vector<int32_t> active;     // indices of the unfinished sequences, creation order
+    std::vector<apar_thread> kids;   // children forked by prepare, in order
+    std::vector<apar_thread> rows;   // thread of every row to append, in order
+};
+
+int step_prepare(apar_group* g, const int32_t* sampled, int n, StepPlan& sp) {
+    sp.active.clear(), sp.kids.clear(), sp.rows.clear();
+    for (int q = 0; q < (int)g->seqs.size(); ++q)
+        if (!g->seqs[q].finished) sp.active.push_back(q);
+    if ((int)sp.active.size() != n) return APAR_ERR_INVALID_ARG;
+    for (int i = 0; i < n; ++i)
+        if (sampled[i] == APAR_TOKEN_CHILD) return APAR_ERR_INVALID_ARG;  // injected, never sampled
+    // fork first (Alg. 1: s' <- s when s.last_token is [Fork]); undone if the rows do not fit
+    for (int i = 0; i < n; ++i) {
+        Seq& s = g->seqs[sp.active[i]];
+        if (s.last_token == APAR_TOKEN_FORK) {
+            apar_thread child;
+            const int rc = apar_fork(g->pool, s.tid, 1, &child);
+            if (rc != APAR_OK) {
+                for (apar_thread c : sp.kids) (void)apar_free_thread(g->pool, c);
+                sp.kids.clear();
+                return rc;
+            }
+            sp.kids.push_back(child);
+            sp.rows.push_back(child);  // the [Child] row
+        }
+        sp.rows.push_back(s.tid);      // the sampled token's row
+    }
+    return APAR_OK;
+}
+
+void step_rollback(apar_group* g, StepPlan& sp) {
+    for (apar_thread c : sp.kids) (void)apar_free_thread(g->pool, c);
+    sp.kids.clear();
+}
+
+void step_commit(apar_group* g, const int32_t* sampled, const StepPlan& sp, apar_group_step_info* info) {
+    const int n = (int)sp.active.size();
+    size_t kid = 0;
+    int n_finished = 0;
+    for (int i = 0; i < n; ++i) {
+        const int32_t q = sp.active[i];
+        g->attended += (int64_t)g->seqs[q].tokens.size();  // predicting x attended to all of s
+        g->generated += 1;
+        if (g->seqs[q].last_token == APAR_TOKEN_FORK) {
+            Seq c;
+            c.tid = sp.kids[kid++];
+            c.tokens = g->seqs[q].tokens;
+            c.tokens.push_back(APAR_TOKEN_CHILD);
+            c.last_token = APAR_TOKEN_CHILD;
+            c.parent = q;
+            c.fork_len = (int64_t)g->seqs[q].tokens.size();
+            const int32_t cq = (int32_t)g->seqs.size();
+            g->seqs.push_back(std::move(c));
+            Seq& s = g->seqs[q];
+            const int32_t n_sib = new_node(g, q, (int64_t)s.tokens.size());
+            const int32_t n_kid = new_node(g, cq, (int64_t)g->seqs[cq].tokens.size());
+            PNode& cur = g->nodes[s.current_node];
+            cur.end = (int64_t)s.tokens.size();
+            cur.next_sibling = n_sib;
+            cur.first_child = n_kid;
+            s.current_node = n_sib;
+            g->seqs[cq].current_node = n_kid;
+        }
+        Seq& s = g->seqs[q];
+        s.tokens.push_back(sampled[i]);
+        s.last_token = sampled[i];
+        if (sampled[i] == APAR_TOKEN_EOS) {
+            s.finished = true;
+            (void)apar_free_thread(g->pool, s.tid);  // ReleaseCache(s)
+            ++n_finished;
+        }
+    }
+    g->steps += 1;
+    g->cached_now = cached_tokens(g);
+    g->max_cached = std::max(g->max_cached, g->cached_now);
+    if (info) {
+        info->n_forked = (int32_t)sp.kids.size();
+        info->n_finished = n_finished;
+        info->n_rows_appended = (int32_t)sp.rows.size();
+        info->n_unfinished = 0;
+        for (const Seq& s : g->seqs) info->n_unfinished += s.finished ? 0 : 1;
+    }
+}
+
+int64_t restore_tokens(const apar_group* g, int32_t* tokens_out, int64_t cap) {
+    // Restore(r): node, then its first child's subtree, then its next sibling's
+    int64_t n = 0;
+    std::vector<int32_t> stack{0};
+    while (!stack.empty()) {
+        const int32_t id = stack.back();
+        stack.pop_back();
+        const PNode& nd = g->nodes[id];
+        const std::vector<int32_t>& tok = g->seqs[nd.seq].tokens;
+        const int64_t end = nd.end < 0 ? (int64_t)tok.size() : nd.end;
+        for (int64_t i = nd.start; i < end; ++i) {
+            if (n < cap) tokens_out[n] = tok[i];
+            ++n;
+        }
+        if (nd.next_sibling >= 0) stack.push_back(nd.next_sibling);
+        if (nd.first_child >= 0) stack.push_back(nd.first_child);
+    }
+    return n;
+}
+
+void fill_info(const apar_group* g, apar_group_info* out) {
+    out->n_sequences = (int64_t)g->seqs.size();
+    out->n_unfinished = 0;
+    for (const Seq& s : g->seqs) out->n_unfinished += s.finished ? 0 : 1;
+    out->n_nodes = (int64_t)g->nodes.size();
+    out->steps = g->steps;
+    out->prompt_tokens = g->prompt_len;
+    out->generated_tokens = g->generated;
+    out->attended_tokens = g->attended;
+    out->cached_tokens = g->cached_now;
+    out->max_cached_tokens = g->max_cached;
 }
 
 }  // namespace
@@ -134,122 +256,307 @@ int apar_group_unfinished(apar_group* g, apar_thread* threads_out, int cap, int*
 int apar_group_step(apar_group* g, const int32_t* sampled, int n, const void* k_dev, const void* v_dev,
                     void* hip_stream, apar_group_step_info* info) {
     if (!g || n < 0 || (n > 0 && !sampled)) return APAR_ERR_INVALID_ARG;
-    std::vector<int32_t> active;
-    for (int q = 0; q < (int)g->seqs.size(); ++q)
-        if (!g->seqs[q].finished) active.push_back(q);
-    if ((int)active.size() != n) return APAR_ERR_INVALID_ARG;
-    for (int i = 0; i < n; ++i)
-        if (sampled[i] == APAR_TOKEN_CHILD) return APAR_ERR_INVALID_ARG;  // injected, never sampled
+    StepPlan sp;
+    int rc = step_prepare(g, sampled, n, sp);
+    if (rc != APAR_OK) return rc;
     if (n == 0) {
         if (info) memset(info, 0, sizeof(*info));
         return APAR_OK;
     }
-    // fork first (Alg. 1: s' <- s when s.last_token is [Fork]); undo them if the rows do not fit
-    g->forking.clear();
-    g->batch.clear();
-    std::vector<apar_thread> kids;
-    int rc = APAR_OK;
-    for (int i = 0; i < n && rc == APAR_OK; ++i) {
-        Seq& s = g->seqs[active[i]];
-        if (s.last_token == APAR_TOKEN_FORK) {
-            apar_thread child;
-            rc = apar_fork(g->pool, s.tid, 1, &child);
-            if (rc != APAR_OK) break;
-            kids.push_back(child);
-            g->forking.push_back(i);
-            g->batch.push_back(child);  // the [Child] row
-        }
-        g->batch.push_back(s.tid);      // the sampled token's row
-    }
-    if (rc == APAR_OK)
-        rc = apar_append_kv_batch(g->pool, g->batch.data(), (int)g->batch.size(), k_dev, v_dev, hip_stream);
+    rc = apar_append_kv_batch(g->pool, sp.rows.data(), (int)sp.rows.size(), k_dev, v_dev, hip_stream);
     if (rc != APAR_OK) {
-        for (apar_thread c : kids) (void)apar_free_thread(g->pool, c);
+        step_rollback(g, sp);
         return rc;
     }
-    // commit: the bookkeeping of Alg. 1
-    size_t kid = 0;
-    int n_finished = 0;
-    for (int i = 0; i < n; ++i) {
-        const int32_t q = active[i];
-        g->attended += (int64_t)g->seqs[q].tokens.size();  // predicting x attended to all of s
-        g->generated += 1;
-        if (g->seqs[q].last_token == APAR_TOKEN_FORK) {
-            Seq c;
-            c.tid = kids[kid++];
-            c.tokens = g->seqs[q].tokens;
-            c.tokens.push_back(APAR_TOKEN_CHILD);
-            c.last_token = APAR_TOKEN_CHILD;
-            c.parent = q;
-            c.fork_len = (int64_t)g->seqs[q].tokens.size();
-            const int32_t cq = (int32_t)g->seqs.size();
-            g->seqs.push_back(std::move(c));
-            Seq& s = g->seqs[q];
-            const int32_t n_sib = new_node(g, q, (int64_t)s.tokens.size());
-            const int32_t n_kid = new_node(g, cq, (int64_t)g->seqs[cq].tokens.size());
-            PNode& cur = g->nodes[s.current_node];
-            cur.end = (int64_t)s.tokens.size();
-            cur.next_sibling = n_sib;
-            cur.first_child = n_kid;
-            s.current_node = n_sib;
-            g->seqs[cq].current_node = n_kid;
-        }
-        Seq& s = g->seqs[q];
-        s.tokens.push_back(sampled[i]);
-        s.last_token = sampled[i];
-        if (sampled[i] == APAR_TOKEN_EOS) {
-            s.finished = true;
-            (void)apar_free_thread(g->pool, s.tid);  // ReleaseCache(s)
-            ++n_finished;
-        }
-    }
-    g->steps += 1;
-    g->cached_now = cached_tokens(g);
-    g->max_cached = std::max(g->max_cached, g->cached_now);
-    if (info) {
-        info->n_forked = (int32_t)kids.size();
-        info->n_finished = n_finished;
-        info->n_rows_appended = (int32_t)g->batch.size();
-        info->n_unfinished = 0;
-        for (const Seq& s : g->seqs) info->n_unfinished += s.finished ? 0 : 1;
-    }
+    step_commit(g, sampled, sp, info);
     return APAR_OK;
 }
 
 int apar_group_restore(apar_group* g, int32_t* tokens_out, int64_t cap, int64_t* n_out) {
     if (!g || !n_out || cap < 0 || (cap > 0 && !tokens_out)) return APAR_ERR_INVALID_ARG;
-    // Restore(r): node, then its first child's subtree, then its next sibling's
-    int64_t n = 0;
-    std::vector<int32_t> stack{0};
-    while (!stack.empty()) {
-        const int32_t id = stack.back();
-        stack.pop_back();
-        const PNode& nd = g->nodes[id];
-        const std::vector<int32_t>& tok = g->seqs[nd.seq].tokens;
-        const int64_t end = nd.end < 0 ? (int64_t)tok.size() : nd.end;
-        for (int64_t i = nd.start; i < end; ++i) {
-            if (n < cap) tokens_out[n] = tok[i];
-            ++n;
-        }
-        if (nd.next_sibling >= 0) stack.push_back(nd.next_sibling);
-        if (nd.first_child >= 0) stack.push_back(nd.first_child);
-    }
+    const int64_t n = restore_tokens(g, tokens_out, cap);
     *n_out = n;
     return n <= cap ? APAR_OK : APAR_ERR_INVALID_ARG;
 }
 
 int apar_group_get_info(apar_group* g, apar_group_info* out) {
     if (!g || !out) return APAR_ERR_INVALID_ARG;
-    out->n_sequences = (int64_t)g->seqs.size();
-    out->n_unfinished = 0;
-    for (const Seq& s : g->seqs) out->n_unfinished += s.finished ? 0 : 1;
-    out->n_nodes = (int64_t)g->nodes.size();
-    out->steps = g->steps;
-    out->prompt_tokens = g->prompt_len;
-    out->generated_tokens = g->generated;
-    out->attended_tokens = g->attended;
-    out->cached_tokens = g->cached_now;
-    out->max_cached_tokens = g->max_cached;
+    fill_info(g, out);
+    return APAR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Serving loop: a queue of requests over one pool, with admission control, early
+// release (inside every group's step) and preemption when the pool runs dry.
+// ---------------------------------------------------------------------------
+struct apar_server {
+    apar_pool* pool = nullptr;
+    apar_server_config cfg{};
+    struct Waiting {
+        int32_t rid;
+        std::vector<int32_t> prompt;
+        int64_t order;  // submission order; a preempted request keeps its own
+    };
+    std::deque<Waiting> waiting;
+    struct Running {
+        int32_t rid;
+        int64_t order;
+        apar_group* g;
+        std::vector<int32_t> prompt;  // kept for a restart after preemption
+    };
+    std::vector<Running> running;  // admission order
+    struct Finished {
+        int32_t rid;
+        std::vector<int32_t> tokens;
+        apar_group_info info;
+    };
+    std::deque<Finished> finished;
+    apar_server_stats st{};
+    int64_t next_order = 0;
+    std::vector<StepPlan> plans;
+    std::vector<apar_thread> batch_threads;
+    std::vector<int32_t> batch_src;
+};
+
+static void server_note_usage(apar_server* s) {
+    apar_stats ps;
+    if (apar_pool_stats(s->pool, &ps) == APAR_OK) s->st.peak_used_blocks = std::max(s->st.peak_used_blocks, ps.used_blocks);
+    s->st.peak_running = std::max<int64_t>(s->st.peak_running, (int64_t)s->running.size());
+}
+
+int apar_server_create(apar_pool* pool, const apar_server_config* cfg, apar_server** out) {
+    if (!pool || !cfg || !out || cfg->max_running < 1 || cfg->watermark_blocks < 0) return APAR_ERR_INVALID_ARG;
+    apar_server* s = new (std::nothrow) apar_server();
+    if (!s) return APAR_ERR_INVALID_ARG;
+    s->pool = pool;
+    s->cfg = *cfg;
+    *out = s;
+    return APAR_OK;
+}
+
+int apar_server_destroy(apar_server* s) {
+    if (!s) return APAR_OK;
+    int rc = APAR_OK;
+    for (auto& r : s->running) {
+        const int e = apar_group_destroy(r.g);
+        if (e != APAR_OK) rc = e;
+    }
+    delete s;
+    return rc;
+}
+
+int apar_server_submit(apar_server* s, int32_t request_id, const int32_t* prompt_tokens, int n_prompt) {
+    if (!s || !prompt_tokens || n_prompt < 1) return APAR_ERR_INVALID_ARG;
+    apar_server::Waiting w;
+    w.rid = request_id;
+    w.prompt.assign(prompt_tokens, prompt_tokens + n_prompt);
+    w.order = s->next_order++;
+    s->waiting.push_back(std::move(w));
+    s->st.n_submitted += 1;
+    return APAR_OK;
+}
+
+int apar_server_admit(apar_server* s, const void* k_dev, const void* v_dev, int64_t rows_available, void* hip_stream,
+                      int32_t* n_admitted_out, int64_t* rows_used_out) {
+    if (!s || rows_available < 0) return APAR_ERR_INVALID_ARG;
+    apar_stats ps;
+    int rc = apar_pool_stats(s->pool, &ps);
+    if (rc != APAR_OK) return rc;
+    const bool dry = k_dev == nullptr && v_dev == nullptr;
+    const int64_t row_bytes = ps.block_bytes / 16 / 2;  // one token's K (or V) row over all kv heads
+    int32_t admitted = 0;
+    int64_t used = 0;
+    while (!s->waiting.empty() && (int)s->running.size() < s->cfg.max_running) {
+        apar_server::Waiting& w = s->waiting.front();
+        const int64_t n = (int64_t)w.prompt.size();
+        const int64_t need = (n + 15) / 16;
+        if ((rc = apar_pool_stats(s->pool, &ps)) != APAR_OK) return rc;
+        // first come first served: the head of the queue waits until it fits, nobody overtakes it
+        if (ps.free_blocks - need < s->cfg.watermark_blocks) break;
+        if (used + n > rows_available) break;
+        apar_group* g = nullptr;
+        rc = apar_group_create(s->pool, w.prompt.data(), (int)n, dry ? nullptr : (const char*)k_dev + used * row_bytes,
+                               dry ? nullptr : (const char*)v_dev + used * row_bytes, hip_stream, &g);
+        if (rc == APAR_ERR_OUT_OF_BLOCKS || rc == APAR_ERR_THREAD_CAPACITY) break;
+        if (rc != APAR_OK) return rc;
+        apar_server::Running r;
+        r.rid = w.rid;
+        r.order = w.order;
+        r.g = g;
+        r.prompt = std::move(w.prompt);
+        s->running.push_back(std::move(r));
+        s->waiting.pop_front();
+        used += n;
+        ++admitted;
+        s->st.n_admissions += 1;
+    }
+    server_note_usage(s);
+    if (n_admitted_out) *n_admitted_out = admitted;
+    if (rows_used_out) *rows_used_out = used;
+    return APAR_OK;
+}
+
+int apar_server_batch(apar_server* s, apar_server_seq* out, int cap, int* n_out) {
+    if (!s || !n_out || cap < 0 || (cap > 0 && !out)) return APAR_ERR_INVALID_ARG;
+    int n = 0;
+    for (const auto& r : s->running) {
+        const apar_group* g = r.g;
+        const int32_t size = (int32_t)g->seqs.size();
+        for (int q = 0; q < size; ++q) {
+            const Seq& sq = g->seqs[q];
+            if (sq.finished) continue;
+            if (n < cap) {
+                apar_server_seq& e = out[n];
+                e.request_id = r.rid;
+                e.thread = sq.tid;
+                e.seq_index = q;
+                e.last_token = sq.last_token;
+                e.length = (int64_t)sq.tokens.size();
+                e.start_len = sq.parent < 0 ? g->prompt_len : sq.fork_len + 1;
+                e.group_size = size;
+                e.reserved = 0;
+            }
+            ++n;
+        }
+    }
+    *n_out = n;
+    return n <= cap ? APAR_OK : APAR_ERR_INVALID_ARG;
+}
+
+int apar_server_step(apar_server* s, const int32_t* sampled, int n, const void* k_dev, const void* v_dev,
+                     void* hip_stream, apar_server_step_info* info) {
+    if (!s || n < 0 || (n > 0 && !sampled)) return APAR_ERR_INVALID_ARG;
+    if (info) memset(info, 0, sizeof(*info));
+    // each running request's slice of `sampled` and of the rows in k_dev, v_dev
+    const size_t n_run = s->running.size();
+    std::vector<int32_t> tok_ofs(n_run + 1, 0), row_ofs(n_run + 1, 0);
+    for (size_t r = 0; r < n_run; ++r) {
+        const apar_group* g = s->running[r].g;
+        int32_t unfinished = 0, forking = 0;
+        for (const Seq& sq : g->seqs)
+            if (!sq.finished) {
+                ++unfinished;
+                forking += sq.last_token == APAR_TOKEN_FORK ? 1 : 0;
+            }
+        tok_ofs[r + 1] = tok_ofs[r] + unfinished;
+        row_ofs[r + 1] = row_ofs[r] + unfinished + forking;
+    }
+    if (tok_ofs[n_run] != n) return APAR_ERR_INVALID_ARG;
+    s->plans.resize(n_run);
+    size_t n_live = n_run;  // requests [0, n_live) take part; the ones after them were preempted in this call
+    // put the preempted requests back, oldest first at the head
+    auto requeue = [&]() {
+        for (size_t r = n_run; r-- > n_live;) {
+            apar_server::Waiting w;
+            w.rid = s->running[r].rid;
+            w.order = s->running[r].order;
+            w.prompt = std::move(s->running[r].prompt);
+            s->waiting.push_front(std::move(w));
+        }
+        s->running.resize(n_live);
+        std::stable_sort(s->waiting.begin(), s->waiting.end(),
+                         [](const apar_server::Waiting& a, const apar_server::Waiting& b) { return a.order < b.order; });
+    };
+    for (;;) {
+        s->batch_threads.clear();
+        s->batch_src.clear();
+        int rc = APAR_OK;
+        size_t prepared = 0;
+        for (; prepared < n_live; ++prepared) {
+            rc = step_prepare(s->running[prepared].g, sampled + tok_ofs[prepared],
+                              tok_ofs[prepared + 1] - tok_ofs[prepared], s->plans[prepared]);
+            if (rc != APAR_OK) break;
+            const StepPlan& sp = s->plans[prepared];
+            for (size_t i = 0; i < sp.rows.size(); ++i) {
+                s->batch_threads.push_back(sp.rows[i]);
+                s->batch_src.push_back(row_ofs[prepared] + (int32_t)i);
+            }
+        }
+        if (rc == APAR_OK && !s->batch_threads.empty())
+            rc = apar_append_kv_gather(s->pool, s->batch_threads.data(), s->batch_src.data(),
+                                       (int)s->batch_threads.size(), k_dev, v_dev, hip_stream);
+        if (rc == APAR_OK) break;
+        for (size_t r = 0; r < prepared; ++r) step_rollback(s->running[r].g, s->plans[r]);
+        if (rc != APAR_ERR_OUT_OF_BLOCKS || n_live == 0) {
+            requeue();
+            return rc;
+        }
+        // the pool cannot hold this step: the most recently admitted request gives way (it is released
+        // and goes back to the head of the queue, to start again from its prompt)
+        apar_server::Running& victim = s->running[n_live - 1];
+        (void)apar_group_destroy(victim.g);
+        victim.g = nullptr;
+        --n_live;
+        s->st.n_preemptions += 1;
+        if (info) info->n_preempted += 1;
+    }
+    requeue();
+    // bookkeeping of Alg. 1 for everyone who stayed; early release happens in there
+    int64_t batch = 0;
+    for (size_t r = 0; r < n_live; ++r) {
+        apar_group_step_info gi;
+        step_commit(s->running[r].g, sampled + tok_ofs[r], s->plans[r], &gi);
+        batch += tok_ofs[r + 1] - tok_ofs[r];
+        if (info) {
+            info->n_forked += gi.n_forked;
+            info->n_finished_sequences += gi.n_finished;
+            info->n_rows_appended += gi.n_rows_appended;
+        }
+    }
+    s->st.steps += 1;
+    s->st.generated_tokens += batch;
+    s->st.batch_sequences_total += batch;
+    s->st.peak_threads = std::max(s->st.peak_threads, batch);
+    server_note_usage(s);  // the peak is reached before the finished requests are collected
+    // completed requests leave, in admission order
+    size_t keep = 0;
+    for (size_t r = 0; r < n_live; ++r) {
+        apar_group* g = s->running[r].g;
+        bool done = true;
+        for (const Seq& sq : g->seqs) done = done && sq.finished;
+        if (!done) {
+            if (keep != r) s->running[keep] = std::move(s->running[r]);
+            ++keep;
+            continue;
+        }
+        apar_server::Finished f;
+        f.rid = s->running[r].rid;
+        f.tokens.resize((size_t)restore_tokens(g, nullptr, 0));
+        (void)restore_tokens(g, f.tokens.data(), (int64_t)f.tokens.size());
+        fill_info(g, &f.info);
+        s->finished.push_back(std::move(f));
+        (void)apar_group_destroy(g);
+        s->st.n_finished += 1;
+        if (info) info->n_finished_requests += 1;
+    }
+    s->running.resize(keep);
+    if (info) info->n_running = (int32_t)keep;
+    return APAR_OK;
+}
+
+int apar_server_pop_finished(apar_server* s, int32_t* request_id_out, int32_t* tokens_out, int64_t cap,
+                             int64_t* n_tokens_out, apar_group_info* info_out) {
+    if (!s || !request_id_out || !n_tokens_out || cap < 0 || (cap > 0 && !tokens_out)) return APAR_ERR_INVALID_ARG;
+    if (s->finished.empty()) {
+        *request_id_out = -1;
+        *n_tokens_out = 0;
+        return APAR_OK;
+    }
+    apar_server::Finished& f = s->finished.front();
+    *request_id_out = f.rid;
+    *n_tokens_out = (int64_t)f.tokens.size();
+    if (cap < (int64_t)f.tokens.size()) return APAR_ERR_INVALID_ARG;  // the request stays at the head
+    if (!f.tokens.empty()) memcpy(tokens_out, f.tokens.data(), f.tokens.size() * sizeof(int32_t));
+    if (info_out) *info_out = f.info;
+    s->finished.pop_front();
+    return APAR_OK;
+}
+
+int apar_server_get_stats(apar_server* s, apar_server_stats* out) {
+    if (!s || !out) return APAR_ERR_INVALID_ARG;
+    *out = s->st;
+    out->n_waiting = (int64_t)s->waiting.size();
+    out->n_running = (int64_t)s->running.size();
     return APAR_OK;
 }
 

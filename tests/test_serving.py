@@ -1,0 +1,132 @@
+"""The serving loop (queue, admission, early release, preemption) of the library against the plain-Python
+oracle loop, on bookkeeping-only pools (CPU)."""
+import numpy as np
+import pytest
+
+import paper_2401_06761_amd as ap
+from apar_workloads import SamplerConfig, make_requests, sample_flat, sample_tokens
+from oracle import BlockLedger
+from oracle.serving import ServingOracle
+from paper_2401_06761_amd.serving import ServingRun
+
+from harness import books_equal
+
+CFG = SamplerConfig(p_fork=0.05, p_eos=0.02, max_threads=6, min_new=12, max_len=260)
+
+
+def _oracle_run(reqs, n_blocks, max_running, watermark, flat=None, check=None):
+    led = BlockLedger(n_blocks, max_threads=1 << 30)
+    o = ServingOracle(led, max_running, watermark)
+    by = {r.rid: r for r in reqs}
+    for r in reqs:
+        o.submit(r.rid, r.prompt_tokens())
+    trace = []
+    while True:
+        adm = o.admit()
+        b = o.batch()
+        if not b:
+            assert not o.waiting
+            break
+        seeds = [by[e["request_id"]].seed for e in b]
+        if flat is None:
+            xs = sample_tokens(CFG, seeds, [e["seq_index"] for e in b], [e["length"] for e in b],
+                               [e["last_token"] for e in b], [e["start_len"] for e in b], [e["group_size"] for e in b])
+        else:
+            xs = sample_flat(CFG, seeds, [e["length"] for e in b], [flat[e["request_id"]] for e in b])
+        info = o.step(xs.tolist())
+        trace.append({"admitted": len(adm), "threads": [e["thread"] for e in b], "sampled": xs.tolist(),
+                      "n_preempted": info["n_preempted"], "n_forked": info["n_forked"],
+                      "n_rows_appended": info["n_rows_appended"], "n_finished_requests": info["n_finished_requests"]})
+        if check is not None:
+            check(len(trace), led)
+    return o, led, trace
+
+
+@pytest.mark.parametrize("n_blocks,max_running,watermark", [(4096, 64, 0), (160, 12, 2), (96, 40, 0), (64, 8, 4)])
+def test_serving_loop_matches_oracle_step_by_step(n_blocks, max_running, watermark):
+    reqs = make_requests(24, seed=n_blocks, prompt_lo=8, prompt_hi=120)
+    pool = ap.Pool(4, 2, 64, "f32", n_blocks, max_threads=1 << 30, dry_run=True)
+    run = ServingRun(pool, reqs, CFG, max_running, watermark)
+    run.keep_trace = True
+    stats = run.run()
+    o, led, trace = _oracle_run(reqs, n_blocks, max_running, watermark)
+    assert run.trace == trace
+    assert run.outputs == {rid: toks for rid, toks, _ in o.finished}
+    assert sorted(run.outputs) == [r.rid for r in reqs]           # everybody completes
+    assert [rid for rid, _, _ in o.finished] == list(run.outputs)  # in the same order
+    for rid, _, g in o.finished:
+        gi = run.infos[rid]
+        assert (gi.max_cached_tokens, gi.attended_tokens, gi.generated_tokens) == (g.max_cached, g.attended, g.generated)
+    assert (stats["steps"], stats["preemptions"], stats["admissions"]) == (o.steps, o.preemptions, o.admissions)
+    assert stats["peak_used_blocks"] == o.peak_used and stats["peak_threads"] == o.peak_threads
+    assert stats["generated_tokens"] == o.generated
+    if n_blocks <= 160:
+        assert stats["preemptions"] > 0   # these pools are tight on purpose
+    books_equal(pool.handle, led)
+    assert ap.apar_pool_stats(pool.handle).used_blocks == 0
+    run.close()
+    pool.close()
+
+
+def test_books_agree_after_every_step_under_preemption():
+    reqs = make_requests(10, seed=3, prompt_lo=8, prompt_hi=100)
+    pool = ap.Pool(4, 2, 64, "f32", 48, max_threads=1 << 30, dry_run=True)
+    run = ServingRun(pool, reqs, CFG, 6, 1)
+    snapshots = []
+
+    def check(step, led):
+        # advance the library to the same step and compare the books
+        while len(snapshots) < step:
+            assert run.step()
+            snapshots.append(1)
+        books_equal(pool.handle, led)
+
+    o, led, trace = _oracle_run(reqs, 48, 6, 1, check=check)
+    assert o.preemptions > 0
+    run.close()
+    pool.close()
+
+
+def test_flat_stand_in_needs_more_steps_and_more_cache_for_the_same_responses():
+    # the same responses decoded sequentially: one sequence per request, as long as prompt + output
+    reqs = make_requests(16, seed=9, prompt_lo=8, prompt_hi=64)
+    big = 4096
+    pool = ap.Pool(4, 2, 64, "f32", big, max_threads=1 << 30, dry_run=True)
+    a = ServingRun(pool, reqs, CFG, 16, 0)
+    sa = a.run()
+    a.close()
+    flat = {r.rid: r.prompt_len + len(a.outputs[r.rid]) for r in reqs}
+    b = ServingRun(pool, reqs, CFG, 16, 0, flat_lengths=flat)
+    sb = b.run()
+    b.close()
+    assert {rid: len(t) for rid, t in b.outputs.items()} == {rid: len(t) for rid, t in a.outputs.items()}
+    assert sb["steps"] > sa["steps"]                      # parallel threads shorten the critical path
+    assert sb["peak_used_blocks"] >= sa["peak_used_blocks"]  # early release: never more cache than sequential
+    # Sec. 3.4: per response, APAR never caches more tokens at once than sequential decoding holds at its end
+    for r in reqs:
+        assert a.infos[r.rid].max_cached_tokens <= flat[r.rid]
+        assert a.infos[r.rid].attended_tokens <= b.infos[r.rid].attended_tokens
+    pool.close()
+
+
+def test_server_argument_checks():
+    pool = ap.Pool(4, 2, 64, "f32", 16, dry_run=True)
+    for bad in ((0, 0), (4, -1)):
+        with pytest.raises(ap.AparError):
+            ap.apar_server_create(pool.handle, *bad)
+    srv = ap.apar_server_create(pool.handle, 2, 0)
+    with pytest.raises(ap.AparError):
+        ap.apar_server_submit(srv, 1, [])
+    ap.apar_server_submit(srv, 7, list(range(20)))
+    assert ap.apar_server_pop_finished(srv) is None
+    assert ap.apar_server_admit(srv, None, None, 1 << 30) == (1, 20)
+    b = ap.apar_server_batch(srv)
+    assert len(b) == 1 and b["request_id"][0] == 7 and b["length"][0] == 20 and b["start_len"][0] == 20
+    with pytest.raises(ap.AparError):
+        ap.apar_server_step(srv, [1, 2], None, None)   # wrong batch size
+    ap.apar_server_step(srv, [ap.APAR_TOKEN_EOS], None, None)
+    rid, toks, info = ap.apar_server_pop_finished(srv)
+    assert (rid, toks) == (7, [ap.APAR_TOKEN_EOS]) and info.generated_tokens == 1
+    assert ap.apar_pool_stats(pool.handle).used_blocks == 0
+    ap.apar_server_destroy(srv)
+    pool.close()
