@@ -208,6 +208,71 @@ def prefill_bench(args, w) -> int:
     return 0
 
 
+def serving_bench(args) -> int:
+    """Secondary measurement: throughput of the serving loop against the size of the KV pool, for APAR
+    decoding and for the sequential stand-in of the same responses (the shape of the paper's
+    throughput-vs-cache-memory experiment, Sec. 3.3), on synthetic requests."""
+    import numpy as np
+    import torch
+
+    import paper_2401_06761_amd as ap
+    from apar_workloads import SamplerConfig, make_requests
+    from paper_2401_06761_amd.serving import ServingRun
+
+    n_q = n_kv = 32
+    d = 128
+    cfg = SamplerConfig()
+    reqs = make_requests(args.requests or 256, seed=args.seed)
+    cap = args.max_running
+    # responses and the cache a sequential decoder needs for them at this concurrency: dry runs
+    dry = ap.Pool(n_q, n_kv, d, "bf16", 1 << 22, max_threads=1 << 30, dry_run=True)
+    a = ServingRun(dry, reqs, cfg, cap, 0)
+    sa = a.run()
+    a.close()
+    flat = {r.rid: r.prompt_len + len(a.outputs[r.rid]) for r in reqs}
+    b = ServingRun(dry, reqs, cfg, cap, 0, flat_lengths=flat)
+    sb = b.run()
+    b.close()
+    dry.close()
+    full = int(sb["peak_used_blocks"])
+    longest = max(flat.values())
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev).manual_seed(args.seed)
+    qb = (0.09 * torch.randn((4096, n_q, d), generator=gen, device=dev)).to(torch.bfloat16)
+    kb = (0.09 * torch.randn((8192, n_kv, d), generator=gen, device=dev)).to(torch.bfloat16)
+    vb = (0.09 * torch.randn((8192, n_kv, d), generator=gen, device=dev)).to(torch.bfloat16)
+    rows = []
+    for frac in (0.1, 0.2, 0.4, 0.8, 1.0):
+        n_blocks = max(int(frac * full), (longest + 15) // 16 * 2 + 8)
+        for mode in ("apar", "sequential"):
+            pool = ap.Pool(n_q, n_kv, d, "bf16", n_blocks, max_threads=1 << 24, device=dev)
+            run = ServingRun(pool, reqs, cfg, cap, max(1, n_blocks // 100),
+                             flat_lengths=None if mode == "apar" else flat, banks=(qb, kb, vb))
+            st = run.run()
+            assert st["finished"] == len(reqs)
+            st.update({"mode": mode, "pool_fraction": frac, "pool_blocks": n_blocks,
+                       "pool_GB": n_blocks * ap.apar_pool_stats(pool.handle).block_bytes / 1e9,
+                       "output_tokens_per_s": st["useful_tokens"] / st["wall_s"],
+                       "ms_per_step": st["wall_s"] / max(st["steps"], 1) * 1e3})
+            rows.append(st)
+            run.close()
+            pool.close()
+    best = max(r["output_tokens_per_s"] for r in rows if r["mode"] == "apar")
+    line = {
+        "metric": "serving loop output tokens/s against KV pool size (secondary; the headline is the decode step)",
+        "value": best, "unit": "output-tokens/s", "n_gpus": 1, "steps": int(sa["steps"]), "warmup": 0,
+        "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{len(reqs)} synthetic requests queued at the start (prompts 16..256 tokens, up to "
+                               f"{cfg.max_threads} threads per response, fork {cfg.p_fork} / eos {cfg.p_eos} per token), "
+                               f"at most {cap} running, Hq=Hkv=32 d=128; pool sized as a fraction of the "
+                               f"{full} blocks the sequential decoder peaks at"},
+        "sweep": rows,
+    }
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap_ = argparse.ArgumentParser()
     ap_.add_argument("--gpus", type=int, default=1)
@@ -222,6 +287,9 @@ def main() -> int:
     ap_.add_argument("--no-cpu-baseline", action="store_true")
     ap_.add_argument("--prefill", action="store_true",
                      help="measure apar_prefill_attention over the workload's segments instead of the decode step")
+    ap_.add_argument("--serving", action="store_true",
+                     help="measure the serving loop (admission, early release, preemption) against the pool size")
+    ap_.add_argument("--max-running", type=int, default=64)
     ap_.add_argument("--two-pass", action="store_true",
                      help="spec128: gather the accepted rows on the caller's side and append them with "
                           "apar_append_kv_batch instead of apar_commit_candidates")
@@ -245,6 +313,8 @@ def main() -> int:
     dev = "cuda:0"
     w = make_config(args.config, seed=args.seed, n_requests=args.requests)
     hd = w.heads
+    if args.serving:
+        return serving_bench(args)
     if args.prefill:
         return prefill_bench(args, w)
     if args.config == "spec128":
