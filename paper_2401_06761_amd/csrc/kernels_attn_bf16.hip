@@ -96,17 +96,12 @@ __device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {  // rou
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
-// Online softmax step and O^T += V^T.P^T for one tile that applies to this lane's row iff in_range.
-// The softmax scale and the reference are folded into one fused multiply-add per logit; rows outside
-// the range, and slots masked to -inf, get probability exp2(-inf) = 0.  V rows of unfilled slots must
-// be finite (the loaders zero them): 0 * V is added for them.
-__device__ __forceinline__ void accumulate(const Frag (&v)[4], RowState& st, const f32x4& s, bool in_range,
-                                           float scale_log2e) {
+// Online softmax step, first half: if some row's logits ran away from its reference (always so for a
+// row's first tile, whose reference is still -inf), move every row's reference to its running maximum
+// (the four lanes of a row agree on it) and rescale what was summed.  Rare, hence behind a branch.
+__device__ __forceinline__ void move_reference(RowState& st, const f32x4& s, bool in_range, float scale_log2e) {
     const float top = in_range ? fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])) * scale_log2e : -INFINITY;
     if (__builtin_amdgcn_ballot_w64(top > st.m + kSlack) != 0) {
-        // some row's logits ran away from its reference (always so for a row's first tile, whose
-        // reference is still -inf): move every row's reference to its running maximum (the four
-        // lanes of a row agree on it) and rescale what was summed
         float mx = fmaxf(top, __shfl_xor(top, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(st.m, mx);
@@ -117,6 +112,14 @@ __device__ __forceinline__ void accumulate(const Frag (&v)[4], RowState& st, con
         for (int j = 0; j < 8; ++j) st.o[j] *= alpha;
         st.m = m_new;
     }
+}
+
+// Second half, straight-line: probabilities and O^T += V^T.P^T for one tile that applies to this lane's
+// row iff in_range.  The softmax scale and the reference are folded into one fused multiply-add per
+// logit; rows outside the range, and slots masked to -inf, get probability exp2(-inf) = 0.  V rows of
+// unfilled slots must be finite (the loaders zero them): 0 * V is added for them.
+__device__ __forceinline__ void weigh_values(const Frag (&v)[4], RowState& st, const f32x4& s, bool in_range,
+                                             float scale_log2e) {
     const float bias = (in_range && st.m != -INFINITY) ? -st.m : -INFINITY;
     float p[4];
 #pragma unroll
@@ -133,6 +136,12 @@ __device__ __forceinline__ void accumulate(const Frag (&v)[4], RowState& st, con
         st.o[2 * r] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v[r].h4[0], pp.h, st.o[2 * r], 0, 0, 0);
         st.o[2 * r + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v[r].h4[1], pp.h, st.o[2 * r + 1], 0, 0, 0);
     }
+}
+
+__device__ __forceinline__ void accumulate(const Frag (&v)[4], RowState& st, const f32x4& s, bool in_range,
+                                           float scale_log2e) {
+    move_reference(st, s, in_range, scale_log2e);
+    weigh_values(v, st, s, in_range, scale_log2e);
 }
 
 // V^T operand pieces out of a ROW-MAJOR V half held in LDS (rows `stride` bytes apart):
@@ -234,6 +243,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         return lo < min((nt + 1) * cap, wi.n_grp) && hi > nt * cap;
     };
 
+    // Makes the query operands' loads known to have landed (an empty statement that names the registers:
+    // the compiler must wait for them there).  Used once in front of the shared-tile loops.  Without it the
+    // compiler's wait-count bookkeeping carries the query loads of the kernel's start into those loops as
+    // if they were the youngest loads in flight, and every product waits for the tile prefetch issued just
+    // before it, which defeats the prefetch.
+    auto settle_queries = [&]() {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) asm("" : "+v"(st[nt].q[kk].u));
+    };
+
     // ---- shared tiles: staged once in LDS for the whole workgroup ---------------------------
     // Tiles go through LDS in groups of four, one whole tile per wavefront: while a group is consumed
     // from LDS, each wavefront already has its tile of the next group in flight to its registers.
@@ -297,16 +318,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
                 for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + c * 256 + g4 * 64 + r * 16);
                 v_operands_from_rows(sb + 4096, 256, g4, c, vs);
             }
+            // phase by phase over the row tiles, so that the products of one overlap the softmax of another
+            f32x4 s[NT];
+            bool on[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                if (NT > 1 && !touches(nt, lo, hi)) continue;
-                f32x4 s = products(ks, st[nt]);
-                if ((!kFull && valid < 16) || (meta >> 30)) mask_tokens(s, visible(meta, my_j[nt] - lo), g4);
-                accumulate(vs, st[nt], s, my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+                on[nt] = NT == 1 || touches(nt, lo, hi);
+                if (on[nt]) s[nt] = products(ks, st[nt]);
             }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                if (!on[nt]) continue;
+                if ((!kFull && valid < 16) || (meta >> 30)) mask_tokens(s[nt], visible(meta, my_j[nt] - lo), g4);
+                move_reference(st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (on[nt]) weigh_values(vs, st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
         };
         if (n_coop_full > 0) {  // the full tiles; which wavefront fetches is a scalar decision
             if (wave < n_coop_full) fetch_full(wave);
+            settle_queries();
             for (int t0 = 0; t0 < n_coop_full; t0 += 4) {
                 if (t0 > 0) __syncthreads();  // everyone is done reading the previous group
                 if (t0 + wave < n_coop_full) to_stage();
@@ -319,6 +351,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         if (n_coop_full < n_coop) {  // the open tiles
             if (n_coop_full > 0) __syncthreads();
             fetch_any(n_coop_full + wave);
+            settle_queries();
             for (int t0 = n_coop_full; t0 < n_coop; t0 += 4) {
                 if (t0 > n_coop_full) __syncthreads();
                 if (t0 + wave < n_coop) to_stage();
@@ -397,8 +430,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             for (int nt = 0; nt < NT; ++nt) {
                 if (NT > 1 && !touches(nt, lo, hi)) continue;
                 if (meta >> 30) mask_tokens(s[nt], visible(meta, my_j[nt] - lo), g4);
-                accumulate(v, st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+                move_reference(st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
             }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (NT == 1 || touches(nt, lo, hi))
+                    weigh_values(v, st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
             issue_v_full(tn);
             meta = meta_n;
         }
