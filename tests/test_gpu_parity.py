@@ -396,3 +396,29 @@ def test_prefill_attention_over_tree_segments(dtype, n_q, n_kv, d):
         ap.apar_decode_attention(pool.handle, qd, live, b)
         t.cuda.synchronize()
         assert np.abs(to_host(a) - to_host(b)).max() <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128)])
+def test_append_kv_gather_takes_the_named_rows(dtype, d):
+    t = torch()
+    with ap.Pool(4, 2, d, dtype, 16) as pool:
+        poison(pool)
+        dense = DenseThreads(4, 2, d)
+        a, b = ap.apar_thread_create(pool.handle), ap.apar_thread_create(pool.handle)
+        assert (dense.create(), dense.create()) == (a, b)
+        rng = np.random.default_rng(2)
+        k = quantise(rng.standard_normal((40, 2, d)).astype(np.float32), dtype)
+        v = quantise(rng.standard_normal((40, 2, d)).astype(np.float32), dtype)
+        threads = [a, b, a, a, b] * 7
+        src = [int(x) for x in rng.integers(0, 40, size=len(threads))]
+        ap.apar_append_kv_gather(pool.handle, threads, src, to_dev(k, dtype), to_dev(v, dtype))
+        for th, s_ in zip(threads, src):
+            dense.append(th, k[s_:s_ + 1], v[s_:s_ + 1])
+        for th in (a, b):
+            L = dense.length(th)
+            ko = t.empty((L, 2, d), dtype=pool.torch_dtype, device="cuda:0")
+            vo = t.empty_like(ko)
+            ap.apar_read_kv_rows(pool.handle, th, 0, L, ko, vo)
+            t.cuda.synchronize()
+            K, V = dense.rows(th)
+            assert np.array_equal(to_host(ko), K) and np.array_equal(to_host(vo), V)

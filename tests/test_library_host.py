@@ -316,3 +316,25 @@ def test_prefill_needs_a_group_size_that_divides_16():
         with pytest.raises(ap.AparError) as e:
             ap.apar_prefill_attention(pool.handle, None, [t], [5], None)
         assert e.value.status == -6
+
+
+def test_empty_calls_are_no_ops_and_gather_checks_its_arguments():
+    with ap.Pool(4, 2, 64, "f32", 8, dry_run=True) as pool:
+        h = pool.handle
+        t = ap.apar_thread_create(h)
+        ap.apar_append_kv(h, t, None, None, 3)
+        before = ap.apar_pool_stats(h).used_blocks
+        ap.apar_commit_candidates(h, [], None, None, 5, [])
+        ap.apar_append_kv_gather(h, [], [], None, None)
+        ap.apar_prefill_attention(h, None, [], [], None)
+        ap.apar_decode_attention(h, None, [], None)
+        assert ap.apar_pool_stats(h).used_blocks == before and ap.apar_thread_len(h, t) == 3
+        ap.apar_append_kv_gather(h, [t, t], [7, 0], None, None)
+        assert ap.apar_thread_len(h, t) == 5
+        with pytest.raises(ap.AparError) as e:
+            ap.apar_append_kv_gather(h, [t], [-1], None, None)
+        assert e.value.status == -1
+        with pytest.raises(ap.AparError) as e:
+            ap.apar_append_kv_gather(h, [99], [0], None, None)
+        assert e.value.status == -2
+        assert ap.apar_thread_len(h, t) == 5
