@@ -117,7 +117,7 @@ __device__ __forceinline__ void move_reference(RowState& st, const f32x4& s, boo
 // Second half, straight-line: probabilities and O^T += V^T.P^T for one tile that applies to this lane's
 // row iff in_range.  The softmax scale and the reference are folded into one fused multiply-add per
 // logit; rows outside the range, and slots masked to -inf, get probability exp2(-inf) = 0.  V rows of
-// unfilled slots must be finite (the loaders zero them): 0 * V is added for them.
+// unfilled slots must be finite (the loaders hand over a copy of row 0 for them): 0 * V is added.
 __device__ __forceinline__ void weigh_values(const Frag (&v)[4], RowState& st, const f32x4& s, bool in_range,
                                              float scale_log2e) {
     const float bias = (in_range && st.m != -INFINITY) ? -st.m : -INFINITY;
@@ -279,16 +279,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             if (fill == 16) {
                 fetch_full(t);
             } else {
-                // an open block is row-major: piece r of this lane belongs to token row 4r + g4, and rows
-                // past the fill count are not fetched at all (they read as zero)
-                const char* tile = head_base + coop[t].blk * block_stride + lane * 16;
+                // an open block is row-major: piece r of this lane belongs to token row 4r + g4.  Rows past the
+                // fill count are never read: their lanes re-read row 0 instead (same cache lines, no extra
+                // traffic, no branch around a load); the masked logits give those slots probability 0.
+                const char* tile = head_base + coop[t].blk * block_stride + c * 16;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    rk[r] = rv[r] = u32x4{0u, 0u, 0u, 0u};
-                    if (4 * r + g4 < fill) {
-                        rk[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + r * 1024));
-                        rv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + r * 1024));
-                    }
+                    const int row = 4 * r + g4 < fill ? 4 * r + g4 : 0;
+                    rk[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + row * 256));
+                    rv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + row * 256));
                 }
             }
         };
@@ -380,30 +379,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
 #pragma unroll
         for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(p + r * 64);
     };
-    // Only the filled rows of an open tile are fetched; the others read as zero.
+    // Only the filled rows of an open tile are read: a lane whose row lies past the fill count re-reads
+    // row 0 (no branch around the loads, no extra traffic), and the masked logits give the slot probability 0.
     auto issue_k = [&](const char* tile, int valid) {
         if (valid == 16) {
             issue_k_full(tile);
         } else {
-            const char* p = tile + c * 256 + g4 * 64;
+            const char* p = tile + (c < valid ? c : 0) * 256 + g4 * 64;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) k[r].u = u32x4{0u, 0u, 0u, 0u};
-            if (c < valid) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    k[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + r * 16));
-            }
+            for (int r = 0; r < 4; ++r)
+                k[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + r * 16));
         }
     };
     auto issue_v = [&](const char* tile, int valid) {
         if (valid == 16) {
             issue_v_full(tile);
         } else {
-            const u32x4* p = reinterpret_cast<const u32x4*>(tile + 4096) + lane;
+            const char* p = tile + 4096 + c * 16;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {  // raw piece r of this lane is part of token row 4r + g4
-                v[r].u = u32x4{0u, 0u, 0u, 0u};
-                if (4 * r + g4 < valid) v[r].u = __builtin_nontemporal_load(p + r * 64);
+                const int row = 4 * r + g4 < valid ? 4 * r + g4 : 0;
+                v[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + row * 256));
             }
         }
     };
@@ -540,10 +536,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             Frag kc[4], vc[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                kc[r].u = u32x4{0u, 0u, 0u, 0u};
-                if (c < n_cand) kc[r].u = *reinterpret_cast<const u32x4*>(kb + c * tok_stride + g4 * 64 + r * 16);
-                u32x4 vr = u32x4{0u, 0u, 0u, 0u};
-                if (4 * r + g4 < n_cand) vr = *reinterpret_cast<const u32x4*>(vb + (4 * r + g4) * tok_stride + c * 16);
+                // rows past the last candidate: re-read candidate 0 (finite values under probability 0)
+                kc[r].u = *reinterpret_cast<const u32x4*>(kb + (c < n_cand ? c : 0) * tok_stride + g4 * 64 + r * 16);
+                const int row = 4 * r + g4 < n_cand ? 4 * r + g4 : 0;
+                const u32x4 vr = *reinterpret_cast<const u32x4*>(vb + row * tok_stride + c * 16);
                 *reinterpret_cast<u32x4*>(scratch + (4 * r + g4) * kOpenRowStride + c * 16) = vr;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
