@@ -422,3 +422,67 @@ def test_append_kv_gather_takes_the_named_rows(dtype, d):
             t.cuda.synchronize()
             K, V = dense.rows(th)
             assert np.array_equal(to_host(ko), K) and np.array_equal(to_host(vo), V)
+
+
+def _random_forest(rng, n_roots, max_nodes):
+    parents, segs = [], []
+    for _ in range(n_roots):
+        parents.append(-1)
+        segs.append(int(rng.integers(1, 90)))
+    while len(parents) < max_nodes:
+        p = int(rng.integers(0, len(parents)))
+        for _ in range(int(rng.integers(1, 7))):
+            parents.append(p)
+            segs.append(int(rng.choice([1, 2, 15, 16, 17, 31, 33, int(rng.integers(1, 70))])))
+    return parents, segs
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_forests_decode_spec_and_prefill(seed):
+    """Seeded random forests (deep and wide mixes, segment lengths around the block boundaries), random head
+    grouping, random unit caps: decode, multi-candidate decode and prefill against the dense oracle."""
+    t = torch()
+    rng = np.random.default_rng(1000 + seed)
+    n_kv = int(rng.choice([1, 2]))
+    group = int(rng.choice([1, 2, 4, 8]))
+    n_q = n_kv * group
+    heads = HeadConfig(n_q, n_kv, 128, "bf16")
+    parents, segs = _random_forest(rng, int(rng.integers(1, 4)), int(rng.integers(8, 120)))
+    w = manual_tree(parents, segs, heads, seed=seed, data_scale=0.5)
+    N = blocks_upper_bound(w)
+    with pool_for(w, N) as pool:
+        poison(pool)
+        chunk = int(rng.choice([0, 1, 3, 7, 512]))
+        if chunk:
+            ap.apar_set_chunk_blocks(pool.handle, chunk)
+        led = BlockLedger(N)
+        dense = DenseThreads(n_q, n_kv, 128)
+        live, nodes = replay_trace(w, pool, led, dense)
+        books_equal(pool.handle, led)
+        n = len(live)
+        order = [int(x) for x in rng.permutation(n)]
+        listed = [live[i] for i in order]
+        got, want = decode_both(w, pool, dense, listed, step=seed)
+        assert np.isfinite(got).all() and np.abs(got - want).max() <= TOL["bf16"]
+        C = int(rng.integers(1, 9))
+        q = quantise(0.5 * rng.standard_normal((n, C, n_q, 128)).astype(np.float32), "bf16")
+        ck = quantise(0.5 * rng.standard_normal((n, C, n_kv, 128)).astype(np.float32), "bf16")
+        cv = quantise(0.5 * rng.standard_normal((n, C, n_kv, 128)).astype(np.float32), "bf16")
+        masks = np.stack([mask_rows_from_parents(draw_candidate_tree(rng, C)) for _ in range(n)])
+        if C * group <= 64:
+            qd = to_dev(q, "bf16")
+            out = t.empty_like(qd)
+            ap.apar_decode_attention_spec(pool.handle, qd, to_dev(ck, "bf16"), to_dev(cv, "bf16"),
+                                          t.from_numpy(masks).cuda(), C, listed, out)
+            t.cuda.synchronize()
+            wants = dense.decode_spec(q, ck, cv, masks, listed)
+            gots = to_host(out)
+            assert np.isfinite(gots).all() and np.abs(gots - wants).max() <= TOL["bf16"]
+        m = [int(rng.integers(1, dense.length(th) + 1)) for th in listed]
+        qp = quantise(0.5 * rng.standard_normal((sum(m), n_q, 128)).astype(np.float32), "bf16")
+        qpd = to_dev(qp, "bf16")
+        outp = t.empty_like(qpd)
+        ap.apar_prefill_attention(pool.handle, qpd, listed, m, outp)
+        t.cuda.synchronize()
+        gotp = to_host(outp)
+        assert np.isfinite(gotp).all() and np.abs(gotp - dense.prefill(qp, listed, m)).max() <= TOL["bf16"]
