@@ -99,18 +99,44 @@ __device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {  // rou
 // Online softmax step, first half: if some row's logits ran away from its reference (always so for a
 // row's first tile, whose reference is still -inf), move every row's reference to its running maximum
 // (the four lanes of a row agree on it) and rescale what was summed.  Rare, hence behind a branch.
-__device__ __forceinline__ void move_reference(RowState& st, const f32x4& s, bool in_range, float scale_log2e) {
-    const float top = in_range ? fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])) * scale_log2e : -INFINITY;
-    if (__builtin_amdgcn_ballot_w64(top > st.m + kSlack) != 0) {
-        float mx = fmaxf(top, __shfl_xor(top, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(st.m, mx);
-        // a row that has seen nothing yet keeps m = -inf and sums of zero
-        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(st.m - m_new);
-        st.l *= alpha;
+__device__ __forceinline__ float top_logit(const f32x4& s, bool in_range, float scale_log2e) {
+    return in_range ? fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])) * scale_log2e : -INFINITY;
+}
+
+__device__ __forceinline__ void raise_reference(RowState& st, float top) {
+    float mx = fmaxf(top, __shfl_xor(top, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(st.m, mx);
+    // a row that has seen nothing yet keeps m = -inf and sums of zero
+    const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(st.m - m_new);
+    st.l *= alpha;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) st.o[j] *= alpha;
-        st.m = m_new;
+    for (int j = 0; j < 8; ++j) st.o[j] *= alpha;
+    st.m = m_new;
+}
+
+__device__ __forceinline__ void move_reference(RowState& st, const f32x4& s, bool in_range, float scale_log2e) {
+    const float top = top_logit(s, in_range, scale_log2e);
+    if (__builtin_amdgcn_ballot_w64(top > st.m + kSlack) != 0) raise_reference(st, top);
+}
+
+// The same for all row tiles of a wavefront behind ONE branch (a branch on a vector compare costs
+// the wavefront some eighty cycles): if any row of any tile ran away, every touched tile's rows move
+// to their running maxima, which is always allowed.
+template <int NT>
+__device__ __forceinline__ void move_references(RowState (&st)[NT], const f32x4 (&s)[NT], const bool (&on)[NT],
+                                                const bool (&in_range)[NT], float scale_log2e) {
+    float top[NT];
+    bool ran_away = false;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        top[nt] = on[nt] ? top_logit(s[nt], in_range[nt], scale_log2e) : -INFINITY;
+        ran_away = ran_away || top[nt] > st[nt].m + kSlack;
+    }
+    if (__builtin_amdgcn_ballot_w64(ran_away) != 0) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            if (on[nt]) raise_reference(st[nt], top[nt]);
     }
 }
 
@@ -319,21 +345,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             }
             // phase by phase over the row tiles, so that the products of one overlap the softmax of another
             f32x4 s[NT];
-            bool on[NT];
+            bool on[NT], in_range[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 on[nt] = NT == 1 || touches(nt, lo, hi);
+                in_range[nt] = my_j[nt] >= lo && my_j[nt] < hi;
                 if (on[nt]) s[nt] = products(ks, st[nt]);
             }
+            if ((!kFull && valid < 16) || (meta >> 30)) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                if (!on[nt]) continue;
-                if ((!kFull && valid < 16) || (meta >> 30)) mask_tokens(s[nt], visible(meta, my_j[nt] - lo), g4);
-                move_reference(st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+                for (int nt = 0; nt < NT; ++nt)
+                    if (on[nt]) mask_tokens(s[nt], visible(meta, my_j[nt] - lo), g4);
             }
+            move_references<NT>(st, s, on, in_range, scale_log2e);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                if (on[nt]) weigh_values(vs, st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+                if (on[nt]) weigh_values(vs, st[nt], s[nt], in_range[nt], scale_log2e);
         };
         if (n_coop_full > 0) {  // the full tiles; which wavefront fetches is a scalar decision
             if (wave < n_coop_full) fetch_full(wave);
@@ -422,16 +449,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             for (int nt = 0; nt < NT; ++nt)
                 if (NT == 1 || touches(nt, lo, hi)) s[nt] = products(k, st[nt]);
             issue_k_full(tn);
+            bool on[NT], in_range[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                if (NT > 1 && !touches(nt, lo, hi)) continue;
-                if (meta >> 30) mask_tokens(s[nt], visible(meta, my_j[nt] - lo), g4);
-                move_reference(st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+                on[nt] = NT == 1 || touches(nt, lo, hi);
+                in_range[nt] = my_j[nt] >= lo && my_j[nt] < hi;
+                if (on[nt] && (meta >> 30)) mask_tokens(s[nt], visible(meta, my_j[nt] - lo), g4);
             }
+            move_references<NT>(st, s, on, in_range, scale_log2e);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                if (NT == 1 || touches(nt, lo, hi))
-                    weigh_values(v, st[nt], s[nt], my_j[nt] >= lo && my_j[nt] < hi, scale_log2e);
+                if (on[nt]) weigh_values(v, st[nt], s[nt], in_range[nt], scale_log2e);
             issue_v_full(tn);
             meta = meta_n;
         }
