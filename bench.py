@@ -160,6 +160,9 @@ def prefill_bench(args, w) -> int:
     hd = w.heads
     run = TreeRun(w, headroom_steps=8, device="cuda:0")
     run.build()
+    ap.apar_set_prefill_kernel(run.h, {"auto": ap.APAR_PREFILL_AUTO, "row_tiles": ap.APAR_PREFILL_ROW_TILES,
+                                       "matrix": ap.APAR_PREFILL_MATRIX}[args.prefill_kernel])
+    kernel_names = {ap.APAR_PREFILL_ROW_TILES: "attention_bf16 (prefill plan)", ap.APAR_PREFILL_MATRIX: "prefill_bf16"}
     live = np.asarray(run.live, dtype=np.int32)
     lens = np.array([ap.apar_thread_len(run.h, int(t)) for t in live], dtype=np.int64)
     own = np.array([w.nodes[run.node_of[int(t)]].seg_len for t in live], dtype=np.int64)
@@ -189,7 +192,8 @@ def prefill_bench(args, w) -> int:
         results[name] = {"query_tokens": rows, "attended_pairs": int(info.path_tokens), "flop_per_call": flops,
                          "kernel_ms_per_call": ms, "wall_ms_per_call": wall / args.steps * 1e3,
                          "plan_host_ms_per_call": prof.plan_host_ms / args.steps,
-                         "tflops": flops / (ms * 1e-3) / 1e12, "workgroups": int(info.n_units)}
+                         "tflops": flops / (ms * 1e-3) / 1e12, "workgroups": int(info.n_units),
+                         "kernel": kernel_names[ap.apar_last_prefill_kernel(run.h)]}
         del q, out
     main_r = results["own_segments"]
     line = {
@@ -199,7 +203,7 @@ def prefill_bench(args, w) -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": hd.dtype, "data": "synthetic",
         "config": {"workload": f"{args.config} forest resident in the pool ({len(live)} live threads); one call = "
                                f"prefill attention of every live thread's own segment under the tree mask"},
-        "roofline": {"bound": "mfma", "kernel": "attention_bf16 (prefill plan)", "achieved": main_r["tflops"],
+        "roofline": {"bound": "mfma", "kernel": main_r["kernel"], "achieved": main_r["tflops"],
                      "peak": 2500.0, "unit": "TFLOP/s", "frac": main_r["tflops"] / 2500.0, "traffic": None},
         "cases": results,
     }
@@ -285,6 +289,8 @@ def main() -> int:
     ap_.add_argument("--churn", type=float, default=0.01)
     ap_.add_argument("--cpu-requests", type=int, default=64)
     ap_.add_argument("--no-cpu-baseline", action="store_true")
+    ap_.add_argument("--prefill-kernel", choices=("auto", "row_tiles", "matrix"), default="auto",
+                     help="with --prefill: let the library choose the kernel per call, or force one")
     ap_.add_argument("--prefill", action="store_true",
                      help="measure apar_prefill_attention over the workload's segments instead of the decode step")
     ap_.add_argument("--serving", action="store_true",

@@ -405,6 +405,15 @@ APAR_API int apar_profile_attention_calls(apar_pool* pool, float* ms_out, int64_
  * Sharing subtrees with more blocks than that are cut into several units whose partial results are
  * merged afterwards; small values exist to exercise that path. */
 APAR_API int apar_set_chunk_blocks(apar_pool* pool, int blocks_per_unit);
+/* Tuning knob: which kernel apar_prefill_attention runs on a bf16 pool.  ROW_TILES is the decode kernel
+ * under a prefill plan (16-row tiles; a prefix shared by sibling threads is read once for all of them),
+ * MATRIX the 32x32 matrix-core kernel (one workgroup per thread and chunk of 128 query rows; needs a
+ * group size that divides 16, otherwise the call stays on ROW_TILES).  AUTO (default) takes MATRIX when
+ * a query token attends to 768 rows or more on average.  Both give the same result to rounding.
+ * fp32 pools ignore the knob.  apar_last_prefill_kernel tells which one the most recent call ran (0: none). */
+enum { APAR_PREFILL_AUTO = 0, APAR_PREFILL_ROW_TILES = 1, APAR_PREFILL_MATRIX = 2 };
+APAR_API int apar_set_prefill_kernel(apar_pool* pool, int which);
+APAR_API int apar_last_prefill_kernel(apar_pool* pool);
 
 APAR_API const char* apar_status_string(int status);
 /* Text of the last HIP error seen on this host thread by the library ("" if none). */

@@ -115,6 +115,8 @@ def _load() -> C.CDLL:
         "apar_profile_read": [P, C.POINTER(AparProfile)],
         "apar_profile_attention_calls": [P, C.POINTER(C.c_float), C.c_int64, C.POINTER(C.c_int64)],
         "apar_set_chunk_blocks": [P, I],
+        "apar_set_prefill_kernel": [P, I],
+        "apar_last_prefill_kernel": [P],
         "apar_append_kv_gather": [P, I32P, I32P, I, V, V, V],
         "apar_server_create": [P, C.POINTER(AparServerConfig), C.POINTER(P)],
         "apar_server_destroy": [P],
@@ -355,6 +357,17 @@ def apar_profile_attention_calls(pool) -> List[float]:
 
 def apar_set_chunk_blocks(pool, blocks_per_unit: int) -> None:
     _check(_L().apar_set_chunk_blocks(pool, blocks_per_unit), "apar_set_chunk_blocks")
+
+
+APAR_PREFILL_AUTO, APAR_PREFILL_ROW_TILES, APAR_PREFILL_MATRIX = 0, 1, 2
+
+
+def apar_set_prefill_kernel(pool, which: int) -> None:
+    _check(_L().apar_set_prefill_kernel(pool, which), "apar_set_prefill_kernel")
+
+
+def apar_last_prefill_kernel(pool) -> int:
+    return int(_L().apar_last_prefill_kernel(pool))
 
 
 def apar_group_create(pool, prompt_tokens: Sequence[int], k, v, stream=None) -> C.c_void_p:

@@ -101,6 +101,16 @@ struct PlanDev {              // device pointers of one staged plan
     int32_t rows_per_thread, rows_per_slice, n_slices;
 };
 
+struct PrefillWg {            // one workgroup of the bf16 prefill kernel: consecutive query tokens of one thread
+    int32_t table_ofs;        // the thread's block table inside the staged tables
+    int32_t q_row0;           // index of its first query token among the call's query tokens
+    int32_t p0;               // position of that token in the thread
+    int32_t n_tok;            // query tokens it holds (n_tok * group <= 128 rows)
+    int32_t len;              // the thread's length
+    int32_t pad[3];
+};
+static_assert(sizeof(PrefillWg) == 32, "PrefillWg is read with one aligned scalar load");
+
 struct Shape {
     int32_t n_q, n_kv, d, group;  // group = n_q / n_kv
     int32_t dtype;
@@ -135,6 +145,8 @@ hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src
 hipError_t launch_attention_partial(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
                                     PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
                                     void* out, ClassStreams& cs, hipStream_t st);
+hipError_t launch_prefill_bf16(const Shape& s, const void* pool, const void* q, const PrefillWg* wgs,
+                               const int32_t* tables, int n_wg, void* out, hipStream_t st);
 hipError_t launch_merge(const Shape& s, const PlanDev& plan, PartialBuf part, const void* q, const void* cand_k,
                         const void* cand_v, const uint8_t* mask, int n_cand, void* out, hipStream_t st);
 

@@ -72,8 +72,12 @@ struct apar_pool {
     // plan builder scratch (pool sized, kept clean between calls)
     std::vector<int32_t> seg_of;  // segment that starts at each block, -1 if none
     int max_unit_tiles = 512;  // longest tile list given to one wavefront
+    int prefill_kernel = APAR_PREFILL_AUTO;
+    int last_prefill_kernel = 0;  // which kernel the most recent prefill call ran (APAR_PREFILL_ROW_TILES / _MATRIX)
     std::vector<PlanThreadView> views;
     std::vector<PrefillThreadView> prefill_views;
+    std::vector<PrefillWg> prefill_wgs;
+    std::vector<int32_t> prefill_tables;
     std::vector<int32_t> scratch_codes, scratch_copies, scratch_seals, scratch_commit_src;
     std::vector<apar_thread> scratch_commit_ids;
     apar_plan_info last_plan{};
@@ -346,6 +350,94 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     return APAR_OK;
 }
 
+// Mean attended rows per query token from which a bf16 prefill call goes to the 32x32 kernel by itself.
+constexpr int64_t kMatrixPrefillMeanWalk = 768;
+
+// bf16 pools: the matrix-core prefill kernel.  One workgroup per (thread, chunk of 128 / group query tokens);
+// the threads' block tables are staged next to the workgroup descriptors.
+int prefill_bf16(apar_pool* p, const std::vector<PrefillThreadView>& views, int64_t rows, int64_t attended,
+                 const void* q, void* out, void* stream, std::chrono::steady_clock::time_point t0) {
+    const int group = p->shape.group;
+    if (group < 1 || group > 16 || 16 % group != 0) return APAR_ERR_UNSUPPORTED;
+    const int chunk = 128 / group;
+    std::vector<PrefillWg>& wgs = p->prefill_wgs;
+    std::vector<int32_t>& tables = p->prefill_tables;
+    wgs.clear();
+    tables.clear();
+    for (const PrefillThreadView& t : views) {
+        if (t.len > INT32_MAX / 2 || tables.size() + (size_t)t.n_blocks > (size_t)INT32_MAX / 2) return APAR_ERR_UNSUPPORTED;
+        const int32_t table_ofs = (int32_t)tables.size();
+        tables.insert(tables.end(), t.table, t.table + t.n_blocks);
+        for (int64_t r0 = 0; r0 < t.m; r0 += chunk) {
+            PrefillWg w{};
+            w.table_ofs = table_ofs;
+            w.q_row0 = (int32_t)(t.q_base + r0);
+            w.p0 = (int32_t)(t.len - t.m + r0);
+            w.n_tok = (int32_t)std::min<int64_t>(chunk, t.m - r0);
+            w.len = (int32_t)t.len;
+            wgs.push_back(w);
+        }
+    }
+    // Workgroups of one tree (same first block) stay together, in the caller's order, so that the threads of a
+    // tree walk their common prefix at about the same time and find it in the L2 of the XCD that serves their
+    // kv head; trees with the longest walk go first so that the launch does not end on a long one.
+    {
+        std::unordered_map<int32_t, int32_t> longest;  // first block of a tree -> its longest walk
+        for (const PrefillWg& w : wgs) {
+            int32_t& e = longest[tables[w.table_ofs]];
+            e = std::max(e, w.p0 + w.n_tok);
+        }
+        std::vector<std::pair<uint64_t, PrefillWg>> keyed;
+        keyed.reserve(wgs.size());
+        for (const PrefillWg& w : wgs) {
+            const int32_t root = tables[w.table_ofs];
+            keyed.emplace_back(((uint64_t)(uint32_t)(INT32_MAX - longest[root]) << 32) | (uint32_t)root, w);
+        }
+        std::stable_sort(keyed.begin(), keyed.end(),
+                         [](const std::pair<uint64_t, PrefillWg>& a, const std::pair<uint64_t, PrefillWg>& b) {
+                             return a.first < b.first;
+                         });
+        for (size_t i = 0; i < wgs.size(); ++i) wgs[i] = keyed[i].second;
+    }
+    apar_plan_info info{};
+    info.n_threads = (int64_t)views.size();
+    info.n_units = (int64_t)wgs.size() * p->shape.n_kv;
+    info.path_tokens = attended;
+    info.algorithmic_bytes = 2 * rows * p->shape.n_q * p->shape.d * 2;
+    p->last_plan = info;
+    DeviceGuard guard(p->device);
+    hipStream_t st = (hipStream_t)stream;
+    const size_t wg_bytes = align_up(wgs.size() * sizeof(PrefillWg), 256);
+    const size_t table_bytes = tables.size() * sizeof(int32_t);
+    StageSlot* s = nullptr;
+    int rc = acquire_stage(p, wg_bytes + table_bytes, &s);
+    if (rc != APAR_OK) return rc;
+    memcpy(s->host, wgs.data(), wgs.size() * sizeof(PrefillWg));
+    memcpy(s->host + wg_bytes, tables.data(), table_bytes);
+    HIP_TRY(hipMemcpyAsync(s->dev, s->host, wg_bytes + table_bytes, hipMemcpyHostToDevice, st));
+    EventPair ev;
+    if (p->profiling) {
+        if ((rc = new_event(p, &ev.a)) != APAR_OK || (rc = new_event(p, &ev.b)) != APAR_OK ||
+            (rc = new_event(p, &ev.c)) != APAR_OK)
+            return rc;
+        HIP_TRY(hipEventRecord(ev.a, st));
+    }
+    HIP_TRY(launch_prefill_bf16(p->shape, p->kv, q, (const PrefillWg*)s->dev, (const int32_t*)(s->dev + wg_bytes),
+                                (int)wgs.size(), out, st));
+    if (p->profiling) {
+        HIP_TRY(hipEventRecord(ev.b, st));
+        HIP_TRY(hipEventRecord(ev.c, st));
+        p->decode_events.push_back(ev);
+        p->n_decode_calls += 1;
+    }
+    HIP_TRY(hipEventRecord(s->ev, st));
+    s->pending = true;
+    if (p->profiling)
+        p->plan_host_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count() -
+                           p->wait_in_call_ms;
+    return APAR_OK;
+}
+
 int prefill_common(apar_pool* p, const void* q, const apar_thread* ids, const int32_t* m, int n, void* out,
                    void* stream) {
     if (!p || n < 0) return APAR_ERR_INVALID_ARG;
@@ -367,7 +459,18 @@ int prefill_common(apar_pool* p, const void* q, const apar_thread* ids, const in
     }
     if (rows > INT32_MAX / 2) return APAR_ERR_UNSUPPORTED;
     PlanHost& ph = p->plan;
-    int rc = build_prefill_plan(views.data(), n, p->shape.group, ph);
+    int rc = APAR_OK;
+    // bf16 pools have two kernels.  The 32x32 matrix-core kernel pays off once the walk of a query token is long
+    // (its fixed cost per workgroup is spread over many super-blocks); short walks stay on the row-tile kernel,
+    // whose plan also reads a prefix shared by sibling threads once for all of them.
+    p->last_prefill_kernel = APAR_PREFILL_ROW_TILES;
+    if (!p->dry_run && p->shape.dtype == APAR_BF16 && 16 % p->shape.group == 0 &&
+        (p->prefill_kernel == APAR_PREFILL_MATRIX ||
+         (p->prefill_kernel == APAR_PREFILL_AUTO && attended >= kMatrixPrefillMeanWalk * rows))) {
+        p->last_prefill_kernel = APAR_PREFILL_MATRIX;
+        return prefill_bf16(p, views, rows, attended, q, out, stream, t0);
+    }
+    rc = build_prefill_plan(views.data(), n, p->shape.group, ph);
     if (rc != APAR_OK) return rc;
     apar_plan_info info{};
     info.n_threads = n;
@@ -828,6 +931,14 @@ int apar_profile_attention_calls(apar_pool* p, float* ms_out, int64_t cap, int64
     if (n > 0) memcpy(ms_out, p->last_attention_ms.data(), (size_t)n * sizeof(float));
     return APAR_OK;
 }
+
+int apar_set_prefill_kernel(apar_pool* p, int which) {
+    if (!p || which < APAR_PREFILL_AUTO || which > APAR_PREFILL_MATRIX) return APAR_ERR_INVALID_ARG;
+    p->prefill_kernel = which;
+    return APAR_OK;
+}
+
+int apar_last_prefill_kernel(apar_pool* p) { return p ? p->last_prefill_kernel : 0; }
 
 int apar_set_chunk_blocks(apar_pool* p, int blocks_per_unit) {
     if (!p || blocks_per_unit < 1 || blocks_per_unit > 65536) return APAR_ERR_INVALID_ARG;

@@ -377,17 +377,24 @@ def test_prefill_attention_over_tree_segments(dtype, n_q, n_kv, d):
         lens = [dense.length(th) for th in live]
         rng = np.random.default_rng(3)
         cases = [[w.nodes[i].seg_len for i in nodes], lens, [1] * len(live), [min(L, 20) for L in lens]]
+        # bf16 pools have two prefill kernels; both are held to the oracle (fp32 pools have one)
+        kernels = [ap.APAR_PREFILL_ROW_TILES, ap.APAR_PREFILL_MATRIX] if dtype == "bf16" else [ap.APAR_PREFILL_AUTO]
         for m in cases:
             q = quantise(0.5 * rng.standard_normal((sum(m), n_q, d)).astype(np.float32), dtype)
             qd = to_dev(q, dtype)
-            out = t.empty_like(qd)
-            ap.apar_prefill_attention(pool.handle, qd, live, m, out)
-            t.cuda.synchronize()
-            got = to_host(out)
             want = dense.prefill(q, live, m)
-            assert np.isfinite(got).all()
-            err = np.abs(got - want).max()
-            assert err <= TOL[dtype], f"m = {m}: max abs err {err}"
+            for kernel in kernels:
+                ap.apar_set_prefill_kernel(pool.handle, kernel)
+                out = t.empty_like(qd)
+                ap.apar_prefill_attention(pool.handle, qd, live, m, out)
+                t.cuda.synchronize()
+                if dtype == "bf16":
+                    assert ap.apar_last_prefill_kernel(pool.handle) == kernel
+                got = to_host(out)
+                assert np.isfinite(got).all()
+                err = np.abs(got - want).max()
+                assert err <= TOL[dtype], f"kernel {kernel}, m = {m}: max abs err {err}"
+        ap.apar_set_prefill_kernel(pool.handle, ap.APAR_PREFILL_AUTO)
         # m = 1 is the decode step
         q = quantise(0.5 * rng.standard_normal((len(live), n_q, d)).astype(np.float32), dtype)
         qd = to_dev(q, dtype)
@@ -481,8 +488,12 @@ def test_random_forests_decode_spec_and_prefill(seed):
         m = [int(rng.integers(1, dense.length(th) + 1)) for th in listed]
         qp = quantise(0.5 * rng.standard_normal((sum(m), n_q, 128)).astype(np.float32), "bf16")
         qpd = to_dev(qp, "bf16")
-        outp = t.empty_like(qpd)
-        ap.apar_prefill_attention(pool.handle, qpd, listed, m, outp)
-        t.cuda.synchronize()
-        gotp = to_host(outp)
-        assert np.isfinite(gotp).all() and np.abs(gotp - dense.prefill(qp, listed, m)).max() <= TOL["bf16"]
+        wantp = dense.prefill(qp, listed, m)
+        for kernel in (ap.APAR_PREFILL_ROW_TILES, ap.APAR_PREFILL_MATRIX):
+            ap.apar_set_prefill_kernel(pool.handle, kernel)
+            outp = t.empty_like(qpd)
+            ap.apar_prefill_attention(pool.handle, qpd, listed, m, outp)
+            t.cuda.synchronize()
+            assert ap.apar_last_prefill_kernel(pool.handle) == kernel
+            gotp = to_host(outp)
+            assert np.isfinite(gotp).all() and np.abs(gotp - wantp).max() <= TOL["bf16"], f"kernel {kernel}"

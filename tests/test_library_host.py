@@ -318,6 +318,24 @@ def test_prefill_needs_a_group_size_that_divides_16():
         assert e.value.status == -6
 
 
+def test_prefill_kernel_knob_checks_its_argument_and_dry_runs_stay_on_row_tiles():
+    with ap.Pool(4, 2, 128, "bf16", 8, dry_run=True) as pool:
+        h = pool.handle
+        assert ap.apar_last_prefill_kernel(h) == 0
+        for bad in (-1, 3):
+            with pytest.raises(ap.AparError) as e:
+                ap.apar_set_prefill_kernel(h, bad)
+            assert e.value.status == -1
+        t = ap.apar_thread_create(h)
+        ap.apar_append_kv(h, t, None, None, 40)
+        for which in (ap.APAR_PREFILL_AUTO, ap.APAR_PREFILL_ROW_TILES, ap.APAR_PREFILL_MATRIX):
+            ap.apar_set_prefill_kernel(h, which)
+            ap.apar_prefill_attention(h, None, [t], [40], None)
+            # a dry run builds (and exports) the row-tile plan whatever the knob says
+            assert ap.apar_last_prefill_kernel(h) == ap.APAR_PREFILL_ROW_TILES
+            assert ap.apar_last_plan_info(h).path_tokens == 40 * 41 // 2
+
+
 def test_empty_calls_are_no_ops_and_gather_checks_its_arguments():
     with ap.Pool(4, 2, 64, "f32", 8, dry_run=True) as pool:
         h = pool.handle
