@@ -625,7 +625,7 @@ int apar_fork(apar_pool* p, apar_thread parent, int n_children, apar_thread* chi
     if (!live_thread(p, parent)) return APAR_ERR_INVALID_THREAD;
     if (n_children < 1) return APAR_ERR_INVALID_ARG;
     if ((int64_t)p->threads.size() + n_children > p->cfg.max_threads) return APAR_ERR_THREAD_CAPACITY;
-    p->threads.reserve(p->threads.size() + n_children);
+    // (no exact-size reserve here: it would re-allocate the whole thread array on every fork)
     for (int c = 0; c < n_children; ++c) {
         p->threads.emplace_back();
         Thread& child = p->threads.back();
