@@ -96,6 +96,7 @@ class SpecLoopPlan:
         st = SpecStep(self.step, live, parents, masks, accepted, finished, forked, children)
         st.accept_bits = bits
         st.accept_masks = chain_bits.astype(np.uint8)
+        st.live_after = self.live  # the live set once this step's releases and forks are done
         self.step += 1
         return st
 

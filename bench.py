@@ -100,6 +100,7 @@ def spec_loop(args, w) -> int:
     run.build()
     if args.chunk:
         ap.apar_set_chunk_blocks(run.h, args.chunk)
+    run.draw_ahead(args.warmup + K)  # the synthetic step plans (masks, accepted chains, coins) exist before the clock starts
     for _ in range(args.warmup):
         run.step()
     torch.cuda.synchronize()

@@ -236,44 +236,76 @@ __global__ __launch_bounds__(64) void attention_f32(const char* __restrict__ poo
 }
 
 // ---------------------------------------------------------------------------
-// Merge: one wavefront per (listed thread, candidate, q head).  Folds the partial
+// Merge: sixteen lanes per (listed thread, candidate, q head).  Folds the partial
 // results on the thread's root path (log-sum-exp in base 2), adds the candidate
 // keys the mask lets this candidate see, normalises and writes the output row.
 // Threads without partial results were already written by the attention kernel.
 // ---------------------------------------------------------------------------
+// E consecutive elements starting at element idx (a multiple of E) as floats: 16-byte loads.
+template <int E, bool BF16>
+__device__ __forceinline__ void load_run(const void* base, int64_t idx, float (&x)[E]) {
+    if constexpr (BF16) {
+        static_assert(E == 8, "a bf16 run is one 16-byte load");
+        const uint4 u = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(base) + idx);
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[2 * e] = __uint_as_float(w[e] << 16);
+            x[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; e += 4) {
+            const float4 f = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + idx + e);
+            x[e] = f.x, x[e + 1] = f.y, x[e + 2] = f.z, x[e + 3] = f.w;
+        }
+    }
+}
+
+__device__ __forceinline__ float sum_over_16_lanes(float x) {
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+// A workgroup takes 16 consecutive q heads of one (listed thread, candidate): sixteen lanes per output
+// row, each with D / 16 consecutive dims, so the four rows of a wavefront read 4 * D consecutive floats
+// of every partial result in one go.
 template <int D, bool BF16>
-__global__ __launch_bounds__(64) void merge_rows(PlanDev plan, PartialBuf part, const void* __restrict__ qv,
-                                                 const void* __restrict__ ckv, const void* __restrict__ cvv,
-                                                 const uint8_t* __restrict__ mask, int n_cand, int n_q, int n_kv,
-                                                 int group, float scale_log2e, void* __restrict__ outv) {
-    constexpr int E = D / 64;
-    const int lane = threadIdx.x;
-    const int hq = blockIdx.x, c = blockIdx.y, i = blockIdx.z;
+__global__ __launch_bounds__(256) void merge_rows(PlanDev plan, PartialBuf part, const void* __restrict__ qv,
+                                                  const void* __restrict__ ckv, const void* __restrict__ cvv,
+                                                  const uint8_t* __restrict__ mask, int n_cand, int n_q, int n_kv,
+                                                  int group, float scale_log2e, void* __restrict__ outv) {
+    constexpr int E = D / 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c16 = lane & 15;
+    const int head = blockIdx.x * 16 + wave * 4 + (lane >> 4);
+    const int c = blockIdx.y, i = blockIdx.z;
     const int p0 = plan.path_ofs[i], p1 = plan.path_ofs[i + 1];
     if (p0 == p1) return;  // the attention kernel wrote this thread's rows itself (candidates included)
+    const bool ok = head < n_q;
+    const int hq = ok ? head : 0;  // rows past the last head redo head 0 and write nothing
     float m = -INFINITY;
     for (int p = p0; p < p1; ++p) {
         const int64_t slot = ((int64_t)plan.path_ids[p] * n_cand + c) * n_q + hq;
         m = fmaxf(m, part.ml[slot * 2]);
     }
-    auto load = [&](const void* base, int64_t idx) -> float {
-        if (BF16) return bf16_to_f32(reinterpret_cast<const uint16_t*>(base)[idx]);
-        return reinterpret_cast<const float*>(base)[idx];
-    };
     // logits of the visible candidates
     float cs[8];
     uint32_t bits = 0;
     if (mask != nullptr) {
         bits = mask[(int64_t)i * n_cand + c];
-        const int64_t qbase = (((int64_t)i * n_cand + c) * n_q + hq) * D;
+        float qr[E];
+        load_run<E, BF16>(qv, (((int64_t)i * n_cand + c) * n_q + hq) * D + c16 * E, qr);
         for (int cp = 0; cp < n_cand; ++cp) {
             cs[cp] = -INFINITY;
             if ((bits >> cp) & 1u) {
-                const int64_t kbase = (((int64_t)i * n_cand + cp) * n_kv + hq / group) * D;
+                float kr[E];
+                load_run<E, BF16>(ckv, (((int64_t)i * n_cand + cp) * n_kv + hq / group) * D + c16 * E, kr);
                 float dot = 0.0f;
 #pragma unroll
-                for (int e = 0; e < E; ++e) dot += load(qv, qbase + lane + 64 * e) * load(ckv, kbase + lane + 64 * e);
-                cs[cp] = wave_sum(dot) * scale_log2e;
+                for (int e = 0; e < E; ++e) dot += qr[e] * kr[e];
+                cs[cp] = sum_over_16_lanes(dot) * scale_log2e;
                 m = fmaxf(m, cs[cp]);
             }
         }
@@ -281,31 +313,43 @@ __global__ __launch_bounds__(64) void merge_rows(PlanDev plan, PartialBuf part, 
     float l = 0.0f, acc[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[e] = 0.0f;
+#pragma unroll 2
     for (int p = p0; p < p1; ++p) {
         const int64_t slot = ((int64_t)plan.path_ids[p] * n_cand + c) * n_q + hq;
-        const float w = exp2f(part.ml[slot * 2] - m);
-        l += w * part.ml[slot * 2 + 1];
+        const float2 ml = *reinterpret_cast<const float2*>(part.ml + slot * 2);
+        float o[E];
+        load_run<E, false>(part.o, slot * D + c16 * E, o);
+        const float w = exp2f(ml.x - m);
+        l += w * ml.y;
 #pragma unroll
-        for (int e = 0; e < E; ++e) acc[e] += w * part.o[slot * D + lane + 64 * e];
+        for (int e = 0; e < E; ++e) acc[e] += w * o[e];
     }
     if (mask != nullptr) {
         for (int cp = 0; cp < n_cand; ++cp) {
             if ((bits >> cp) & 1u) {
                 const float w = exp2f(cs[cp] - m);
-                const int64_t vbase = (((int64_t)i * n_cand + cp) * n_kv + hq / group) * D;
+                float vr[E];
+                load_run<E, BF16>(cvv, (((int64_t)i * n_cand + cp) * n_kv + hq / group) * D + c16 * E, vr);
                 l += w;
 #pragma unroll
-                for (int e = 0; e < E; ++e) acc[e] += w * load(cvv, vbase + lane + 64 * e);
+                for (int e = 0; e < E; ++e) acc[e] += w * vr[e];
             }
         }
     }
+    if (!ok) return;
     const float inv = 1.0f / l;
-    const int64_t obase = (((int64_t)i * n_cand + c) * n_q + hq) * D;
+    const int64_t obase = (((int64_t)i * n_cand + c) * n_q + hq) * D + c16 * E;
+    if constexpr (BF16) {
+        uint32_t w[E / 2];
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const float r = acc[e] * inv;
-        if (BF16) reinterpret_cast<uint16_t*>(outv)[obase + lane + 64 * e] = f32_to_bf16_rne(r);
-        else reinterpret_cast<float*>(outv)[obase + lane + 64 * e] = r;
+        for (int e = 0; e < E / 2; ++e)
+            w[e] = (uint32_t)f32_to_bf16_rne(acc[2 * e] * inv) | ((uint32_t)f32_to_bf16_rne(acc[2 * e + 1] * inv) << 16);
+        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(outv) + obase) = uint4{w[0], w[1], w[2], w[3]};
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; e += 4)
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(outv) + obase + e) =
+                float4{acc[e] * inv, acc[e + 1] * inv, acc[e + 2] * inv, acc[e + 3] * inv};
     }
 }
 
@@ -406,9 +450,9 @@ hipError_t launch_merge(const Shape& s, const PlanDev& plan, PartialBuf part, co
         const void* cv2 = cand_v ? (const char*)cand_v + kofs : nullptr;
         const uint8_t* mk2 = mask ? mask + (int64_t)i0 * n_cand : nullptr;
         void* out2 = (char*)out + qofs;
-        dim3 grid(s.n_q, n_cand, ni);
+        dim3 grid((s.n_q + 15) / 16, n_cand, ni);
 #define APAR_MERGE(DD, BF)                                                                                        \
-    hipLaunchKernelGGL((merge_rows<DD, BF>), grid, dim3(64), 0, st, pl, part, q2, ck2, cv2, mk2, n_cand, s.n_q, \
+    hipLaunchKernelGGL((merge_rows<DD, BF>), grid, dim3(256), 0, st, pl, part, q2, ck2, cv2, mk2, n_cand, s.n_q, \
                        s.n_kv, s.group, s.scale_log2e, out2)
         if (s.dtype == APAR_BF16) APAR_MERGE(128, true);
         else if (s.d == 64) APAR_MERGE(64, false);

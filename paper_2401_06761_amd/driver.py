@@ -181,6 +181,7 @@ class SpecRun:
         self.step_no = 0
         self.bank = None
         self.out = None
+        self._drawn = []  # step plans drawn ahead of time, next one last
 
     def build(self) -> None:
         w, h, hd = self.w, self.h, self.w.heads
@@ -217,10 +218,16 @@ class SpecRun:
         return (rows_device(self.w, self.TAG_CHILD_K, step + 1, (n, hd.n_kv_heads, hd.head_dim), self.device),
                 rows_device(self.w, self.TAG_CHILD_V, step + 1, (n, hd.n_kv_heads, hd.head_dim), self.device))
 
+    def draw_ahead(self, n_steps: int) -> None:
+        """Draws the step plans of the next n_steps iterations now (the plan depends on nothing the library
+        returns), so that a timed loop does not pay for generating its own synthetic input."""
+        ahead = [self.plan.next_step() for _ in range(n_steps)]
+        self._drawn = ahead[::-1] + self._drawn
+
     def step(self):
         """One loop iteration; returns (step plan, q, cand_k, cand_v, out view, child k, child v)."""
         torch, h, C = self.torch, self.h, self.C
-        st = self.plan.next_step()
+        st = self._drawn.pop() if self._drawn else self.plan.next_step()
         n = len(st.live)
         if self.fixed_bank:
             q, ck, cv = (x[:n] for x in self.bank)
@@ -254,7 +261,7 @@ class SpecRun:
             else:
                 kk, vv = self.child_rows_for(st.step, m)
             ap.apar_append_kv_batch(h, np.asarray(st.children, dtype=np.int32), kk, vv)
-        self.live = list(self.plan.live)
+        self.live = list(st.live_after)
         self.step_no += 1
         return st, q, ck, cv, out, kk, vv
 
