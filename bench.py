@@ -213,6 +213,66 @@ def prefill_bench(args, w) -> int:
     return 0
 
 
+def shared_prefix_bench(args) -> int:
+    """Secondary measurement: decode attention when several hundred query rows share one long prefix
+    (16 requests, a root of `root` tokens forked into 512 one-token leaves, 32 MHA heads): the root is more
+    rows than a fused workgroup carries, so it runs as stand-alone units - on the row-tile kernel or, from
+    1024 tokens on by default, on the 32x32 matrix-core kernel.  Times both for two root lengths."""
+    import numpy as np
+    import torch
+
+    import paper_2401_06761_amd as ap
+    from apar_workloads import HeadConfig, manual_tree
+    from paper_2401_06761_amd.driver import TreeRun
+
+    n_req, fan = 16, 512
+    cases = {}
+    for root in (4096, 1024):
+        parents, segs = [], []
+        for _ in range(n_req):
+            base = len(parents)
+            parents.append(-1)
+            segs.append(root)
+            parents += [base] * fan
+            segs += [1] * fan
+        w = manual_tree(parents, segs, HeadConfig(32, 32, 128, "bf16"), seed=args.seed, data_scale=0.09)
+        run = TreeRun(w, headroom_steps=4, churn=0.0)
+        run.build()
+        ids = np.asarray(run.live, dtype=np.int32)
+        q, out = run.banks[0][0], run.out
+        res = {}
+        for name, knob in (("row_tile_units", (0, 1)), ("matrix_units", (1, 1)), ("default", (64, 64))):
+            ap.apar_set_matrix_units(run.h, *knob)
+            for _ in range(args.warmup):
+                ap.apar_decode_attention(run.h, q, ids, out)
+            torch.cuda.synchronize()
+            ap.apar_profile_read(run.h)
+            ap.apar_profile_enable(run.h, True)
+            for _ in range(args.steps):
+                ap.apar_decode_attention(run.h, q, ids, out)
+            torch.cuda.synchronize()
+            prof = ap.apar_profile_read(run.h)
+            ap.apar_profile_enable(run.h, False)
+            info = ap.apar_last_plan_info(run.h)
+            ms = prof.attention_kernel_ms / args.steps
+            res[name] = {"attention_kernel_ms": ms, "merge_kernel_ms": prof.merge_kernel_ms / args.steps,
+                         "tflops": 4.0 * 128 * 32 * info.path_tokens / (ms * 1e-3) / 1e12,
+                         "achieved_gb_s": info.algorithmic_bytes / (ms * 1e-3) / 1e9}
+        cases[f"root_{root}"] = res
+        run.close()
+    main_r = cases["root_4096"]["default"]
+    print(json.dumps({
+        "metric": "decode attention over a prefix shared by 512 threads (secondary; the headline is the ht256 decode step)",
+        "value": n_req * fan / (main_r["attention_kernel_ms"] * 1e-3), "unit": "thread-queries/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_r["attention_kernel_ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{n_req} requests, root of 4096 tokens forked into {fan} one-token leaves, Hq=Hkv=32, d=128"},
+        "roofline": {"bound": "mfma", "kernel": "attention_units_bf16 + attention_bf16", "achieved": main_r["tflops"],
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": main_r["tflops"] / 2500.0, "traffic": None},
+        "cases": cases}))
+    return 0
+
+
 def serving_bench(args) -> int:
     """Secondary measurement: throughput of the serving loop against the size of the KV pool, for APAR
     decoding and for the sequential stand-in of the same responses (the shape of the paper's
@@ -292,6 +352,8 @@ def main() -> int:
     ap_.add_argument("--no-cpu-baseline", action="store_true")
     ap_.add_argument("--prefill-kernel", choices=("auto", "row_tiles", "matrix"), default="auto",
                      help="with --prefill: let the library choose the kernel per call, or force one")
+    ap_.add_argument("--shared-prefix", action="store_true",
+                     help="measure decode attention over long prefixes shared by 512 threads, row-tile vs matrix units")
     ap_.add_argument("--prefill", action="store_true",
                      help="measure apar_prefill_attention over the workload's segments instead of the decode step")
     ap_.add_argument("--serving", action="store_true",
@@ -320,6 +382,8 @@ def main() -> int:
     dev = "cuda:0"
     w = make_config(args.config, seed=args.seed, n_requests=args.requests)
     hd = w.heads
+    if args.shared_prefix:
+        return shared_prefix_bench(args)
     if args.serving:
         return serving_bench(args)
     if args.prefill:

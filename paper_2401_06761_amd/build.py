@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libapar.so")
-SOURCES = ["apar_pool.cpp", "plan.cpp", "controller.cpp", "kernels_misc.hip", "kernels_attn_bf16.hip", "kernels_prefill_bf16.hip"]
+SOURCES = ["apar_pool.cpp", "plan.cpp", "controller.cpp", "kernels_misc.hip", "kernels_attn_bf16.hip", "kernels_matrix_bf16.hip"]
 
 
 def hipcc() -> str:

@@ -65,6 +65,12 @@ struct TileRef {     // one block to read, and the row groups it applies to
 // from the accumulation registers around every use: measured slower than two tiles plus partial results
 // (decode) or more workgroups (prefill), so the plans stop at 2.
 constexpr int kMaxRowTiles = 2;
+// Value of a workgroup descriptor's row-tile byte that marks a matrix unit (bf16 pools): a stand-alone
+// chunk of a shared segment for up to 128 query rows, run by the 32x32 kernel.  Its shared tile list is
+// the chunk; wavefront entry 0 names the threads (row groups of whole threads, rows laid flat over the
+// workgroup) and the first thread's partial-result row; entries 1..3 are empty.
+constexpr int kMatrixUnitRows = 32;
+constexpr int kMatrixUnitMaxRows = 128;
 
 struct WaveItem {    // what one wavefront computes
     int32_t tile_ofs, n_tiles;  // its own tile list
@@ -147,6 +153,9 @@ hipError_t launch_attention_partial(const Shape& s, const void* pool, const void
                                     void* out, ClassStreams& cs, hipStream_t st);
 hipError_t launch_prefill_bf16(const Shape& s, const void* pool, const void* q, const PrefillWg* wgs,
                                const int32_t* tables, int n_wg, void* out, hipStream_t st);
+// workgroups [wg_first, wg_first + n_wg) of the plan: matrix units (row_tiles byte = kMatrixUnitRows)
+hipError_t launch_attention_units_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan,
+                                       int wg_first, int n_wg, int n_cand, PartialBuf part, hipStream_t st);
 hipError_t launch_merge(const Shape& s, const PlanDev& plan, PartialBuf part, const void* q, const void* cand_k,
                         const void* cand_v, const uint8_t* mask, int n_cand, void* out, hipStream_t st);
 

@@ -73,6 +73,9 @@ struct apar_pool {
     std::vector<int32_t> seg_of;  // segment that starts at each block, -1 if none
     int max_unit_tiles = 512;  // longest tile list given to one wavefront
     int prefill_kernel = APAR_PREFILL_AUTO;
+    // stand-alone segments with at least this many query rows and blocks run as matrix units (bf16 pools): the
+    // 32x32 kernel has the higher fixed cost per workgroup and only wins on long walks
+    int matrix_min_rows = 64, matrix_min_blocks = 64;
     int last_prefill_kernel = 0;  // which kernel the most recent prefill call ran (APAR_PREFILL_ROW_TILES / _MATRIX)
     std::vector<PlanThreadView> views;
     std::vector<PrefillThreadView> prefill_views;
@@ -256,6 +259,8 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     prm.max_unit_tiles = p->max_unit_tiles;
     prm.allow_direct = true;
     prm.fuse = true;
+    prm.matrix_min_rows = (p->shape.dtype == APAR_BF16) ? p->matrix_min_rows : 0;
+    prm.matrix_min_blocks = p->matrix_min_blocks;
     int rc = build_plan(p->views.data(), n, p->ref.data(), p->seg_of.data(), prm, ph);
     if (rc != APAR_OK) return rc;
     const int64_t e = p->shape.dtype == APAR_F32 ? 4 : 2;
@@ -929,6 +934,13 @@ int apar_profile_attention_calls(apar_pool* p, float* ms_out, int64_t cap, int64
     *n_out = n;
     if (cap < n) return APAR_ERR_INVALID_ARG;
     if (n > 0) memcpy(ms_out, p->last_attention_ms.data(), (size_t)n * sizeof(float));
+    return APAR_OK;
+}
+
+int apar_set_matrix_units(apar_pool* p, int min_rows, int min_blocks) {
+    if (!p || min_rows < 0 || min_blocks < 0) return APAR_ERR_INVALID_ARG;
+    p->matrix_min_rows = min_rows;
+    p->matrix_min_blocks = min_blocks;
     return APAR_OK;
 }
 

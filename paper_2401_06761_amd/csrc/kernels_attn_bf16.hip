@@ -630,7 +630,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
 hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,
                                  PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
                                  void* out, ClassStreams& cs, hipStream_t st) {
-    // workgroups are sorted by row tiles per wavefront: [4-tile | 2-tile | 1-tile], heaviest first in each.
+    // workgroups are sorted by class: [matrix units | 2 row tiles per wavefront | 1], heaviest first in each.
     // The last class present runs on the caller's stream; the ones before it run beside it on side
     // streams that wait for the caller's stream first and that the caller's stream then waits for.
     int first[3], last = -1, n_present = 0;
@@ -667,8 +667,9 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
     hipLaunchKernelGGL((attention_bf16<NTV>), dim3(n_wg), dim3(256), 0, on, (const char*)pool, (const uint16_t*)q, \
                        plan, first[cls], n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part,                      \
                        (const uint16_t*)cand_k, (const uint16_t*)cand_v, mask, (uint16_t*)out)
-        if (cls == 0) return hipErrorInvalidValue;  // four row tiles per wavefront: not built (see kMaxRowTiles)
-        else if (cls == 1) APAR_LAUNCH(2);
+        if (cls == 0) {
+            if ((e = launch_attention_units_bf16(s, pool, q, plan, first[cls], count, n_cand, part, on)) != hipSuccess) return e;
+        } else if (cls == 1) APAR_LAUNCH(2);
         else APAR_LAUNCH(1);
 #undef APAR_LAUNCH
         if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -125,6 +125,27 @@ struct Builder {
                 const int32_t n_full = (int32_t)ph.tiles.size() - ofs;
                 ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
                 emit_narrow(ofs, nb, n_full, grp0, groups, pbase, 0);
+            } else if (prm.matrix_min_rows > 0 && (int64_t)s.n_shr * prm.rows_per_thread >= prm.matrix_min_rows &&
+                       s.n_blk >= prm.matrix_min_blocks) {
+                // matrix units: whole threads, as evenly over the workgroups as they go
+                const int per_wg = kMatrixUnitMaxRows / prm.rows_per_thread;  // >= 2: rows_per_thread <= 64
+                const int n_wg = (s.n_shr + per_wg - 1) / per_wg;
+                const int each = (s.n_shr + n_wg - 1) / n_wg;
+                for (int t0 = 0; t0 < s.n_shr; t0 += each) {
+                    const int nt = std::min(each, s.n_shr - t0);
+                    PlanHost::WideItem wi{};
+                    wi.wg.coop_ofs = (int32_t)ph.tiles.size();
+                    wi.wg.n_coop = nb;
+                    wi.wg.grp_base = grp0 + t0 * n_sl;
+                    ph.open_tmp.clear();
+                    push_tiles(ph.tiles, ph.open_tmp, s, b0, nb, 0, nt * n_sl);
+                    wi.wg.row_tiles = kMatrixUnitRows | (((int32_t)ph.tiles.size() - wi.wg.coop_ofs) << 8);
+                    ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
+                    wi.wg.w[0] = WaveItem{0, 0, wi.wg.grp_base, nt * n_sl, pbase + t0, 0};
+                    for (int k = 1; k < 4; ++k) wi.wg.w[k] = WaveItem{0, 0, 0, 0, -1, 0};
+                    wi.cost = nb;
+                    ph.wide_items.push_back(wi);
+                }
             } else {
                 const int nt = pick_row_tiles(groups), wcap = nt * cap;
                 for (int g0 = 0; g0 < groups; g0 += 4 * wcap) {
@@ -451,7 +472,7 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         }
     }
 
-    // 7. workgroups: by row tiles per wavefront (4, 2, 1), heaviest first within a class
+    // 7. workgroups: matrix units, then by row tiles per wavefront (2, 1), heaviest first within a class
     std::stable_sort(ph.wide_items.begin(), ph.wide_items.end(),
                      [](const PlanHost::WideItem& a, const PlanHost::WideItem& b) {
                          const int ta = a.wg.row_tiles & 255, tb = b.wg.row_tiles & 255;
@@ -461,7 +482,7 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
     ph.n_wg_class[0] = ph.n_wg_class[1] = ph.n_wg_class[2] = 0;
     for (const PlanHost::WideItem& w : ph.wide_items) {
         ph.wgs.push_back(w.wg);
-        ph.n_wg_class[(w.wg.row_tiles & 255) == 4 ? 0 : (w.wg.row_tiles & 255) == 2 ? 1 : 2] += 1;
+        ph.n_wg_class[(w.wg.row_tiles & 255) == kMatrixUnitRows ? 0 : (w.wg.row_tiles & 255) == 2 ? 1 : 2] += 1;
     }
     const size_t n_wide = ph.wgs.size();
     {
@@ -573,7 +594,7 @@ int build_prefill_plan(const PrefillThreadView* threads, int n, int group, PlanH
     ph.wgs.reserve(ph.wide_items.size());
     for (const PlanHost::WideItem& w : ph.wide_items) {
         ph.wgs.push_back(w.wg);
-        ph.n_wg_class[(w.wg.row_tiles & 255) == 4 ? 0 : (w.wg.row_tiles & 255) == 2 ? 1 : 2] += 1;
+        ph.n_wg_class[(w.wg.row_tiles & 255) == kMatrixUnitRows ? 0 : (w.wg.row_tiles & 255) == 2 ? 1 : 2] += 1;
     }
     return APAR_OK;
 }

@@ -63,6 +63,8 @@ struct PlanParams {
     int32_t max_unit_tiles;   // longest tile list one wavefront may be given
     bool allow_direct;        // threads whose whole path is one unit may write their output directly
     bool fuse;                // build tree-fused units (false: every segment stands alone)
+    int32_t matrix_min_rows = 0;    // stand-alone segments with at least this many query rows (0: never) ...
+    int32_t matrix_min_blocks = 0;  // ... and at least this many blocks become matrix units
 };
 
 struct PrefillThreadView {  // one listed thread of a prefill call

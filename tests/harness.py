@@ -109,9 +109,15 @@ def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per
     tile_reads = 0
     for wg_index, wg in enumerate(wgs):
         coop_ofs, n_coop, grp_base, row_tiles, coop_full = wg[0], wg[1], wg[2], wg[3] & 255, wg[3] >> 8
-        assert row_tiles in (1, 2)
-        if wg_index:  # classes are stored 4, 2, 1
+        # 32 marks a matrix unit: a stand-alone chunk for up to 128 rows of whole threads, all named by entry 0
+        assert row_tiles in (1, 2, 32)
+        if wg_index:  # classes are stored matrix units, 2, 1
             assert row_tiles <= wgs[wg_index - 1][3] & 255
+        if row_tiles == 32:
+            assert wg[4 + 3] > 0 and (wg[4 + 3] // n_sl) * rpt <= 128 and wg[4 + 3] % n_sl == 0 and wg[4 + 2] % n_sl == 0
+            assert wg[4 + 2] == grp_base and not wg[4 + 5] & 1 and wg[4 + 1] == 0
+            assert all(wg[4 + 6 * k + 3] == 0 for k in (1, 2, 3))
+            assert ((tiles[coop_ofs:coop_ofs + n_coop, 1] >> 10) & 1023 == wg[4 + 3]).all()
         # every list holds its full tiles first, then its open ones, and says how many are full
         assert 0 <= coop_full <= n_coop
         fills = (tiles[coop_ofs:coop_ofs + n_coop, 1] >> 20) & 31
@@ -119,7 +125,7 @@ def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per
         tile_reads += n_coop
         for k in range(4):
             t_ofs, n_t, g_lo, n_g, pbase, flags = wg[4 + 6 * k: 10 + 6 * k]
-            assert 0 <= n_g <= row_tiles * cap
+            assert 0 <= n_g <= (128 if row_tiles == 32 else row_tiles * cap)
             fills = (tiles[t_ofs:t_ofs + n_t, 1] >> 20) & 31
             assert 0 <= wg[28 + k] <= n_t
             assert (fills[:wg[28 + k]] == 16).all() and (fills[wg[28 + k]:] < 16).all()

@@ -43,13 +43,15 @@ def decode_both(w, pool, dense, live, step=0, q=None):
     return got, want
 
 
-def run_workload(w, chunk=None, check_each=False, sample=None):
+def run_workload(w, chunk=None, check_each=False, sample=None, matrix_rows=None):
     N = blocks_upper_bound(w)
     hd = w.heads
     with pool_for(w, N) as pool:
         poison(pool)
         if chunk:
             ap.apar_set_chunk_blocks(pool.handle, chunk)
+        if matrix_rows is not None:
+            ap.apar_set_matrix_units(pool.handle, matrix_rows, 1)
         led = BlockLedger(N)
         dense = DenseThreads(hd.n_q_heads, hd.n_kv_heads, hd.head_dim)
         live, nodes = replay_trace(w, pool, led, dense, check_each=check_each)
@@ -288,19 +290,23 @@ def _fan_tree(fan, heads, seed):
 @pytest.mark.parametrize("chunk", [None, 3])
 def test_wide_sharing_groups(dtype, n_q, n_kv, fan, chunk):
     w = _fan_tree(fan, HeadConfig(n_q, n_kv, 128, dtype), seed=fan)
-    err, info = run_workload(w, chunk=chunk)
-    print(f"fan {fan}: {info.n_threads} threads, {info.n_partial_rows} partial rows, err {err:.2e}")
+    # stand-alone shared segments on the row-tile kernel, on the 32x32 kernel whenever they are wide, and by default
+    for matrix_rows in ((0, 1, 64) if dtype == "bf16" else (None,)):
+        err, info = run_workload(w, chunk=chunk, matrix_rows=matrix_rows)
+        print(f"fan {fan}, matrix rows {matrix_rows}: {info.n_threads} threads, {info.n_partial_rows} partial rows, err {err:.2e}")
 
 
-@pytest.mark.parametrize("dtype,fan,C", [("bf16", 1, 5), ("bf16", 3, 5), ("bf16", 6, 5), ("bf16", 40, 2),
-                                         ("bf16", 11, 8), ("f32", 3, 5)])
-def test_multi_candidate_wide_groups(dtype, fan, C):
+@pytest.mark.parametrize("dtype,fan,C,matrix_rows", [("bf16", 1, 5, 64), ("bf16", 3, 5, 64), ("bf16", 6, 5, 64), ("bf16", 6, 5, 1),
+                                                     ("bf16", 40, 2, 64), ("bf16", 40, 2, 0), ("bf16", 11, 8, 64), ("bf16", 11, 8, 1),
+                                                     ("f32", 3, 5, 64)])
+def test_multi_candidate_wide_groups(dtype, fan, C, matrix_rows):
     t = torch()
     heads = HeadConfig(8, 1, 128, dtype)
     w = _fan_tree(fan, heads, seed=100 + fan)
     N = blocks_upper_bound(w)
     with pool_for(w, N) as pool:
         poison(pool)
+        ap.apar_set_matrix_units(pool.handle, matrix_rows, 1)
         dense = DenseThreads(8, 1, 128)
         live, _ = replay_trace(w, pool, None, dense)
         n = len(live)
@@ -462,6 +468,8 @@ def test_random_forests_decode_spec_and_prefill(seed):
         chunk = int(rng.choice([0, 1, 3, 7, 512]))
         if chunk:
             ap.apar_set_chunk_blocks(pool.handle, chunk)
+        # stand-alone shared segments: never / always / by default on the 32x32 kernel
+        ap.apar_set_matrix_units(pool.handle, int(rng.choice([0, 1, 64])), int(rng.choice([1, 2, 64])))
         led = BlockLedger(N)
         dense = DenseThreads(n_q, n_kv, 128)
         live, nodes = replay_trace(w, pool, led, dense)

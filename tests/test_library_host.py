@@ -211,8 +211,9 @@ def test_wide_sharing_groups_use_more_row_tiles(n_q, n_kv, fan, n_cand):
     rpt = n_cand * n_q // n_kv
     with pool_for(w, N, dry_run=True) as pool:
         live, _ = replay_trace(w, pool, None, dry_run=True)
-        for chunk in (2, 512):
+        for chunk, matrix_rows in ((2, 64), (512, 64), (2, 0), (512, 0), (512, 1)):
             ap.apar_set_chunk_blocks(pool.handle, chunk)
+            ap.apar_set_matrix_units(pool.handle, matrix_rows, 1)
             if n_cand == 1:
                 ap.apar_decode_attention(pool.handle, None, live, None)
             else:
@@ -227,7 +228,9 @@ def test_wide_sharing_groups_use_more_row_tiles(n_q, n_kv, fan, n_cand):
                 want = 1 if groups <= 4 * cap else 2
                 assert res["partial_rows"] == 0 and len(wgs) == 1 and wgs[0][3] & 255 == want
             if groups > 8 * cap:
-                assert res["partial_rows"] > 0 and wgs[0][3] & 255 == 2
+                # the root stands alone: as matrix units (marked 32) when its holders bring enough rows
+                want = 32 if matrix_rows and len(live) * rpt >= matrix_rows else 2
+                assert res["partial_rows"] > 0 and wgs[0][3] & 255 == want
 
 
 def test_commit_candidates_books_and_errors():
@@ -321,6 +324,10 @@ def test_prefill_needs_a_group_size_that_divides_16():
 def test_prefill_kernel_knob_checks_its_argument_and_dry_runs_stay_on_row_tiles():
     with ap.Pool(4, 2, 128, "bf16", 8, dry_run=True) as pool:
         h = pool.handle
+        for bad in ((-1, 1), (1, -1)):
+            with pytest.raises(ap.AparError) as e:
+                ap.apar_set_matrix_units(h, *bad)
+            assert e.value.status == -1
         assert ap.apar_last_prefill_kernel(h) == 0
         for bad in (-1, 3):
             with pytest.raises(ap.AparError) as e:
