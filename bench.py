@@ -100,6 +100,8 @@ def spec_loop(args, w) -> int:
     run.build()
     if args.chunk:
         ap.apar_set_chunk_blocks(run.h, args.chunk)
+    if args.matrix_units:
+        ap.apar_set_matrix_units(run.h, *(int(x) for x in args.matrix_units.split(",")))
     run.draw_ahead(args.warmup + K)  # the synthetic step plans (masks, accepted chains, coins) exist before the clock starts
     for _ in range(args.warmup):
         run.step()
@@ -217,7 +219,7 @@ def shared_prefix_bench(args) -> int:
     """Secondary measurement: decode attention when several hundred query rows share one long prefix
     (16 requests, a root of `root` tokens forked into 512 one-token leaves, 32 MHA heads): the root is more
     rows than a fused workgroup carries, so it runs as stand-alone units - on the row-tile kernel or, from
-    1024 tokens on by default, on the 32x32 matrix-core kernel.  Times both for two root lengths."""
+    256 tokens on by default, on the 32x32 matrix-core kernel.  Times both for two root lengths."""
     import numpy as np
     import torch
 
@@ -241,7 +243,7 @@ def shared_prefix_bench(args) -> int:
         ids = np.asarray(run.live, dtype=np.int32)
         q, out = run.banks[0][0], run.out
         res = {}
-        for name, knob in (("row_tile_units", (0, 1)), ("matrix_units", (1, 1)), ("default", (64, 64))):
+        for name, knob in (("row_tile_units", (0, 1)), ("matrix_units", (1, 1)), ("default", (64, 16))):
             ap.apar_set_matrix_units(run.h, *knob)
             for _ in range(args.warmup):
                 ap.apar_decode_attention(run.h, q, ids, out)
@@ -352,6 +354,8 @@ def main() -> int:
     ap_.add_argument("--no-cpu-baseline", action="store_true")
     ap_.add_argument("--prefill-kernel", choices=("auto", "row_tiles", "matrix"), default="auto",
                      help="with --prefill: let the library choose the kernel per call, or force one")
+    ap_.add_argument("--matrix-units", default=None, metavar="ROWS,BLOCKS",
+                     help="thresholds from which a stand-alone shared segment runs on the 32x32 kernel (library default 64,16; 0,0 never)")
     ap_.add_argument("--shared-prefix", action="store_true",
                      help="measure decode attention over long prefixes shared by 512 threads, row-tile vs matrix units")
     ap_.add_argument("--prefill", action="store_true",
@@ -396,6 +400,8 @@ def main() -> int:
     t_build = time.perf_counter() - t_build
     if args.chunk:
         ap.apar_set_chunk_blocks(run.h, args.chunk)
+    if args.matrix_units:
+        ap.apar_set_matrix_units(run.h, *(int(x) for x in args.matrix_units.split(",")))
     st0 = ap.apar_pool_stats(run.h)
 
     if args.copy_calibration:

@@ -408,9 +408,9 @@ APAR_API int apar_set_chunk_blocks(apar_pool* pool, int blocks_per_unit);
 /* Tuning knob (bf16 pools): a shared segment that stands alone as a unit - its holders have more query rows
  * than one fused workgroup carries (128) - goes to the 32x32 matrix-core kernel, up to 128 rows per workgroup,
  * when its holders bring at least min_rows query rows (candidates x q heads per kv head x threads; default 64)
- * and it has at least min_blocks blocks (default 64: that kernel has the higher fixed cost per workgroup and
- * wins from about a thousand tokens on).  min_rows = 0 keeps every unit on the row-tile kernel; (1, 1) sends
- * every such segment to the matrix kernel.  Results agree to rounding.  fp32 pools ignore the knob. */
+ * and it has at least min_blocks blocks (default 16).  Matrix units are launched ahead of the other units of a
+ * call, not beside them.  min_rows = 0 keeps every unit on the row-tile kernel; (1, 1) sends every such segment
+ * to the matrix kernel.  Results agree to rounding.  fp32 pools ignore the knob. */
 APAR_API int apar_set_matrix_units(apar_pool* pool, int min_rows, int min_blocks);
 /* Tuning knob: which kernel apar_prefill_attention runs on a bf16 pool.  ROW_TILES is the decode kernel
  * under a prefill plan (16-row tiles; a prefix shared by sibling threads is read once for all of them),

@@ -73,9 +73,8 @@ struct apar_pool {
     std::vector<int32_t> seg_of;  // segment that starts at each block, -1 if none
     int max_unit_tiles = 512;  // longest tile list given to one wavefront
     int prefill_kernel = APAR_PREFILL_AUTO;
-    // stand-alone segments with at least this many query rows and blocks run as matrix units (bf16 pools): the
-    // 32x32 kernel has the higher fixed cost per workgroup and only wins on long walks
-    int matrix_min_rows = 64, matrix_min_blocks = 64;
+    // stand-alone segments with at least this many query rows and blocks run as matrix units (bf16 pools)
+    int matrix_min_rows = 64, matrix_min_blocks = 16;
     int last_prefill_kernel = 0;  // which kernel the most recent prefill call ran (APAR_PREFILL_ROW_TILES / _MATRIX)
     std::vector<PlanThreadView> views;
     std::vector<PrefillThreadView> prefill_views;

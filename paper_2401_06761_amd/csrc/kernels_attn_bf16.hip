@@ -631,17 +631,23 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
                                  PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
                                  void* out, ClassStreams& cs, hipStream_t st) {
     // workgroups are sorted by class: [matrix units | 2 row tiles per wavefront | 1], heaviest first in each.
-    // The last class present runs on the caller's stream; the ones before it run beside it on side
-    // streams that wait for the caller's stream first and that the caller's stream then waits for.
+    // Matrix units go first, alone, on the caller's stream: their workgroups need 64 KB of LDS and most of a
+    // SIMD's registers, and beside a kernel of small workgroups they wait until that kernel has drained
+    // (measured: a 100 us launch took as long as the 800 us launch beside it).  Of the two row-tile classes
+    // the last one present runs on the caller's stream and the other beside it on a side stream that waits
+    // for the caller's stream first and that the caller's stream then waits for.
     int first[3], last = -1, n_present = 0;
     for (int cls = 0, f = 0; cls < 3; ++cls) {
         first[cls] = f;
         f += plan.n_wg_class[cls];
-        if (plan.n_wg_class[cls] > 0) last = cls, ++n_present;
+        if (cls > 0 && plan.n_wg_class[cls] > 0) last = cls, ++n_present;
         if ((int64_t)plan.n_wg_class[cls] * s.n_kv > 0x7fffffff) return hipErrorInvalidValue;
     }
-    if (last < 0) return hipSuccess;
     hipError_t e;
+    if (plan.n_wg_class[0] > 0 &&
+        (e = launch_attention_units_bf16(s, pool, q, plan, first[0], plan.n_wg_class[0], n_cand, part, st)) != hipSuccess)
+        return e;
+    if (last < 0) return hipSuccess;
     if (n_present > 1) {
         if (!cs.fork) {
             if ((e = hipEventCreateWithFlags(&cs.fork, hipEventDisableTiming)) != hipSuccess) return e;
@@ -654,7 +660,7 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
     }
     int side = 0;
     bool used[2] = {false, false};
-    for (int cls = 0; cls < 3; ++cls) {
+    for (int cls = 1; cls < 3; ++cls) {
         const int count = plan.n_wg_class[cls];
         if (count == 0) continue;
         hipStream_t on = st;
@@ -667,9 +673,7 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
     hipLaunchKernelGGL((attention_bf16<NTV>), dim3(n_wg), dim3(256), 0, on, (const char*)pool, (const uint16_t*)q, \
                        plan, first[cls], n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part,                      \
                        (const uint16_t*)cand_k, (const uint16_t*)cand_v, mask, (uint16_t*)out)
-        if (cls == 0) {
-            if ((e = launch_attention_units_bf16(s, pool, q, plan, first[cls], count, n_cand, part, on)) != hipSuccess) return e;
-        } else if (cls == 1) APAR_LAUNCH(2);
+        if (cls == 1) APAR_LAUNCH(2);
         else APAR_LAUNCH(1);
 #undef APAR_LAUNCH
         if ((e = hipGetLastError()) != hipSuccess) return e;
