@@ -111,7 +111,7 @@ __device__ __forceinline__ void walk_blocks(const Walk& wk, char* lds, f32x16 (&
     // this wavefront stages block `wave` of every group
     u32x4 sk[4], sv[4];
     auto fetch = [&](int g) {
-        // a group's last blocks may lie past the last attended token: they are masked, re-read the last one
+        // a group's last blocks may lie past the walk's last block: they are masked, re-read the last one
         const int blk = min(4 * g + wave, n_blk - 1);
         const int fill = min(16, wk.len - blk * 16);
         const char* tile = head_base + wk.table[blk * wk.table_stride] * block_stride;
@@ -122,7 +122,7 @@ __device__ __forceinline__ void walk_blocks(const Walk& wk, char* lds, f32x16 (&
                 sv[r] = *reinterpret_cast<const u32x4*>(tile + kHalf + r * 1024 + lane * 16);
             }
         } else {
-            // the thread's last block is still open: row-major.  Piece r of this lane belongs to token row
+            // the walk's last block is still open: row-major.  Piece r of this lane belongs to token row
             // 4r + g4; rows past the fill count re-read row 0 (finite values under probability 0)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -207,7 +207,7 @@ __device__ __forceinline__ void walk_blocks(const Walk& wk, char* lds, f32x16 (&
                     va[T][jj].u = *reinterpret_cast<const u32x4*>(buf + (2 * sub + T) * kTileBytes + kHalf +
                                                                   v_operand_offset(jj, n >> 4, n & 15, h));
             __builtin_amdgcn_sched_barrier(0);
-            // ---- causal mask on the diagonal: slot t0 + 8 (i / 4) + 4 h + i % 4 is visible up to the row's position
+            // ---- mask near the rows' limits: slot t0 + 8 (i / 4) + 4 h + i % 4 is visible up to the row's pos
             if (t0 + 31 > w_first) {
                 const int room = row_ok ? pos - t0 - 4 * h : -1;  // visible iff 8 (i / 4) + i % 4 <= room
 #pragma unroll
