@@ -218,8 +218,9 @@ def prefill_bench(args, w) -> int:
 def shared_prefix_bench(args) -> int:
     """Secondary measurement: decode attention when several hundred query rows share one long prefix
     (16 requests, a root of `root` tokens forked into 512 one-token leaves, 32 MHA heads): the root is more
-    rows than a fused workgroup carries, so it runs as stand-alone units - on the row-tile kernel or, from
-    256 tokens on by default, on the 32x32 matrix-core kernel.  Times both for two root lengths."""
+    rows than a fused workgroup carries: it is inlined (read again by every unit of 128 rows below it, nothing
+    to merge) or stands alone with partial results, on the row-tile kernel or on the 32x32 matrix-core kernel
+    (the default from 2048 tokens on).  Times the variants for two root lengths."""
     import numpy as np
     import torch
 
@@ -243,7 +244,9 @@ def shared_prefix_bench(args) -> int:
         ids = np.asarray(run.live, dtype=np.int32)
         q, out = run.banks[0][0], run.out
         res = {}
-        for name, knob in (("row_tile_units", (0, 1)), ("matrix_units", (1, 1)), ("default", (64, 16))):
+        for name, inline, knob in (("inlined", True, (0, 1)), ("stand_alone_row_tile_units", False, (0, 1)),
+                                   ("stand_alone_matrix_units", False, (1, 1)), ("default", True, (64, 128))):
+            ap.apar_set_inline_shared(run.h, inline)
             ap.apar_set_matrix_units(run.h, *knob)
             for _ in range(args.warmup):
                 ap.apar_decode_attention(run.h, q, ids, out)
@@ -355,7 +358,7 @@ def main() -> int:
     ap_.add_argument("--prefill-kernel", choices=("auto", "row_tiles", "matrix"), default="auto",
                      help="with --prefill: let the library choose the kernel per call, or force one")
     ap_.add_argument("--matrix-units", default=None, metavar="ROWS,BLOCKS",
-                     help="thresholds from which a stand-alone shared segment runs on the 32x32 kernel (library default 64,16; 0,0 never)")
+                     help="thresholds from which a stand-alone shared segment runs on the 32x32 kernel (library default 64,128; 0,0 never)")
     ap_.add_argument("--shared-prefix", action="store_true",
                      help="measure decode attention over long prefixes shared by 512 threads, row-tile vs matrix units")
     ap_.add_argument("--prefill", action="store_true",

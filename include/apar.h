@@ -408,10 +408,16 @@ APAR_API int apar_set_chunk_blocks(apar_pool* pool, int blocks_per_unit);
 /* Tuning knob (bf16 pools): a shared segment that stands alone as a unit - its holders have more query rows
  * than one fused workgroup carries (128) - goes to the 32x32 matrix-core kernel, up to 128 rows per workgroup,
  * when its holders bring at least min_rows query rows (candidates x q heads per kv head x threads; default 64)
- * and it has at least min_blocks blocks (default 16).  Matrix units are launched ahead of the other units of a
- * call, not beside them.  min_rows = 0 keeps every unit on the row-tile kernel; (1, 1) sends every such segment
+ * and it has at least min_blocks blocks (default 128; shorter ones are cheaper inlined, see apar_set_inline_shared).
+ * Matrix units are launched ahead of the other units of a call, not beside them.  min_rows = 0 keeps every unit on the row-tile kernel; (1, 1) sends every such segment
  * to the matrix kernel.  Results agree to rounding.  fp32 pools ignore the knob. */
 APAR_API int apar_set_matrix_units(apar_pool* pool, int min_rows, int min_blocks);
+/* Tuning knob: what happens to a shared segment whose holders bring more query rows than one unit carries
+ * (128) and that does not go to the matrix kernel.  On (default): its holders are cut into units of
+ * consecutive threads (whole child subtrees where they fit) and every such unit reads the segment's blocks
+ * again - no partial results, no merge; used while the chain of such segments above a unit stays shorter
+ * than half the unit cap.  Off: the segment stands alone with one partial result per (chunk, thread). */
+APAR_API int apar_set_inline_shared(apar_pool* pool, int on);
 /* Tuning knob: which kernel apar_prefill_attention runs on a bf16 pool.  ROW_TILES is the decode kernel
  * under a prefill plan (16-row tiles; a prefix shared by sibling threads is read once for all of them),
  * MATRIX the 32x32 matrix-core kernel (one workgroup per thread and chunk of 128 query rows; needs a

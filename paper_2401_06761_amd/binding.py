@@ -117,6 +117,7 @@ def _load() -> C.CDLL:
         "apar_set_chunk_blocks": [P, I],
         "apar_set_prefill_kernel": [P, I],
         "apar_set_matrix_units": [P, I, I],
+        "apar_set_inline_shared": [P, I],
         "apar_last_prefill_kernel": [P],
         "apar_append_kv_gather": [P, I32P, I32P, I, V, V, V],
         "apar_server_create": [P, C.POINTER(AparServerConfig), C.POINTER(P)],
@@ -361,6 +362,10 @@ def apar_set_chunk_blocks(pool, blocks_per_unit: int) -> None:
 
 
 APAR_PREFILL_AUTO, APAR_PREFILL_ROW_TILES, APAR_PREFILL_MATRIX = 0, 1, 2
+
+
+def apar_set_inline_shared(pool, on: bool) -> None:
+    _check(_L().apar_set_inline_shared(pool, 1 if on else 0), "apar_set_inline_shared")
 
 
 def apar_set_matrix_units(pool, min_rows: int, min_blocks: int) -> None:

@@ -74,7 +74,8 @@ struct apar_pool {
     int max_unit_tiles = 512;  // longest tile list given to one wavefront
     int prefill_kernel = APAR_PREFILL_AUTO;
     // stand-alone segments with at least this many query rows and blocks run as matrix units (bf16 pools)
-    int matrix_min_rows = 64, matrix_min_blocks = 16;
+    int matrix_min_rows = 64, matrix_min_blocks = 128;
+    bool inline_shared = true;  // short shared segments with too many rows below: read again per unit instead of partial results
     int last_prefill_kernel = 0;  // which kernel the most recent prefill call ran (APAR_PREFILL_ROW_TILES / _MATRIX)
     std::vector<PlanThreadView> views;
     std::vector<PrefillThreadView> prefill_views;
@@ -260,6 +261,7 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     prm.fuse = true;
     prm.matrix_min_rows = (p->shape.dtype == APAR_BF16) ? p->matrix_min_rows : 0;
     prm.matrix_min_blocks = p->matrix_min_blocks;
+    prm.inline_shared = p->inline_shared;
     int rc = build_plan(p->views.data(), n, p->ref.data(), p->seg_of.data(), prm, ph);
     if (rc != APAR_OK) return rc;
     const int64_t e = p->shape.dtype == APAR_F32 ? 4 : 2;
@@ -933,6 +935,12 @@ int apar_profile_attention_calls(apar_pool* p, float* ms_out, int64_t cap, int64
     *n_out = n;
     if (cap < n) return APAR_ERR_INVALID_ARG;
     if (n > 0) memcpy(ms_out, p->last_attention_ms.data(), (size_t)n * sizeof(float));
+    return APAR_OK;
+}
+
+int apar_set_inline_shared(apar_pool* p, int on) {
+    if (!p) return APAR_ERR_INVALID_ARG;
+    p->inline_shared = on != 0;
     return APAR_OK;
 }
 

@@ -20,9 +20,14 @@
 // output written directly.  Inside such a unit a block whose holders all sit in one
 // wavefront goes on that wavefront's private list (no barrier, registers only);
 // blocks needed by several wavefronts go on the shared list (staged once in LDS).
-// Subtrees with too many rows or blocks are cut: the top segment stands alone,
-// chunked, with one partial result per (chunk, thread), and its children are tried
-// again.  Attention is a set operation, so a unit may visit its blocks in any order.
+// Subtrees with too many rows or blocks are cut at their top segment and its children
+// are tried again.  A top segment with too many ROWS below it is inlined where it is
+// short enough: its threads are cut into units of consecutive ranks (whole child
+// subtrees where they fit) and each of those units reads the segment's blocks again,
+// as often as stand-alone units would, with nothing to merge afterwards.  Otherwise it
+// stands alone, chunked, with one partial result per (chunk, thread); long ones with
+// many rows as matrix units.  Attention is a set operation, so a unit may visit its
+// blocks in any order.
 #include "plan.hpp"
 
 #include <algorithm>
@@ -105,26 +110,37 @@ struct Builder {
         if (n_plain < nb) open.push_back(TileRef{blk[b0 + nb - 1], make_meta(lo, hi, s.last_valid)});
     }
 
-    void emit_standalone(int32_t sid) {
+    // Segment sid stands alone: chunks of its blocks, one partial result per (chunk, thread).  `anc` (-1:
+    // none) is the inlined chain directly above it, whose blocks (all full: every segment of the chain has
+    // children) its first chunk reads too.
+    void emit_standalone(int32_t sid, int32_t anc) {
         PlanHost::Segment& s = ph.segs[sid];
         const int groups = s.n_shr * n_sl;
         const int chunk = std::max(1, prm.max_unit_tiles);
-        const int nch = (s.n_blk + chunk - 1) / chunk;
+        const int chain = anc >= 0 ? inline_blocks[anc] : 0;  // <= chunk / 2
+        const int first_nb = std::min(s.n_blk, chunk - chain);
+        const int nch = 1 + (s.n_blk - first_nb + chunk - 1) / chunk;
         n_chunks[sid] = nch;
         part0[sid] = (int32_t)ph.n_partial_rows;
         ph.n_partial_rows += (int64_t)nch * s.n_shr;
         ph.any_partial = true;
         const int32_t grp0 = s.t_lo * n_sl;
+        // the chunk's tiles for row groups [0, hi) of a list owner: the chain first (chunk 0 only)
+        auto chunk_tiles = [&](int c, int b0, int nb, int hi) {
+            ph.open_tmp.clear();
+            if (c == 0)
+                for (int32_t a = anc; a >= 0; a = ph.segs[a].parent) push_tiles(ph.tiles, ph.open_tmp, ph.segs[a], 0, ph.segs[a].n_blk, 0, hi);
+            push_tiles(ph.tiles, ph.open_tmp, s, b0, nb, 0, hi);
+        };
         for (int c = 0; c < nch; ++c) {
-            const int b0 = c * chunk, nb = std::min(chunk, s.n_blk - b0);
+            const int b0 = c == 0 ? 0 : first_nb + (c - 1) * chunk, nb = c == 0 ? first_nb : std::min(chunk, s.n_blk - b0);
             const int32_t pbase = part0[sid] + c * s.n_shr;
             if (groups <= cap) {
                 const int32_t ofs = (int32_t)ph.tiles.size();
-                ph.open_tmp.clear();
-                push_tiles(ph.tiles, ph.open_tmp, s, b0, nb, 0, groups);
+                chunk_tiles(c, b0, nb, groups);
                 const int32_t n_full = (int32_t)ph.tiles.size() - ofs;
                 ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
-                emit_narrow(ofs, nb, n_full, grp0, groups, pbase, 0);
+                emit_narrow(ofs, (int32_t)ph.tiles.size() - ofs, n_full, grp0, groups, pbase, 0);
             } else if (prm.matrix_min_rows > 0 && (int64_t)s.n_shr * prm.rows_per_thread >= prm.matrix_min_rows &&
                        s.n_blk >= prm.matrix_min_blocks) {
                 // matrix units: whole threads, as evenly over the workgroups as they go
@@ -135,15 +151,14 @@ struct Builder {
                     const int nt = std::min(each, s.n_shr - t0);
                     PlanHost::WideItem wi{};
                     wi.wg.coop_ofs = (int32_t)ph.tiles.size();
-                    wi.wg.n_coop = nb;
                     wi.wg.grp_base = grp0 + t0 * n_sl;
-                    ph.open_tmp.clear();
-                    push_tiles(ph.tiles, ph.open_tmp, s, b0, nb, 0, nt * n_sl);
+                    chunk_tiles(c, b0, nb, nt * n_sl);
                     wi.wg.row_tiles = kMatrixUnitRows | (((int32_t)ph.tiles.size() - wi.wg.coop_ofs) << 8);
                     ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
+                    wi.wg.n_coop = (int32_t)ph.tiles.size() - wi.wg.coop_ofs;
                     wi.wg.w[0] = WaveItem{0, 0, wi.wg.grp_base, nt * n_sl, pbase + t0, 0};
                     for (int k = 1; k < 4; ++k) wi.wg.w[k] = WaveItem{0, 0, 0, 0, -1, 0};
-                    wi.cost = nb;
+                    wi.cost = wi.wg.n_coop;
                     ph.wide_items.push_back(wi);
                 }
             } else {
@@ -153,50 +168,70 @@ struct Builder {
                     PlanHost::WideItem wi{};
                     wi.wg.row_tiles = nt;
                     wi.wg.coop_ofs = (int32_t)ph.tiles.size();
-                    wi.wg.n_coop = nb;
                     wi.wg.grp_base = grp0 + g0;
-                    ph.open_tmp.clear();
-                    push_tiles(ph.tiles, ph.open_tmp, s, b0, nb, 0, gn);
+                    chunk_tiles(c, b0, nb, gn);
                     wi.wg.row_tiles |= ((int32_t)ph.tiles.size() - wi.wg.coop_ofs) << 8;
                     ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
+                    wi.wg.n_coop = (int32_t)ph.tiles.size() - wi.wg.coop_ofs;
                     for (int k = 0; k < 4; ++k) {
                         const int lo = k * wcap, cnt = std::max(0, std::min(wcap, gn - lo));
                         wi.wg.w[k] = WaveItem{0, 0, grp0 + g0 + lo, cnt, pbase + (g0 + lo) / n_sl, 0};
                     }
-                    wi.cost = 2 * nb * nt;
+                    wi.cost = 2 * wi.wg.n_coop * nt;
                     ph.wide_items.push_back(wi);
                 }
             }
         }
     }
 
-    void emit_fused(int32_t rid) {
-        PlanHost::Segment& r = ph.segs[rid];
-        const int groups = r.n_shr * n_sl;
-        const bool direct = prm.allow_direct && r.n_above == 0;
+    // A unit over the consecutive depth-first ranks [r_lo, r_lo + n_thr).  The rows' softmax state stays in
+    // registers over everything the unit reads.  `anc` (-1: none) is the innermost of a chain of inlined
+    // segments (it and all its ancestors) whose blocks every row of the unit reads; the first n_lead threads
+    // end at `anc` itself; the rest are the subtrees of `roots`, in rank order.
+    struct UnitSpec {
+        int32_t anc, r_lo, n_thr, n_lead;
+        const int32_t* roots;
+        int n_roots;
+        bool direct;
+    };
+
+    // f(segment index, lo, hi): the segments a unit reads, with their row groups relative to the unit's first
+    template <class F>
+    void for_unit_segments(const UnitSpec& u, F&& f) {
+        const int groups = u.n_thr * n_sl;
+        for (int32_t a = u.anc; a >= 0; a = ph.segs[a].parent) f(a, 0, groups);
+        for (int k = 0; k < u.n_roots; ++k)
+            for_subtree(u.roots[k], [&](int32_t m) {
+                const PlanHost::Segment& sg = ph.segs[m];
+                const int lo = (sg.t_lo - u.r_lo) * n_sl;
+                f(m, lo, lo + sg.n_shr * n_sl);
+            });
+    }
+
+    // Returns the unit's first partial-result row (-1 for a direct unit).
+    int32_t emit_unit(const UnitSpec& u) {
+        const int groups = u.n_thr * n_sl;
         int32_t pbase = -1;
-        if (!direct) {
+        if (!u.direct) {
             pbase = (int32_t)ph.n_partial_rows;
-            part0[rid] = pbase;
-            ph.n_partial_rows += r.n_shr;
+            ph.n_partial_rows += u.n_thr;
             ph.any_partial = true;
         } else {
-            ph.n_direct_threads += r.n_shr;
+            ph.n_direct_threads += u.n_thr;
         }
-        const int32_t flags = direct ? kWaveDirect : 0;
-        const int32_t grp0 = r.t_lo * n_sl;
+        const int32_t flags = u.direct ? kWaveDirect : 0;
+        const int32_t grp0 = u.r_lo * n_sl;
         if (groups <= cap) {
             const int32_t ofs = (int32_t)ph.tiles.size();
             ph.open_tmp.clear();
-            for_subtree(rid, [&](int32_t m) {
-                const PlanHost::Segment& s = ph.segs[m];
-                const int lo = (s.t_lo - r.t_lo) * n_sl, hi = lo + s.n_shr * n_sl;
-                push_tiles(ph.tiles, ph.open_tmp, s, 0, s.n_blk, lo, hi);
+            for_unit_segments(u, [&](int32_t m, int lo, int hi) {
+                const PlanHost::Segment& sg = ph.segs[m];
+                push_tiles(ph.tiles, ph.open_tmp, sg, 0, sg.n_blk, lo, hi);
             });
             const int32_t n_full = (int32_t)ph.tiles.size() - ofs;
             ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
             emit_narrow(ofs, (int32_t)ph.tiles.size() - ofs, n_full, grp0, groups, pbase, flags);
-            return;
+            return pbase;
         }
         // several wavefronts: give each a contiguous range of row groups, keeping subtrees that fit
         // one wavefront whole where possible
@@ -217,27 +252,29 @@ struct Builder {
             }
             fill += cnt;
         };
+        auto thread_atoms = [&](int lo_rel) {  // one thread: whole if it fits a wavefront, else slice by slice
+            if (n_sl <= wcap) atom(lo_rel, n_sl);
+            else
+                for (int sl = 0; sl < n_sl; ++sl) atom(lo_rel + sl, 1);
+        };
+        for (int e = 0; e < u.n_lead; ++e) thread_atoms(e * n_sl);
         {
             // a walk that stops descending where a subtree fits one wavefront
             std::vector<int32_t>& st = ph.stack;
             const size_t base = st.size();
-            st.push_back(rid);
+            for (int k = u.n_roots - 1; k >= 0; --k) st.push_back(u.roots[k]);
             while (st.size() > base && !overflow) {
                 const int32_t m = st.back();
                 st.pop_back();
-                const PlanHost::Segment& s = ph.segs[m];
-                const int lo = (s.t_lo - r.t_lo) * n_sl, mg = s.n_shr * n_sl;
+                const PlanHost::Segment& sg = ph.segs[m];
+                const int lo = (sg.t_lo - u.r_lo) * n_sl, mg = sg.n_shr * n_sl;
                 if (mg <= wcap) {
                     atom(lo, mg);
                     continue;
                 }
-                for (int e = 0; e < s.n_end; ++e) {  // threads that end here come first in depth-first order
-                    if (n_sl <= wcap) atom(lo + e * n_sl, n_sl);
-                    else
-                        for (int sl = 0; sl < n_sl; ++sl) atom(lo + e * n_sl + sl, 1);
-                }
+                for (int e = 0; e < sg.n_end; ++e) thread_atoms(lo + e * n_sl);  // threads that end here come first in depth-first order
                 const size_t mark = st.size();
-                for (int32_t c = s.first_child; c >= 0; c = ph.segs[c].next_sibling) st.push_back(c);
+                for (int32_t c = sg.first_child; c >= 0; c = ph.segs[c].next_sibling) st.push_back(c);
                 std::reverse(st.begin() + mark, st.end());
             }
             st.resize(base);
@@ -249,21 +286,22 @@ struct Builder {
                 wave_n[k] = std::max(0, std::min(wcap, groups - k * wcap));
             }
         }
-        // first pass: who owns each segment of the subtree (a wavefront whose row groups contain all its
-        // holders, else the shared list), and how long the lists get; second pass: write the tiles in place
+        // first pass: who owns each segment the unit reads (a wavefront whose row groups contain all its
+        // rows here, else the shared list), and how long the lists get; second pass: write the tiles in place
         int n_plain[5] = {0, 0, 0, 0, 0}, n_open[5] = {0, 0, 0, 0, 0};  // [0]: shared list, [1 + k]: wavefront k
         std::vector<int32_t>& visit = ph.order;
         visit.clear();
-        for_subtree(rid, [&](int32_t m) {
-            const PlanHost::Segment& s = ph.segs[m];
-            const int lo = (s.t_lo - r.t_lo) * n_sl, hi = lo + s.n_shr * n_sl;
+        for_unit_segments(u, [&](int32_t m, int lo, int hi) {
+            const PlanHost::Segment& sg = ph.segs[m];
             int owner = -1;
             for (int k = 0; k < 4; ++k)
                 if (wave_n[k] > 0 && lo >= wave_lo[k] && hi <= wave_lo[k] + wave_n[k]) owner = k;
             visit.push_back(m);
             visit.push_back(owner);
-            const bool open = s.last_valid < B;
-            n_plain[owner + 1] += s.n_blk - (open ? 1 : 0);
+            visit.push_back(lo);
+            visit.push_back(hi);
+            const bool open = sg.last_valid < B;
+            n_plain[owner + 1] += sg.n_blk - (open ? 1 : 0);
             n_open[owner + 1] += open ? 1 : 0;
         });
         const size_t base = ph.tiles.size();
@@ -279,18 +317,18 @@ struct Builder {
             plain_at[l] = ph.tiles.data() + list_ofs[l];
             open_at[l] = plain_at[l] + n_plain[l];
         }
-        for (size_t i = 0; i < visit.size(); i += 2) {
-            const PlanHost::Segment& s = ph.segs[visit[i]];
+        for (size_t i = 0; i < visit.size(); i += 4) {
+            const PlanHost::Segment& sg = ph.segs[visit[i]];
             const int owner = visit[i + 1];
             const int rel = owner >= 0 ? wave_lo[owner] : 0;
-            const int lo = (s.t_lo - r.t_lo) * n_sl - rel, hi = lo + s.n_shr * n_sl;
-            const bool open = s.last_valid < B;
-            const int np = s.n_blk - (open ? 1 : 0);
+            const int lo = visit[i + 2] - rel, hi = visit[i + 3] - rel;
+            const bool open = sg.last_valid < B;
+            const int np = sg.n_blk - (open ? 1 : 0);
             const int32_t meta = make_meta(lo, hi, B);
             TileRef* dst = plain_at[owner + 1];
-            for (int b2 = 0; b2 < np; ++b2) dst[b2] = TileRef{s.blocks[b2], meta};
+            for (int b2 = 0; b2 < np; ++b2) dst[b2] = TileRef{sg.blocks[b2], meta};
             plain_at[owner + 1] += np;
-            if (open) *open_at[owner + 1]++ = TileRef{s.blocks[np], make_meta(lo, hi, s.last_valid)};
+            if (open) *open_at[owner + 1]++ = TileRef{sg.blocks[np], make_meta(lo, hi, sg.last_valid)};
         }
         PlanHost::WideItem wi{};
         wi.wg.coop_ofs = (int32_t)list_ofs[0];
@@ -301,12 +339,70 @@ struct Builder {
         for (int k = 0; k < 4; ++k) {
             const int32_t cnt = n_plain[k + 1] + n_open[k + 1];
             wi.wg.w[k] = WaveItem{(int32_t)list_ofs[k + 1], cnt, grp0 + wave_lo[k], wave_n[k],
-                                  direct ? -1 : pbase + wave_lo[k] / n_sl, flags};
+                                  u.direct ? -1 : pbase + wave_lo[k] / n_sl, flags};
             wi.wg.n_full[k] = n_plain[k + 1];
             longest = std::max(longest, (int)cnt);
         }
         wi.cost = nt * (2 * wi.wg.n_coop + longest);
         ph.wide_items.push_back(wi);
+        return pbase;
+    }
+
+    // A whole sharing subtree as one unit; `anc`: the inlined chain above it (-1: none).
+    void emit_fused(int32_t rid, int32_t anc) {
+        PlanHost::Segment& r = ph.segs[rid];
+        const bool direct = prm.allow_direct && r.n_above == 0;
+        const int32_t roots[1] = {rid};
+        const int32_t pbase = emit_unit(UnitSpec{anc, r.t_lo, r.n_shr, 0, roots, 1, direct});
+        if (!direct) part0[rid] = pbase;
+    }
+
+    // Segment sid is inlined (its blocks, and those of the inlined chain above it, are read by every unit
+    // below it): cut its threads into units of consecutive ranks.  The threads that end at sid come first,
+    // then its children's subtrees in order; a subtree that does not fit a unit is left to the caller's
+    // loop (it is inlined or stands alone in turn).  All these units are direct: nothing above them leaves
+    // a partial result.
+    std::vector<int32_t> inline_blocks;  // per inlined segment: blocks of the chain from its forest root down to it
+    std::vector<int32_t> pack_roots;
+    void pack_under(int32_t sid) {
+        const PlanHost::Segment& S = ph.segs[sid];
+        const int max_groups = 4 * kMaxRowTiles * cap;
+        const int64_t above = inline_blocks[sid];
+        int32_t cur_lo = S.t_lo, cur_thr = 0, cur_lead = 0;
+        int64_t cur_tiles = 0;
+        pack_roots.clear();
+        auto room = [&](int thr_after, int64_t tiles_after) {
+            const int g = thr_after * n_sl;
+            return g <= max_groups && above + tiles_after <= (int64_t)(g <= cap ? 1 : 4) * prm.max_unit_tiles;
+        };
+        auto flush = [&]() {
+            if (cur_thr > 0) {
+                emit_unit(UnitSpec{sid, cur_lo, cur_thr, cur_lead, pack_roots.data(), (int)pack_roots.size(), true});
+                for (int32_t r : pack_roots) ph.segs[r].unit = pack_roots[0];
+            }
+            cur_lo += cur_thr;
+            cur_thr = cur_lead = 0;
+            cur_tiles = 0;
+            pack_roots.clear();
+        };
+        for (int e = 0; e < S.n_end; ++e) {
+            if (!room(cur_thr + 1, cur_tiles)) flush();
+            cur_thr += 1;
+            cur_lead += 1;
+        }
+        for (int32_t c = S.first_child; c >= 0; c = ph.segs[c].next_sibling) {
+            const PlanHost::Segment& C = ph.segs[c];
+            if (!room(C.n_shr, C.tiles_sub)) {  // too big even alone
+                flush();
+                cur_lo = C.t_lo + C.n_shr;
+                continue;
+            }
+            if (!room(cur_thr + C.n_shr, cur_tiles + C.tiles_sub)) flush();
+            pack_roots.push_back(c);
+            cur_thr += C.n_shr;
+            cur_tiles += C.tiles_sub;
+        }
+        flush();
     }
 };
 
@@ -418,11 +514,13 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
     // 5. cut the forest into units, parents first
     bld.part0.assign(n_seg, -1);
     bld.n_chunks.assign(n_seg, 0);
+    bld.inline_blocks.assign(n_seg, 0);
     const int cap = bld.cap, n_sl = bld.n_sl;
     for (int32_t m = 0; m < n_seg; ++m) {
         PlanHost::Segment& s = segs[m];
         ph.unique_blocks += s.n_blk;
         ph.unique_tokens += (int64_t)(s.n_blk - 1) * B + s.last_valid;
+        if (s.unit >= 0) continue;  // packed into a unit by its inlined parent
         const int32_t par = s.parent;
         if (par >= 0 && segs[par].unit >= 0) {
             s.unit = segs[par].unit;
@@ -430,13 +528,34 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
             continue;
         }
         s.n_above = par >= 0 ? segs[par].n_above + bld.n_chunks[par] : 0;
+        // an inlined chain is read by whatever sits directly below it: a unit, or the first chunk of a
+        // segment that stands alone
+        const int32_t anc = (par >= 0 && segs[par].inlined) ? par : -1;
+        const int64_t above = anc >= 0 ? bld.inline_blocks[anc] : 0;
         const int groups = s.n_shr * n_sl;
-        const bool fits = groups <= 4 * kMaxRowTiles * cap && s.tiles_sub <= (groups <= cap ? 1 : 4) * prm.max_unit_tiles;
+        const bool fits = groups <= 4 * kMaxRowTiles * cap &&
+                          above + s.tiles_sub <= (int64_t)(groups <= cap ? 1 : 4) * prm.max_unit_tiles;
         if (prm.fuse && fits) {
-            s.unit = m;  // a unit is named after its root segment
-            bld.emit_fused(m);
+            s.unit = m;  // a unit is named after its (first) root segment
+            bld.emit_fused(m, anc);
+            continue;
+        }
+        // Too many rows (or blocks) below for one unit.  Either the segment stands alone - chunked, one
+        // partial result per (chunk, thread), merged afterwards - or it is inlined: every unit below reads
+        // its blocks again, up to 128 rows at a time (as often as stand-alone units would), and nothing is
+        // written but output rows.  Inlining is for too many ROWS (with too many blocks for few rows the
+        // segment is better read once), needs the whole path above to be inlined too (so that the units
+        // below are direct) and a chain short enough to leave the units room; long segments with many
+        // rows are better off alone on the matrix kernel.
+        const bool to_matrix = prm.matrix_min_rows > 0 && (int64_t)s.n_shr * prm.rows_per_thread >= prm.matrix_min_rows &&
+                               s.n_blk >= prm.matrix_min_blocks;
+        if (prm.fuse && prm.inline_shared && s.n_above == 0 && !to_matrix && groups > 4 * kMaxRowTiles * cap &&
+            2 * (above + s.n_blk) <= prm.max_unit_tiles) {
+            s.inlined = 1;
+            bld.inline_blocks[m] = (int32_t)(above + s.n_blk);
+            bld.pack_under(m);
         } else {
-            bld.emit_standalone(m);
+            bld.emit_standalone(m, anc);
         }
     }
     if (ph.n_partial_rows > INT32_MAX / 2 || ph.tiles.size() > (size_t)INT32_MAX / 2) return APAR_ERR_UNSUPPORTED;

@@ -37,6 +37,7 @@ struct PlanHost {
         int32_t tiles_sub;        // blocks in its whole subtree
         int32_t unit;             // fused unit it belongs to, -1 if it stands alone
         int32_t n_above;          // partial results produced above it on the path (same for all its threads)
+        int32_t inlined;          // 1: no unit of its own; every unit below reads its blocks
     };
     std::vector<Segment> segs;
     std::vector<int32_t> thread_last_seg, end_threads, order, stack;
@@ -63,6 +64,8 @@ struct PlanParams {
     int32_t max_unit_tiles;   // longest tile list one wavefront may be given
     bool allow_direct;        // threads whose whole path is one unit may write their output directly
     bool fuse;                // build tree-fused units (false: every segment stands alone)
+    bool inline_shared = true;  // a short shared segment with too many rows below is read again by every unit below
+                                // instead of standing alone with partial results
     int32_t matrix_min_rows = 0;    // stand-alone segments with at least this many query rows (0: never) ...
     int32_t matrix_min_blocks = 0;  // ... and at least this many blocks become matrix units
 };

@@ -6,7 +6,7 @@ from typing import Dict, List, Optional, Sequence
 import numpy as np
 
 import paper_2401_06761_amd as ap
-from apar_workloads import build_trace, node_kv
+from apar_workloads import build_trace, manual_tree, node_kv
 from oracle import BlockLedger, DenseThreads
 
 
@@ -86,6 +86,16 @@ def pool_for(w, num_blocks: int, dry_run: bool = False, **kw) -> "ap.Pool":
 def blocks_upper_bound(w) -> int:
     """Enough blocks for any replay of w: every node's segment rounded up, plus one copy per node."""
     return sum((n.seg_len + 15) // 16 + 1 for n in w.nodes) + 4
+
+
+def nested_wide_tree(heads, seed=0):
+    # a root with three children; two of them have more leaves below than one unit carries
+    parents, lens = [-1, 0, 0, 0], [40, 20, 200, 33]
+    for kid, n_leaves in ((1, 150), (2, 140), (3, 10)):
+        for i in range(n_leaves):
+            parents.append(kid)
+            lens.append(1 + (i * 5) % 37)
+    return manual_tree(parents, lens, heads, seed=seed, data_scale=0.5)
 
 
 def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per_thread: int = 1) -> Dict[str, int]:

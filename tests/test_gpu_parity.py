@@ -11,7 +11,7 @@ from apar_workloads import (HeadConfig, make_config, manual_tree, mask_rows_from
                             node_kv, quantise, step_q, tiny_tree)
 from oracle import BlockLedger, DenseThreads
 
-from harness import blocks_upper_bound, books_equal, pool_for, replay_trace, to_dev, to_host
+from harness import blocks_upper_bound, books_equal, nested_wide_tree, pool_for, replay_trace, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -294,6 +294,50 @@ def test_wide_sharing_groups(dtype, n_q, n_kv, fan, chunk):
     for matrix_rows in ((0, 1, 64) if dtype == "bf16" else (None,)):
         err, info = run_workload(w, chunk=chunk, matrix_rows=matrix_rows)
         print(f"fan {fan}, matrix rows {matrix_rows}: {info.n_threads} threads, {info.n_partial_rows} partial rows, err {err:.2e}")
+
+
+@pytest.mark.parametrize("n_cand", [1, 5])
+def test_nested_wide_groups_inlined_stand_alone_and_matrix(n_cand):
+    """A root with children that have more leaves than one unit carries, plus 200 threads listed right
+    after their fork (they end at a shared segment): the plan inlines the short shared segments, or lets
+    them stand alone (row-tile or matrix units), or mixes both; every variant against the oracle."""
+    t = torch()
+    heads = HeadConfig(2, 2, 128, "bf16")
+    w = nested_wide_tree(heads, seed=9)
+    N = blocks_upper_bound(w) + 600
+    with pool_for(w, N) as pool:
+        poison(pool)
+        h = pool.handle
+        dense = DenseThreads(2, 2, 128)
+        live, _ = replay_trace(w, pool, None, dense)
+        kids = ap.apar_fork(h, live[0], 200)
+        assert dense.fork(live[0], 200) == kids
+        listed = live + kids
+        n = len(listed)
+        rng = np.random.default_rng(4)
+        q = quantise(0.5 * rng.standard_normal((n, n_cand, 2, 128)).astype(np.float32), "bf16")
+        ck = quantise(0.5 * rng.standard_normal((n, n_cand, 2, 128)).astype(np.float32), "bf16")
+        cv = quantise(0.5 * rng.standard_normal((n, n_cand, 2, 128)).astype(np.float32), "bf16")
+        masks = np.stack([mask_rows_from_parents(draw_candidate_tree(rng, n_cand)) for _ in range(n)])
+        want = dense.decode_spec(q, ck, cv, masks, listed) if n_cand > 1 else dense.decode(q[:, 0], listed)[:, None]
+        qd, ckd, cvd, md = to_dev(q, "bf16"), to_dev(ck, "bf16"), to_dev(cv, "bf16"), t.from_numpy(masks).cuda()
+        seen_partials = set()
+        for inline, matrix, chunk in ((True, (0, 0), 512), (False, (0, 0), 512), (True, (64, 8), 512), (True, (1, 1), 512),
+                                      (True, (64, 8), 4), (False, (1, 1), 3), (True, (64, 16), 512)):
+            ap.apar_set_inline_shared(h, inline)
+            ap.apar_set_matrix_units(h, *matrix)
+            ap.apar_set_chunk_blocks(h, chunk)
+            out = t.empty_like(qd)
+            if n_cand > 1:
+                ap.apar_decode_attention_spec(h, qd, ckd, cvd, md, n_cand, listed, out)
+            else:
+                ap.apar_decode_attention(h, qd[:, 0].contiguous(), listed, out[:, 0])
+            t.cuda.synchronize()
+            got = to_host(out)
+            err = np.abs(got - want).max()
+            assert np.isfinite(got).all() and err <= TOL["bf16"], f"inline {inline} matrix {matrix} chunk {chunk}: {err}"
+            seen_partials.add(ap.apar_last_plan_info(h).n_partial_rows)
+        assert 0 in seen_partials and len(seen_partials) >= 4  # the variants really are different plans
 
 
 @pytest.mark.parametrize("dtype,fan,C,matrix_rows", [("bf16", 1, 5, 64), ("bf16", 3, 5, 64), ("bf16", 6, 5, 64), ("bf16", 6, 5, 1),

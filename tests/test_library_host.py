@@ -10,7 +10,7 @@ import paper_2401_06761_amd as ap
 from apar_workloads import HeadConfig, make_config, manual_tree, tiny_tree
 from oracle import BlockLedger
 
-from harness import blocks_upper_bound, books_equal, check_plan_covers_tables, pool_for, replay_trace
+from harness import blocks_upper_bound, books_equal, check_plan_covers_tables, nested_wide_tree, pool_for, replay_trace
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -211,9 +211,11 @@ def test_wide_sharing_groups_use_more_row_tiles(n_q, n_kv, fan, n_cand):
     rpt = n_cand * n_q // n_kv
     with pool_for(w, N, dry_run=True) as pool:
         live, _ = replay_trace(w, pool, None, dry_run=True)
-        for chunk, matrix_rows in ((2, 64), (512, 64), (2, 0), (512, 0), (512, 1)):
+        for chunk, matrix_rows, inline in ((2, 64, True), (512, 64, True), (2, 0, True), (512, 0, True), (512, 1, True),
+                                           (2, 64, False), (512, 0, False), (512, 1, False)):
             ap.apar_set_chunk_blocks(pool.handle, chunk)
             ap.apar_set_matrix_units(pool.handle, matrix_rows, 1)
+            ap.apar_set_inline_shared(pool.handle, inline)
             if n_cand == 1:
                 ap.apar_decode_attention(pool.handle, None, live, None)
             else:
@@ -228,9 +230,50 @@ def test_wide_sharing_groups_use_more_row_tiles(n_q, n_kv, fan, n_cand):
                 want = 1 if groups <= 4 * cap else 2
                 assert res["partial_rows"] == 0 and len(wgs) == 1 and wgs[0][3] & 255 == want
             if groups > 8 * cap:
-                # the root stands alone: as matrix units (marked 32) when its holders bring enough rows
-                want = 32 if matrix_rows and len(live) * rpt >= matrix_rows else 2
-                assert res["partial_rows"] > 0 and wgs[0][3] & 255 == want
+                to_matrix = matrix_rows and len(live) * rpt >= matrix_rows
+                if inline and not to_matrix and chunk == 512:
+                    # the root (3 blocks) is inlined: read again by every unit below, nothing to merge
+                    assert res["partial_rows"] == 0 and res["direct_threads"] == len(live)
+                    assert res["unit_block_reads"] > res["unique_blocks"] and all(x & 255 in (1, 2) for x in wgs[:, 3])
+                else:
+                    # the root stands alone: as matrix units (marked 32) when its holders bring enough rows
+                    assert res["partial_rows"] > 0 and wgs[0][3] & 255 == (32 if to_matrix else 2)
+
+
+@pytest.mark.parametrize("n_cand", [1, 5])
+def test_nested_wide_groups_are_inlined_or_stand_alone(n_cand):
+    w = nested_wide_tree(HeadConfig(2, 2, 128, "bf16"))
+    N = blocks_upper_bound(w) + 600
+    with pool_for(w, N, dry_run=True) as pool:
+        h = pool.handle
+        live, _ = replay_trace(w, pool, None, dry_run=True)
+        # 200 threads forked off one leaf and listed before they get rows of their own: they all end at a
+        # segment that is shared by more rows than one unit carries
+        kids = ap.apar_fork(h, live[0], 200)
+        listed = live + kids
+
+        def plan():
+            if n_cand == 1:
+                ap.apar_decode_attention(h, None, listed, None)
+            else:
+                ap.apar_decode_attention_spec(h, None, None, None, None, n_cand, listed, None)
+            return check_plan_covers_tables(h, listed, 2, n_cand)
+
+        ap.apar_set_matrix_units(h, 0, 0)
+        res = plan()  # everything wide is short: inlined, nothing to merge
+        assert res["partial_rows"] == 0 and res["direct_threads"] == len(listed)
+        ap.apar_set_inline_shared(h, False)
+        off = plan()
+        assert off["partial_rows"] > 0 and off["unit_block_reads"] <= res["unit_block_reads"]
+        ap.apar_set_inline_shared(h, True)
+        # the 13-block child goes to the matrix kernel and stands alone below the inlined root
+        ap.apar_set_matrix_units(h, 64, 8)
+        res = plan()
+        assert 0 < res["partial_rows"] < off["partial_rows"]
+        # a unit cap too small for the root: it stands alone, and so does everything wide below it
+        ap.apar_set_chunk_blocks(h, 4)
+        res = plan()
+        assert res["partial_rows"] > 0
 
 
 def test_commit_candidates_books_and_errors():
