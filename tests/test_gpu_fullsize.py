@@ -95,3 +95,118 @@ def test_full_size_step_matches_oracle_on_sampled_threads(name, n_req, steps):
         print(f"{name}: {len(live)} threads, sampled {len(sample)}, max abs err {worst:.2e}")
     finally:
         run.close()
+
+
+def test_full_size_speculative_loop_on_sampled_threads():
+    """The 256-step multi-candidate loop on all 128 requests of spec128, as bench.py runs it (fixed candidate
+    bank, accepted rows committed from the candidate arrays): the ledger follows every operation; counters
+    and the tables of a fixed sample of threads are compared after every step, all tables and refcounts at
+    steps 0, 1, 2, 64, 128 and 255; at those steps the attention outputs of threads of four requests are
+    compared with the dense oracle, whose rows are gathered from the tensors handed to the library along the
+    history of each thread (tree nodes, accepted candidate rows, the row a forked child received)."""
+    import torch
+
+    from oracle import attend_spec
+    from paper_2401_06761_amd.driver import SpecRun
+
+    n_steps, C = 256, 5
+    check_steps = {0, 1, 2, 64, 128, 255}
+    w = make_config("spec128")
+    hd = w.heads
+    scale = 1.0 / np.sqrt(hd.head_dim)
+    run = SpecRun(w, n_steps, n_cand=C)
+    try:
+        run.build()
+        h = run.h
+        N = run.peak_blocks + 64
+        led = BlockLedger(N)
+        ops, live, live_nodes = build_trace(w)
+        for op in ops:
+            if op.kind == "create":
+                led.create()
+            elif op.kind == "append":
+                led.append(op.tid, op.n_tokens)
+            elif op.kind == "fork":
+                led.fork(op.tid, len(op.children))
+            else:
+                led.free(op.tid)
+        books_equal(h, led, check_blocks=range(0, N, 97))
+        tracked_requests = {0, 17, 64, 127}
+        hist = {t: [("node", a) for a in w.root_path(nd)] for t, nd in zip(live, live_nodes)
+                if w.nodes[nd].request in tracked_requests}
+        node_rows = {}
+
+        def rows_of(t, bank_k, bank_v, child_k, child_v):
+            ks, vs = [], []
+            for item in hist[t]:
+                if item[0] == "node":
+                    if item[1] not in node_rows:
+                        k, v = node_kv_device(w, item[1])
+                        node_rows[item[1]] = (k.float().cpu().numpy(), v.float().cpu().numpy())
+                    k, v = node_rows[item[1]]
+                elif item[0] == "cand":
+                    k = bank_k[item[1], item[2]][None].float().cpu().numpy()
+                    v = bank_v[item[1], item[2]][None].float().cpu().numpy()
+                else:
+                    k = child_k[item[1]][None].float().cpu().numpy()
+                    v = child_v[item[1]][None].float().cpu().numpy()
+                ks.append(k), vs.append(v)
+            return np.concatenate(ks).astype(np.float64), np.concatenate(vs).astype(np.float64)
+
+        rng = np.random.default_rng(1)
+        watch = [int(t) for t in rng.choice(live, size=24, replace=False)]  # tables checked after every step
+        worst, n_checked, peak = 0.0, 0, led.used_blocks()
+        bank_q, bank_k, bank_v = run.bank
+        child_k, child_v = run.child_bank
+        for s in range(n_steps):
+            st, q, ck, cv, out, kk, vv = run.step()
+            if s in check_steps:
+                torch.cuda.synchronize()
+                pos_of = {t: i for i, t in enumerate(st.live)}
+                mine = [t for t in st.live if t in hist]
+                pick = [int(t) for t in rng.choice(mine, size=min(10, len(mine)), replace=False)]
+                for t in pick:
+                    i = pos_of[t]
+                    K, V = rows_of(t, bank_k, bank_v, child_k, child_v)
+                    assert K.shape[0] == led.len[t]
+                    want = attend_spec(q[i].float().cpu().numpy().astype(np.float64), K, V,
+                                       ck[i].float().cpu().numpy().astype(np.float64),
+                                       cv[i].float().cpu().numpy().astype(np.float64), st.masks[i], scale)
+                    got = out[i].float().cpu().numpy().astype(np.float64)
+                    assert np.isfinite(got).all()
+                    worst = max(worst, float(np.abs(got - want).max()))
+                    n_checked += 1
+                assert worst <= 2e-2, f"step {s}: max abs err {worst}"
+            # the same bookkeeping on the oracle side
+            led.commit_candidates(st.live, st.accept_masks)
+            peak = max(peak, led.used_blocks())
+            for i, t in enumerate(st.live):
+                if t in hist:
+                    hist[t] += [("cand", i, c) for c in range(C) if st.accept_bits[i, c]]
+            for t in st.finished:
+                led.free(t)
+                hist.pop(t, None)
+            for m, (t, child) in enumerate(zip(st.forked, st.children)):
+                assert led.fork(t, 1) == [child]
+                if t in hist:
+                    hist[child] = hist[t] + [("child", m)]
+                if t in watch and len(watch) < 48:
+                    watch.append(child)
+            if st.children:
+                led.append_batch(st.children)
+            peak = max(peak, led.used_blocks())
+            stats = ap.apar_pool_stats(h)
+            assert stats.used_blocks == led.used_blocks() and stats.live_threads == len(run.live)
+            assert stats.cow_copies == led.cow_copies and stats.threads_issued == led.next_tid
+            watch = [t for t in watch if t in led.table]
+            for t in watch:
+                assert ap.apar_thread_len(h, t) == led.len[t] and ap.apar_thread_block_table(h, t) == led.table[t]
+            if s in check_steps:
+                books_equal(h, led, check_blocks=range(0, N, 97))
+                assert sorted(run.live) == led.live()
+        led.check_invariants()
+        assert peak == run.peak_blocks and n_checked >= 50
+        print(f"spec128 loop, 128 requests x {n_steps} steps: {len(run.live)} live threads at the end, "
+              f"{n_checked} sampled outputs, worst max abs err {worst:.2e}, peak {peak} blocks")
+    finally:
+        run.close()
