@@ -251,7 +251,9 @@ APAR_API int apar_last_plan_info(apar_pool* pool, apar_plan_info* out);
  * `slices` slices of at most 16 rows, and row group = rank * slices + slice.  `which`:
  *   APAR_PLAN_WORKGROUPS  32 ints per workgroup: [0] first shared tile, [1] shared tile count,
  *                         [2] row group the shared tiles' ranges are relative to, [3] bits 0-7: 16-row tiles per wavefront
- *                         (1 or 2; workgroups with 2 are stored first), bits 8-31: how many
+ *                         (1 or 2), or 32 for a matrix unit - a stand-alone chunk of a shared segment for up to 128
+ *                         rows of whole threads, all named by wavefront entry 0, the other entries empty -
+ *                         (workgroups are stored 32 first, then 2, then 1), bits 8-31: how many
  *                         of the shared tiles are full (every list holds its full tiles first), then
  *                         4 wavefronts x 6: first own tile, own tile count, first row group, row
  *                         group count, first partial-result row (of the thread owning the first
