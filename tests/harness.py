@@ -98,6 +98,20 @@ def nested_wide_tree(heads, seed=0):
     return manual_tree(parents, lens, heads, seed=seed, data_scale=0.5)
 
 
+def random_forest(rng, n_roots, max_nodes):
+    """Parents and segment lengths of a seeded random forest (deep and wide mixes, lengths around block boundaries)."""
+    parents, segs = [], []
+    for _ in range(n_roots):
+        parents.append(-1)
+        segs.append(int(rng.integers(1, 90)))
+    while len(parents) < max_nodes:
+        p = int(rng.integers(0, len(parents)))
+        for _ in range(int(rng.integers(1, 7))):
+            parents.append(p)
+            segs.append(int(rng.choice([1, 2, 15, 16, 17, 31, 33, int(rng.integers(1, 70))])))
+    return parents, segs
+
+
 def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per_thread: int = 1) -> Dict[str, int]:
     """The exported plan must read, on behalf of every row group of every listed thread, exactly the
     blocks of that thread's table (each once, with the right fill counts); a thread is either written

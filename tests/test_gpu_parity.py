@@ -11,7 +11,7 @@ from apar_workloads import (HeadConfig, make_config, manual_tree, mask_rows_from
                             node_kv, quantise, step_q, tiny_tree)
 from oracle import BlockLedger, DenseThreads
 
-from harness import blocks_upper_bound, books_equal, nested_wide_tree, pool_for, replay_trace, to_dev, to_host
+from harness import blocks_upper_bound, books_equal, nested_wide_tree, pool_for, random_forest, replay_trace, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -481,19 +481,6 @@ def test_append_kv_gather_takes_the_named_rows(dtype, d):
             assert np.array_equal(to_host(ko), K) and np.array_equal(to_host(vo), V)
 
 
-def _random_forest(rng, n_roots, max_nodes):
-    parents, segs = [], []
-    for _ in range(n_roots):
-        parents.append(-1)
-        segs.append(int(rng.integers(1, 90)))
-    while len(parents) < max_nodes:
-        p = int(rng.integers(0, len(parents)))
-        for _ in range(int(rng.integers(1, 7))):
-            parents.append(p)
-            segs.append(int(rng.choice([1, 2, 15, 16, 17, 31, 33, int(rng.integers(1, 70))])))
-    return parents, segs
-
-
 @pytest.mark.parametrize("seed", range(10))
 def test_random_forests_decode_spec_and_prefill(seed):
     """Seeded random forests (deep and wide mixes, segment lengths around the block boundaries), random head
@@ -504,7 +491,7 @@ def test_random_forests_decode_spec_and_prefill(seed):
     group = int(rng.choice([1, 2, 4, 8]))
     n_q = n_kv * group
     heads = HeadConfig(n_q, n_kv, 128, "bf16")
-    parents, segs = _random_forest(rng, int(rng.integers(1, 4)), int(rng.integers(8, 120)))
+    parents, segs = random_forest(rng, int(rng.integers(1, 4)), int(rng.integers(8, 120)))
     w = manual_tree(parents, segs, heads, seed=seed, data_scale=0.5)
     N = blocks_upper_bound(w)
     with pool_for(w, N) as pool:
@@ -514,6 +501,7 @@ def test_random_forests_decode_spec_and_prefill(seed):
             ap.apar_set_chunk_blocks(pool.handle, chunk)
         # stand-alone shared segments: never / always / by default on the 32x32 kernel
         ap.apar_set_matrix_units(pool.handle, int(rng.choice([0, 1, 64])), int(rng.choice([1, 2, 64])))
+        ap.apar_set_inline_shared(pool.handle, bool(rng.integers(0, 2)))
         led = BlockLedger(N)
         dense = DenseThreads(n_q, n_kv, 128)
         live, nodes = replay_trace(w, pool, led, dense)

@@ -10,7 +10,8 @@ import paper_2401_06761_amd as ap
 from apar_workloads import HeadConfig, make_config, manual_tree, tiny_tree
 from oracle import BlockLedger
 
-from harness import blocks_upper_bound, books_equal, check_plan_covers_tables, nested_wide_tree, pool_for, replay_trace
+from harness import (blocks_upper_bound, books_equal, check_plan_covers_tables, nested_wide_tree, pool_for, random_forest,
+                     replay_trace)
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -274,6 +275,38 @@ def test_nested_wide_groups_are_inlined_or_stand_alone(n_cand):
         ap.apar_set_chunk_blocks(h, 4)
         res = plan()
         assert res["partial_rows"] > 0
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_forest_plans_cover_every_table(seed):
+    """Planner fuzz on bookkeeping-only pools: random forests, head grouping, candidates, unit caps and policy
+    knobs; every plan must show every row group exactly its thread's blocks, once."""
+    rng = np.random.default_rng(5000 + seed)
+    n_kv = int(rng.choice([1, 2]))
+    group = int(rng.choice([1, 2, 4, 8, 16]))
+    parents, segs = random_forest(rng, int(rng.integers(1, 4)), int(rng.integers(8, 260)))
+    w = manual_tree(parents, segs, HeadConfig(n_kv * group, n_kv, 128, "bf16"), seed=seed)
+    N = blocks_upper_bound(w) + 64
+    with pool_for(w, N, dry_run=True) as pool:
+        h = pool.handle
+        live, _ = replay_trace(w, pool, None, dry_run=True)
+        # some threads forked and listed before they get rows of their own
+        extra = []
+        for t in rng.choice(live, size=min(3, len(live)), replace=False):
+            extra += ap.apar_fork(h, int(t), int(rng.integers(1, 40)))
+        listed = [int(x) for x in rng.permutation(live + extra)]
+        for _ in range(3):
+            ap.apar_set_chunk_blocks(h, int(rng.choice([1, 2, 5, 16, 512])))
+            ap.apar_set_matrix_units(h, int(rng.choice([0, 1, 64])), int(rng.choice([1, 3, 128])))
+            ap.apar_set_inline_shared(h, bool(rng.integers(0, 2)))
+            C = int(rng.choice([1, 1, 2, 4]))
+            if C * group > 64:
+                C = 1
+            if C == 1 and rng.integers(0, 2):
+                ap.apar_decode_attention(h, None, listed, None)
+            else:
+                ap.apar_decode_attention_spec(h, None, None, None, None, C, listed, None)
+            check_plan_covers_tables(h, listed, n_kv, C * group)
 
 
 def test_commit_candidates_books_and_errors():
