@@ -102,7 +102,7 @@ struct PlanDev {              // device pointers of one staged plan
     const int32_t* path_ofs;     // [n_threads + 1], by listed index
     const int32_t* path_ids;     // partial-result rows to merge for each listed thread (none: written directly)
     int32_t n_wg;
-    int32_t n_wg_class[3];       // workgroups with 4, 2 and 1 row tiles per wavefront, stored in that order
+    int32_t n_wg_class[3];       // matrix units, workgroups with 2 and with 1 row tiles per wavefront, stored in that order
     int32_t n_threads;
     int32_t rows_per_thread, rows_per_slice, n_slices;
 };

@@ -17,7 +17,7 @@ struct PlanThreadView {  // what the planner needs to know about one listed thre
 
 struct PlanHost {
     // device-format tables
-    std::vector<WgDesc> wgs;            // by row tiles per wavefront (4, 2, 1), heaviest first within a class
+    std::vector<WgDesc> wgs;            // by class (matrix units, then 2 and 1 row tiles per wavefront), heaviest first within a class
     int32_t n_wg_class[3] = {0, 0, 0};
     std::vector<TileRef> tiles;
     std::vector<int32_t> dfs_threads;   // listed-thread indices in depth-first order of the sharing tree
@@ -60,7 +60,6 @@ struct PlanHost {
 
 struct PlanParams {
     int32_t rows_per_thread;  // candidates * q heads per kv head
-    int32_t chunk_blocks;     // blocks per stand-alone unit (lower bound)
     int32_t max_unit_tiles;   // longest tile list one wavefront may be given
     bool allow_direct;        // threads whose whole path is one unit may write their output directly
     bool fuse;                // build tree-fused units (false: every segment stands alone)
@@ -79,7 +78,7 @@ struct PrefillThreadView {  // one listed thread of a prefill call
 };
 
 // Plan of a prefill call: the query tokens take the place of the listed threads of a decode plan (row
-// group = query token, numbered across the call), a workgroup holds up to 256 / group consecutive tokens
+// group = query token, numbered across the call), a workgroup holds up to 128 / group consecutive tokens
 // of one thread, the tiles below its first token go on its shared list and the tiles on the diagonal
 // on the wavefronts' own lists, marked causal.  group = q heads per kv head, a divisor of 16.
 int build_prefill_plan(const PrefillThreadView* threads, int n, int group, PlanHost& ph);
