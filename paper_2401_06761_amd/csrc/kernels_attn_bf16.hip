@@ -291,12 +291,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         const int shift = wi.grp_lo - wg->grp_base;  // shared ranges are relative to the group's base
         const int n_coop_full = wg->row_tiles >> 8;
         u32x4 rk[4], rv[4];
+        // Shared tiles are fetched with plain loads, private ones (below) with non-temporal loads: a shared
+        // tile may be read again by another workgroup (the units below an inlined segment all read it; so do
+        // the stand-alone units of a segment with many rows) and is worth a place in L2, a private tile is
+        // read exactly once.  Measured: plain loads here take 6-10 % off the HBM traffic of the speculative
+        // loop and 2 % off the headline launch; plain loads for the private tiles cost 8 %.
         auto fetch_full = [&](int t) {
             const char* tile = head_base + coop[t].blk * block_stride + lane * 16;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                rk[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + r * 1024));
-                rv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + r * 1024));
+                rk[r] = *reinterpret_cast<const u32x4*>(tile + r * 1024);
+                rv[r] = *reinterpret_cast<const u32x4*>(tile + 4096 + r * 1024);
             }
         };
         auto fetch_any = [&](int t) {
@@ -312,8 +317,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int row = 4 * r + g4 < fill ? 4 * r + g4 : 0;
-                    rk[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + row * 256));
-                    rv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 4096 + row * 256));
+                    rk[r] = *reinterpret_cast<const u32x4*>(tile + row * 256);
+                    rv[r] = *reinterpret_cast<const u32x4*>(tile + 4096 + row * 256);
                 }
             }
         };

@@ -159,6 +159,7 @@ struct Builder {
                     wi.wg.w[0] = WaveItem{0, 0, wi.wg.grp_base, nt * n_sl, pbase + t0, 0};
                     for (int k = 1; k < 4; ++k) wi.wg.w[k] = WaveItem{0, 0, 0, 0, -1, 0};
                     wi.cost = wi.wg.n_coop;
+                    wi.family = -1;
                     ph.wide_items.push_back(wi);
                 }
             } else {
@@ -178,6 +179,7 @@ struct Builder {
                         wi.wg.w[k] = WaveItem{0, 0, grp0 + g0 + lo, cnt, pbase + (g0 + lo) / n_sl, 0};
                     }
                     wi.cost = 2 * wi.wg.n_coop * nt;
+                    wi.family = -1;
                     ph.wide_items.push_back(wi);
                 }
             }
@@ -344,6 +346,8 @@ struct Builder {
             longest = std::max(longest, (int)cnt);
         }
         wi.cost = nt * (2 * wi.wg.n_coop + longest);
+        wi.family = -1;
+        for (int32_t a = u.anc; a >= 0; a = ph.segs[a].parent) wi.family = a;
         ph.wide_items.push_back(wi);
         return pbase;
     }
@@ -591,11 +595,22 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         }
     }
 
-    // 7. workgroups: matrix units, then by row tiles per wavefront (2, 1), heaviest first within a class
+    // 7. workgroups: matrix units, then by row tiles per wavefront (2, 1); within a class the heaviest first,
+    // but the units that read one inlined chain stay together (ordered among the others by their heaviest)
+    {
+        std::vector<int32_t>& fam = ph.order;  // per segment: cost of the heaviest unit of the family it roots
+        fam.assign(n_seg, 0);
+        for (const PlanHost::WideItem& w : ph.wide_items)
+            if (w.family >= 0) fam[w.family] = std::max(fam[w.family], w.cost);
+        for (PlanHost::WideItem& w : ph.wide_items) w.family_cost = w.family >= 0 ? fam[w.family] : w.cost;
+    }
     std::stable_sort(ph.wide_items.begin(), ph.wide_items.end(),
                      [](const PlanHost::WideItem& a, const PlanHost::WideItem& b) {
                          const int ta = a.wg.row_tiles & 255, tb = b.wg.row_tiles & 255;
-                         return ta != tb ? ta > tb : a.cost > b.cost;
+                         if (ta != tb) return ta > tb;
+                         if (a.family_cost != b.family_cost) return a.family_cost > b.family_cost;
+                         if (a.family != b.family) return a.family > b.family;
+                         return a.cost > b.cost;
                      });
     ph.wgs.reserve(ph.wide_items.size() + (ph.narrow_items.size() + 3) / 4);
     ph.n_wg_class[0] = ph.n_wg_class[1] = ph.n_wg_class[2] = 0;

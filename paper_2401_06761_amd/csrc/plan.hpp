@@ -52,6 +52,9 @@ struct PlanHost {
     struct WideItem {
         WgDesc wg;
         int32_t cost;
+        int32_t family;      // forest root of the inlined chain the unit reads (-1: none): units of one family are
+                             // launched next to each other, so that the chain is found in L2 when it is read again
+        int32_t family_cost; // cost of the family's heaviest unit (its own cost if it has no family)
     };
     std::vector<WideItem> wide_items;
 
