@@ -245,7 +245,7 @@ def shared_prefix_bench(args) -> int:
         q, out = run.banks[0][0], run.out
         res = {}
         for name, inline, knob in (("inlined", True, (0, 1)), ("stand_alone_row_tile_units", False, (0, 1)),
-                                   ("stand_alone_matrix_units", False, (1, 1)), ("default", True, (64, 128))):
+                                   ("stand_alone_matrix_units", False, (1, 1)), ("default", True, (256, 128))):
             ap.apar_set_inline_shared(run.h, inline)
             ap.apar_set_matrix_units(run.h, *knob)
             for _ in range(args.warmup):
@@ -358,7 +358,7 @@ def main() -> int:
     ap_.add_argument("--prefill-kernel", choices=("auto", "row_tiles", "matrix"), default="auto",
                      help="with --prefill: let the library choose the kernel per call, or force one")
     ap_.add_argument("--matrix-units", default=None, metavar="ROWS,BLOCKS",
-                     help="thresholds from which a stand-alone shared segment runs on the 32x32 kernel (library default 64,128; 0,0 never)")
+                     help="thresholds from which a stand-alone shared segment runs on the 32x32 kernel (library default 256,128; 0,0 never)")
     ap_.add_argument("--shared-prefix", action="store_true",
                      help="measure decode attention over long prefixes shared by 512 threads, row-tile vs matrix units")
     ap_.add_argument("--prefill", action="store_true",

@@ -409,7 +409,7 @@ APAR_API int apar_profile_attention_calls(apar_pool* pool, float* ms_out, int64_
 APAR_API int apar_set_chunk_blocks(apar_pool* pool, int blocks_per_unit);
 /* Tuning knob (bf16 pools): a shared segment that stands alone as a unit - its holders have more query rows
  * than one fused workgroup carries (128) - goes to the 32x32 matrix-core kernel, up to 128 rows per workgroup,
- * when its holders bring at least min_rows query rows (candidates x q heads per kv head x threads; default 64)
+ * when its holders bring at least min_rows query rows (candidates x q heads per kv head x threads; default 256)
  * and it has at least min_blocks blocks (default 128; shorter ones are cheaper inlined, see apar_set_inline_shared).
  * Matrix units are launched ahead of the other units of a call, not beside them.  min_rows = 0 keeps every unit on the row-tile kernel; (1, 1) sends every such segment
  * to the matrix kernel.  Results agree to rounding.  fp32 pools ignore the knob. */

@@ -74,7 +74,7 @@ struct apar_pool {
     int max_unit_tiles = 512;  // longest tile list given to one wavefront
     int prefill_kernel = APAR_PREFILL_AUTO;
     // stand-alone segments with at least this many query rows and blocks run as matrix units (bf16 pools)
-    int matrix_min_rows = 64, matrix_min_blocks = 128;
+    int matrix_min_rows = 256, matrix_min_blocks = 128;
     bool inline_shared = true;  // short shared segments with too many rows below: read again per unit instead of partial results
     int last_prefill_kernel = 0;  // which kernel the most recent prefill call ran (APAR_PREFILL_ROW_TILES / _MATRIX)
     std::vector<PlanThreadView> views;
