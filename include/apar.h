@@ -424,7 +424,7 @@ APAR_API int apar_set_inline_shared(apar_pool* pool, int on);
  * under a prefill plan (16-row tiles; a prefix shared by sibling threads is read once for all of them),
  * MATRIX the 32x32 matrix-core kernel (one workgroup per thread and chunk of 128 query rows; needs a
  * group size that divides 16, otherwise the call stays on ROW_TILES).  AUTO (default) takes MATRIX when
- * a query token attends to 768 rows or more on average.  Both give the same result to rounding.
+ * a query token attends to 1024 rows or more on average.  Both give the same result to rounding.
  * fp32 pools ignore the knob.  apar_last_prefill_kernel tells which one the most recent call ran (0: none). */
 enum { APAR_PREFILL_AUTO = 0, APAR_PREFILL_ROW_TILES = 1, APAR_PREFILL_MATRIX = 2 };
 APAR_API int apar_set_prefill_kernel(apar_pool* pool, int which);

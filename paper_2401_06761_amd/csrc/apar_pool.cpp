@@ -357,7 +357,7 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
 }
 
 // Mean attended rows per query token from which a bf16 prefill call goes to the 32x32 kernel by itself.
-constexpr int64_t kMatrixPrefillMeanWalk = 768;
+constexpr int64_t kMatrixPrefillMeanWalk = 1024;
 
 // bf16 pools: the matrix-core prefill kernel.  One workgroup per (thread, chunk of 128 / group query tokens);
 // the threads' block tables are staged next to the workgroup descriptors.
