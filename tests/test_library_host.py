@@ -309,6 +309,33 @@ def test_random_forest_plans_cover_every_table(seed):
             check_plan_covers_tables(h, listed, n_kv, C * group)
 
 
+def test_plan_builder_under_sanitizers(tmp_path):
+    """The plan builder compiled as plain host C++ with the address and undefined-behaviour sanitizers and
+    fuzzed over random forests, geometries and policy knobs (tests/native/fuzz_plan.cpp checks coverage too)."""
+    import shutil
+    import subprocess
+
+    cxx = shutil.which("g++")
+    if cxx is None:
+        pytest.skip("no g++")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "fuzz_plan")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-I" + os.path.join(root, "include"),
+           "-I" + os.path.join(root, "paper_2401_06761_amd", "csrc"),
+           os.path.join(root, "tests", "native", "fuzz_plan.cpp"),
+           os.path.join(root, "paper_2401_06761_amd", "csrc", "plan.cpp"), "-o", exe]
+    built = subprocess.run(cmd, capture_output=True, text=True)
+    if built.returncode != 0 and "sanitize" in built.stderr:
+        pytest.skip("this g++ has no sanitizer runtime")
+    assert built.returncode == 0, built.stderr[-2000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
+    ran = subprocess.run([exe, "0", "60"], capture_output=True, text=True, env=env, timeout=600)
+    if "ASan runtime does not come first" in ran.stderr:
+        pytest.skip("a preloaded library keeps the sanitizer runtime from starting here")
+    assert ran.returncode == 0 and "ok: 60 forests" in ran.stdout, (ran.stdout + ran.stderr)[-3000:]
+
+
 def test_commit_candidates_books_and_errors():
     # dry-run pools: the commit leaves the same books as one batched append per accepted candidate
     heads = HeadConfig(4, 2, 64, "f32")
