@@ -309,9 +309,9 @@ def test_random_forest_plans_cover_every_table(seed):
             check_plan_covers_tables(h, listed, n_kv, C * group)
 
 
-def test_plan_builder_under_sanitizers(tmp_path):
-    """The plan builder compiled as plain host C++ with the address and undefined-behaviour sanitizers and
-    fuzzed over random forests, geometries and policy knobs (tests/native/fuzz_plan.cpp checks coverage too)."""
+def _sanitizer_build(tmp_path, name, sources, extra=()):
+    """Compiles tests/native/<name>.cpp with the given library sources as plain host C++ under the address and
+    undefined-behaviour sanitizers; returns the executable, or skips when the toolchain cannot."""
     import shutil
     import subprocess
 
@@ -319,21 +319,45 @@ def test_plan_builder_under_sanitizers(tmp_path):
     if cxx is None:
         pytest.skip("no g++")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    exe = str(tmp_path / "fuzz_plan")
+    csrc = os.path.join(root, "paper_2401_06761_amd", "csrc")
+    exe = str(tmp_path / name)
     cmd = [cxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
-           "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-I" + os.path.join(root, "include"),
-           "-I" + os.path.join(root, "paper_2401_06761_amd", "csrc"),
-           os.path.join(root, "tests", "native", "fuzz_plan.cpp"),
-           os.path.join(root, "paper_2401_06761_amd", "csrc", "plan.cpp"), "-o", exe]
+           "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-I" + os.path.join(root, "include"), "-I" + csrc,
+           os.path.join(root, "tests", "native", name + ".cpp")] + [os.path.join(csrc, f) for f in sources] + \
+          list(extra) + ["-o", exe]
     built = subprocess.run(cmd, capture_output=True, text=True)
     if built.returncode != 0 and "sanitize" in built.stderr:
         pytest.skip("this g++ has no sanitizer runtime")
     assert built.returncode == 0, built.stderr[-2000:]
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
-    ran = subprocess.run([exe, "0", "60"], capture_output=True, text=True, env=env, timeout=600)
+    return exe
+
+
+def _run_sanitized(exe, count, what):
+    import subprocess
+
+    ran = subprocess.run([exe, "0", str(count)], capture_output=True, text=True, timeout=900)
     if "ASan runtime does not come first" in ran.stderr:
         pytest.skip("a preloaded library keeps the sanitizer runtime from starting here")
-    assert ran.returncode == 0 and "ok: 60 forests" in ran.stdout, (ran.stdout + ran.stderr)[-3000:]
+    assert ran.returncode == 0 and f"ok: {count} {what}" in ran.stdout, (ran.stdout + ran.stderr)[-3000:]
+
+
+def test_plan_builder_under_sanitizers(tmp_path):
+    """The plan builder compiled as plain host C++ with the address and undefined-behaviour sanitizers and
+    fuzzed over random forests, geometries and policy knobs (tests/native/fuzz_plan.cpp checks coverage too)."""
+    exe = _sanitizer_build(tmp_path, "fuzz_plan", ["plan.cpp"])
+    _run_sanitized(exe, 60, "forests")
+
+
+def test_pool_controller_and_server_under_sanitizers(tmp_path):
+    """The library's host side (allocator, copy-on-write, commits, plans, Algorithm 1 controller, serving loop)
+    on bookkeeping-only pools, under the sanitizers (leak detection included), driven by random operation
+    sequences on pools small enough to run out of blocks (tests/native/fuzz_pool.cpp; the kernels' launchers
+    are stubs there)."""
+    if not os.path.exists("/opt/rocm/lib/libamdhip64.so"):
+        pytest.skip("no HIP runtime to link the host side against")
+    exe = _sanitizer_build(tmp_path, "fuzz_pool", ["plan.cpp", "apar_pool.cpp", "controller.cpp"],
+                           extra=["-L/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib"])
+    _run_sanitized(exe, 30, "sequences")
 
 
 def test_commit_candidates_books_and_errors():
