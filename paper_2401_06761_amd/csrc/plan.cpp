@@ -553,7 +553,7 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         // rows are better off alone on the matrix kernel.
         const bool to_matrix = prm.matrix_min_rows > 0 && (int64_t)s.n_shr * prm.rows_per_thread >= prm.matrix_min_rows &&
                                s.n_blk >= prm.matrix_min_blocks;
-        if (prm.fuse && prm.inline_shared && s.n_above == 0 && !to_matrix && groups > 4 * kMaxRowTiles * cap &&
+        if (prm.fuse && prm.inline_shared && prm.allow_direct && s.n_above == 0 && !to_matrix && groups > 4 * kMaxRowTiles * cap &&
             2 * (above + s.n_blk) <= prm.max_unit_tiles) {
             s.inlined = 1;
             bld.inline_blocks[m] = (int32_t)(above + s.n_blk);

@@ -85,7 +85,7 @@ static int one(int seed) {
         prm.rows_per_thread = rpts[rng() % 9];
         const int caps[] = {1, 2, 5, 16, 64, 512};
         prm.max_unit_tiles = caps[rng() % 6];
-        prm.allow_direct = true;
+        prm.allow_direct = rng() % 8 != 0;
         prm.fuse = rng() % 8 != 0;
         prm.inline_shared = rng() % 2;
         const int mrows[] = {0, 1, 64, 256};
