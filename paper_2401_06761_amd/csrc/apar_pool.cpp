@@ -43,7 +43,8 @@ struct StageSlot {
     char* host = nullptr;
     char* dev = nullptr;
     size_t cap = 0;
-    hipEvent_t ev = nullptr;
+    hipEvent_t ev = nullptr;   // recorded after the kernels that read the slot
+    hipEvent_t up = nullptr;   // recorded after the slot's upload
     bool pending = false;
 };
 constexpr int kStageSlots = 4;
@@ -92,6 +93,7 @@ struct apar_pool {
     PartialBuf part{};
     size_t part_slots_cap = 0;
     ClassStreams class_streams;
+    hipStream_t copy_stream = nullptr;  // uploads of plans and row codes run here, beside the caller's stream
 
     bool profiling = false;
     std::vector<EventPair> decode_events, append_events;
@@ -151,6 +153,19 @@ int acquire_stage(apar_pool* p, size_t bytes, StageSlot** out) {
     return APAR_OK;
 }
 
+// Uploads the first `bytes` of a staging slot on the pool's own copy stream and makes the caller's stream wait
+// for it: the copy then runs beside whatever the caller's stream is still busy with (the previous step's
+// attention, typically) instead of queueing behind it.  The slot is free by construction: acquire_stage waited
+// for the kernels that last read it.
+int upload(apar_pool* p, StageSlot* s, size_t bytes, hipStream_t st) {
+    if (!p->copy_stream) HIP_TRY(hipStreamCreateWithFlags(&p->copy_stream, hipStreamNonBlocking));
+    if (!s->up) HIP_TRY(hipEventCreateWithFlags(&s->up, hipEventDisableTiming));
+    HIP_TRY(hipMemcpyAsync(s->dev, s->host, bytes, hipMemcpyHostToDevice, p->copy_stream));
+    HIP_TRY(hipEventRecord(s->up, p->copy_stream));
+    HIP_TRY(hipStreamWaitEvent(st, s->up, 0));
+    return APAR_OK;
+}
+
 int new_event(apar_pool* p, hipEvent_t* ev) {
     if (!p->spare_events.empty()) {
         *ev = p->spare_events.back();
@@ -205,7 +220,7 @@ int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vecto
     memcpy(s->host + copy_bytes, codes.data(), codes.size() * sizeof(int32_t));
     if (!seals.empty()) memcpy(s->host + copy_bytes + code_bytes, seals.data(), seals.size() * sizeof(int32_t));
     if (src_bytes) memcpy(s->host + copy_bytes + code_bytes + seal_bytes, src_rows->data(), src_bytes);
-    HIP_TRY(hipMemcpyAsync(s->dev, s->host, total, hipMemcpyHostToDevice, st));
+    if ((rc = upload(p, s, total, st)) != APAR_OK) return rc;
     EventPair ev;
     if (p->profiling) {
         if ((rc = new_event(p, &ev.a)) != APAR_OK || (rc = new_event(p, &ev.b)) != APAR_OK) return rc;
@@ -316,7 +331,7 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
         p->part_slots_cap = cap;
     }
 
-    HIP_TRY(hipMemcpyAsync(s->dev, s->host, ofs[5], hipMemcpyHostToDevice, st));
+    if ((rc = upload(p, s, ofs[5], st)) != APAR_OK) return rc;
     PlanDev pd;
     pd.wgs = (const WgDesc*)(s->dev + ofs[0]);
     pd.tiles = (const TileRef*)(s->dev + ofs[1]);
@@ -420,7 +435,7 @@ int prefill_bf16(apar_pool* p, const std::vector<PrefillThreadView>& views, int6
     if (rc != APAR_OK) return rc;
     memcpy(s->host, wgs.data(), wgs.size() * sizeof(PrefillWg));
     memcpy(s->host + wg_bytes, tables.data(), table_bytes);
-    HIP_TRY(hipMemcpyAsync(s->dev, s->host, wg_bytes + table_bytes, hipMemcpyHostToDevice, st));
+    if ((rc = upload(p, s, wg_bytes + table_bytes, st)) != APAR_OK) return rc;
     EventPair ev;
     if (p->profiling) {
         if ((rc = new_event(p, &ev.a)) != APAR_OK || (rc = new_event(p, &ev.b)) != APAR_OK ||
@@ -496,7 +511,7 @@ int prefill_common(apar_pool* p, const void* q, const apar_thread* ids, const in
     if ((rc = acquire_stage(p, wg_bytes + tile_bytes, &s)) != APAR_OK) return rc;
     memcpy(s->host, ph.wgs.data(), ph.wgs.size() * sizeof(WgDesc));
     if (tile_bytes) memcpy(s->host + wg_bytes, ph.tiles.data(), tile_bytes);
-    HIP_TRY(hipMemcpyAsync(s->dev, s->host, wg_bytes + tile_bytes, hipMemcpyHostToDevice, st));
+    if ((rc = upload(p, s, wg_bytes + tile_bytes, st)) != APAR_OK) return rc;
     PlanDev pd{};
     pd.wgs = (const WgDesc*)s->dev;
     pd.tiles = (const TileRef*)(s->dev + wg_bytes);
@@ -600,7 +615,9 @@ int apar_pool_destroy(apar_pool* p) {
         if (s.host) (void)hipHostFree(s.host);
         if (s.dev) (void)hipFree(s.dev);
         if (s.ev) (void)hipEventDestroy(s.ev);
+        if (s.up) (void)hipEventDestroy(s.up);
     }
+    if (p->copy_stream) (void)hipStreamDestroy(p->copy_stream);
     if (p->part.o) (void)hipFree(p->part.o);
     if (p->part.ml) (void)hipFree(p->part.ml);
     auto drop = [](hipEvent_t e) {
@@ -879,7 +896,7 @@ int apar_read_kv_rows(apar_pool* p, apar_thread thread, int64_t first, int n, vo
         const bool sealed = p->shape.dtype == APAR_BF16 && (pos / kBlockTokens + 1) * kBlockTokens <= t->len;
         codes[i] = slot_code(*t, pos) | (sealed ? kCodeSealed : 0);
     }
-    HIP_TRY(hipMemcpyAsync(s->dev, s->host, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    if ((rc = upload(p, s, (size_t)n * sizeof(int32_t), st)) != APAR_OK) return rc;
     HIP_TRY(launch_read_rows(p->shape, p->kv, (const int32_t*)s->dev, n, k_out_dev, v_out_dev, st));
     HIP_TRY(hipEventRecord(s->ev, st));
     s->pending = true;
