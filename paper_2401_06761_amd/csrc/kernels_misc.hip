@@ -24,20 +24,23 @@ __device__ __forceinline__ float wave_sum(float x) {
 }
 
 // ---------------------------------------------------------------------------
-// Row writes.  One wavefront per (row, kv head).  Row i of the call is taken from
-// row src_rows[i] of k and v (from row i when src_rows is null).
+// Row writes.  Row i of the call is taken from row src_rows[i] of k and v (from row
+// i when src_rows is null).  bf16: 32 lanes per (row, kv head), eight pairs per
+// workgroup; fp32: one wavefront per pair.
 // bf16 pools keep a block that is still filling in plain row-major form (K rows
 // then V rows, 256 contiguous bytes each), so an appended row is two full-line
 // writes per half; seal_blocks_bf16 rewrites a block into matrix-core order once
 // its sixteenth slot is written.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void append_rows_bf16(char* __restrict__ pool, const uint16_t* __restrict__ k,
-                                                       const uint16_t* __restrict__ v,
-                                                       const int32_t* __restrict__ codes,
-                                                       const int32_t* __restrict__ src_rows, int n_kv,
-                                                       int64_t tile_bytes) {
-    const int row = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
-    if (lane >= 32) return;
+__global__ __launch_bounds__(256) void append_rows_bf16(char* __restrict__ pool, const uint16_t* __restrict__ k,
+                                                        const uint16_t* __restrict__ v,
+                                                        const int32_t* __restrict__ codes,
+                                                        const int32_t* __restrict__ src_rows, int n_rows, int n_kv,
+                                                        int64_t tile_bytes) {
+    const int64_t pair = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);  // (row, kv head), heads fastest
+    const int lane = threadIdx.x & 31;
+    if (pair >= (int64_t)n_rows * n_kv) return;
+    const int row = (int)(pair / n_kv), h = (int)(pair - (int64_t)row * n_kv);
     const int32_t code = codes[row];
     const int slot = code & 15;
     char* tile = pool + ((int64_t)(code >> 4) * n_kv + h) * tile_bytes;
@@ -371,9 +374,10 @@ hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const v
         const int64_t row_elems = src_rows ? 0 : (int64_t)s.n_kv * s.d;
         const int32_t* from = src_rows ? src_rows + r0 : nullptr;
         if (s.dtype == APAR_BF16) {
-            hipLaunchKernelGGL(append_rows_bf16, grid, dim3(64), 0, st, (char*)pool,
+            const unsigned n_wg = (unsigned)(((int64_t)nr * s.n_kv + 7) / 8);
+            hipLaunchKernelGGL(append_rows_bf16, dim3(n_wg), dim3(256), 0, st, (char*)pool,
                                (const uint16_t*)k + r0 * row_elems, (const uint16_t*)v + r0 * row_elems,
-                               dst_codes + r0, from, s.n_kv, s.tile_bytes);
+                               dst_codes + r0, from, nr, s.n_kv, s.tile_bytes);
         } else {
             hipLaunchKernelGGL(append_rows_f32, grid, dim3(64), 0, st, (char*)pool, (const float*)k + r0 * row_elems,
                                (const float*)v + r0 * row_elems, dst_codes + r0, from, s.n_kv, s.d, s.tile_bytes);
