@@ -135,7 +135,7 @@ def spec_loop(args, w) -> int:
         "candidate_queries_per_s": 5 * n_q / elapsed,
         "roofline": {"bound": "hbm", "kernel": "attention_bf16 (multi-candidate call)",
                      "achieved": (alg / K) / (attn_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": (alg / K) / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "frac": (alg / K) / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": read_traffic("spec128"),
                      "algorithmic_bytes_per_launch": alg / K, "kernel_ms_per_launch": attn_ms},
         "breakdown_ms_per_step": {"attention_kernel": attn_ms, "merge_kernel": prof.merge_kernel_ms / K,
                                   "append_kernels": prof.append_kernels_ms / K, "plan_host": prof.plan_host_ms / K,
