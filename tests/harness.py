@@ -39,8 +39,9 @@ def books_equal(handle, led: BlockLedger, check_blocks: Optional[Sequence[int]] 
 
 
 def replay_trace(w, pool: "ap.Pool", led: Optional[BlockLedger] = None, dense: Optional[DenseThreads] = None,
-                 dry_run: bool = False, dense_nodes: Optional[set] = None, check_each: bool = False):
+                 dry_run: bool = False, dense_nodes: Optional[set] = None, check_each: bool = False, kv_of=node_kv):
     """Runs build_trace(w) on the library and, if given, on the ledger and the dense oracle.
+    kv_of(w, node) gives the K and V rows of a node's segment (the seeded recipe unless a test brings its own).
     Returns (live thread ids ascending, their node indices)."""
     ops, live, live_nodes = build_trace(w)
     h = pool.handle
@@ -55,7 +56,7 @@ def replay_trace(w, pool: "ap.Pool", led: Optional[BlockLedger] = None, dense: O
             if dry_run:
                 ap.apar_append_kv(h, op.tid, None, None, op.n_tokens)
             else:
-                k, v = node_kv(w, op.node)
+                k, v = kv_of(w, op.node)
                 ap.apar_append_kv(h, op.tid, to_dev(k, w.heads.dtype), to_dev(v, w.heads.dtype), op.n_tokens)
                 if dense is not None:
                     dense.append(op.tid, k, v)

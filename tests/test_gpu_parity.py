@@ -340,6 +340,93 @@ def test_nested_wide_groups_inlined_stand_alone_and_matrix(n_cand):
         assert 0 in seen_partials and len(seen_partials) >= 4  # the variants really are different plans
 
 
+def _drift_direction(d):
+    # 64 entries of +-1/8 (exact in bf16), norm 1
+    u = np.zeros(d, dtype=np.float32)
+    u[::2] = 0.125 * np.where(np.arange(d // 2) % 3 == 0, -1.0, 1.0)
+    return u
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("mode", ["rising", "falling", "spread"])
+def test_logits_far_from_the_running_reference(dtype, mode):
+    """Softmax under stress.  rising: a token's logit grows by one bit per position, so every block of a
+    path lifts the running maximum by sixteen bits (each unit rescales what it has summed at every tile, the
+    partial results of a shared segment weigh nothing against the private ones).  falling: the mirror image
+    (everything after a thread's first block underflows to probability zero, the shared root decides).
+    spread: logits with a standard deviation of eleven bits.  Decode, multi-candidate and prefill calls, in
+    every plan variant, against the oracle.
+
+    fp32 pools are held to 1e-3 here rather than 1e-5: a dot product of magnitude 2600 carries an fp32
+    rounding error of some 2e-3, i.e. 2e-4 in the logit and as much, relative, in a probability."""
+    t = torch()
+    tol = TOL["bf16"] if dtype == "bf16" else 1e-3
+    heads = HeadConfig(2, 2, 128, dtype)
+    w = nested_wide_tree(heads, seed=12)
+    u = _drift_direction(128)
+    slope = {"rising": 0.5, "falling": -0.5, "spread": 0.0}[mode]
+
+    def kv_of(w_, node):
+        k, v = node_kv(w_, node)
+        start = w_.path_len(node) - w_.nodes[node].seg_len
+        drift = slope * (start + np.arange(w_.nodes[node].seg_len, dtype=np.float32))
+        return quantise(k + drift[:, None, None] * u, dtype), v
+
+    def queries(rng, shape):
+        noise = 0.5 * rng.standard_normal(shape).astype(np.float32)
+        return quantise(32.0 * noise if mode == "spread" else 16.0 * u + noise, dtype)
+
+    N = blocks_upper_bound(w) + 300
+    with pool_for(w, N) as pool:
+        poison(pool)
+        h = pool.handle
+        dense = DenseThreads(2, 2, 128)
+        live, nodes = replay_trace(w, pool, None, dense, kv_of=kv_of)
+        kids = ap.apar_fork(h, live[0], 100)
+        assert dense.fork(live[0], 100) == kids
+        listed = live + kids
+        n = len(listed)
+        rng = np.random.default_rng(31)
+        for n_cand in (1, 5):
+            q = queries(rng, (n, n_cand, 2, 128))
+            # candidate keys continue the drift of their thread
+            ck = 0.5 * rng.standard_normal((n, n_cand, 2, 128)).astype(np.float32)
+            for i, th in enumerate(listed):
+                ck[i] += slope * dense.length(th) * u
+            ck = quantise(ck, dtype)
+            cv = quantise(0.5 * rng.standard_normal((n, n_cand, 2, 128)).astype(np.float32), dtype)
+            masks = np.stack([mask_rows_from_parents(draw_candidate_tree(rng, n_cand)) for _ in range(n)])
+            want = dense.decode_spec(q, ck, cv, masks, listed) if n_cand > 1 else dense.decode(q[:, 0], listed)[:, None]
+            qd, ckd, cvd, md = to_dev(q, dtype), to_dev(ck, dtype), to_dev(cv, dtype), t.from_numpy(masks).cuda()
+            for inline, matrix, chunk in ((True, (0, 0), 512), (False, (0, 0), 512), (True, (1, 1), 512), (False, (1, 1), 3)):
+                ap.apar_set_inline_shared(h, inline)
+                ap.apar_set_matrix_units(h, *matrix)
+                ap.apar_set_chunk_blocks(h, chunk)
+                out = t.empty_like(qd)
+                if n_cand > 1:
+                    ap.apar_decode_attention_spec(h, qd, ckd, cvd, md, n_cand, listed, out)
+                else:
+                    ap.apar_decode_attention(h, qd[:, 0].contiguous(), listed, out[:, 0])
+                t.cuda.synchronize()
+                got = to_host(out)
+                err = np.abs(got - want).max()
+                assert np.isfinite(got).all() and err <= tol, f"{n_cand} candidates, inline {inline} matrix {matrix} chunk {chunk}: {err}"
+        # prefill over the last tokens of a few threads, both kernels on bf16 pools
+        some = live[::40] + kids[:2]
+        m = [min(dense.length(th), 50) for th in some]
+        q = queries(rng, (sum(m), 2, 128))
+        want = dense.prefill(q, some, m)
+        qd = to_dev(q, dtype)
+        for kernel in ([ap.APAR_PREFILL_ROW_TILES, ap.APAR_PREFILL_MATRIX] if dtype == "bf16" else [ap.APAR_PREFILL_AUTO]):
+            ap.apar_set_prefill_kernel(h, kernel)
+            out = t.empty_like(qd)
+            ap.apar_prefill_attention(h, qd, some, m, out)
+            t.cuda.synchronize()
+            got = to_host(out)
+            err = np.abs(got - want).max()
+            assert np.isfinite(got).all() and err <= tol, f"prefill kernel {kernel}: {err}"
+
+
 @pytest.mark.parametrize("dtype,fan,C,matrix_rows", [("bf16", 1, 5, 64), ("bf16", 3, 5, 64), ("bf16", 6, 5, 64), ("bf16", 6, 5, 1),
                                                      ("bf16", 40, 2, 64), ("bf16", 40, 2, 0), ("bf16", 11, 8, 64), ("bf16", 11, 8, 1),
                                                      ("f32", 3, 5, 64)])
