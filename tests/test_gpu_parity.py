@@ -11,7 +11,7 @@ from apar_workloads import (HeadConfig, make_config, manual_tree, mask_rows_from
                             node_kv, quantise, step_q, tiny_tree)
 from oracle import BlockLedger, DenseThreads
 
-from harness import blocks_upper_bound, books_equal, nested_wide_tree, pool_for, random_forest, replay_trace, to_dev, to_host
+from harness import blocks_upper_bound, books_equal, check_plan_covers_tables, nested_wide_tree, pool_for, random_forest, replay_trace, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -338,6 +338,57 @@ def test_nested_wide_groups_inlined_stand_alone_and_matrix(n_cand):
             assert np.isfinite(got).all() and err <= TOL["bf16"], f"inline {inline} matrix {matrix} chunk {chunk}: {err}"
             seen_partials.add(ap.apar_last_plan_info(h).n_partial_rows)
         assert 0 in seen_partials and len(seen_partials) >= 4  # the variants really are different plans
+
+
+@pytest.mark.parametrize("dtype,n_q,n_kv,d", [("bf16", 4, 2, 128), ("f32", 2, 2, 64)])
+def test_long_threads_at_default_settings(dtype, n_q, n_kv, d):
+    """Threads longer than the longest tile list one wavefront is given (512 blocks), with every knob at its
+    default: a thread of 9000 tokens on its own, a shared segment of 8200 tokens below three threads, and a
+    segment of 2100 tokens below 260 threads (wide and long enough for matrix units on a bf16 pool)."""
+    t = torch()
+    heads = HeadConfig(n_q, n_kv, d, dtype)
+    parents, segs = [-1, -1, 1, 1, 1, -1], [9000, 8200, 1, 20, 600, 2100]
+    for i in range(260):
+        parents.append(5)
+        segs.append(1 + i % 30)
+    w = manual_tree(parents, segs, heads, seed=77, data_scale=0.5)
+    with pool_for(w, blocks_upper_bound(w)) as pool:
+        poison(pool)
+        h = pool.handle
+        dense = DenseThreads(n_q, n_kv, d)
+        live, _ = replay_trace(w, pool, None, dense)
+        n = len(live)
+        rng = np.random.default_rng(6)
+        q = quantise(0.5 * rng.standard_normal((n, 3, n_q, d)).astype(np.float32), dtype)
+        ck = quantise(0.5 * rng.standard_normal((n, 3, n_kv, d)).astype(np.float32), dtype)
+        cv = quantise(0.5 * rng.standard_normal((n, 3, n_kv, d)).astype(np.float32), dtype)
+        masks = np.stack([mask_rows_from_parents(draw_candidate_tree(rng, 3)) for _ in range(n)])
+        qd, ckd, cvd, md = to_dev(q, dtype), to_dev(ck, dtype), to_dev(cv, dtype), t.from_numpy(masks).cuda()
+        q1 = qd[:, 0].contiguous()
+        out1, out = t.empty_like(q1), t.empty_like(qd)
+        ap.apar_decode_attention(h, q1, live, out1)
+        t.cuda.synchronize()
+        info = ap.apar_last_plan_info(h)
+        # all but the last child of a parent whose last block is open hold a copy of its filled slots
+        assert info.n_partial_rows > 0 and info.unique_tokens == sum(segs) + 2 * (8200 % 16) + 259 * (2100 % 16)
+        err = np.abs(to_host(out1) - dense.decode(q[:, 0], live)).max()
+        assert err <= TOL[dtype], f"decode: {err}"
+        check = check_plan_covers_tables(h, live, n_kv, rows_per_thread=n_q // n_kv)
+        assert check["unit_block_reads"] >= check["unique_blocks"]
+        ap.apar_decode_attention_spec(h, qd, ckd, cvd, md, 3, live, out)
+        t.cuda.synchronize()
+        err = np.abs(to_host(out) - dense.decode_spec(q, ck, cv, masks, live)).max()
+        assert err <= TOL[dtype], f"three candidates: {err}"
+        # prefill of the long threads' last tokens (their whole private tail where it is short)
+        some = live[:4] + live[-2:]
+        m = [min(dense.length(th), 40) for th in some]
+        qp = quantise(0.5 * rng.standard_normal((sum(m), n_q, d)).astype(np.float32), dtype)
+        qpd = to_dev(qp, dtype)
+        outp = t.empty_like(qpd)
+        ap.apar_prefill_attention(h, qpd, some, m, outp)
+        t.cuda.synchronize()
+        err = np.abs(to_host(outp) - dense.prefill(qp, some, m)).max()
+        assert err <= TOL[dtype], f"prefill: {err}"
 
 
 def _drift_direction(d):
