@@ -367,11 +367,68 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             for (int nt = 0; nt < NT; ++nt)
                 if (on[nt]) weigh_values(vs, st[nt], s[nt], in_range[nt], scale_log2e);
         };
+        // A full tile that every row group of the workgroup sees (the segments at the top of a unit: the common
+        // case) needs no range, no mask and no decision per row tile: straight-line code around one rare branch
+        // (the move of the references), a dozen scalar branches and a scalar load fewer per tile than the
+        // general code.  Measured: 4 % off a prefill call, under 1 % off the decode calls.
+        // Such tiles are taken in a loop of their own - inside one loop, next to the general code, the two
+        // paths would disagree on the accumulators' registers and every tile would end in 64 register moves.
+        auto consume_seen_by_all = [&](const char* sb) {
+            if (wi.n_grp == 0) return;
+            Frag ks[4], vs[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
+            f32x4 s[NT];
+            float top[NT];
+            bool ran_away = false;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) s[nt] = products(ks, st[nt]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                top[nt] = top_logit(s[nt], my_j[nt] != 0x7fff, scale_log2e);
+                ran_away = ran_away || top[nt] > st[nt].m + kSlack;
+            }
+            if (__builtin_amdgcn_ballot_w64(ran_away) != 0) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) raise_reference(st[nt], top[nt]);
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) weigh_values(vs, st[nt], s[nt], my_j[nt] != 0x7fff, scale_log2e);
+        };
         if (n_coop_full > 0) {  // the full tiles; which wavefront fetches is a scalar decision
             if (wave < n_coop_full) fetch_full(wave);
+            // how many tiles at the head of the list are seen by all (the same count in every wavefront)
+            int n_all = 0;
+            for (int k = 0; k < 4; ++k)
+                if (wg->w[k].n_grp > 0) n_all = max(n_all, wg->w[k].grp_lo + wg->w[k].n_grp - wg->grp_base);
+            int n_lead = 0;
+            for (int base = 0; base < n_coop_full; base += 64) {
+                bool seen_by_all = false;
+                if (base + lane < n_coop_full) {
+                    const int meta = coop[base + lane].meta;
+                    seen_by_all = (meta & 1023) == 0 && ((meta >> 10) & 1023) >= n_all && !(meta >> 30);
+                }
+                const uint64_t others = ~__builtin_amdgcn_ballot_w64(seen_by_all);
+                const int run = others == 0 ? 64 : __builtin_ctzll(others);
+                n_lead += run;
+                if (run < 64) break;
+            }
+            // whole groups of four, or the whole list
+            const int n_fast = n_lead >= n_coop_full ? n_coop_full : (n_lead & ~3);
             settle_queries();
-            for (int t0 = 0; t0 < n_coop_full; t0 += 4) {
+            int t0 = 0;
+            for (; t0 < n_fast; t0 += 4) {
                 if (t0 > 0) __syncthreads();  // everyone is done reading the previous group
+                if (t0 + wave < n_coop_full) to_stage();
+                __syncthreads();
+                if (t0 + 4 + wave < n_coop_full) fetch_full(t0 + 4 + wave);
+                const int n_here = min(4, n_coop_full - t0);
+                for (int u = 0; u < n_here; ++u) consume_seen_by_all(stage[u]);
+            }
+            for (; t0 < n_coop_full; t0 += 4) {
+                if (t0 > 0) __syncthreads();
                 if (t0 + wave < n_coop_full) to_stage();
                 __syncthreads();
                 if (t0 + 4 + wave < n_coop_full) fetch_full(t0 + 4 + wave);
