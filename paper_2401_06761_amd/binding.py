@@ -198,11 +198,17 @@ def _ptr(t) -> int:
     return t.data_ptr()
 
 
+_HAVE_GPU = None  # torch.cuda.is_available(), asked once
+
+
 def _stream(stream) -> int:
+    global _HAVE_GPU
     if stream is None:
         import torch
 
-        if not torch.cuda.is_available():
+        if _HAVE_GPU is None:
+            _HAVE_GPU = bool(torch.cuda.is_available())
+        if not _HAVE_GPU:
             return 0  # only dry-run pools can be used without a GPU; they ignore the stream
         return torch.cuda.current_stream().cuda_stream
     return int(getattr(stream, "cuda_stream", stream))

@@ -26,6 +26,12 @@ class ServingRun:
         flat_lengths: request id -> total sequence length (prompt included) for the sequential stand-in."""
         self.pool, self.h = pool, pool.handle
         self.requests = {r.rid: r for r in requests}
+        # seed of every request by id, for one vectorised look-up per step
+        self._rids = np.array(sorted(self.requests), dtype=np.int64)
+        self._seeds = np.array([self.requests[int(r)].seed for r in self._rids], dtype=np.int64)
+        self._flat_target = None
+        if flat_lengths is not None:
+            self._flat_target = np.array([flat_lengths[int(r)] for r in self._rids], dtype=np.int64)
         self.sampler = sampler
         self.flat = flat_lengths
         self.banks = banks
@@ -55,12 +61,12 @@ class ServingRun:
             if self.out is None or self.out.shape[0] < n:
                 self.out = q.new_empty((max(n, q.shape[0]),) + tuple(q.shape[1:]))
             ap.apar_decode_attention(self.h, q[:n], batch["thread"], self.out[:n])
-        seeds = np.array([self.requests[int(r)].seed for r in batch["request_id"]], dtype=np.int64)
+        seeds = self._seeds[np.searchsorted(self._rids, batch["request_id"])]
         if self.flat is None:
             sampled = sample_tokens(self.sampler, seeds, batch["seq_index"], batch["length"], batch["last_token"],
                                     batch["start_len"], batch["group_size"])
         else:
-            target = np.array([self.flat[int(r)] for r in batch["request_id"]], dtype=np.int64)
+            target = self._flat_target[np.searchsorted(self._rids, batch["request_id"])]
             sampled = sample_flat(self.sampler, seeds, batch["length"], target)
         info = ap.apar_server_step(self.srv, sampled, k, v)
         if self.keep_trace:
@@ -68,7 +74,7 @@ class ServingRun:
                                "n_preempted": info.n_preempted, "n_forked": info.n_forked,
                                "n_rows_appended": info.n_rows_appended,
                                "n_finished_requests": info.n_finished_requests})
-        while True:
+        for _ in range(info.n_finished_requests):
             done = ap.apar_server_pop_finished(self.srv)
             if done is None:
                 break
@@ -82,6 +88,11 @@ class ServingRun:
         steps = 0
         while steps < max_steps and self.step():
             steps += 1
+        while True:  # nothing should be left; a request the loop above did not collect shows up here
+            done = ap.apar_server_pop_finished(self.srv)
+            if done is None:
+                break
+            self.outputs[done[0]], self.infos[done[0]] = done[1], done[2]
         if self.banks is not None:
             import torch
 
