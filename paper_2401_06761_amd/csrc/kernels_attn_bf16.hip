@@ -397,6 +397,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) weigh_values(vs, st[nt], s[nt], my_j[nt] != 0x7fff, scale_log2e);
         };
+        // Two such tiles at once: twice as many independent chains of matrix instructions and one decision
+        // about the references instead of two (a wavefront spends most of its time between dependent
+        // instructions, not in them).
+        auto consume_two_seen_by_all = [&](const char* sa, const char* sb) {
+            if (wi.n_grp == 0) return;
+            Frag ka[4], kb[4], va[4], vb[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ka[r].u = *reinterpret_cast<const u32x4*>(sa + r * 1024 + lane * 16);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) kb[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) va[r].u = *reinterpret_cast<const u32x4*>(sa + 4096 + r * 1024 + lane * 16);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) vb[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
+            f32x4 s0[NT], s1[NT];
+            float top[NT];
+            bool ran_away = false;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) s0[nt] = products(ka, st[nt]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) s1[nt] = products(kb, st[nt]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const bool mine = my_j[nt] != 0x7fff;
+                top[nt] = fmaxf(top_logit(s0[nt], mine, scale_log2e), top_logit(s1[nt], mine, scale_log2e));
+                ran_away = ran_away || top[nt] > st[nt].m + kSlack;
+            }
+            if (__builtin_amdgcn_ballot_w64(ran_away) != 0) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) raise_reference(st[nt], top[nt]);
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                weigh_values(va, st[nt], s0[nt], my_j[nt] != 0x7fff, scale_log2e);
+                weigh_values(vb, st[nt], s1[nt], my_j[nt] != 0x7fff, scale_log2e);
+            }
+        };
         if (n_coop_full > 0) {  // the full tiles; which wavefront fetches is a scalar decision
             if (wave < n_coop_full) fetch_full(wave);
             // how many tiles at the head of the list are seen by all (the same count in every wavefront)
@@ -425,7 +462,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
                 __syncthreads();
                 if (t0 + 4 + wave < n_coop_full) fetch_full(t0 + 4 + wave);
                 const int n_here = min(4, n_coop_full - t0);
-                for (int u = 0; u < n_here; ++u) consume_seen_by_all(stage[u]);
+                int u = 0;
+                for (; u + 1 < n_here; u += 2) consume_two_seen_by_all(stage[u], stage[u + 1]);
+                if (u < n_here) consume_seen_by_all(stage[u]);
             }
             for (; t0 < n_coop_full; t0 += 4) {
                 if (t0 > 0) __syncthreads();
