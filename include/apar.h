@@ -21,7 +21,11 @@
  *     waiting.  Host bookkeeping changes at call time, so introspection
  *     reflects every earlier call.  Calls on one pool must be issued from one
  *     host thread, and on one stream at a time (work on different streams
- *     must be ordered by the caller);
+ *     must be ordered by the caller).  Parts of a call may run on streams
+ *     that the pool owns (large table uploads, kernels of different classes
+ *     side by side); they are ordered before and after `hip_stream` with
+ *     events, so the caller sees the call as work on `hip_stream` alone, but
+ *     a call may allocate staging memory and cannot be captured into a graph;
  *   - a call that fails with any status but APAR_ERR_HIP leaves the pool exactly
  *     as it was; after APAR_ERR_HIP the pool should be destroyed;
  *   - the layout of the pool buffer is private to the library (KV tiles are
