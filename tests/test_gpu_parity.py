@@ -3,6 +3,8 @@
 Tolerances (max abs error of attention outputs): 1e-5 for fp32 pools, 2e-2 for bf16 pools (bf16
 inputs, fp32 accumulation, probabilities rounded to bf16 before the P.V product, bf16 output).
 Block tables, lengths and refcounts are compared bit-exactly."""
+import os
+
 import numpy as np
 import pytest
 
@@ -619,7 +621,8 @@ def test_append_kv_gather_takes_the_named_rows(dtype, d):
             assert np.array_equal(to_host(ko), K) and np.array_equal(to_host(vo), V)
 
 
-@pytest.mark.parametrize("seed", range(10))
+# APAR_TEST_FOREST_SEEDS / APAR_TEST_FOREST_NODES widen the sweep (more seeds, larger forests) for a one-off run
+@pytest.mark.parametrize("seed", range(int(os.environ.get("APAR_TEST_FOREST_SEEDS", "10"))))
 def test_random_forests_decode_spec_and_prefill(seed):
     """Seeded random forests (deep and wide mixes, segment lengths around the block boundaries), random head
     grouping, random unit caps: decode, multi-candidate decode and prefill against the dense oracle."""
@@ -629,7 +632,8 @@ def test_random_forests_decode_spec_and_prefill(seed):
     group = int(rng.choice([1, 2, 4, 8]))
     n_q = n_kv * group
     heads = HeadConfig(n_q, n_kv, 128, "bf16")
-    parents, segs = random_forest(rng, int(rng.integers(1, 4)), int(rng.integers(8, 120)))
+    parents, segs = random_forest(rng, int(rng.integers(1, 4)),
+                                  int(rng.integers(8, int(os.environ.get("APAR_TEST_FOREST_NODES", "120")))))
     w = manual_tree(parents, segs, heads, seed=seed, data_scale=0.5)
     N = blocks_upper_bound(w)
     with pool_for(w, N) as pool:
