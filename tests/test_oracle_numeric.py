@@ -173,6 +173,25 @@ def test_peaked_closed_form(where):
     np.testing.assert_allclose(out, star_v, atol=1e-12 + 40 * T * math.exp(-alpha))
 
 
+# logits far beyond the range of exp: two keys a fixed distance apart, closed form ----
+@pytest.mark.parametrize("level", [0.0, 2000.0, -2000.0, 1e5])
+def test_two_keys_at_any_logit_level(level):
+    """softmax is invariant under a shift of all logits: two keys whose logits are level and level + delta
+    give weights 1 / (1 + e^delta) and e^delta / (1 + e^delta) whatever the level, also where e^level
+    overflows or underflows a double."""
+    d, delta = 4, 1.25
+    q = np.array([[2.0, 0.0, 0.0, 0.0]])
+    scale = 0.5
+    # logit = scale * <q, k> = k[0]
+    K = np.array([[[level, 3.0, -1.0, 0.5]], [[level + delta, -2.0, 4.0, 1.0]]])
+    V = np.array([[[1.0, -2.0, 0.25, 8.0]], [[-3.0, 5.0, 0.5, -1.0]]])
+    out = attend(q, K, V, scale)[0]
+    w1 = math.exp(delta) / (1.0 + math.exp(delta))
+    expect = (1.0 - w1) * V[0, 0] + w1 * V[1, 0]
+    assert np.isfinite(out).all()
+    np.testing.assert_allclose(out, expect, rtol=0, atol=1e-9 * max(1.0, abs(level)) * 1e-3 + 1e-12)
+
+
 # softmax shift invariance and the scale actually being applied -----------------
 def test_scale_is_applied_and_default_is_inv_sqrt_d():
     r = _rng(11)
