@@ -42,6 +42,91 @@ def _oracle_run(reqs, n_blocks, max_running, watermark, flat=None, check=None):
     return o, led, trace
 
 
+def _decode_alone(req):
+    """One request through Algorithm 1 with nothing else around: what its response must be under any schedule,
+    because the sampler depends on (request seed, sequence index, sequence length) only."""
+    from oracle.controller import SequenceGroup
+
+    g = SequenceGroup(req.prompt_tokens())
+    start = {0: req.prompt_len}
+    steps = 0
+    while not g.is_finished():
+        todo = g.unfinished()
+        xs = sample_tokens(CFG, [req.seed] * len(todo), [s.sid for s in todo], [len(s.tokens) for s in todo],
+                           [s.last_token for s in todo], [start[s.sid] for s in todo], [len(g.G)] * len(todo))
+        before = len(g.G)
+        g.step(xs.tolist())
+        for c in g.G[before:]:
+            start[c.sid] = len(c.tokens)
+        steps += 1
+    return g.restore(), steps, g
+
+
+@pytest.mark.parametrize("n_blocks,max_running,watermark", [(4096, 64, 0), (4096, 5, 0), (160, 12, 2), (96, 40, 0), (64, 8, 4)])
+def test_oracle_loop_against_what_the_policy_fixes(n_blocks, max_running, watermark):
+    """The oracle's loop alone, against facts that do not come from it: every response equals the request
+    decoded alone (whatever was preempted and restarted); requests are admitted in submission order and
+    never overtake; the pool, the watermark and the cap on running requests are respected at every step;
+    with room for everything nothing is preempted and the loop takes as many steps as the longest request;
+    the books are empty at the end."""
+    reqs = make_requests(24, seed=n_blocks + max_running, prompt_lo=8, prompt_hi=120)
+    by = {r.rid: r for r in reqs}
+    alone = {r.rid: _decode_alone(r) for r in reqs}
+    order_of = {r.rid: i for i, r in enumerate(reqs)}
+    seen = {"max_used": 0}
+
+    def check(step, led):
+        led.check_invariants()
+        assert led.used_blocks() <= n_blocks
+        seen["max_used"] = max(seen["max_used"], led.used_blocks())
+
+    led = BlockLedger(n_blocks, max_threads=1 << 30)
+    o = ServingOracle(led, max_running, watermark)
+    for r in reqs:
+        o.submit(r.rid, r.prompt_tokens())
+    done_before = set()
+    while True:
+        free_before = led.free_blocks()
+        adm = o.admit()
+        # admission: queue order, and each one left the watermark standing
+        free = free_before
+        for rid in adm:
+            free -= (by[rid].prompt_len + 15) // 16
+            assert free >= watermark
+        assert free == led.free_blocks()
+        running = [r["rid"] for r in o.running]
+        assert len(running) <= max_running
+        # no overtaking: whoever runs or is done was submitted before everybody still waiting
+        waiting = [rid for _, rid, _ in o.waiting]
+        if waiting:
+            first_waiting = min(order_of[rid] for rid in waiting)
+            assert all(order_of[rid] < first_waiting for rid in running)
+            assert [order_of[rid] for rid in waiting] == sorted(order_of[rid] for rid in waiting)
+        b = o.batch()
+        if not b:
+            assert not o.waiting
+            break
+        seeds = [by[e["request_id"]].seed for e in b]
+        xs = sample_tokens(CFG, seeds, [e["seq_index"] for e in b], [e["length"] for e in b],
+                           [e["last_token"] for e in b], [e["start_len"] for e in b], [e["group_size"] for e in b])
+        o.step(xs.tolist())
+        check(o.steps, led)
+    assert sorted(rid for rid, _, _ in o.finished) == sorted(by)
+    for rid, toks, g in o.finished:
+        want, _, g_alone = alone[rid]
+        assert toks == want, f"request {rid}"
+        assert (g.attended, g.generated, g.max_cached) == (g_alone.attended, g_alone.generated, g_alone.max_cached)
+    assert led.used_blocks() == 0
+    if n_blocks == 4096:
+        assert o.preemptions == 0 and o.admissions == len(reqs)
+        if max_running >= len(reqs):
+            assert o.steps == max(steps for _, steps, _ in alone.values())
+            assert o.generated == sum(g.generated for _, _, g in alone.values())
+    else:
+        assert o.preemptions > 0 and o.admissions == len(reqs) + o.preemptions
+        assert o.generated > sum(g.generated for _, _, g in alone.values())  # restarted work is counted
+
+
 @pytest.mark.parametrize("n_blocks,max_running,watermark", [(4096, 64, 0), (160, 12, 2), (96, 40, 0), (64, 8, 4)])
 def test_serving_loop_matches_oracle_step_by_step(n_blocks, max_running, watermark):
     reqs = make_requests(24, seed=n_blocks, prompt_lo=8, prompt_hi=120)
