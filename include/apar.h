@@ -57,7 +57,9 @@ typedef enum apar_status {
     APAR_ERR_OUT_OF_BLOCKS = -3,   /* the pool cannot supply the blocks the call needs   */
     APAR_ERR_THREAD_CAPACITY = -4, /* more than max_threads ids would be issued          */
     APAR_ERR_HIP = -5,             /* a HIP runtime call failed (see apar_last_hip_error) */
-    APAR_ERR_UNSUPPORTED = -6      /* shape outside what the kernels are built for       */
+    APAR_ERR_UNSUPPORTED = -6,     /* shape outside what the kernels are built for       */
+    APAR_ERR_WORKSPACE_LIMIT = -7  /* apar_decode_attention_fixed: the call needs more than */
+                                   /* the fixed workspace holds; nothing was enqueued       */
 } apar_status;
 
 enum { APAR_F32 = 0, APAR_BF16 = 1 };
@@ -194,6 +196,31 @@ APAR_API int apar_decode_attention(apar_pool* pool, const void* q_dev, const apa
 APAR_API int apar_decode_attention_spec(apar_pool* pool, const void* q_dev, const void* cand_k_dev,
                                const void* cand_v_dev, const uint8_t* mask_dev, int n_cand,
                                const apar_thread* threads, int n, void* out_dev, void* hip_stream);
+/*
+ * apar_decode_attention for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result, same kernels - but
+ * the call's plan tables and partial results live in a workspace of fixed size that is part of the
+ * library's device image (one copy per GPU, held until the process ends) instead of in memory the
+ * library allocates, every kernel runs on `hip_stream` itself, and the call creates no stream or
+ * event and is never profiled.  It calls no hipMalloc, hipFree, hipHostMalloc or any other
+ * allocating routine (what it needs besides - the workspace's address on the pool's device, a
+ * pinned staging buffer of APAR_FIXED_PLAN_BYTES and one event - apar_pool_create obtained).
+ * Limits: the staged plan (128 bytes per workgroup, 8 per block read, 8 per listed thread and 4
+ * per partial result to merge) must fit APAR_FIXED_PLAN_BYTES, and the partial results
+ * ((head_dim + 2) floats per (partial row, q head); none when every sharing subtree fits one work
+ * unit) APAR_FIXED_PARTIAL_BYTES; beyond either the call returns APAR_ERR_WORKSPACE_LIMIT and
+ * enqueues nothing.  The host may wait for the previous fixed call's plan upload (not for its kernels).
+ * All pools on one GPU share that GPU's workspace, which keeps the last call's contents: nothing
+ * in it has to start at zero (a call overwrites every table and every partial result it reads),
+ * but two fixed calls that overlap on one GPU - different streams, or different pools, without an
+ * order between them - race on it.  Calls on one stream are ordered by the stream.
+ * Errors: as apar_decode_attention, plus WORKSPACE_LIMIT, and INVALID_ARG on a dry-run pool.
+ */
+#define APAR_FIXED_PLAN_BYTES (2 << 20)
+#define APAR_FIXED_PARTIAL_BYTES (6 << 20)
+APAR_API int apar_decode_attention_fixed(apar_pool* pool, const void* q_dev, const apar_thread* threads, int n,
+                                void* out_dev, void* hip_stream);
+
 /* As apar_append_kv_batch, but row i of the call is read from row src_rows[i] (>= 0, host array) of
  * k_dev, v_dev, so that a caller can append a subset of a larger array of rows without gathering it
  * first (Alg. 1 batches the rows of many sequence groups; a scheduler may have dropped some). */

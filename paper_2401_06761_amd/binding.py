@@ -100,6 +100,7 @@ def _load() -> C.CDLL:
         "apar_append_kv": [P, C.c_int32, V, V, I, V],
         "apar_append_kv_batch": [P, I32P, I, V, V, V],
         "apar_decode_attention": [P, V, I32P, I, V, V],
+        "apar_decode_attention_fixed": [P, V, I32P, I, V, V],
         "apar_decode_attention_spec": [P, V, V, V, V, I, I32P, I, V, V],
         "apar_commit_candidates": [P, I32P, I, V, V, I, C.POINTER(C.c_uint8), V],
         "apar_prefill_attention": [P, V, I32P, I32P, I, V, V],
@@ -257,6 +258,12 @@ def apar_append_kv_batch(pool, threads: Sequence[int], k, v, stream=None) -> Non
 def apar_decode_attention(pool, q, threads: Sequence[int], out, stream=None) -> None:
     arr, n = _ids(threads)
     _check(_L().apar_decode_attention(pool, _ptr(q), arr, n, _ptr(out), _stream(stream)), "apar_decode_attention")
+
+
+def apar_decode_attention_fixed(pool, q, threads: Sequence[int], out, stream=None) -> None:
+    arr, n = _ids(threads)
+    _check(_L().apar_decode_attention_fixed(pool, _ptr(q), arr, n, _ptr(out), _stream(stream)),
+           "apar_decode_attention_fixed")
 
 
 def apar_decode_attention_spec(pool, q, cand_k, cand_v, mask, n_cand: int, threads: Sequence[int], out,

@@ -138,7 +138,14 @@ struct PartialBuf {
 struct ClassStreams {
     hipStream_t aux[2] = {nullptr, nullptr};
     hipEvent_t fork = nullptr, join[2] = {nullptr, nullptr};
+    bool serial = false;  // true: every class is launched on the caller's stream, one after the other, and
+                          // no stream or event is ever created (for the entry point that must not allocate)
 };
+
+// Where `device`'s copy of the library's static workspace (APAR_FIXED_PLAN_BYTES of plan tables followed by
+// APAR_FIXED_PARTIAL_BYTES of partial results) lives.  `device` must be the current device.  The address is
+// asked for once per device and kept.
+hipError_t fixed_workspace_of_device(int device, char** out);
 
 // ---- launchers (defined next to their kernels) ------------------------------
 hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const void* v, const int32_t* dst_codes,

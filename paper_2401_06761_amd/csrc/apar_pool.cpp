@@ -56,6 +56,9 @@ struct EventPair {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+constexpr size_t kFixedPlanBytes = (size_t)APAR_FIXED_PLAN_BYTES;
+constexpr size_t kFixedPartBytes = (size_t)APAR_FIXED_PARTIAL_BYTES;
+
 }  // namespace
 
 struct apar_pool {
@@ -95,6 +98,13 @@ struct apar_pool {
     size_t part_slots_cap = 0;
     ClassStreams class_streams;
     hipStream_t copy_stream = nullptr;  // uploads of plans and row codes run here, beside the caller's stream
+
+    // apar_decode_attention_fixed: this device's copy of the static workspace, a pinned host buffer the plan
+    // is staged in, and the event after its upload; all three obtained at pool creation
+    char* fixed_dev = nullptr;
+    char* fixed_host = nullptr;
+    hipEvent_t fixed_up = nullptr;
+    bool fixed_pending = false;
 
     bool profiling = false;
     std::vector<EventPair> decode_events, append_events;
@@ -250,9 +260,12 @@ int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vecto
     return APAR_OK;
 }
 
+// fixed: the plan and the partial results go to the device's static workspace, nothing is allocated, no
+// stream or event is created and profiling is off for the call.
 int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* cand_v, const uint8_t* mask,
-                  int n_cand, const apar_thread* ids, int n, void* out, void* stream, bool spec) {
+                  int n_cand, const apar_thread* ids, int n, void* out, void* stream, bool spec, bool fixed = false) {
     if (!p || n < 0) return APAR_ERR_INVALID_ARG;
+    if (fixed && (p->dry_run || !p->fixed_dev || !p->fixed_host)) return APAR_ERR_INVALID_ARG;
     if (n == 0) return APAR_OK;
     if (!ids) return APAR_ERR_INVALID_ARG;
     if (spec && (n_cand < 1 || n_cand > 8)) return APAR_ERR_INVALID_ARG;
@@ -316,17 +329,36 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     ofs[3] = align_up(ofs[2] + ph.dfs_threads.size() * 4, 256);
     ofs[4] = align_up(ofs[3] + ph.path_ofs.size() * 4, 256);
     ofs[5] = align_up(ofs[4] + ph.path_ids.size() * 4, 256);
+    const size_t slots = (size_t)ph.n_partial_rows * n_cand * p->shape.n_q;
     StageSlot* s = nullptr;
-    if ((rc = acquire_stage(p, ofs[5], &s)) != APAR_OK) return rc;
-    memcpy(s->host + ofs[0], ph.wgs.data(), ph.wgs.size() * sizeof(WgDesc));
-    memcpy(s->host + ofs[1], ph.tiles.data(), ph.tiles.size() * sizeof(TileRef));
-    memcpy(s->host + ofs[2], ph.dfs_threads.data(), ph.dfs_threads.size() * 4);
-    memcpy(s->host + ofs[3], ph.path_ofs.data(), ph.path_ofs.size() * 4);
-    if (!ph.path_ids.empty()) memcpy(s->host + ofs[4], ph.path_ids.data(), ph.path_ids.size() * 4);
+    char *host = nullptr, *dev = nullptr;
+    PartialBuf part = p->part;
+    if (fixed) {
+        // the workspace has a fixed size: a plan or a set of partial results beyond it is refused
+        const size_t slot_bytes = (size_t)(p->shape.d + 2) * sizeof(float);
+        const size_t cap_slots = kFixedPartBytes / slot_bytes;
+        if (ofs[5] > kFixedPlanBytes || slots > cap_slots) return APAR_ERR_WORKSPACE_LIMIT;
+        if (p->fixed_pending) {  // the previous call's upload may still be reading the pinned buffer
+            HIP_TRY(hipEventSynchronize(p->fixed_up));
+            p->fixed_pending = false;
+        }
+        host = p->fixed_host;
+        dev = p->fixed_dev;
+        part.o = (float*)(p->fixed_dev + kFixedPlanBytes);
+        part.ml = part.o + cap_slots * p->shape.d;
+    } else {
+        if ((rc = acquire_stage(p, ofs[5], &s)) != APAR_OK) return rc;
+        host = s->host;
+        dev = s->dev;
+    }
+    memcpy(host + ofs[0], ph.wgs.data(), ph.wgs.size() * sizeof(WgDesc));
+    memcpy(host + ofs[1], ph.tiles.data(), ph.tiles.size() * sizeof(TileRef));
+    memcpy(host + ofs[2], ph.dfs_threads.data(), ph.dfs_threads.size() * 4);
+    memcpy(host + ofs[3], ph.path_ofs.data(), ph.path_ofs.size() * 4);
+    if (!ph.path_ids.empty()) memcpy(host + ofs[4], ph.path_ids.data(), ph.path_ids.size() * 4);
 
     // partial-result buffer
-    const size_t slots = (size_t)ph.n_partial_rows * n_cand * p->shape.n_q;
-    if (slots > p->part_slots_cap) {
+    if (!fixed && slots > p->part_slots_cap) {
         HIP_TRY(hipDeviceSynchronize());
         if (p->part.o) HIP_TRY(hipFree(p->part.o));
         if (p->part.ml) HIP_TRY(hipFree(p->part.ml));
@@ -336,15 +368,22 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
         HIP_TRY(hipMalloc((void**)&p->part.o, cap * p->shape.d * sizeof(float)));
         HIP_TRY(hipMalloc((void**)&p->part.ml, cap * 2 * sizeof(float)));
         p->part_slots_cap = cap;
+        part = p->part;
     }
 
-    if ((rc = upload(p, s, ofs[5], st)) != APAR_OK) return rc;
+    if (fixed) {
+        HIP_TRY(hipMemcpyAsync(dev, host, ofs[5], hipMemcpyHostToDevice, st));
+        HIP_TRY(hipEventRecord(p->fixed_up, st));
+        p->fixed_pending = true;
+    } else if ((rc = upload(p, s, ofs[5], st)) != APAR_OK) {
+        return rc;
+    }
     PlanDev pd;
-    pd.wgs = (const WgDesc*)(s->dev + ofs[0]);
-    pd.tiles = (const TileRef*)(s->dev + ofs[1]);
-    pd.dfs_threads = (const int32_t*)(s->dev + ofs[2]);
-    pd.path_ofs = (const int32_t*)(s->dev + ofs[3]);
-    pd.path_ids = (const int32_t*)(s->dev + ofs[4]);
+    pd.wgs = (const WgDesc*)(dev + ofs[0]);
+    pd.tiles = (const TileRef*)(dev + ofs[1]);
+    pd.dfs_threads = (const int32_t*)(dev + ofs[2]);
+    pd.path_ofs = (const int32_t*)(dev + ofs[3]);
+    pd.path_ids = (const int32_t*)(dev + ofs[4]);
     pd.n_wg = (int32_t)ph.wgs.size();
     for (int k = 0; k < 3; ++k) pd.n_wg_class[k] = ph.n_wg_class[k];
     if (pd.n_wg_class[0] + pd.n_wg_class[1] + pd.n_wg_class[2] != pd.n_wg) return APAR_ERR_INVALID_ARG;
@@ -354,25 +393,31 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     pd.n_slices = p->plan_geom[2];
 
     EventPair ev;
-    if (p->profiling) {
+    const bool profiling = p->profiling && !fixed;
+    if (profiling) {
         if ((rc = new_event(p, &ev.a)) != APAR_OK || (rc = new_event(p, &ev.b)) != APAR_OK ||
             (rc = new_event(p, &ev.c)) != APAR_OK)
             return rc;
         HIP_TRY(hipEventRecord(ev.a, st));
     }
-    HIP_TRY(launch_attention_partial(p->shape, p->kv, q, pd, n_cand, p->part, cand_k, cand_v, mask, out, p->class_streams, st));
-    if (p->profiling) HIP_TRY(hipEventRecord(ev.b, st));
+    ClassStreams one_stream;
+    one_stream.serial = true;
+    HIP_TRY(launch_attention_partial(p->shape, p->kv, q, pd, n_cand, part, cand_k, cand_v, mask, out,
+                                     fixed ? one_stream : p->class_streams, st));
+    if (profiling) HIP_TRY(hipEventRecord(ev.b, st));
     if (ph.any_partial)
-        HIP_TRY(launch_merge(p->shape, pd, p->part, q, cand_k, cand_v, mask, n_cand, out, st));
-    if (p->profiling) {
+        HIP_TRY(launch_merge(p->shape, pd, part, q, cand_k, cand_v, mask, n_cand, out, st));
+    if (profiling) {
         HIP_TRY(hipEventRecord(ev.c, st));
         p->decode_events.push_back(ev);
         p->n_decode_calls += 1;
     }
-    HIP_TRY(hipEventRecord(s->ev, st));
-    s->pending = true;
+    if (s) {
+        HIP_TRY(hipEventRecord(s->ev, st));
+        s->pending = true;
+    }
     p->last_plan = info;
-    if (p->profiling)
+    if (profiling)
         p->plan_host_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count() -
                            p->wait_in_call_ms;
     return APAR_OK;
@@ -591,6 +636,20 @@ int apar_pool_create(const apar_pool_config* cfg, void* kv_dev, size_t kv_bytes,
         hipPointerAttribute_t attr;
         if (hipPointerGetAttributes(&attr, kv_dev) == hipSuccess) p->device = attr.device;
         else (void)hipGetLastError();
+        // what apar_decode_attention_fixed needs and may not obtain itself: the address of this device's copy of
+        // the static workspace, a pinned buffer to stage its plan in and the event that follows the upload
+        DeviceGuard guard(p->device);
+        int rc = APAR_OK;
+        if (!hip_ok(fixed_workspace_of_device(p->device, &p->fixed_dev), "hipGetSymbolAddress(scratch)")) rc = APAR_ERR_HIP;
+        if (rc == APAR_OK && !hip_ok(hipHostMalloc((void**)&p->fixed_host, kFixedPlanBytes, hipHostMallocDefault), "hipHostMalloc"))
+            rc = APAR_ERR_HIP;
+        if (rc == APAR_OK && !hip_ok(hipEventCreateWithFlags(&p->fixed_up, hipEventDisableTiming), "hipEventCreate"))
+            rc = APAR_ERR_HIP;
+        if (rc != APAR_OK) {
+            if (p->fixed_host) (void)hipHostFree(p->fixed_host);
+            delete p;
+            return rc;
+        }
     }
     const float scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
     p->shape.n_q = cfg->n_q_heads;
@@ -625,6 +684,8 @@ int apar_pool_destroy(apar_pool* p) {
         if (s.up) (void)hipEventDestroy(s.up);
     }
     if (p->copy_stream) (void)hipStreamDestroy(p->copy_stream);
+    if (p->fixed_host) (void)hipHostFree(p->fixed_host);
+    if (p->fixed_up) (void)hipEventDestroy(p->fixed_up);
     if (p->part.o) (void)hipFree(p->part.o);
     if (p->part.ml) (void)hipFree(p->part.ml);
     auto drop = [](hipEvent_t e) {
@@ -795,6 +856,11 @@ int apar_decode_attention_spec(apar_pool* p, const void* q_dev, const void* cand
                                const uint8_t* mask_dev, int n_cand, const apar_thread* threads, int n, void* out_dev,
                                void* hip_stream) {
     return decode_common(p, q_dev, cand_k_dev, cand_v_dev, mask_dev, n_cand, threads, n, out_dev, hip_stream, true);
+}
+
+int apar_decode_attention_fixed(apar_pool* p, const void* q_dev, const apar_thread* threads, int n, void* out_dev,
+                                void* hip_stream) {
+    return decode_common(p, q_dev, nullptr, nullptr, nullptr, 1, threads, n, out_dev, hip_stream, false, true);
 }
 
 int apar_prefill_attention(apar_pool* p, const void* q_dev, const apar_thread* threads, const int32_t* m, int n,
@@ -998,6 +1064,7 @@ const char* apar_status_string(int status) {
         case APAR_ERR_THREAD_CAPACITY: return "thread capacity exceeded";
         case APAR_ERR_HIP: return "HIP runtime error";
         case APAR_ERR_UNSUPPORTED: return "unsupported shape";
+        case APAR_ERR_WORKSPACE_LIMIT: return "call exceeds the fixed workspace";
         default: return "unknown status";
     }
 }

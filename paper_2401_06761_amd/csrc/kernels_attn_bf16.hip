@@ -749,7 +749,8 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
         (e = launch_attention_units_bf16(s, pool, q, plan, first[0], plan.n_wg_class[0], n_cand, part, st)) != hipSuccess)
         return e;
     if (last < 0) return hipSuccess;
-    if (n_present > 1) {
+    const bool side_by_side = n_present > 1 && !cs.serial;
+    if (side_by_side) {
         if (!cs.fork) {
             if ((e = hipEventCreateWithFlags(&cs.fork, hipEventDisableTiming)) != hipSuccess) return e;
         }
@@ -765,7 +766,7 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
         const int count = plan.n_wg_class[cls];
         if (count == 0) continue;
         hipStream_t on = st;
-        if (cls != last) {
+        if (cls != last && side_by_side) {
             on = cs.aux[side];
             if ((e = hipStreamWaitEvent(on, cs.fork, 0)) != hipSuccess) return e;
         }
@@ -778,7 +779,7 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
         else APAR_LAUNCH(1);
 #undef APAR_LAUNCH
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        if (cls != last) {
+        if (cls != last && side_by_side) {
             if ((e = hipEventRecord(cs.join[side], on)) != hipSuccess) return e;
             used[side] = true;
             ++side;

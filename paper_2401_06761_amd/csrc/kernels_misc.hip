@@ -362,6 +362,33 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
                                  PartialBuf part, const void* cand_k, const void* cand_v, const uint8_t* mask,
                                  void* out, ClassStreams& cs, hipStream_t st);
 
+// ---------------------------------------------------------------------------
+// Fixed workspace of apar_decode_attention_fixed: the plan tables and the partial results of one call live
+// in this array instead of in memory the library allocates.  Every GPU the library runs on holds its own
+// copy of the array, at its own address, until the process ends.  In host code the array's name is only a
+// handle of the symbol, not a device address: the address comes from hipGetSymbolAddress, once per device
+// with that device current, and that pointer is what kernels and copies are given.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[(size_t)APAR_FIXED_PLAN_BYTES + (size_t)APAR_FIXED_PARTIAL_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+char* g_scratch_ptr[kMaxDevices] = {};  // per device: where its copy of `scratch` lives (null: not asked yet)
+}  // namespace
+
+hipError_t fixed_workspace_of_device(int device, char** out) {
+    if (device < 0 || device >= kMaxDevices || !out) return hipErrorInvalidValue;
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr || ((uintptr_t)ptr & 255)) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = (char*)ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
 hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const void* v, const int32_t* dst_codes,
                               const int32_t* src_rows, int n_rows, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;
