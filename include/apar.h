@@ -71,7 +71,7 @@ typedef struct apar_pool_config {
     int32_t block_size;  /* tokens per KV block; must be 16                              */
     int32_t dtype;       /* APAR_F32 or APAR_BF16: type of K, V, Q and of the output     */
     int32_t max_threads; /* upper bound on ids ever issued by this pool                  */
-    int64_t num_blocks;  /* N: blocks in the pool, < 2^27                                */
+    int64_t num_blocks;  /* N: blocks in the pool, at most 2^26                          */
     float softmax_scale; /* 0 means 1/sqrt(head_dim)                                     */
 } apar_pool_config;
 
@@ -140,7 +140,7 @@ APAR_API int apar_pool_destroy(apar_pool* pool);
 APAR_API int apar_thread_create(apar_pool* pool, apar_thread* out);
 
 /*
- * Fork (Alg. 1: s' <- s; Sec. 2.3): n_children new threads whose table and
+ * Fork (Alg. 1: a sequence that ends in [Fork] spawns a copy of itself; Sec. 2.3): n_children new threads whose table and
  * length equal the parent's; every block the parent holds gains n_children
  * references.  Allocates no block and copies nothing; the copy of a shared,
  * partly filled tail block is deferred to the first append that needs it.  The
@@ -309,7 +309,7 @@ APAR_API int apar_read_kv_rows(apar_pool* pool, apar_thread thread, int64_t firs
 /* ---- decoding controller (Alg. 1) ---------------------------------------
  * One sequence group per prompt (Sec. 2.3).  The controller keeps each sequence's
  * tokens, the paragraph tree (Sec. 2.2: a node points at a slice of a sequence and
- * has a first-child and a next-sibling pointer) and applies one AparDecode step of
+ * has a first-child and a next-sibling pointer) and applies one decoding step of
  * Alg. 1 to the tokens the caller sampled.  It samples nothing and runs no model:
  * per step the caller lists the unfinished sequences (apar_group_unfinished), runs
  * apar_decode_attention over them, draws one token per sequence and calls
@@ -336,7 +336,7 @@ typedef struct apar_group_info {
 } apar_group_info;
 
 /* Starts a group: a root sequence holding the prompt (n_prompt >= 1 rows in k_dev, v_dev:
- * [n_prompt, Hkv, d]) and the root paragraph node r = PNode(p, p.len).  Errors as
+ * [n_prompt, Hkv, d]) and the root paragraph node, which starts where the prompt ends.  Errors as
  * apar_thread_create and apar_append_kv; nothing is left behind on failure. */
 APAR_API int apar_group_create(apar_pool* pool, const int32_t* prompt_tokens, int n_prompt, const void* k_dev,
                                const void* v_dev, void* hip_stream, apar_group** out);
@@ -345,10 +345,10 @@ APAR_API int apar_group_destroy(apar_group* group);
 /* Thread ids of the unfinished sequences, in creation order; n_out is always set. */
 APAR_API int apar_group_unfinished(apar_group* group, apar_thread* threads_out, int cap, int* n_out);
 /*
- * One AparDecode step (Alg. 1).  sampled[i] is the token drawn for the i-th unfinished sequence s
+ * One decoding step of Alg. 1.  sampled[i] is the token drawn for the i-th unfinished sequence s
  * (the order of apar_group_unfinished; n must equal their number).  For each s in order: if
- * s.last_token is [Fork], s is forked (s' <- s), [Child] is appended to s', two paragraph nodes
- * are created and s's current node is closed with next_sibling / first_child set; then sampled[i]
+ * s ends in [Fork], s is forked, [Child] is appended to the new sequence, s's open paragraph node is
+ * closed and two nodes are opened: the new sequence's as its first child, s's next one as its next sibling; then sampled[i]
  * is appended to s; if it is [EOS], s is finished and its cache released.  A child joins the
  * group's list from the next step on.  k_dev, v_dev: one row per appended token, in this order:
  * for each s in order, the [Child] row of its new thread if it forks, then the row of sampled[i].
@@ -366,7 +366,7 @@ APAR_API int apar_group_get_info(apar_group* group, apar_group_info* out);
 /* ---- serving loop (Sec. 3.3 "Results in High-Throughput Scenarios", App. C.2) -------------
  * Requests wait in a first-come-first-served queue over one pool.  Per decode step the caller
  * admits (apar_server_admit), lists the batch (apar_server_batch), runs apar_decode_attention
- * over its threads, samples one token per entry and applies one AparDecode step to every running
+ * over its threads, samples one token per entry and applies one decoding step of Alg. 1 to every running
  * request at once (apar_server_step): forks, one batched append of all rows, early release of
  * every sequence that drew [EOS] (Sec. 2.4 feature 2) and collection of completed requests.  The
  * paper serves through an existing paged-attention engine and says only that concurrency is
@@ -375,7 +375,9 @@ APAR_API int apar_group_get_info(apar_group* group, apar_group_info* out);
  *                free_blocks - ceil(prompt / 16) >= watermark_blocks;
  *   preemption - when a step's rows do not fit, the most recently admitted running request is
  *                released and goes back to the head of the queue (it restarts from its prompt:
- *                recomputation), and the step is retried without it until it fits. */
+ *                recomputation), and the step is retried without it until it fits.  The oldest running
+ *                request is never released: when the step does not fit with it alone, the pool is too
+ *                small for that request and apar_server_step returns OUT_OF_BLOCKS. */
 typedef struct apar_server apar_server;
 typedef struct apar_server_config {
     int32_t max_running;
@@ -415,7 +417,8 @@ APAR_API int apar_server_batch(apar_server* server, apar_server_seq* out, int ca
 /* sampled[i]: the token drawn for batch entry i (n = batch size).  k_dev, v_dev: the rows of the
  * step, request by request in batch order, each request's rows as in apar_group_step.  The entries
  * and rows of a request preempted by this call are skipped.  Errors: INVALID_ARG, THREAD_CAPACITY,
- * HIP; then no step was applied (requests preempted before the error stay preempted). */
+ * HIP, and OUT_OF_BLOCKS when the step does not fit even with the oldest running request alone; then
+ * no step was applied (requests preempted before the error stay preempted). */
 APAR_API int apar_server_step(apar_server* server, const int32_t* sampled, int n, const void* k_dev, const void* v_dev,
                               void* hip_stream, apar_server_step_info* info_out);
 /* The oldest completed request: its id (-1 if none), its tokens in Restore order (Alg. 1) and its

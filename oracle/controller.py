@@ -2,15 +2,15 @@
 
 Sequences are private token lists (a fork deep-copies the parent's list, as in dense.py);
 paragraph nodes are objects with first_child / next_sibling pointers (Sec. 2.2 "Paragraph tree");
-one call of step() is one AparDecode of Alg. 1 over the unfinished sequences; restore() is
-Restore(r): root, then first child, then next sibling.  The two savings metrics of Sec. 3.4 are
+one call of step() is one decoding step of Alg. 1 over the unfinished sequences; restore() is the
+algorithm's Restore: a node, then its first child's subtree, then its next sibling's.  The two savings metrics of Sec. 3.4 are
 counted by brute force: attended tokens = length of the sequence a token was predicted from;
 cached tokens = number of distinct token identities reachable from the unfinished sequences
 (every token carries the identity (sequence that generated it, index), and a fork copies identities).
 
 Readings fixed here (the algorithm listing leaves them open): a child created in a step starts
 decoding in the next step; the prompt is not part of the restored output (the root node starts
-at p.len); the forced [Child] token lies before its node's start, so it is not restored either.
+where the prompt ends); the forced [Child] token lies before its node's start, so it is not restored either.
 """
 from __future__ import annotations
 
@@ -67,32 +67,37 @@ class SequenceGroup:
             held.update(s.idents)
         return len(held)
 
+    def _branch_off(self, parent: Sequence_) -> Sequence_:
+        """parent ends in [Fork]: a detail thread branches off.  The new sequence starts as a copy of the
+        parent plus the forced [Child] token.  In the paragraph tree the parent's open paragraph is closed
+        where it stands; the detail paragraph hangs below it (first child) and whatever the parent writes
+        from here on comes after it on the same level (next sibling)."""
+        detail_seq = Sequence_(len(self.G), parent.tokens, parent.idents)
+        detail_seq.append_token(CHILD)
+        self.G.append(detail_seq)
+        closed = parent.current_node
+        closed.end = len(parent.tokens)
+        closed.first_child = PNode(detail_seq, len(detail_seq.tokens))
+        closed.next_sibling = PNode(parent, len(parent.tokens))
+        detail_seq.current_node, parent.current_node = closed.first_child, closed.next_sibling
+        return detail_seq
+
     def step(self, sampled: List[int]) -> List[Sequence_]:
-        """One AparDecode.  Returns the sequences whose KV rows were appended, one entry per row, in
-        order ([Child] row of a new thread, then the sampled token's row of its parent)."""
+        """One decoding step of Alg. 1 over the unfinished sequences, sampled[i] being the token drawn for
+        the i-th of them.  Returns the sequences whose KV rows were appended, one entry per row, in order
+        (the [Child] row of a new thread, then the sampled token's row of its parent)."""
         todo = self.unfinished()
         assert len(todo) == len(sampled)
         rows: List[Sequence_] = []
-        for s, x in zip(todo, sampled):
-            assert x != CHILD
-            self.attended += len(s.tokens)
+        for seq, token in zip(todo, sampled):
+            assert token != CHILD
+            self.attended += len(seq.tokens)   # the token was predicted from the whole sequence
             self.generated += 1
-            if s.last_token == FORK:
-                c = Sequence_(len(self.G), s.tokens, s.idents)
-                c.append_token(CHILD)
-                self.G.append(c)
-                rows.append(c)
-                n = PNode(s, len(s.tokens))
-                n2 = PNode(c, len(c.tokens))
-                s.current_node.end = len(s.tokens)
-                s.current_node.next_sibling = n
-                s.current_node.first_child = n2
-                s.current_node = n
-                c.current_node = n2
-            s.append_token(x)
-            rows.append(s)
-            if x == EOS:
-                s.finished = True
+            if seq.last_token == FORK:
+                rows.append(self._branch_off(seq))
+            seq.append_token(token)
+            rows.append(seq)
+            seq.finished = token == EOS        # a finished sequence no longer counts in cached_tokens()
         self.max_cached = max(self.max_cached, self.cached_tokens())
         return rows
 

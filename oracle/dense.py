@@ -8,7 +8,7 @@ copy of its rows; a fork deep-copies the parent's rows, which is the paper's own
 contiguous layout without prefix sharing (App. C.1).
 
 Readings fixed here (the paper is silent on them):
-  * the query's own K,V row is attended ("to themselves with a causal mask"):
+  * the query's own K,V row is attended (Sec. 2.2: a token sees itself under the causal mask):
     callers append the new token's row first, then decode over all len rows;
   * softmax scale is 1/sqrt(head_dim) unless given;
   * grouped-query attention: q head h reads kv head h // (Hq / Hkv);

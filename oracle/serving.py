@@ -10,7 +10,9 @@ is this build's reading, stated in the library header as well:
   step     fork every sequence whose last token is [Fork], append all rows of all requests as one
            batch; if the ledger cannot hold them, undo the forks, release the most recently admitted
            running request (it returns to the head of the queue and restarts from its prompt) and try
-           again without it;
+           again without it; the oldest running request is never released - if the step does not fit
+           with it alone the pool is too small for it and the step raises OutOfBlocks (no step applied,
+           the requests released so far stay in the queue);
   after    sequences that drew [EOS] are released at once (early release, Sec. 2.4 feature 2);
            requests with no unfinished sequence leave with Restore(r) as their output.
 """
@@ -65,6 +67,13 @@ class ServingOracle:
                             "group_size": len(g.G)})
         return out
 
+    def _requeue(self, n_live: int) -> None:
+        """The requests released in this step go back to the queue, in submission order."""
+        for r in self.running[n_live:]:
+            self.waiting.append((r["order"], r["rid"], r["prompt"]))
+        self.waiting.sort(key=lambda w: w[0])
+        self.running = self.running[:n_live]
+
     def step(self, sampled: Sequence[int]) -> dict:
         """Applies one step; returns what the library's step info reports plus, for a caller that mirrors
         the rows elsewhere: the (running index, row index) and the thread of every appended row, the
@@ -104,7 +113,8 @@ class ServingOracle:
                 for kids in kids_of:
                     for c in kids:
                         self.led.free(c)
-                if n_live == 0:
+                if n_live <= 1:
+                    self._requeue(n_live)
                     raise
                 victim = self.running[n_live - 1]
                 for s in victim["g"].unfinished():  # release in creation order
@@ -112,10 +122,7 @@ class ServingOracle:
                 n_live -= 1
                 preempted += 1
                 self.preemptions += 1
-        for r in self.running[n_live:]:
-            self.waiting.append((r["order"], r["rid"], r["prompt"]))
-        self.waiting.sort(key=lambda w: w[0])
-        self.running = self.running[:n_live]
+        self._requeue(n_live)
         info = {"n_preempted": preempted, "n_forked": 0, "n_finished_sequences": 0, "n_finished_requests": 0,
                 "n_rows_appended": len(rows), "rows": row_src, "row_threads": rows, "forks": forks, "freed": []}
         batch = 0

@@ -10,6 +10,8 @@ namespace apar {
 
 constexpr int kBlockTokens = 16;
 constexpr int32_t kCodeSealed = 1 << 30;  // flag on a (block * 16 + slot) code: the block is sealed
+constexpr int64_t kMaxPoolBlocks = (int64_t)1 << 26;  // block * 16 + slot must stay below the flag bit
+static_assert(kMaxPoolBlocks * kBlockTokens <= kCodeSealed, "a slot code must not reach the sealed flag");
 
 // ---------------------------------------------------------------------------
 // Pool layout in HBM.

@@ -610,7 +610,7 @@ int apar_pool_create(const apar_pool_config* cfg, void* kv_dev, size_t kv_bytes,
     *out = nullptr;
     if (cfg->block_size != kBlockTokens) return APAR_ERR_INVALID_ARG;
     if (cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return APAR_ERR_INVALID_ARG;
-    if (cfg->num_blocks < 1 || cfg->num_blocks >= ((int64_t)1 << 27) || cfg->max_threads < 1)
+    if (cfg->num_blocks < 1 || cfg->num_blocks > kMaxPoolBlocks || cfg->max_threads < 1)
         return APAR_ERR_INVALID_ARG;
     if (cfg->dtype != APAR_F32 && cfg->dtype != APAR_BF16) return APAR_ERR_INVALID_ARG;
     if (!(cfg->softmax_scale >= 0.0f) || !std::isfinite(cfg->softmax_scale)) return APAR_ERR_INVALID_ARG;

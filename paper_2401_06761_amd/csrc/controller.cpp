@@ -72,7 +72,7 @@ int64_t cached_tokens(const apar_group* g) {
     return total;
 }
 
-// One AparDecode step of a group in three parts, so that several groups can share one batched append:
+// One decoding step of Alg. 1 for a group, in three parts, so that several groups can share one batched append:
 // prepare forks the sequences whose last token is [Fork] and lists the threads of the rows to append
 // ([Child] row of a new thread, then the sampled token's row of its parent); commit does the bookkeeping
 // of Alg. 1 once the rows are in; rollback releases the forked children when they are not.
@@ -89,7 +89,7 @@ int step_prepare(apar_group* g, const int32_t* sampled, int n, StepPlan& sp) {
     if ((int)sp.active.size() != n) return APAR_ERR_INVALID_ARG;
     for (int i = 0; i < n; ++i)
         if (sampled[i] == APAR_TOKEN_CHILD) return APAR_ERR_INVALID_ARG;  // injected, never sampled
-    // fork first (Alg. 1: s' <- s when s.last_token is [Fork]); undone if the rows do not fit
+    // fork first (Alg. 1: a sequence that ends in [Fork] spawns a copy of itself); undone if the rows do not fit
     for (int i = 0; i < n; ++i) {
         Seq& s = g->seqs[sp.active[i]];
         if (s.last_token == APAR_TOKEN_FORK) {
@@ -113,40 +113,48 @@ void step_rollback(apar_group* g, StepPlan& sp) {
     sp.kids.clear();
 }
 
+// A sequence that ends in [Fork] gets a detail thread: the new sequence holds the parent's tokens and the
+// forced [Child] token; the parent's open paragraph ends where the parent stands, the detail paragraph
+// becomes its first child and what the parent writes next its next sibling (Alg. 1; Sec. 2.2 "Paragraph tree").
+void attach_detail_thread(apar_group* g, int32_t parent, apar_thread child_tid) {
+    const int32_t detail = (int32_t)g->seqs.size();
+    {
+        Seq d;
+        d.tid = child_tid;
+        d.parent = parent;
+        d.fork_len = (int64_t)g->seqs[parent].tokens.size();
+        d.tokens.reserve((size_t)d.fork_len + 64);
+        d.tokens = g->seqs[parent].tokens;
+        d.tokens.push_back(APAR_TOKEN_CHILD);
+        d.last_token = APAR_TOKEN_CHILD;
+        g->seqs.push_back(std::move(d));
+    }
+    const int64_t at = g->seqs[detail].fork_len;
+    const int32_t below = new_node(g, detail, at + 1);  // after the [Child] token
+    const int32_t after = new_node(g, parent, at);
+    PNode& closed = g->nodes[g->seqs[parent].current_node];
+    closed.end = at;
+    closed.first_child = below;
+    closed.next_sibling = after;
+    g->seqs[detail].current_node = below;
+    g->seqs[parent].current_node = after;
+}
+
 void step_commit(apar_group* g, const int32_t* sampled, const StepPlan& sp, apar_group_step_info* info) {
     const int n = (int)sp.active.size();
     size_t kid = 0;
     int n_finished = 0;
     for (int i = 0; i < n; ++i) {
         const int32_t q = sp.active[i];
-        g->attended += (int64_t)g->seqs[q].tokens.size();  // predicting x attended to all of s
+        g->attended += (int64_t)g->seqs[q].tokens.size();  // the sampled token was predicted from the whole sequence
         g->generated += 1;
-        if (g->seqs[q].last_token == APAR_TOKEN_FORK) {
-            Seq c;
-            c.tid = sp.kids[kid++];
-            c.tokens = g->seqs[q].tokens;
-            c.tokens.push_back(APAR_TOKEN_CHILD);
-            c.last_token = APAR_TOKEN_CHILD;
-            c.parent = q;
-            c.fork_len = (int64_t)g->seqs[q].tokens.size();
-            const int32_t cq = (int32_t)g->seqs.size();
-            g->seqs.push_back(std::move(c));
-            Seq& s = g->seqs[q];
-            const int32_t n_sib = new_node(g, q, (int64_t)s.tokens.size());
-            const int32_t n_kid = new_node(g, cq, (int64_t)g->seqs[cq].tokens.size());
-            PNode& cur = g->nodes[s.current_node];
-            cur.end = (int64_t)s.tokens.size();
-            cur.next_sibling = n_sib;
-            cur.first_child = n_kid;
-            s.current_node = n_sib;
-            g->seqs[cq].current_node = n_kid;
-        }
+        if (g->seqs[q].last_token == APAR_TOKEN_FORK) attach_detail_thread(g, q, sp.kids[kid++]);
         Seq& s = g->seqs[q];
         s.tokens.push_back(sampled[i]);
         s.last_token = sampled[i];
         if (sampled[i] == APAR_TOKEN_EOS) {
             s.finished = true;
-            (void)apar_free_thread(g->pool, s.tid);  // ReleaseCache(s)
+            (void)apar_free_thread(g->pool, s.tid);  // Alg. 1 ReleaseCache: only blocks no other thread holds go back
             ++n_finished;
         }
     }
@@ -163,7 +171,7 @@ void step_commit(apar_group* g, const int32_t* sampled, const StepPlan& sp, apar
 }
 
 int64_t restore_tokens(const apar_group* g, int32_t* tokens_out, int64_t cap) {
-    // Restore(r): node, then its first child's subtree, then its next sibling's
+    // Alg. 1 Restore: a node, then its first child's subtree, then its next sibling's
     int64_t n = 0;
     std::vector<int32_t> stack{0};
     while (!stack.empty()) {
@@ -223,7 +231,7 @@ int apar_group_create(apar_pool* pool, const int32_t* prompt_tokens, int n_promp
     s.tokens.assign(prompt_tokens, prompt_tokens + n_prompt);
     s.last_token = prompt_tokens[n_prompt - 1];
     g->seqs.push_back(std::move(s));
-    g->seqs[0].current_node = new_node(g, 0, n_prompt);  // r <- PNode(p, p.len)
+    g->seqs[0].current_node = new_node(g, 0, n_prompt);  // the root paragraph starts where the prompt ends
     g->cached_now = g->max_cached = n_prompt;
     *out = g;
     return APAR_OK;
@@ -477,7 +485,10 @@ int apar_server_step(apar_server* s, const int32_t* sampled, int n, const void* 
                                        (int)s->batch_threads.size(), k_dev, v_dev, hip_stream);
         if (rc == APAR_OK) break;
         for (size_t r = 0; r < prepared; ++r) step_rollback(s->running[r].g, s->plans[r]);
-        if (rc != APAR_ERR_OUT_OF_BLOCKS || n_live == 0) {
+        // A request that does not fit the pool even when it runs alone can never finish: requeueing it would
+        // admit it again (its prompt fits) and replay the same overflow for ever.  It stays where it is and the
+        // caller gets the error.
+        if (rc != APAR_ERR_OUT_OF_BLOCKS || n_live <= 1) {
             requeue();
             return rc;
         }

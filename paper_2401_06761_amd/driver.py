@@ -31,11 +31,14 @@ class TreeRun:
     """One workload resident in one pool."""
 
     def __init__(self, w: Workload, headroom_steps: int = 64, n_banks: int = 4, churn: float = 0.01,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", kv_of=node_kv_device):
+        """kv_of(w, node index, device) -> (k, v) rows of a tree node's segment: the seeded recipe unless a
+        caller brings rows of its own (a test whose values say which rows were read)."""
         import torch
 
         self.torch = torch
         self.w = w
+        self.kv_of = kv_of
         self.device = device
         self.churn = churn
         hd = w.heads
@@ -65,7 +68,7 @@ class TreeRun:
             if op.kind == "create":
                 assert ap.apar_thread_create(h) == op.tid
             elif op.kind == "append":
-                k, v = node_kv_device(w, op.node, self.device)
+                k, v = self.kv_of(w, op.node, self.device)
                 ap.apar_append_kv(h, op.tid, k, v, op.n_tokens)
             elif op.kind == "fork":
                 assert tuple(ap.apar_fork(h, op.tid, len(op.children))) == op.children

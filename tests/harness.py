@@ -22,6 +22,49 @@ def to_host(t) -> np.ndarray:
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
+# bf16 pools: the bound the task states (max abs 2e-2) says little where outputs are small, so every bf16
+# comparison also holds the error to the size of the outputs compared.  An output element is rounded to bf16
+# once (relative 2^-8) and the probabilities once before the P.V product (2^-8 each, averaging out over the
+# row): 2^-6 of the largest expected magnitude leaves a factor of about three over what is observed and is
+# failed by an output of zeros, by a row of another thread and by a missing or foreign block.
+REL_BF16 = 2.0 ** -6
+
+
+def assert_close(got: np.ndarray, want: np.ndarray, dtype: str, what: str = "") -> float:
+    """max abs error of got against want (fp64 arrays), asserted against both bounds; returns it."""
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = float(np.abs(got - want).max())
+    if dtype == "f32":
+        assert err <= 1e-5, f"{what}: max abs err {err}"
+    else:
+        top = float(np.abs(want).max())
+        assert err <= 2e-2, f"{what}: max abs err {err}"
+        assert err <= REL_BF16 * top, f"{what}: max abs err {err} against outputs of magnitude {top}"
+    return err
+
+
+# Values that say which token they belong to (for checks with a zero query, whose output is the plain mean of
+# the V rows on a thread's root path).  Per token id, 128 channels: 0..23 the id's bits, 64..87 their
+# complements, 40..63 twenty-four pseudo-random signs of the id (+-1, balanced, so that their means are small
+# and bf16 resolves a change of a few counts at any path length); 32..39 and 96..103 are left for the caller
+# (the kv head's bits).  Sums of these values over up to 2^24 rows are exact in fp32.
+N_ID_BITS = 24
+_HASH_MULT = np.array([0x9E3779B1 + 2 * 0x632BE5AB * j for j in range(24)], dtype=np.uint64)
+
+
+def id_channels(ids: np.ndarray) -> np.ndarray:
+    ids = np.asarray(ids, dtype=np.int64)
+    out = np.zeros((len(ids), 128), dtype=np.float32)
+    bits = ((ids[:, None] >> np.arange(N_ID_BITS)) & 1).astype(np.float32)
+    out[:, :N_ID_BITS] = bits
+    out[:, 64:64 + N_ID_BITS] = 1.0 - bits
+    mixed = ((ids[:, None].astype(np.uint64) + np.uint64(1)) * _HASH_MULT[None, :]) & np.uint64(0xFFFFFFFF)
+    mixed ^= mixed >> np.uint64(15)
+    mixed = (mixed * np.uint64(0x2C1B3C6D)) & np.uint64(0xFFFFFFFF)
+    out[:, 40:64] = 1.0 - 2.0 * ((mixed >> np.uint64(13)) & np.uint64(1)).astype(np.float32)
+    return out
+
+
 def books_equal(handle, led: BlockLedger, check_blocks: Optional[Sequence[int]] = None) -> None:
     """Block tables, lengths, refcounts and counters of the library against the ledger, bit-exact."""
     for t in led.live():

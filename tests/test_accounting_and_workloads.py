@@ -25,6 +25,31 @@ def test_star_closed_forms(R, k, L):
     assert acc.path_lens(parents, segs)[1:] == [R + L] * k
 
 
+def test_flatten_order_on_a_hand_worked_depth_two_tree():
+    # Sec. 3.4 compares with the ordinary auto-regressive output of the same response, i.e. the paragraph tree
+    # linearised in the order Alg. 1 restores it: a node, then its first child's subtree, then what followed.
+    # Hand-worked, nodes in creation order (children created breadth first, so that depth-first and
+    # breadth-first numbering disagree):
+    #   0 root (5 tokens)  children 1, 2, 3
+    #   1 (3 tokens)       children 4, 5        2 (2 tokens) no children        3 (4 tokens) child 6
+    #   4 (7)   5 (1)   6 (6)
+    # depth-first order of the nodes: 0 1 4 5 2 3 6, so the first tokens sit at
+    #   0: 0   1: 5   4: 8   5: 15   2: 16   3: 18   6: 22      (total 28 tokens)
+    # (breadth first would put node 2 at 8 and node 4 at 14).
+    parents = [-1, 0, 0, 0, 1, 1, 3]
+    segs = [5, 3, 2, 4, 7, 1, 6]
+    assert acc.flatten_offsets(parents, segs) == [0, 5, 16, 18, 8, 15, 22]
+    # attended tokens of the linearised sequence: token at position p (0-based) attends to p + 1 tokens
+    assert acc.attended_tokens_flatten(parents, segs) == 28 * 29 // 2
+    # in the tree a token sees its root path only: prefixes 0 / 5 5 5 / 8 8 / 9
+    pre = [0, 5, 5, 5, 8, 8, 9]
+    assert acc.prefix_lens(parents, segs) == pre
+    # per node seg * prefix + seg (seg + 1) / 2:  15 + 21 + 13 + 30 + 84 + 9 + 75
+    assert acc.attended_tokens_tree(parents, segs) == 247
+    # a second tree after it starts again at 0
+    assert acc.flatten_offsets(parents + [-1, 7], segs + [4, 2]) == [0, 5, 16, 18, 8, 15, 22, 0, 4]
+
+
 def test_tree_never_attends_more_than_flatten():
     w = make_config("ht256", n_requests=12)
     parents = [n.parent for n in w.nodes]

@@ -36,11 +36,14 @@ def _parse_golden():
 def test_oracle_worked_example():
     prompt, steps, want = _parse_golden()
     g = SequenceGroup(prompt)
+    cached = []
     for s in steps:
         g.step(s)
+        cached.append(g.cached_tokens())
     assert g.is_finished()
     assert g.restore() == want["restore"]
     assert g.attended == want["attended"][0] and g.generated == want["generated"][0]
+    assert cached == want["cached"] and g.max_cached == want["max_cached"][0]
 
 
 def test_oracle_without_forks_is_plain_decoding():
@@ -151,8 +154,12 @@ def test_golden_example_through_the_library():
     prompt, steps, want = _parse_golden()
     with ap.Pool(2, 2, 64, "f32", 16, dry_run=True) as pool:
         grp = ap.apar_group_create(pool.handle, prompt, None, None)
+        cached = []
         for s in steps:
             ap.apar_group_step(grp, s, None, None)
+            cached.append(ap.apar_group_get_info(grp).cached_tokens)
+        assert cached == want["cached"]
+        assert ap.apar_group_get_info(grp).max_cached_tokens == want["max_cached"][0]
         assert ap.apar_group_unfinished(grp) == []
         assert ap.apar_group_restore(grp) == want["restore"]
         gi = ap.apar_group_get_info(grp)

@@ -13,7 +13,7 @@ from apar_workloads import (HeadConfig, make_config, manual_tree, mask_rows_from
                             node_kv, quantise, step_q, tiny_tree)
 from oracle import BlockLedger, DenseThreads
 
-from harness import blocks_upper_bound, books_equal, check_plan_covers_tables, nested_wide_tree, pool_for, random_forest, replay_trace, to_dev, to_host
+from harness import assert_close, blocks_upper_bound, books_equal, check_plan_covers_tables, nested_wide_tree, pool_for, random_forest, replay_trace, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -59,9 +59,7 @@ def run_workload(w, chunk=None, check_each=False, sample=None, matrix_rows=None)
         live, nodes = replay_trace(w, pool, led, dense, check_each=check_each)
         books_equal(pool.handle, led)
         got, want = decode_both(w, pool, dense, live)
-        err = np.abs(got - want).max()
-        assert np.isfinite(got).all()
-        assert err <= TOL[hd.dtype], f"max abs err {err}"
+        err = assert_close(got, want, hd.dtype, w.name)
         info = ap.apar_last_plan_info(pool.handle)
         assert info.unique_blocks == led.used_blocks()
         return err, info

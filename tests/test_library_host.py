@@ -175,7 +175,7 @@ def test_error_codes_and_noops():
         assert ap.apar_thread_block_table(h, c) == [0, 1, 2, 3]
         ap.apar_free_thread(h, c)
         assert ap.apar_pool_stats(h).free_blocks == 4
-    for bad in (dict(block_size=8), dict(n_q_heads=3), dict(num_blocks=0), dict(dtype=7)):
+    for bad in (dict(block_size=8), dict(n_q_heads=3), dict(num_blocks=0), dict(num_blocks=(1 << 26) + 1), dict(dtype=7)):
         kw = dict(n_q_heads=4, n_kv_heads=2, head_dim=64, block_size=16, dtype=0, max_threads=8, num_blocks=4,
                   softmax_scale=0.0)
         kw.update(bad)

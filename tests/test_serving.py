@@ -215,3 +215,50 @@ def test_server_argument_checks():
     assert ap.apar_pool_stats(pool.handle).used_blocks == 0
     ap.apar_server_destroy(srv)
     pool.close()
+
+
+def test_a_request_that_outgrows_the_pool_is_an_error_not_an_endless_replay():
+    # one request whose response needs more blocks than the pool has: its prompt fits, so a policy that sent it
+    # back to the queue would admit it again and replay the same overflow for ever.  The oldest running request
+    # is never released; the step that does not fit returns OUT_OF_BLOCKS, in the library and in the oracle
+    # alike, and leaves the books as they were.
+    reqs = make_requests(1, seed=4, prompt_lo=40, prompt_hi=40)
+    n_blocks = 4  # 64 token slots; the sampler writes at least 12 tokens per sequence and up to 260
+    led = BlockLedger(n_blocks, max_threads=1 << 30)
+    o = ServingOracle(led, 4, 0)
+    pool = ap.Pool(4, 2, 64, "f32", n_blocks, max_threads=1 << 30, dry_run=True)
+    srv = ap.apar_server_create(pool.handle, 4, 0)
+    for r in reqs:
+        o.submit(r.rid, r.prompt_tokens())
+        ap.apar_server_submit(srv, r.rid, r.prompt_tokens())
+    assert o.admit() == [0] and ap.apar_server_admit(srv, None, None, 1 << 30) == (1, 40)
+    from oracle.ledger import OutOfBlocks
+
+    for step in range(400):
+        b = o.batch()
+        lb = ap.apar_server_batch(srv)
+        assert [e["thread"] for e in b] == lb["thread"].tolist() and b, "the request must still be running"
+        xs = sample_tokens(CFG, [reqs[0].seed] * len(b), [e["seq_index"] for e in b], [e["length"] for e in b],
+                           [e["last_token"] for e in b], [e["start_len"] for e in b], [e["group_size"] for e in b])
+        # keep the response going: an [EOS] would let it finish before the pool is full
+        xs = np.where(xs == ap.APAR_TOKEN_EOS, 5, xs).astype(np.int32)
+        before = ap.apar_pool_stats(pool.handle)
+        try:
+            o.step(xs.tolist())
+        except OutOfBlocks:
+            with pytest.raises(ap.AparError) as e:
+                ap.apar_server_step(srv, xs, None, None)
+            assert e.value.status == -3
+            after = ap.apar_pool_stats(pool.handle)
+            assert (after.used_blocks, after.live_threads) == (before.used_blocks, before.live_threads)
+            st = ap.apar_server_get_stats(srv)
+            assert st.n_running == 1 and st.n_waiting == 0 and st.n_preemptions == 0
+            assert len(o.running) == 1 and not o.waiting and o.preemptions == 0
+            books_equal(pool.handle, led)
+            break
+        ap.apar_server_step(srv, xs, None, None)
+        books_equal(pool.handle, led)
+    else:
+        raise AssertionError("the pool never filled up")
+    ap.apar_server_destroy(srv)
+    pool.close()
