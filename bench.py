@@ -24,67 +24,122 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 
-def cpu_baseline(w_name: str, seed: int, n_req: int, device: str):
-    """The fp64 oracle, as it stands, on the first n_req requests of the same workload."""
-    import numpy as np
-    import torch
+def _oracle_requests(task):
+    """Worker of the cpu_baseline leg (its own process: numpy and the oracle only, one BLAS thread).
+    Decodes one step for every live thread of the given requests of a workload with the fp64 oracle as it
+    stands; returns (pid, threads, attended tokens, seconds decoding, seconds materialising the copies)."""
+    w_name, seed, n_req, requests = task
+    import numpy as np  # noqa: F401
+    from threadpoolctl import threadpool_limits
 
-    from apar_workloads import build_trace, make_config, node_kv_device, rows_device
+    from apar_workloads import build_trace, make_config, manual_tree, node_kv, step_q
     from oracle import DenseThreads
 
     w = make_config(w_name, seed=seed, n_requests=n_req)
     hd = w.heads
-    dense = DenseThreads(hd.n_q_heads, hd.n_kv_heads, hd.head_dim)
-    ops, live, _ = build_trace(w)
-    t0 = time.perf_counter()
-    for op in ops:
-        if op.kind == "create":
-            dense.create()
-        elif op.kind == "append":
-            k, v = node_kv_device(w, op.node, device)
-            dense.append(op.tid, k.float().cpu().numpy(), v.float().cpu().numpy())
-        elif op.kind == "fork":
-            dense.fork(op.tid, len(op.children))
-        else:
-            dense.free(op.tid)
-    t_mat = time.perf_counter() - t0
-    q = rows_device(w, 1, 0, (len(live), hd.n_q_heads, hd.head_dim), device).float().cpu().numpy()
-    try:
-        from threadpoolctl import threadpool_info
+    n_thr = attended = 0
+    t_dec = t_mat = 0.0
+    with threadpool_limits(limits=1):
+        for r in requests:
+            idx = [n.idx for n in w.nodes if n.request == r]
+            base = idx[0]
+            sub = manual_tree([-1 if w.nodes[i].parent < 0 else w.nodes[i].parent - base for i in idx],
+                              [w.nodes[i].seg_len for i in idx], hd, seed=seed + 1000 * r, data_scale=w.data_scale)
+            dense = DenseThreads(hd.n_q_heads, hd.n_kv_heads, hd.head_dim)
+            ops, live, _ = build_trace(sub)
+            t0 = time.perf_counter()
+            for op in ops:
+                if op.kind == "create":
+                    dense.create()
+                elif op.kind == "append":
+                    dense.append(op.tid, *node_kv(sub, op.node))
+                elif op.kind == "fork":
+                    dense.fork(op.tid, len(op.children))
+                else:
+                    dense.free(op.tid)
+            q = step_q(sub, 0, len(live))
+            t1 = time.perf_counter()
+            dense.decode(q, live)
+            t2 = time.perf_counter()
+            t_mat += t1 - t0
+            t_dec += t2 - t1
+            n_thr += len(live)
+            attended += sum(dense.length(t) for t in live)
+    return os.getpid(), n_thr, attended, t_dec, t_mat
 
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = 1
+
+def cpu_baseline(w_name: str, seed: int, n_req: int, n_total: int):
+    """The fp64 oracle, as it stands, on the first n_req requests of the same workload shapes, spread over
+    the host cores with a process pool over requests (one BLAS thread per worker).  Runs before the GPU
+    is touched, in spawned processes that import numpy and the oracle only; the rows are drawn on the host
+    by the seeded recipe (their values do not change the oracle's work)."""
+    import multiprocessing as mp
+
+    from apar_workloads import make_config
+
+    workers = max(1, min(16, os.cpu_count() or 1, n_req))  # a one-GPU box gives a job 16 cores whatever it shows
+    hd = make_config(w_name, seed=seed, n_requests=1).heads
+    tasks = [(w_name, seed, n_req, list(range(i, n_req, 4 * workers))) for i in range(min(4 * workers, n_req))]
     t0 = time.perf_counter()
-    dense.decode(q, live)
-    t_dec = time.perf_counter() - t0
-    attended = sum(dense.length(t) for t in live)
+    with mp.get_context("spawn").Pool(workers) as pool:
+        t_up = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        got = list(pool.imap_unordered(_oracle_requests, tasks))
+        wall = time.perf_counter() - t0
+    per_pid = {}
+    for pid, n, att, t_dec, t_mat in got:
+        d = per_pid.setdefault(pid, [0.0, 0.0])
+        d[0] += t_dec
+        d[1] += t_mat
+    n_thr = sum(g[1] for g in got)
+    attended = sum(g[2] for g in got)
+    dec = max(d[0] for d in per_pid.values())  # the decode phase ends when the slowest worker is done
     return {
-        "value": len(live) / t_dec,
+        "value": n_thr / dec,
         "unit": "thread-queries/s",
-        "cores": int(cores),
+        "cores": len(per_pid),
+        "blas_threads_per_worker": 1,
         "host_cpus": os.cpu_count(),
         "kind": "oracle",
-        "sample": f"first {n_req} requests of {w_name} (seed {seed}): {len(live)} threads, {attended} attended "
-                  f"tokens, fp64 dense attention over deep-copied per-thread rows; decode {t_dec:.2f} s "
-                  f"(materialising the copies took another {t_mat:.2f} s, not counted)",
-        "effective_GBps": attended * hd.kv_bytes_per_token / t_dec / 1e9,
+        "sample": f"first {n_req} of {n_total} requests of {w_name} (seed {seed}): {n_thr} threads, {attended} "
+                  f"attended tokens, fp64 dense attention over deep-copied per-thread rows, a process pool over "
+                  f"requests; decode time of the slowest of {len(per_pid)} workers {dec:.2f} s (sum over workers "
+                  f"{sum(d[0] for d in per_pid.values()):.1f} s; materialising the copies another "
+                  f"{sum(d[1] for d in per_pid.values()):.1f} s, not counted; whole pool.map {wall:.1f} s after "
+                  f"{t_up:.1f} s of start-up)",
+        "effective_GBps": attended * hd.kv_bytes_per_token / dec / 1e9,
     }
 
 
-def read_traffic(workload: str):
-    """HBM bytes per launch of the attention kernel from the committed rocprofv3 counter summary."""
+def read_traffic(workload: str, algorithmic_bytes: float):
+    """HBM traffic of a launch as algorithmic bytes x (fetched + written) / algorithmic, the ratio taken from
+    the committed rocprofv3 counter summary of the same workload (counters cannot be read from inside the
+    run; the ratio, unlike the byte count, does not depend on how many steps a run takes).
+    Returns (traffic bytes, ratio, source) or (None, None, None)."""
     path = os.path.join(ROOT, "profiles", f"attention_bf16_{workload}_pmc.txt")
+    vals = {}
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split()[1])
+            f = line.split()
+            if len(f) == 2 and not line.startswith("#"):
+                try:
+                    vals[f[0]] = float(f[1])
+                except ValueError:
+                    pass
     except OSError:
-        pass
-    return None
+        return None, None, None
+    need = ("fetch_bytes_per_launch", "write_bytes_per_launch", "algorithmic_bytes_per_launch_same_launches")
+    if any(k not in vals for k in need):
+        return None, None, None
+    ratio = (vals[need[0]] + vals[need[1]]) / vals[need[2]]
+    return algorithmic_bytes * ratio, ratio, os.path.relpath(path, ROOT)
 
 
-def spec_loop(args, w) -> int:
+def _pct(sorted_ms, p):
+    return sorted_ms[min(len(sorted_ms) - 1, int(round(p * (len(sorted_ms) - 1))))] if sorted_ms else None
+
+
+def spec_loop(args, w, K=None, warmup=None) -> dict:
     """The speculative decode loop: every step is multi-candidate attention (5 candidates per thread under
     a random tree mask), append of the accepted rows, release of finished threads, fork of new ones."""
     import torch
@@ -93,17 +148,18 @@ def spec_loop(args, w) -> int:
     from paper_2401_06761_amd.driver import SpecRun
 
     hd = w.heads
-    K = args.steps
+    K = args.steps if K is None else K
+    warmup = args.warmup if warmup is None else warmup
     t0 = time.perf_counter()
-    run = SpecRun(w, K + args.warmup, n_cand=5, commit=not args.two_pass)
+    run = SpecRun(w, K + warmup, n_cand=5, commit=not args.two_pass)
     t_dry = time.perf_counter() - t0
     run.build()
     if args.chunk:
         ap.apar_set_chunk_blocks(run.h, args.chunk)
     if args.matrix_units:
         ap.apar_set_matrix_units(run.h, *(int(x) for x in args.matrix_units.split(",")))
-    run.draw_ahead(args.warmup + K)  # the synthetic step plans (masks, accepted chains, coins) exist before the clock starts
-    for _ in range(args.warmup):
+    run.draw_ahead(warmup + K)  # the synthetic step plans (masks, accepted chains, coins) exist before the clock starts
+    for _ in range(warmup):
         run.step()
     torch.cuda.synchronize()
     ap.apar_profile_read(run.h)
@@ -120,11 +176,13 @@ def spec_loop(args, w) -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = ap.apar_profile_read(run.h)
+    calls_ms = sorted(ap.apar_profile_attention_calls(run.h))
     st1 = ap.apar_pool_stats(run.h)
     attn_ms = prof.attention_kernel_ms / K
+    traffic, ratio, source = read_traffic("spec128", alg / K)
     result = {
         "metric": "decode-attn thread-queries/s + achieved HBM GB/s on fork-tree paged KV",
-        "value": n_q / elapsed, "unit": "thread-queries/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "value": n_q / elapsed, "unit": "thread-queries/s", "n_gpus": 1, "steps": K, "warmup": warmup,
         "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": hd.dtype, "data": "synthetic",
         "config": {"workload": f"spec128: {w.n_requests} requests, depth-2 fork trees, then a {K}-step speculative "
@@ -135,8 +193,10 @@ def spec_loop(args, w) -> int:
         "candidate_queries_per_s": 5 * n_q / elapsed,
         "roofline": {"bound": "hbm", "kernel": "attention_bf16 (multi-candidate call)",
                      "achieved": (alg / K) / (attn_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": (alg / K) / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": read_traffic("spec128"),
-                     "algorithmic_bytes_per_launch": alg / K, "kernel_ms_per_launch": attn_ms},
+                     "frac": (alg / K) / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_over_algorithmic": ratio, "traffic_ratio_from": source,
+                     "algorithmic_bytes_per_launch": alg / K, "kernel_ms_per_launch": attn_ms,
+                     "kernel_ms_median_p10_p90": [_pct(calls_ms, 0.5), _pct(calls_ms, 0.1), _pct(calls_ms, 0.9)]},
         "breakdown_ms_per_step": {"attention_kernel": attn_ms, "merge_kernel": prof.merge_kernel_ms / K,
                                   "append_kernels": prof.append_kernels_ms / K, "plan_host": prof.plan_host_ms / K,
                                   "host_issue": t_host / K * 1e3, "host_waiting_for_gpu": prof.host_wait_ms / K},
@@ -146,8 +206,7 @@ def spec_loop(args, w) -> int:
                      "ratio": st1.bytes_vanilla / max(st1.bytes_resident, 1)},
     }
     run.close()
-    print(json.dumps(result))
-    return 0
+    return result
 
 
 def prefill_bench(args, w) -> int:
@@ -343,62 +402,19 @@ def serving_bench(args) -> int:
     return 0
 
 
-def main() -> int:
-    ap_ = argparse.ArgumentParser()
-    ap_.add_argument("--gpus", type=int, default=1)
-    ap_.add_argument("--steps", type=int, default=50)
-    ap_.add_argument("--warmup", type=int, default=10)
-    ap_.add_argument("--config", default="ht256", choices=["mha64", "ht256", "gqa1024", "spec128"])
-    ap_.add_argument("--seed", type=int, default=0)
-    ap_.add_argument("--requests", type=int, default=None, help="first n requests only (debugging)")
-    ap_.add_argument("--chunk", type=int, default=None, help="blocks per work unit")
-    ap_.add_argument("--churn", type=float, default=0.01)
-    ap_.add_argument("--cpu-requests", type=int, default=64)
-    ap_.add_argument("--no-cpu-baseline", action="store_true")
-    ap_.add_argument("--prefill-kernel", choices=("auto", "row_tiles", "matrix"), default="auto",
-                     help="with --prefill: let the library choose the kernel per call, or force one")
-    ap_.add_argument("--matrix-units", default=None, metavar="ROWS,BLOCKS",
-                     help="thresholds from which a stand-alone shared segment runs on the 32x32 kernel (library default 256,128; 0,0 never)")
-    ap_.add_argument("--shared-prefix", action="store_true",
-                     help="measure decode attention over long prefixes shared by 512 threads, row-tile vs matrix units")
-    ap_.add_argument("--prefill", action="store_true",
-                     help="measure apar_prefill_attention over the workload's segments instead of the decode step")
-    ap_.add_argument("--serving", action="store_true",
-                     help="measure the serving loop (admission, early release, preemption) against the pool size")
-    ap_.add_argument("--max-running", type=int, default=64)
-    ap_.add_argument("--two-pass", action="store_true",
-                     help="spec128: gather the accepted rows on the caller's side and append them with "
-                          "apar_append_kv_batch instead of apar_commit_candidates")
-    ap_.add_argument("--copy-calibration", action="store_true",
-                     help="also run one plain 4 GiB device copy (reference for HBM byte counters)")
-    args = ap_.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by request with no exchange; "
-              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
-        return 2
-
+def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None) -> dict:
+    """Decode steps over one resident fork-tree workload (mha64, ht256, gqa1024); returns the result line."""
     import torch
 
     import paper_2401_06761_amd as ap
     from apar_workloads import make_config
     from paper_2401_06761_amd.driver import TreeRun
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 3
     dev = "cuda:0"
-    w = make_config(args.config, seed=args.seed, n_requests=args.requests)
+    w = make_config(name, seed=args.seed, n_requests=n_requests)
     hd = w.heads
-    if args.shared_prefix:
-        return shared_prefix_bench(args)
-    if args.serving:
-        return serving_bench(args)
-    if args.prefill:
-        return prefill_bench(args, w)
-    if args.config == "spec128":
-        return spec_loop(args, w)
     t_build = time.perf_counter()
-    run = TreeRun(w, headroom_steps=args.steps + args.warmup + 8, churn=args.churn, device=dev)
+    run = TreeRun(w, headroom_steps=steps + warmup + 8, churn=args.churn, device=dev)
     run.build()
     t_build = time.perf_counter() - t_build
     if args.chunk:
@@ -414,7 +430,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         run.step()
     torch.cuda.synchronize()
     ap.apar_profile_read(run.h)
@@ -424,7 +440,7 @@ def main() -> int:
     n_queries = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         run.step()
         info = ap.apar_last_plan_info(run.h)
         alg_bytes += info.algorithmic_bytes
@@ -440,21 +456,19 @@ def main() -> int:
     st1 = ap.apar_pool_stats(run.h)
     info = ap.apar_last_plan_info(run.h)
 
-    def pct(p):
-        return calls_ms[min(len(calls_ms) - 1, int(round(p * (len(calls_ms) - 1))))] if calls_ms else None
-
-    K = args.steps
+    K = steps
     attn_ms = prof.attention_kernel_ms / K
     merge_ms = prof.merge_kernel_ms / K
     append_ms = prof.append_kernels_ms / max(prof.n_append_calls, 1)
     achieved = (alg_bytes / K) / (attn_ms * 1e-3) / 1e9
+    traffic, ratio, source = read_traffic(name, alg_bytes / K)
     result = {
         "metric": "decode-attn thread-queries/s + achieved HBM GB/s on fork-tree paged KV",
         "value": n_queries / elapsed,
         "unit": "thread-queries/s",
         "n_gpus": 1,
         "steps": K,
-        "warmup": args.warmup,
+        "warmup": warmup,
         "ms_per_step": elapsed / K * 1e3,
         "higher_is_better": True,
         "scaling": "weak",
@@ -462,7 +476,7 @@ def main() -> int:
         "dtype": hd.dtype,
         "data": "synthetic",
         "config": {
-            "workload": f"{args.config}: {w.n_requests} requests, fork trees of depth "
+            "workload": f"{name}: {w.n_requests} requests, fork trees of depth "
                         f"{max(n.depth for n in w.nodes)}, {len(run.live)} live threads, Hq={hd.n_q_heads} "
                         f"Hkv={hd.n_kv_heads} d={hd.head_dim} block=16, seed {args.seed}",
             "step": "fork+free churn %.3g of threads, append 1 KV row per thread, decode attention over all "
@@ -478,10 +492,12 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": read_traffic(args.config),
+            "traffic": traffic,
+            "traffic_over_algorithmic": ratio,
+            "traffic_ratio_from": source,
             "algorithmic_bytes_per_launch": alg_bytes / K,
             "kernel_ms_per_launch": attn_ms,
-            "kernel_ms_median_p10_p90": [pct(0.5), pct(0.1), pct(0.9)],
+            "kernel_ms_median_p10_p90": [_pct(calls_ms, 0.5), _pct(calls_ms, 0.1), _pct(calls_ms, 0.9)],
         },
         "breakdown_ms_per_step": {
             "attention_kernel": attn_ms,
@@ -505,9 +521,98 @@ def main() -> int:
                  "unique_blocks": info.unique_blocks},
         "build_s": t_build,
     }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(args.config, args.seed, min(args.cpu_requests, w.n_requests), dev)
     run.close()
+    del run
+    torch.cuda.empty_cache()
+    return result
+
+
+def _secondary_view(r: dict) -> dict:
+    """What the headline line keeps of another configuration's result."""
+    keep = ("value", "unit", "steps", "warmup", "ms_per_step", "config", "roofline", "breakdown_ms_per_step",
+            "kv_bytes", "candidate_queries_per_s", "attention_call_thread_queries_per_s", "build_s")
+    return {k: r[k] for k in keep if k in r}
+
+
+def main() -> int:
+    ap_ = argparse.ArgumentParser()
+    ap_.add_argument("--gpus", type=int, default=1)
+    ap_.add_argument("--steps", type=int, default=50)
+    ap_.add_argument("--warmup", type=int, default=10)
+    ap_.add_argument("--config", default="ht256", choices=["mha64", "ht256", "gqa1024", "spec128"])
+    ap_.add_argument("--seed", type=int, default=0)
+    ap_.add_argument("--requests", type=int, default=None, help="first n requests only (debugging)")
+    ap_.add_argument("--chunk", type=int, default=None, help="blocks per work unit")
+    ap_.add_argument("--churn", type=float, default=0.01)
+    ap_.add_argument("--cpu-requests", type=int, default=128,
+                     help="requests of the workload the oracle decodes for the cpu_baseline leg")
+    ap_.add_argument("--no-cpu-baseline", action="store_true",
+                     help="skip the oracle (use under rocprofv3: the leg starts worker processes)")
+    ap_.add_argument("--no-secondary", action="store_true",
+                     help="only the named configuration (default: ht256 as the headline plus mha64, gqa1024 and a "
+                          "spec128 loop under 'secondary')")
+    ap_.add_argument("--spec-steps", type=int, default=256, help="steps of the secondary spec128 loop")
+    ap_.add_argument("--prefill-kernel", choices=("auto", "row_tiles", "matrix"), default="auto",
+                     help="with --prefill: let the library choose the kernel per call, or force one")
+    ap_.add_argument("--matrix-units", default=None, metavar="ROWS,BLOCKS",
+                     help="thresholds from which a stand-alone shared segment runs on the 32x32 kernel (library default 256,128; 0,0 never)")
+    ap_.add_argument("--shared-prefix", action="store_true",
+                     help="measure decode attention over long prefixes shared by 512 threads, row-tile vs matrix units")
+    ap_.add_argument("--prefill", action="store_true",
+                     help="measure apar_prefill_attention over the workload's segments instead of the decode step")
+    ap_.add_argument("--serving", action="store_true",
+                     help="measure the serving loop (admission, early release, preemption) against the pool size")
+    ap_.add_argument("--max-running", type=int, default=64)
+    ap_.add_argument("--two-pass", action="store_true",
+                     help="spec128: gather the accepted rows on the caller's side and append them with "
+                          "apar_append_kv_batch instead of apar_commit_candidates")
+    ap_.add_argument("--copy-calibration", action="store_true",
+                     help="also run one plain 4 GiB device copy (reference for HBM byte counters)")
+    args = ap_.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by request with no exchange; "
+              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        return 2
+    special = args.shared_prefix or args.serving or args.prefill
+    headline_default = not special and args.config == "ht256" and args.requests is None
+
+    # The oracle leg comes first: it starts worker processes, which must happen before this process touches the GPU.
+    cpu = None
+    if not special and not args.no_cpu_baseline:
+        from apar_workloads import make_config as _mk
+
+        n_total = _mk(args.config, seed=args.seed, n_requests=args.requests).n_requests
+        cpu = cpu_baseline(args.config, args.seed, min(args.cpu_requests, n_total), n_total)
+
+    import torch
+
+    from apar_workloads import make_config
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    if args.shared_prefix:
+        return shared_prefix_bench(args)
+    if args.serving:
+        return serving_bench(args)
+    w = make_config(args.config, seed=args.seed, n_requests=args.requests)
+    if args.prefill:
+        return prefill_bench(args, w)
+    if args.config == "spec128":
+        result = spec_loop(args, w)
+    else:
+        result = tree_bench(args, args.config, args.steps, args.warmup, args.requests)
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
+    if headline_default and not args.no_secondary:
+        # the other configurations, each a run of its own after the headline's pool is gone; short enough
+        # for the whole command to stay within a couple of minutes
+        sec = {}
+        sec["mha64"] = _secondary_view(tree_bench(args, "mha64", min(args.steps, 50), min(args.warmup, 10)))
+        sec["gqa1024"] = _secondary_view(tree_bench(args, "gqa1024", min(args.steps, 20), min(args.warmup, 5)))
+        sec["spec128_loop"] = _secondary_view(spec_loop(args, make_config("spec128", seed=args.seed),
+                                                        K=args.spec_steps, warmup=0))
+        result["secondary"] = sec
     print(json.dumps(result))
     return 0
 
