@@ -20,14 +20,15 @@
 // output written directly.  Inside such a unit a block whose holders all sit in one
 // wavefront goes on that wavefront's private list (no barrier, registers only);
 // blocks needed by several wavefronts go on the shared list (staged once in LDS).
-// Subtrees with too many rows or blocks are cut at their top segment and its children
-// are tried again.  A top segment with too many ROWS below it is inlined where it is
-// short enough: its threads are cut into units of consecutive ranks (whole child
-// subtrees where they fit) and each of those units reads the segment's blocks again,
-// as often as stand-alone units would, with nothing to merge afterwards.  Otherwise it
-// stands alone, chunked, with one partial result per (chunk, thread); long ones with
-// many rows as matrix units.  Attention is a set operation, so a unit may visit its
-// blocks in any order.
+// A subtree with too many ROWS for one workgroup is cut by rank instead: its threads,
+// in depth-first order, go to units of consecutive ranks, every unit full, and a unit
+// reads every segment on the root paths of its threads - the segments near the root
+// once per unit (as often as stand-alone units would read them), everything for its
+// rows' state to stay in registers, nothing to merge afterwards.  Only where that does
+// not work (partial results above, more blocks than a unit may be given, long segments
+// with many rows that are better off on the matrix kernel) a top segment stands alone,
+// chunked, with one partial result per (chunk, thread), and its children are tried
+// again.  Attention is a set operation, so a unit may visit its blocks in any order.
 #include "plan.hpp"
 
 #include <algorithm>
@@ -110,26 +111,21 @@ struct Builder {
         if (n_plain < nb) open.push_back(TileRef{blk[b0 + nb - 1], make_meta(lo, hi, s.last_valid)});
     }
 
-    // Segment sid stands alone: chunks of its blocks, one partial result per (chunk, thread).  `anc` (-1:
-    // none) is the inlined chain directly above it, whose blocks (all full: every segment of the chain has
-    // children) its first chunk reads too.
-    void emit_standalone(int32_t sid, int32_t anc) {
+    // Segment sid stands alone: chunks of its blocks, one partial result per (chunk, thread).
+    void emit_standalone(int32_t sid) {
         PlanHost::Segment& s = ph.segs[sid];
         const int groups = s.n_shr * n_sl;
         const int chunk = std::max(1, prm.max_unit_tiles);
-        const int chain = anc >= 0 ? inline_blocks[anc] : 0;  // <= chunk / 2
-        const int first_nb = std::min(s.n_blk, chunk - chain);
+        const int first_nb = std::min(s.n_blk, chunk);
         const int nch = 1 + (s.n_blk - first_nb + chunk - 1) / chunk;
         n_chunks[sid] = nch;
         part0[sid] = (int32_t)ph.n_partial_rows;
         ph.n_partial_rows += (int64_t)nch * s.n_shr;
         ph.any_partial = true;
         const int32_t grp0 = s.t_lo * n_sl;
-        // the chunk's tiles for row groups [0, hi) of a list owner: the chain first (chunk 0 only)
-        auto chunk_tiles = [&](int c, int b0, int nb, int hi) {
+        // the chunk's tiles for row groups [0, hi) of a list owner
+        auto chunk_tiles = [&](int, int b0, int nb, int hi) {
             ph.open_tmp.clear();
-            if (c == 0)
-                for (int32_t a = anc; a >= 0; a = ph.segs[a].parent) push_tiles(ph.tiles, ph.open_tmp, ph.segs[a], 0, ph.segs[a].n_blk, 0, hi);
             push_tiles(ph.tiles, ph.open_tmp, s, b0, nb, 0, hi);
         };
         for (int c = 0; c < nch; ++c) {
@@ -187,27 +183,30 @@ struct Builder {
     }
 
     // A unit over the consecutive depth-first ranks [r_lo, r_lo + n_thr).  The rows' softmax state stays in
-    // registers over everything the unit reads.  `anc` (-1: none) is the innermost of a chain of inlined
-    // segments (it and all its ancestors) whose blocks every row of the unit reads; the first n_lead threads
-    // end at `anc` itself; the rest are the subtrees of `roots`, in rank order.
+    // registers over everything the unit reads: either the whole subtree of `root` (whose threads are exactly
+    // those ranks), or - root < 0 - every segment on the root paths of those threads, listed in range_segs (a
+    // slice of a larger subtree cut by rank; `family` names that subtree's top segment).
     struct UnitSpec {
-        int32_t anc, r_lo, n_thr, n_lead;
-        const int32_t* roots;
-        int n_roots;
+        int32_t root, r_lo, n_thr, family;
         bool direct;
     };
+    std::vector<int32_t> range_segs;   // segments read by the rank-range unit being emitted
+    std::vector<int32_t> seg_mark;     // per segment: last rank-range unit that listed it
 
-    // f(segment index, lo, hi): the segments a unit reads, with their row groups relative to the unit's first
+    // f(segment index, lo, hi): the segments a unit reads, with the row groups (relative to the unit's first)
+    // that hold them
     template <class F>
     void for_unit_segments(const UnitSpec& u, F&& f) {
         const int groups = u.n_thr * n_sl;
-        for (int32_t a = u.anc; a >= 0; a = ph.segs[a].parent) f(a, 0, groups);
-        for (int k = 0; k < u.n_roots; ++k)
-            for_subtree(u.roots[k], [&](int32_t m) {
-                const PlanHost::Segment& sg = ph.segs[m];
-                const int lo = (sg.t_lo - u.r_lo) * n_sl;
-                f(m, lo, lo + sg.n_shr * n_sl);
-            });
+        auto clipped = [&](int32_t m) {
+            const PlanHost::Segment& sg = ph.segs[m];
+            const int lo = std::max(0, (sg.t_lo - u.r_lo) * n_sl);
+            const int hi = std::min(groups, (sg.t_lo + sg.n_shr - u.r_lo) * n_sl);
+            f(m, lo, hi);
+        };
+        if (u.root >= 0) for_subtree(u.root, clipped);
+        else
+            for (int32_t m : range_segs) clipped(m);
     }
 
     // Returns the unit's first partial-result row (-1 for a direct unit).
@@ -259,12 +258,12 @@ struct Builder {
             else
                 for (int sl = 0; sl < n_sl; ++sl) atom(lo_rel + sl, 1);
         };
-        for (int e = 0; e < u.n_lead; ++e) thread_atoms(e * n_sl);
-        {
+        if (u.root < 0) overflow = true;  // a slice cut by rank is full: dense packing
+        else {
             // a walk that stops descending where a subtree fits one wavefront
             std::vector<int32_t>& st = ph.stack;
             const size_t base = st.size();
-            for (int k = u.n_roots - 1; k >= 0; --k) st.push_back(u.roots[k]);
+            st.push_back(u.root);
             while (st.size() > base && !overflow) {
                 const int32_t m = st.back();
                 st.pop_back();
@@ -346,68 +345,62 @@ struct Builder {
             longest = std::max(longest, (int)cnt);
         }
         wi.cost = nt * (2 * wi.wg.n_coop + longest);
-        wi.family = -1;
-        for (int32_t a = u.anc; a >= 0; a = ph.segs[a].parent) wi.family = a;
+        wi.family = u.family;
         ph.wide_items.push_back(wi);
         return pbase;
     }
 
-    // A whole sharing subtree as one unit; `anc`: the inlined chain above it (-1: none).
-    void emit_fused(int32_t rid, int32_t anc) {
+    // A whole sharing subtree as one unit.
+    void emit_fused(int32_t rid) {
         PlanHost::Segment& r = ph.segs[rid];
         const bool direct = prm.allow_direct && r.n_above == 0;
-        const int32_t roots[1] = {rid};
-        const int32_t pbase = emit_unit(UnitSpec{anc, r.t_lo, r.n_shr, 0, roots, 1, direct});
+        const int32_t pbase = emit_unit(UnitSpec{rid, r.t_lo, r.n_shr, -1, direct});
         if (!direct) part0[rid] = pbase;
     }
 
-    // Segment sid is inlined (its blocks, and those of the inlined chain above it, are read by every unit
-    // below it): cut its threads into units of consecutive ranks.  The threads that end at sid come first,
-    // then its children's subtrees in order; a subtree that does not fit a unit is left to the caller's
-    // loop (it is inlined or stands alone in turn).  All these units are direct: nothing above them leaves
-    // a partial result.
-    std::vector<int32_t> inline_blocks;  // per inlined segment: blocks of the chain from its forest root down to it
-    std::vector<int32_t> pack_roots;
-    void pack_under(int32_t sid) {
-        const PlanHost::Segment& S = ph.segs[sid];
-        const int max_groups = 4 * kMaxRowTiles * cap;
-        const int64_t above = inline_blocks[sid];
-        int32_t cur_lo = S.t_lo, cur_thr = 0, cur_lead = 0;
-        int64_t cur_tiles = 0;
-        pack_roots.clear();
-        auto room = [&](int thr_after, int64_t tiles_after) {
-            const int g = thr_after * n_sl;
-            return g <= max_groups && above + tiles_after <= (int64_t)(g <= cap ? 1 : 4) * prm.max_unit_tiles;
-        };
-        auto flush = [&]() {
-            if (cur_thr > 0) {
-                emit_unit(UnitSpec{sid, cur_lo, cur_thr, cur_lead, pack_roots.data(), (int)pack_roots.size(), true});
-                for (int32_t r : pack_roots) ph.segs[r].unit = pack_roots[0];
+    // The segments on the root paths of the threads with ranks [r_lo, r_lo + n_thr) -> range_segs; returns their blocks.
+    int64_t collect_range(int32_t r_lo, int32_t n_thr, int32_t stamp) {
+        range_segs.clear();
+        int64_t blocks = 0;
+        for (int32_t rank = r_lo; rank < r_lo + n_thr; ++rank)
+            for (int32_t m = ph.thread_last_seg[ph.dfs_threads[rank]]; m >= 0 && seg_mark[m] != stamp; m = ph.segs[m].parent) {
+                seg_mark[m] = stamp;  // everything above a marked segment is marked too
+                range_segs.push_back(m);
+                blocks += ph.segs[m].n_blk;
             }
-            cur_lo += cur_thr;
-            cur_thr = cur_lead = 0;
-            cur_tiles = 0;
-            pack_roots.clear();
-        };
-        for (int e = 0; e < S.n_end; ++e) {
-            if (!room(cur_thr + 1, cur_tiles)) flush();
-            cur_thr += 1;
-            cur_lead += 1;
-        }
-        for (int32_t c = S.first_child; c >= 0; c = ph.segs[c].next_sibling) {
-            const PlanHost::Segment& C = ph.segs[c];
-            if (!room(C.n_shr, C.tiles_sub)) {  // too big even alone
-                flush();
-                cur_lo = C.t_lo + C.n_shr;
-                continue;
-            }
-            if (!room(cur_thr + C.n_shr, cur_tiles + C.tiles_sub)) flush();
-            pack_roots.push_back(c);
-            cur_thr += C.n_shr;
-            cur_tiles += C.tiles_sub;
-        }
-        flush();
+        return blocks;
     }
+
+    // The subtree of segment rid has more query rows than one workgroup carries (and nothing above it leaves
+    // partial results): its threads are cut by rank into the fewest units that hold them, evenly filled.  Every
+    // unit is direct.  Returns false, with nothing emitted, if some unit would read more blocks than it may.
+    int32_t next_stamp = 0;
+    bool emit_by_rank(int32_t rid) {
+        const PlanHost::Segment& r = ph.segs[rid];
+        const int per_unit = std::max(1, 4 * kMaxRowTiles * cap / n_sl);  // threads
+        const int n_units = (r.n_shr + per_unit - 1) / per_unit;
+        const int64_t block_cap = (int64_t)4 * prm.max_unit_tiles;
+        if (seg_mark.size() != ph.segs.size()) seg_mark.assign(ph.segs.size(), -1);
+        auto slice = [&](int k, int32_t& lo, int32_t& cnt) {
+            lo = r.t_lo + (int32_t)((int64_t)r.n_shr * k / n_units);
+            cnt = r.t_lo + (int32_t)((int64_t)r.n_shr * (k + 1) / n_units) - lo;
+        };
+        if (r.tiles_sub > block_cap)  // (otherwise no slice can exceed the cap)
+            for (int k = 0; k < n_units; ++k) {
+                int32_t lo, cnt;
+                slice(k, lo, cnt);
+                if (collect_range(lo, cnt, next_stamp++) > block_cap) return false;
+            }
+        for (int k = 0; k < n_units; ++k) {
+            int32_t lo, cnt;
+            slice(k, lo, cnt);
+            collect_range(lo, cnt, next_stamp++);
+            emit_unit(UnitSpec{-1, lo, cnt, rid, true});
+        }
+        for_subtree(rid, [&](int32_t m) { ph.segs[m].unit = rid; });
+        return true;
+    }
+
 };
 
 }  // namespace
@@ -518,13 +511,13 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
     // 5. cut the forest into units, parents first
     bld.part0.assign(n_seg, -1);
     bld.n_chunks.assign(n_seg, 0);
-    bld.inline_blocks.assign(n_seg, 0);
+    bld.seg_mark.clear();
     const int cap = bld.cap, n_sl = bld.n_sl;
     for (int32_t m = 0; m < n_seg; ++m) {
         PlanHost::Segment& s = segs[m];
         ph.unique_blocks += s.n_blk;
         ph.unique_tokens += (int64_t)(s.n_blk - 1) * B + s.last_valid;
-        if (s.unit >= 0) continue;  // packed into a unit by its inlined parent
+        if (s.unit >= 0) continue;  // part of a subtree that was cut by rank
         const int32_t par = s.parent;
         if (par >= 0 && segs[par].unit >= 0) {
             s.unit = segs[par].unit;
@@ -532,35 +525,25 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
             continue;
         }
         s.n_above = par >= 0 ? segs[par].n_above + bld.n_chunks[par] : 0;
-        // an inlined chain is read by whatever sits directly below it: a unit, or the first chunk of a
-        // segment that stands alone
-        const int32_t anc = (par >= 0 && segs[par].inlined) ? par : -1;
-        const int64_t above = anc >= 0 ? bld.inline_blocks[anc] : 0;
         const int groups = s.n_shr * n_sl;
-        const bool fits = groups <= 4 * kMaxRowTiles * cap &&
-                          above + s.tiles_sub <= (int64_t)(groups <= cap ? 1 : 4) * prm.max_unit_tiles;
-        if (prm.fuse && fits) {
-            s.unit = m;  // a unit is named after its (first) root segment
-            bld.emit_fused(m, anc);
+        const bool few_rows = groups <= 4 * kMaxRowTiles * cap;
+        if (prm.fuse && few_rows && s.tiles_sub <= (int64_t)(groups <= cap ? 1 : 4) * prm.max_unit_tiles) {
+            s.unit = m;  // a unit is named after its root segment
+            bld.emit_fused(m);
             continue;
         }
-        // Too many rows (or blocks) below for one unit.  Either the segment stands alone - chunked, one
-        // partial result per (chunk, thread), merged afterwards - or it is inlined: every unit below reads
-        // its blocks again, up to 128 rows at a time (as often as stand-alone units would), and nothing is
-        // written but output rows.  Inlining is for too many ROWS (with too many blocks for few rows the
-        // segment is better read once), needs the whole path above to be inlined too (so that the units
-        // below are direct) and a chain short enough to leave the units room; long segments with many
-        // rows are better off alone on the matrix kernel.
+        // Too many rows (or blocks) below for one unit.  Too many ROWS: the subtree is cut by rank into full
+        // units that each read the segments above their threads again (as often as stand-alone units would
+        // read them) and write nothing but output rows; that needs the path above to be free of partial
+        // results, so that the units are direct.  Long segments with many rows are better off alone on the
+        // matrix kernel, and with too many blocks for few rows a segment is better read once: those stand
+        // alone - chunked, one partial result per (chunk, thread), merged afterwards - and their children
+        // are tried again.
         const bool to_matrix = prm.matrix_min_rows > 0 && (int64_t)s.n_shr * prm.rows_per_thread >= prm.matrix_min_rows &&
                                s.n_blk >= prm.matrix_min_blocks;
-        if (prm.fuse && prm.inline_shared && prm.allow_direct && s.n_above == 0 && !to_matrix && groups > 4 * kMaxRowTiles * cap &&
-            2 * (above + s.n_blk) <= prm.max_unit_tiles) {
-            s.inlined = 1;
-            bld.inline_blocks[m] = (int32_t)(above + s.n_blk);
-            bld.pack_under(m);
-        } else {
-            bld.emit_standalone(m, anc);
-        }
+        if (prm.fuse && prm.inline_shared && prm.allow_direct && s.n_above == 0 && !to_matrix && !few_rows && bld.emit_by_rank(m))
+            continue;
+        bld.emit_standalone(m);
     }
     if (ph.n_partial_rows > INT32_MAX / 2 || ph.tiles.size() > (size_t)INT32_MAX / 2) return APAR_ERR_UNSUPPORTED;
 
@@ -596,7 +579,7 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
     }
 
     // 7. workgroups: matrix units, then by row tiles per wavefront (2, 1); within a class the heaviest first,
-    // but the units that read one inlined chain stay together (ordered among the others by their heaviest)
+    // but the units cut out of one subtree stay together (ordered among the others by their heaviest)
     {
         std::vector<int32_t>& fam = ph.order;  // per segment: cost of the heaviest unit of the family it roots
         fam.assign(n_seg, 0);

@@ -37,7 +37,6 @@ struct PlanHost {
         int32_t tiles_sub;        // blocks in its whole subtree
         int32_t unit;             // fused unit it belongs to, -1 if it stands alone
         int32_t n_above;          // partial results produced above it on the path (same for all its threads)
-        int32_t inlined;          // 1: no unit of its own; every unit below reads its blocks
     };
     std::vector<Segment> segs;
     std::vector<int32_t> thread_last_seg, end_threads, order, stack;
@@ -52,8 +51,8 @@ struct PlanHost {
     struct WideItem {
         WgDesc wg;
         int32_t cost;
-        int32_t family;      // forest root of the inlined chain the unit reads (-1: none): units of one family are
-                             // launched next to each other, so that the chain is found in L2 when it is read again
+        int32_t family;      // top segment of the subtree the unit was cut out of by rank (-1: none): units of one family
+                             // are launched next to each other, so that the segments they all read are found in L2
         int32_t family_cost; // cost of the family's heaviest unit (its own cost if it has no family)
     };
     std::vector<WideItem> wide_items;
@@ -66,8 +65,8 @@ struct PlanParams {
     int32_t max_unit_tiles;   // longest tile list one wavefront may be given
     bool allow_direct;        // threads whose whole path is one unit may write their output directly
     bool fuse;                // build tree-fused units (false: every segment stands alone)
-    bool inline_shared = true;  // a short shared segment with too many rows below is read again by every unit below
-                                // instead of standing alone with partial results
+    bool inline_shared = true;  // a subtree with more rows than one unit carries is cut by rank into direct units that each
+                                // read the shared segments above their threads, instead of standing alone with partial results
     int32_t matrix_min_rows = 0;    // stand-alone segments with at least this many query rows (0: never) ...
     int32_t matrix_min_blocks = 0;  // ... and at least this many blocks become matrix units
 };

@@ -232,10 +232,13 @@ def test_wide_sharing_groups_use_more_row_tiles(n_q, n_kv, fan, n_cand):
                 assert res["partial_rows"] == 0 and len(wgs) == 1 and wgs[0][3] & 255 == want
             if groups > 8 * cap:
                 to_matrix = matrix_rows and len(live) * rpt >= matrix_rows
-                if inline and not to_matrix and chunk == 512:
-                    # the root (3 blocks) is inlined: read again by every unit below, nothing to merge
+                if inline and not to_matrix and (chunk == 512 or res["partial_rows"] == 0):
+                    # the tree is cut by rank: full units of consecutive threads, each reading the segments above
+                    # its threads again (the root by every unit), all direct, nothing to merge
                     assert res["partial_rows"] == 0 and res["direct_threads"] == len(live)
                     assert res["unit_block_reads"] > res["unique_blocks"] and all(x & 255 in (1, 2) for x in wgs[:, 3])
+                    per_unit = max(1, 8 * cap // n_sl)
+                    assert len(wgs) == -(-len(live) // per_unit)  # as few units as the rows allow
                 else:
                     # the root stands alone: as matrix units (marked 32) when its holders bring enough rows
                     assert res["partial_rows"] > 0 and wgs[0][3] & 255 == (32 if to_matrix else 2)
@@ -261,17 +264,20 @@ def test_nested_wide_groups_are_inlined_or_stand_alone(n_cand):
             return check_plan_covers_tables(h, listed, 2, n_cand)
 
         ap.apar_set_matrix_units(h, 0, 0)
-        res = plan()  # everything wide is short: inlined, nothing to merge
+        res = plan()  # the whole tree is cut by rank into direct units: nothing to merge
         assert res["partial_rows"] == 0 and res["direct_threads"] == len(listed)
         ap.apar_set_inline_shared(h, False)
         off = plan()
         assert off["partial_rows"] > 0 and off["unit_block_reads"] <= res["unit_block_reads"]
         ap.apar_set_inline_shared(h, True)
-        # the 13-block child goes to the matrix kernel and stands alone below the inlined root
+        # a matrix-kernel threshold that only a segment inside the tree meets changes nothing: the root decides
         ap.apar_set_matrix_units(h, 64, 8)
-        res = plan()
-        assert 0 < res["partial_rows"] < off["partial_rows"]
-        # a unit cap too small for the root: it stands alone, and so does everything wide below it
+        assert plan() == res
+        # a root that meets it stands alone on the matrix kernel, and what is wide below it follows
+        ap.apar_set_matrix_units(h, 64, 2)
+        assert plan()["partial_rows"] > 0
+        ap.apar_set_matrix_units(h, 0, 0)
+        # a unit cap too small for the paths of a unit's threads: the root stands alone, and so does everything wide below it
         ap.apar_set_chunk_blocks(h, 4)
         res = plan()
         assert res["partial_rows"] > 0
