@@ -58,8 +58,11 @@ typedef enum apar_status {
     APAR_ERR_THREAD_CAPACITY = -4, /* more than max_threads ids would be issued          */
     APAR_ERR_HIP = -5,             /* a HIP runtime call failed (see apar_last_hip_error) */
     APAR_ERR_UNSUPPORTED = -6,     /* shape outside what the kernels are built for       */
-    APAR_ERR_WORKSPACE_LIMIT = -7  /* apar_decode_attention_fixed: the call needs more than */
+    APAR_ERR_WORKSPACE_LIMIT = -7, /* apar_decode_attention_fixed: the call needs more than */
                                    /* the fixed workspace holds; nothing was enqueued       */
+    APAR_ERR_INTERNAL = -8         /* a write check (apar_set_write_checks) found a kernel  */
+                                   /* about to write a block that other threads hold; nothing */
+                                   /* was launched, the pool should be destroyed             */
 } apar_status;
 
 enum { APAR_F32 = 0, APAR_BF16 = 1 };
@@ -277,30 +280,6 @@ APAR_API int apar_thread_block_table(apar_pool* pool, apar_thread thread, int32_
 APAR_API int apar_block_refcount(apar_pool* pool, int32_t block, int32_t* refcount_out);
 APAR_API int apar_pool_stats(apar_pool* pool, apar_stats* out);
 APAR_API int apar_last_plan_info(apar_pool* pool, apar_plan_info* out);
-/* Tables of the last decode call's plan, for inspection (int32 arrays).  The listed threads are
- * numbered depth-first along their sharing tree ("rank"); a thread's query rows are cut into
- * `slices` slices of at most 16 rows, and row group = rank * slices + slice.  `which`:
- *   APAR_PLAN_WORKGROUPS  32 ints per workgroup: [0] first shared tile, [1] shared tile count,
- *                         [2] row group the shared tiles' ranges are relative to, [3] bits 0-7: 16-row tiles per wavefront
- *                         (1 or 2), or 32 for a matrix unit - a stand-alone chunk of a shared segment for up to 128
- *                         rows of whole threads, all named by wavefront entry 0, the other entries empty -
- *                         (workgroups are stored 32 first, then 2, then 1), bits 8-31: how many
- *                         of the shared tiles are full (every list holds its full tiles first), then
- *                         4 wavefronts x 6: first own tile, own tile count, first row group, row
- *                         group count, first partial-result row (of the thread owning the first
- *                         row group), flags (bit 0: writes output rows directly); [28..31] full tiles at the head
- *                         of each wavefront's own list;
- *   APAR_PLAN_TILES       2 ints per tile: block id, lo | hi << 10 | filled_slots << 20, where
- *                         [lo, hi) are the row groups the block applies to, relative to the
- *                         wavefront's first row group (own tiles) or to [2] (shared tiles);
- *   APAR_PLAN_DFS_THREADS rank -> index into the listed threads;
- *   APAR_PLAN_PATH_OFS    [n+1] offsets into PATH_IDS by listed index;  APAR_PLAN_PATH_IDS  the
- *                         partial-result rows merged for each listed thread (none: written directly);
- *   APAR_PLAN_GEOMETRY    rows per thread, rows per slice, slices.
- * Stores the element count in n_out; INVALID_ARG if cap is too small. */
-enum { APAR_PLAN_WORKGROUPS = 0, APAR_PLAN_TILES = 1, APAR_PLAN_DFS_THREADS = 2, APAR_PLAN_PATH_OFS = 3,
-       APAR_PLAN_PATH_IDS = 4, APAR_PLAN_GEOMETRY = 5 };
-APAR_API int apar_last_plan_export(apar_pool* pool, int which, int32_t* out, int64_t cap, int64_t* n_out);
 /* Gathers rows [first, first+n) of a thread out of the pool's private layout
  * into row-major k_out_dev, v_out_dev : [n, Hkv, d]. */
 APAR_API int apar_read_kv_rows(apar_pool* pool, apar_thread thread, int64_t first, int n, void* k_out_dev,
@@ -437,6 +416,40 @@ APAR_API int apar_profile_read(apar_pool* pool, apar_profile* out);
  * apar_profile_read summed, in call order, so that a caller can report a median and percentiles.
  * Stores the count in n_out; INVALID_ARG if cap is too small (n_out is still set). */
 APAR_API int apar_profile_attention_calls(apar_pool* pool, float* ms_out, int64_t cap, int64_t* n_out);
+
+/* ---- testing and tuning ---------------------------------------------------
+ * Everything in this section exists for the test-suite and for experiments.  It is NOT part of the
+ * stable interface: the knobs steer internal policies whose defaults are the product, and the plan
+ * export hands out the kernels' private tables, whose layout changes with the kernels.
+ * APAR_PLAN_RECORD_VERSION names the layout documented below; apar_plan_record_version() returns the
+ * one the loaded library was built with, so that a reader of the tables can refuse a layout it does
+ * not know. */
+#define APAR_PLAN_RECORD_VERSION 2
+APAR_API int apar_plan_record_version(void);
+/* Tables of the last decode call's plan, for inspection (int32 arrays).  The listed threads are
+ * numbered depth-first along their sharing tree ("rank"); a thread's query rows are cut into
+ * `slices` slices of at most 16 rows, and row group = rank * slices + slice.  `which`:
+ *   APAR_PLAN_WORKGROUPS  32 ints per workgroup: [0] first shared tile, [1] shared tile count,
+ *                         [2] row group the shared tiles' ranges are relative to, [3] bits 0-7: 16-row tiles per wavefront
+ *                         (1 or 2), or 32 for a matrix unit - a stand-alone chunk of a shared segment for up to 128
+ *                         rows of whole threads, all named by wavefront entry 0, the other entries empty -
+ *                         (workgroups are stored 32 first, then 2, then 1), bits 8-31: how many
+ *                         of the shared tiles are full (every list holds its full tiles first), then
+ *                         4 wavefronts x 6: first own tile, own tile count, first row group, row
+ *                         group count, first partial-result row (of the thread owning the first
+ *                         row group), flags (bit 0: writes output rows directly); [28..31] full tiles at the head
+ *                         of each wavefront's own list;
+ *   APAR_PLAN_TILES       2 ints per tile: block id, lo | hi << 10 | filled_slots << 20, where
+ *                         [lo, hi) are the row groups the block applies to, relative to the
+ *                         wavefront's first row group (own tiles) or to [2] (shared tiles);
+ *   APAR_PLAN_DFS_THREADS rank -> index into the listed threads;
+ *   APAR_PLAN_PATH_OFS    [n+1] offsets into PATH_IDS by listed index;  APAR_PLAN_PATH_IDS  the
+ *                         partial-result rows merged for each listed thread (none: written directly);
+ *   APAR_PLAN_GEOMETRY    rows per thread, rows per slice, slices.
+ * Stores the element count in n_out; INVALID_ARG if cap is too small. */
+enum { APAR_PLAN_WORKGROUPS = 0, APAR_PLAN_TILES = 1, APAR_PLAN_DFS_THREADS = 2, APAR_PLAN_PATH_OFS = 3,
+       APAR_PLAN_PATH_IDS = 4, APAR_PLAN_GEOMETRY = 5 };
+APAR_API int apar_last_plan_export(apar_pool* pool, int which, int32_t* out, int64_t cap, int64_t* n_out);
 /* Tuning knob: the most blocks one wavefront is given in one work unit (1..65536; default 512).
  * Sharing subtrees with more blocks than that are cut into several units whose partial results are
  * merged afterwards; small values exist to exercise that path. */
@@ -444,15 +457,17 @@ APAR_API int apar_set_chunk_blocks(apar_pool* pool, int blocks_per_unit);
 /* Tuning knob (bf16 pools): a shared segment that stands alone as a unit - its holders have more query rows
  * than one fused workgroup carries (128) - goes to the 32x32 matrix-core kernel, up to 128 rows per workgroup,
  * when its holders bring at least min_rows query rows (candidates x q heads per kv head x threads; default 256)
- * and it has at least min_blocks blocks (default 128; shorter ones are cheaper inlined, see apar_set_inline_shared).
+ * and it has at least min_blocks blocks (default 128; shorter ones are cheaper read again by every unit below,
+ * see apar_set_inline_shared).
  * Matrix units are launched ahead of the other units of a call, not beside them.  min_rows = 0 keeps every unit on the row-tile kernel; (1, 1) sends every such segment
  * to the matrix kernel.  Results agree to rounding.  fp32 pools ignore the knob. */
 APAR_API int apar_set_matrix_units(apar_pool* pool, int min_rows, int min_blocks);
-/* Tuning knob: what happens to a shared segment whose holders bring more query rows than one unit carries
- * (128) and that does not go to the matrix kernel.  On (default): its holders are cut into units of
- * consecutive threads (whole child subtrees where they fit) and every such unit reads the segment's blocks
- * again - no partial results, no merge; used while the chain of such segments above a unit stays shorter
- * than half the unit cap.  Off: the segment stands alone with one partial result per (chunk, thread). */
+/* Tuning knob: what happens to a sharing subtree whose threads bring more query rows than one unit carries
+ * (128) and whose top segment does not go to the matrix kernel.  On (default): its threads, in depth-first
+ * order, are cut into full units of consecutive threads, and every unit reads the segments above its
+ * threads again - no partial results, no merge; used when nothing above leaves partial results and no unit
+ * would read more blocks than four times the unit cap.  Off: the top segment stands alone with one partial
+ * result per (chunk, thread) and its children are tried again. */
 APAR_API int apar_set_inline_shared(apar_pool* pool, int on);
 /* Tuning knob: which kernel apar_prefill_attention runs on a bf16 pool.  ROW_TILES is the decode kernel
  * under a prefill plan (16-row tiles; a prefix shared by sibling threads is read once for all of them),
@@ -463,6 +478,14 @@ APAR_API int apar_set_inline_shared(apar_pool* pool, int on);
 enum { APAR_PREFILL_AUTO = 0, APAR_PREFILL_ROW_TILES = 1, APAR_PREFILL_MATRIX = 2 };
 APAR_API int apar_set_prefill_kernel(apar_pool* pool, int which);
 APAR_API int apar_last_prefill_kernel(apar_pool* pool);
+
+/* Write checks (off by default).  While on, every call that is about to launch kernels writing KV
+ * blocks - appended rows, copy-on-write copies, the re-layout of a block that just became full -
+ * first verifies on the host that each destination block is held by exactly one thread (Sec. 2.3: a
+ * block that several sequences share is never written; the writer copies it first).  A violation is
+ * a bug in the library's bookkeeping: the call returns APAR_ERR_INTERNAL and launches nothing.  The
+ * check runs on bookkeeping-only pools as well. */
+APAR_API int apar_set_write_checks(apar_pool* pool, int on);
 
 APAR_API const char* apar_status_string(int status);
 /* Text of the last HIP error seen on this host thread by the library ("" if none). */

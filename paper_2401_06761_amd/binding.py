@@ -119,6 +119,7 @@ def _load() -> C.CDLL:
         "apar_set_prefill_kernel": [P, I],
         "apar_set_matrix_units": [P, I, I],
         "apar_set_inline_shared": [P, I],
+        "apar_set_write_checks": [P, I],
         "apar_last_prefill_kernel": [P],
         "apar_append_kv_gather": [P, I32P, I32P, I, V, V, V],
         "apar_server_create": [P, C.POINTER(AparServerConfig), C.POINTER(P)],
@@ -141,6 +142,8 @@ def _load() -> C.CDLL:
         fn = getattr(lib, name)
         fn.argtypes = args
         fn.restype = C.c_int
+    lib.apar_plan_record_version.argtypes = []
+    lib.apar_plan_record_version.restype = C.c_int
     lib.apar_status_string.argtypes = [C.c_int]
     lib.apar_status_string.restype = C.c_char_p
     lib.apar_last_hip_error.argtypes = []
@@ -340,6 +343,8 @@ def apar_last_plan_info(pool) -> AparPlanInfo:
 
 
 def apar_last_plan_export(pool, which: int) -> List[int]:
+    if apar_plan_record_version() != APAR_PLAN_RECORD_VERSION:
+        raise RuntimeError("the library's plan tables have another layout than this binding reads")
     n = C.c_int64()
     _L().apar_last_plan_export(pool, which, None, 0, C.byref(n))
     buf = (C.c_int32 * max(n.value, 1))()
@@ -379,6 +384,17 @@ APAR_PREFILL_AUTO, APAR_PREFILL_ROW_TILES, APAR_PREFILL_MATRIX = 0, 1, 2
 
 def apar_set_inline_shared(pool, on: bool) -> None:
     _check(_L().apar_set_inline_shared(pool, 1 if on else 0), "apar_set_inline_shared")
+
+
+def apar_set_write_checks(pool, on: bool) -> None:
+    _check(_L().apar_set_write_checks(pool, 1 if on else 0), "apar_set_write_checks")
+
+
+APAR_PLAN_RECORD_VERSION = 2  # the layout apar_last_plan_export's readers here were written for
+
+
+def apar_plan_record_version() -> int:
+    return int(_L().apar_plan_record_version())
 
 
 def apar_set_matrix_units(pool, min_rows: int, min_blocks: int) -> None:

@@ -80,7 +80,8 @@ struct apar_pool {
     int prefill_kernel = APAR_PREFILL_AUTO;
     // stand-alone segments with at least this many query rows and blocks run as matrix units (bf16 pools)
     int matrix_min_rows = 256, matrix_min_blocks = 128;
-    bool inline_shared = true;  // short shared segments with too many rows below: read again per unit instead of partial results
+    bool inline_shared = true;  // subtrees with too many rows are cut by rank into direct units instead of leaving partial results
+    bool check_writes = false;  // verify before every launch that no destination block is shared
     int last_prefill_kernel = 0;  // which kernel the most recent prefill call ran (APAR_PREFILL_ROW_TILES / _MATRIX)
     std::vector<PlanThreadView> views;
     std::vector<PrefillThreadView> prefill_views;
@@ -219,6 +220,19 @@ inline int32_t append_one(apar_pool* p, Thread& t, std::vector<int32_t>& copies,
     if (slot == kBlockTokens - 1) seals.push_back(t.table.back());  // the block is full after this row
     t.len += 1;
     return code;
+}
+
+// Write check (apar_set_write_checks): every block about to be written - appended rows, destinations of
+// copy-on-write copies, blocks about to be re-laid-out - must be held by exactly one thread.
+int writes_are_private(const apar_pool* p, const std::vector<int32_t>& codes, const std::vector<int32_t>& copies,
+                       const std::vector<int32_t>& seals) {
+    for (int32_t c : codes)
+        if (p->ref[c / kBlockTokens] != 1) return APAR_ERR_INTERNAL;
+    for (size_t i = 0; i + 1 < copies.size(); i += 2)
+        if (p->ref[copies[i + 1]] != 1 || copies[i] == copies[i + 1]) return APAR_ERR_INTERNAL;
+    for (int32_t b : seals)
+        if (p->ref[b] != 1) return APAR_ERR_INTERNAL;
+    return APAR_OK;
 }
 
 // src_rows (may be null): which row of k, v each appended row is taken from.
@@ -744,6 +758,7 @@ int apar_append_kv(apar_pool* p, apar_thread thread, const void* k_dev, const vo
     if (need > (int64_t)p->free_stack.size()) return APAR_ERR_OUT_OF_BLOCKS;
     std::vector<int32_t> codes(n_tokens), copies, seals;
     for (int i = 0; i < n_tokens; ++i) codes[i] = append_one(p, *t, copies, seals);
+    if (p->check_writes && writes_are_private(p, codes, copies, seals) != APAR_OK) return APAR_ERR_INTERNAL;
     if (p->dry_run) return APAR_OK;
     DeviceGuard guard(p->device);
     return run_append(p, codes, copies, seals, nullptr, k_dev, v_dev, (hipStream_t)hip_stream);
@@ -791,6 +806,7 @@ static int append_rows_of(apar_pool* p, const apar_thread* threads, int n, const
     copies.clear();
     seals.clear();
     for (int i = 0; i < n; ++i) codes[i] = append_one(p, p->threads[threads[i]], copies, seals);
+    if (p->check_writes && writes_are_private(p, codes, copies, seals) != APAR_OK) return APAR_ERR_INTERNAL;
     if (p->dry_run) return APAR_OK;
     DeviceGuard guard(p->device);
     return run_append(p, codes, copies, seals, src_rows, k_dev, v_dev, (hipStream_t)hip_stream);
@@ -1028,6 +1044,14 @@ int apar_profile_attention_calls(apar_pool* p, float* ms_out, int64_t cap, int64
     return APAR_OK;
 }
 
+int apar_plan_record_version(void) { return APAR_PLAN_RECORD_VERSION; }
+
+int apar_set_write_checks(apar_pool* p, int on) {
+    if (!p) return APAR_ERR_INVALID_ARG;
+    p->check_writes = on != 0;
+    return APAR_OK;
+}
+
 int apar_set_inline_shared(apar_pool* p, int on) {
     if (!p) return APAR_ERR_INVALID_ARG;
     p->inline_shared = on != 0;
@@ -1065,6 +1089,7 @@ const char* apar_status_string(int status) {
         case APAR_ERR_HIP: return "HIP runtime error";
         case APAR_ERR_UNSUPPORTED: return "unsupported shape";
         case APAR_ERR_WORKSPACE_LIMIT: return "call exceeds the fixed workspace";
+        case APAR_ERR_INTERNAL: return "internal invariant violated";
         default: return "unknown status";
     }
 }

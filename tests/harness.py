@@ -124,7 +124,10 @@ def replay_trace(w, pool: "ap.Pool", led: Optional[BlockLedger] = None, dense: O
 
 def pool_for(w, num_blocks: int, dry_run: bool = False, **kw) -> "ap.Pool":
     hd = w.heads
-    return ap.Pool(hd.n_q_heads, hd.n_kv_heads, hd.head_dim, hd.dtype, num_blocks, dry_run=dry_run, **kw)
+    pool = ap.Pool(hd.n_q_heads, hd.n_kv_heads, hd.head_dim, hd.dtype, num_blocks, dry_run=dry_run, **kw)
+    # every test pool verifies, before each launch that writes KV blocks, that no destination block is shared
+    ap.apar_set_write_checks(pool.handle, True)
+    return pool
 
 
 def blocks_upper_bound(w) -> int:

@@ -48,6 +48,7 @@ static int pool_ops(int seed) {
     cfg.num_blocks = rnd(4, 300);
     apar_pool* p = nullptr;
     CHECK(apar_pool_create(&cfg, nullptr, 0, &p) == APAR_OK);
+    CHECK(apar_set_write_checks(p, 1) == APAR_OK);
     std::vector<apar_thread> live;
     std::map<apar_thread, int64_t> len;
     auto stats_ok = [&](int seed) -> int {
@@ -169,6 +170,7 @@ static int serving(int seed) {
     cfg.num_blocks = rnd(24, 200);
     apar_pool* p = nullptr;
     CHECK(apar_pool_create(&cfg, nullptr, 0, &p) == APAR_OK);
+    CHECK(apar_set_write_checks(p, 1) == APAR_OK);
     apar_server_config sc{rnd(1, 12), rnd(0, 4)};
     apar_server* sv = nullptr;
     CHECK(apar_server_create(p, &sc, &sv) == APAR_OK);
