@@ -39,19 +39,44 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def quantise(x: np.ndarray, dtype: str) -> np.ndarray:
-    """Round fp32 values to the pool dtype and return them as fp32 (exactly representable)."""
+# Pools of type "bf16_fp8kv" keep full blocks in fp8 (OCP e4m3: 1 sign, 4 exponent, 3 mantissa bits, largest
+# magnitude 448) with a power-of-two scale per tile that the library derives from the tile's largest
+# magnitude.  K and V rows for such pools are rounded HERE, once, to a grid the library's rounding leaves
+# untouched whatever tile a row ends up in: e4m3 under the fixed scale 2^-6 (magnitudes up to 7, plenty for
+# N(0,1) data and below).  A tile's own scale is never larger than that, and every value of this grid is
+# representable under any smaller power-of-two scale that covers the tile's maximum, so the library stores
+# these values exactly and the oracle, given the same values, sees what the kernels see.  Queries stay bf16.
+FP8_GRID_EXP = -6
+FP8_MAX = 448.0
+
+
+def round_to_fp8_grid(x: np.ndarray) -> np.ndarray:
+    """fp32 -> nearest (ties to even) multiple-of-quantum value of e4m3 under the scale 2^FP8_GRID_EXP, as fp32."""
+    y = np.ascontiguousarray(x, dtype=np.float64) / 2.0 ** FP8_GRID_EXP
+    y = np.clip(y, -FP8_MAX, FP8_MAX)
+    mag = np.abs(y)
+    expo = np.floor(np.log2(np.maximum(mag, 2.0 ** -6)))          # binade; below 2^-6 the format is subnormal
+    quantum = 2.0 ** (expo - 3)
+    r = np.rint(y / quantum) * quantum                              # rint rounds ties to even
+    return (r * 2.0 ** FP8_GRID_EXP).astype(np.float32)
+
+
+def quantise(x: np.ndarray, dtype: str, kv: bool = False) -> np.ndarray:
+    """Round fp32 values to what a pool of the given type holds and return them as fp32 (exactly representable).
+    kv: the values are K or V rows (only matters for "bf16_fp8kv", whose queries and outputs are plain bf16)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     if dtype == "f32":
         return x
-    if dtype == "bf16":
+    if dtype == "bf16" or (dtype == "bf16_fp8kv" and not kv):
         return bf16_bits_to_f32(round_to_bf16_bits(x))
+    if dtype == "bf16_fp8kv":
+        return round_to_fp8_grid(x)
     raise ValueError(dtype)
 
 
-def _normal(gen: np.random.Generator, shape, scale: float, dtype: str) -> np.ndarray:
+def _normal(gen: np.random.Generator, shape, scale: float, dtype: str, kv: bool = False) -> np.ndarray:
     x = gen.standard_normal(size=shape, dtype=np.float32) * np.float32(scale)
-    return quantise(x, dtype)
+    return quantise(x, dtype, kv)
 
 
 def node_kv(w, node_idx: int) -> Tuple[np.ndarray, np.ndarray]:
@@ -60,8 +85,8 @@ def node_kv(w, node_idx: int) -> Tuple[np.ndarray, np.ndarray]:
     n = w.nodes[node_idx].seg_len
     gen = _stream(w.seed, _KIND_NODE, node_idx)
     shape = (n, h.n_kv_heads, h.head_dim)
-    k = _normal(gen, shape, w.data_scale, h.dtype)
-    v = _normal(gen, shape, w.data_scale, h.dtype)
+    k = _normal(gen, shape, w.data_scale, h.dtype, kv=True)
+    v = _normal(gen, shape, w.data_scale, h.dtype, kv=True)
     return k, v
 
 
@@ -77,8 +102,8 @@ def spec_step_qkv(w, step: int, n_rows: int, n_cand: int):
     h = w.heads
     gen = _stream(w.seed, _KIND_SPEC, step)
     q = _normal(gen, (n_rows, n_cand, h.n_q_heads, h.head_dim), w.data_scale, h.dtype)
-    k = _normal(gen, (n_rows, n_cand, h.n_kv_heads, h.head_dim), w.data_scale, h.dtype)
-    v = _normal(gen, (n_rows, n_cand, h.n_kv_heads, h.head_dim), w.data_scale, h.dtype)
+    k = _normal(gen, (n_rows, n_cand, h.n_kv_heads, h.head_dim), w.data_scale, h.dtype, kv=True)
+    v = _normal(gen, (n_rows, n_cand, h.n_kv_heads, h.head_dim), w.data_scale, h.dtype, kv=True)
     return q, k, v
 
 
@@ -87,7 +112,7 @@ def child_rows(w, step: int, n_rows: int):
     h = w.heads
     gen = _stream(w.seed, _KIND_CHILD_ROW, step)
     shape = (n_rows, h.n_kv_heads, h.head_dim)
-    return _normal(gen, shape, w.data_scale, h.dtype), _normal(gen, shape, w.data_scale, h.dtype)
+    return _normal(gen, shape, w.data_scale, h.dtype, kv=True), _normal(gen, shape, w.data_scale, h.dtype, kv=True)
 
 
 # ---------------------------------------------------------------------------
@@ -97,25 +122,30 @@ def child_rows(w, step: int, n_rows: int):
 # streams above but are just as reproducible.  The oracle receives the very
 # tensors that were handed to the library, copied to the host.
 # ---------------------------------------------------------------------------
-def _torch_normal(shape, scale: float, dtype: str, seed: int, device):
+def _torch_normal(shape, scale: float, dtype: str, seed: int, device, kv: bool = False):
     import torch
 
     g = torch.Generator(device=device)
     g.manual_seed(int(seed) & 0x7FFFFFFFFFFFFFFF)
     x = torch.randn(shape, generator=g, device=device, dtype=torch.float32) * float(scale)
-    return x if dtype == "f32" else x.to(torch.bfloat16)
+    if dtype == "f32":
+        return x
+    if dtype == "bf16_fp8kv" and kv:  # the fixed fp8 grid of round_to_fp8_grid (torch's cast rounds to nearest even too)
+        s = 2.0 ** FP8_GRID_EXP
+        x = (x / s).clamp(-FP8_MAX, FP8_MAX).to(torch.float8_e4m3fn).to(torch.float32) * s
+    return x.to(torch.bfloat16)
 
 
 def node_kv_device(w, node_idx: int, device="cuda:0"):
     h = w.heads
     shape = (w.nodes[node_idx].seg_len, h.n_kv_heads, h.head_dim)
     base = (int(w.seed) << 40) + (int(node_idx) << 2)
-    return (_torch_normal(shape, w.data_scale, h.dtype, base + 1, device),
-            _torch_normal(shape, w.data_scale, h.dtype, base + 2, device))
+    return (_torch_normal(shape, w.data_scale, h.dtype, base + 1, device, kv=True),
+            _torch_normal(shape, w.data_scale, h.dtype, base + 2, device, kv=True))
 
 
-def rows_device(w, tag: int, index: int, shape, device="cuda:0"):
-    """Any other seeded tensor of a run (queries, per-step rows): stream (tag, index)."""
+def rows_device(w, tag: int, index: int, shape, device="cuda:0", kv: bool = False):
+    """Any other seeded tensor of a run (queries, per-step rows): stream (tag, index).  kv: rows that will be cached."""
     h = w.heads
     seed = (int(w.seed) << 40) + (int(tag) << 32) + (int(index) << 2) + 3
-    return _torch_normal(tuple(shape), w.data_scale, h.dtype, seed, device)
+    return _torch_normal(tuple(shape), w.data_scale, h.dtype, seed, device, kv)

@@ -22,7 +22,7 @@ class HeadConfig:
     n_q_heads: int
     n_kv_heads: int
     head_dim: int
-    dtype: str  # "f32" or "bf16"
+    dtype: str  # "f32", "bf16" or "bf16_fp8kv" (bf16 at the interface, full blocks cached in fp8)
     block_size: int = 16
 
     @property
@@ -153,13 +153,18 @@ def manual_tree(parents: Sequence[int], seg_lens: Sequence[int], heads: HeadConf
 
 
 def make_config(name: str, seed: int = 0, n_requests: Optional[int] = None,
-                data_scale: Optional[float] = None) -> Workload:
+                data_scale: Optional[float] = None, kv_fp8: bool = False) -> Workload:
     """The five named configurations.  `n_requests` takes the first n requests of
     the same stream (a prefix of the full forest), for subsampled parity runs."""
     if name == "tiny":
         return tiny_tree()
     rng = np.random.Generator(np.random.PCG64(seed))
     scale = 1.0 / np.sqrt(128.0) if data_scale is None else float(data_scale)
+    if kv_fp8:  # the same shapes on a pool that keeps full blocks in fp8
+        w = make_config(name, seed, n_requests, data_scale)
+        w.heads = HeadConfig(w.heads.n_q_heads, w.heads.n_kv_heads, w.heads.head_dim, "bf16_fp8kv")
+        w.name = name + "_fp8kv"
+        return w
     if name == "mha64":
         n_req = 64 if n_requests is None else n_requests
         nodes: List[Node] = []

@@ -402,8 +402,9 @@ def serving_bench(args) -> int:
     return 0
 
 
-def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None) -> dict:
-    """Decode steps over one resident fork-tree workload (mha64, ht256, gqa1024); returns the result line."""
+def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None, kv_fp8: bool = False) -> dict:
+    """Decode steps over one resident fork-tree workload (mha64, ht256, gqa1024); returns the result line.
+    kv_fp8: the same workload on a pool that keeps full blocks in fp8 (bf16 at the interface)."""
     import torch
 
     import paper_2401_06761_amd as ap
@@ -411,7 +412,7 @@ def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None) -> dic
     from paper_2401_06761_amd.driver import TreeRun
 
     dev = "cuda:0"
-    w = make_config(name, seed=args.seed, n_requests=n_requests)
+    w = make_config(name, seed=args.seed, n_requests=n_requests, kv_fp8=kv_fp8)
     hd = w.heads
     t_build = time.perf_counter()
     run = TreeRun(w, headroom_steps=steps + warmup + 8, churn=args.churn, device=dev)
@@ -461,7 +462,7 @@ def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None) -> dic
     merge_ms = prof.merge_kernel_ms / K
     append_ms = prof.append_kernels_ms / max(prof.n_append_calls, 1)
     achieved = (alg_bytes / K) / (attn_ms * 1e-3) / 1e9
-    traffic, ratio, source = read_traffic(name, alg_bytes / K)
+    traffic, ratio, source = read_traffic(w.name, alg_bytes / K)
     result = {
         "metric": "decode-attn thread-queries/s + achieved HBM GB/s on fork-tree paged KV",
         "value": n_queries / elapsed,
@@ -473,9 +474,11 @@ def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None) -> dic
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": hd.dtype,
+        "dtype": "bf16" if kv_fp8 else hd.dtype,
         "data": "synthetic",
         "config": {
+            "kv_cache": "full blocks in fp8 (e4m3, one power-of-two scale per block, kv head and K|V), filling "
+                        "blocks bf16; matrix-core arithmetic in bf16" if kv_fp8 else hd.dtype,
             "workload": f"{name}: {w.n_requests} requests, fork trees of depth "
                         f"{max(n.depth for n in w.nodes)}, {len(run.live)} live threads, Hq={hd.n_q_heads} "
                         f"Hkv={hd.n_kv_heads} d={hd.head_dim} block=16, seed {args.seed}",
@@ -487,7 +490,7 @@ def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None) -> dic
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "attention_bf16",
+            "kernel": "attention_bf16 (fp8 tiles)" if kv_fp8 else "attention_bf16",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
@@ -566,6 +569,8 @@ def main() -> int:
     ap_.add_argument("--two-pass", action="store_true",
                      help="spec128: gather the accepted rows on the caller's side and append them with "
                           "apar_append_kv_batch instead of apar_commit_candidates")
+    ap_.add_argument("--kv-fp8", action="store_true",
+                     help="mha64 / ht256 / gqa1024 on a pool that keeps full KV blocks in fp8 (half the bytes per cached token)")
     ap_.add_argument("--copy-calibration", action="store_true",
                      help="also run one plain 4 GiB device copy (reference for HBM byte counters)")
     args = ap_.parse_args()
@@ -574,7 +579,7 @@ def main() -> int:
               "see DESIGN.md); --gpus must be 1", file=sys.stderr)
         return 2
     special = args.shared_prefix or args.serving or args.prefill
-    headline_default = not special and args.config == "ht256" and args.requests is None
+    headline_default = not special and args.config == "ht256" and args.requests is None and not args.kv_fp8
 
     # The oracle leg comes first: it starts worker processes, which must happen before this process touches the GPU.
     cpu = None
@@ -601,7 +606,7 @@ def main() -> int:
     if args.config == "spec128":
         result = spec_loop(args, w)
     else:
-        result = tree_bench(args, args.config, args.steps, args.warmup, args.requests)
+        result = tree_bench(args, args.config, args.steps, args.warmup, args.requests, kv_fp8=args.kv_fp8)
     if cpu is not None:
         result["cpu_baseline"] = cpu
     if headline_default and not args.no_secondary:
@@ -612,6 +617,7 @@ def main() -> int:
         sec["gqa1024"] = _secondary_view(tree_bench(args, "gqa1024", min(args.steps, 20), min(args.warmup, 5)))
         sec["spec128_loop"] = _secondary_view(spec_loop(args, make_config("spec128", seed=args.seed),
                                                         K=args.spec_steps, warmup=0))
+        sec["ht256_fp8_kv_cache"] = _secondary_view(tree_bench(args, "ht256", args.steps, args.warmup, kv_fp8=True))
         result["secondary"] = sec
     print(json.dumps(result))
     return 0

@@ -65,14 +65,22 @@ typedef enum apar_status {
                                    /* was launched, the pool should be destroyed             */
 } apar_status;
 
-enum { APAR_F32 = 0, APAR_BF16 = 1 };
+/* Pool types.  APAR_BF16_FP8KV: K, V, Q and the output are bf16 at the interface, as for APAR_BF16, but a
+ * block whose sixteen slots are written is kept in fp8 (OCP e4m3, round to nearest even, saturating at 448)
+ * with one power-of-two scale per (block, kv head) for K and one for V, chosen so that the largest magnitude
+ * of the tile lands in the top binade of the format; a block that is still filling stays bf16.  Decode
+ * attention then reads half the bytes per cached token (Sec. 3.3 measures throughput against the memory the
+ * KV cache takes).  The kernels multiply the stored codes by the scale on their way into the bf16 matrix-core
+ * operands, so the arithmetic is that of a bf16 pool holding the rounded values.  Blocks keep their bf16
+ * size in the pool buffer (a block must be able to hold sixteen bf16 rows while it fills). */
+enum { APAR_F32 = 0, APAR_BF16 = 1, APAR_BF16_FP8KV = 2 };
 
 typedef struct apar_pool_config {
     int32_t n_q_heads;   /* Hq; multiple of n_kv_heads                                   */
     int32_t n_kv_heads;  /* Hkv                                                          */
-    int32_t head_dim;    /* d: 128 for APAR_BF16; 64 or 128 for APAR_F32                 */
+    int32_t head_dim;    /* d: 128 for APAR_BF16 and APAR_BF16_FP8KV; 64 or 128 for APAR_F32 */
     int32_t block_size;  /* tokens per KV block; must be 16                              */
-    int32_t dtype;       /* APAR_F32 or APAR_BF16: type of K, V, Q and of the output     */
+    int32_t dtype;       /* APAR_F32, APAR_BF16 or APAR_BF16_FP8KV (bf16 at the interface) */
     int32_t max_threads; /* upper bound on ids ever issued by this pool                  */
     int64_t num_blocks;  /* N: blocks in the pool, at most 2^26                          */
     float softmax_scale; /* 0 means 1/sqrt(head_dim)                                     */
@@ -102,7 +110,9 @@ typedef struct apar_plan_info {
     int64_t unique_tokens;     /* filled slots in those blocks: each cached row once     */
     int64_t path_tokens;       /* sum of the listed threads' lengths                     */
     int64_t algorithmic_bytes; /* unique_tokens * 2*Hkv*d*e + q read + output written    */
-                               /* (+ candidates' k, v for the multi-candidate call)      */
+                               /* (+ candidates' k, v for the multi-candidate call); on  */
+                               /* an fp8 pool the tokens of full blocks count 1 byte per */
+                               /* element plus 8 bytes of scales per (block, kv head)    */
 } apar_plan_info;
 
 /* Device time measured with HIP events on the caller's stream while profiling is on. */

@@ -11,11 +11,13 @@ Two independent halves:
                  (block tables, refcounts, free list, copy-on-write count).
   * controller.py - Algorithm 1 (fork on [Fork], paragraph nodes, Restore) in plain Python.
   * serving.py - the serving loop (queue, admission, preemption) over controller + ledger.
+  * fp8.py     - what a pool that keeps full blocks in fp8 holds of the rows it was given.
   * accounting.py - the paper's max-cached-tokens / attended-tokens metrics and
                  the resident-vs-copied-prefix byte counts.
 """
 from .dense import DenseThreads, attend, attend_spec  # noqa: F401
 from .ledger import BlockLedger, OutOfBlocks, InvalidThread  # noqa: F401
 from . import accounting  # noqa: F401
+from . import fp8  # noqa: F401
 from . import controller  # noqa: F401
 from . import serving  # noqa: F401

@@ -8,7 +8,7 @@ from typing import List, Optional, Sequence
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libapar.so")
 
-APAR_F32, APAR_BF16 = 0, 1
+APAR_F32, APAR_BF16, APAR_BF16_FP8KV = 0, 1, 2
 
 
 class AparError(RuntimeError):
@@ -529,11 +529,13 @@ class Pool:
                  dry_run: bool = False):
         import torch
 
-        self.torch_dtype = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+        # "bf16_fp8kv": bf16 at the interface, full blocks cached in fp8 (APAR_BF16_FP8KV)
+        self.torch_dtype = {"f32": torch.float32, "bf16": torch.bfloat16, "bf16_fp8kv": torch.bfloat16}[dtype]
         e = 4 if dtype == "f32" else 2
         self.block_bytes = 2 * n_kv_heads * 16 * head_dim * e
         self.kv = None if dry_run else torch.empty(num_blocks * self.block_bytes, dtype=torch.uint8, device=device)
-        self.cfg = AparPoolConfig(n_q_heads, n_kv_heads, head_dim, 16, APAR_F32 if dtype == "f32" else APAR_BF16,
+        self.cfg = AparPoolConfig(n_q_heads, n_kv_heads, head_dim, 16,
+                                  {"f32": APAR_F32, "bf16": APAR_BF16, "bf16_fp8kv": APAR_BF16_FP8KV}[dtype],
                                   max_threads, num_blocks, softmax_scale)
         self.n_q, self.n_kv, self.d = n_q_heads, n_kv_heads, head_dim
         self.device = device

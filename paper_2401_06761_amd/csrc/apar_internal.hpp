@@ -34,7 +34,23 @@ static_assert(kMaxPoolBlocks * kBlockTokens <= kCodeSealed, "a slot code must no
 //   K half: K[token c][dims 32*g + 8*r .. +8]               (A operand of K.Q^T)
 //   V half: V[tokens 4*g .. 4*g+3][dim 32*r + c] followed by
 //           V[tokens 4*g .. 4*g+3][dim 32*r + 16 + c]       (A operand of V^T.P^T)
+//
+// fp8 pools (APAR_BF16_FP8KV) seal a block into fp8 codes (OCP e4m3) in the same element order, one
+// byte per element: the K half is bytes [0, 2048) of the tile, the V half [2048, 4096), and piece r
+// of a lane is the 8 bytes at  half + (r/2)*1024 + lane*16 + (r%2)*8  (a 16-byte load brings two
+// pieces).  Bytes [4096, 4104) hold two floats, the scale of the K half and of the V half: powers
+// of two, value = code * scale.  The rest of the 8 KiB tile is unused while the block is sealed.
 // ---------------------------------------------------------------------------
+constexpr int kFp8HalfBytes = 2048;   // one half (K or V) of a sealed fp8 tile
+constexpr int kFp8ScaleOfs = 4096;    // float K scale, float V scale
+__host__ __device__ inline int fp8_k_offset(int token, int dim) {  // byte offset of an element inside the K half
+    const int r = (dim & 31) >> 3, lane = (dim >> 5) * 16 + token;
+    return (r >> 1) * 1024 + lane * 16 + (r & 1) * 8 + (dim & 7);
+}
+__host__ __device__ inline int fp8_v_offset(int token, int dim) {  // byte offset of an element inside the V half
+    const int r = dim >> 5, lane = (token >> 2) * 16 + (dim & 15);
+    return (r >> 1) * 1024 + lane * 16 + (r & 1) * 8 + ((dim >> 4) & 1) * 4 + (token & 3);
+}
 __host__ __device__ inline int bf16_k_offset(int token, int dim) {  // byte offset inside the K half
     return ((dim & 31) >> 3) * 1024 + (((dim >> 5) * 16 + token) * 16) + (dim & 7) * 2;
 }
@@ -121,7 +137,8 @@ static_assert(sizeof(PrefillWg) == 32, "PrefillWg is read with one aligned scala
 
 struct Shape {
     int32_t n_q, n_kv, d, group;  // group = n_q / n_kv
-    int32_t dtype;
+    int32_t dtype;                // element type of rows at the interface and in blocks that are still filling: APAR_F32 or APAR_BF16
+    int32_t fp8_sealed;           // 1: full blocks are kept in fp8 with a power-of-two scale per (block, kv head) and half
     float scale_log2e;            // softmax scale * log2(e): logits are kept in base 2
     int64_t tile_bytes;           // one (block, kv head): 2 * 16 * d * e
     int64_t block_bytes;          // n_kv tiles

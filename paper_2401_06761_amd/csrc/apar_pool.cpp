@@ -308,7 +308,8 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     prm.max_unit_tiles = p->max_unit_tiles;
     prm.allow_direct = true;
     prm.fuse = true;
-    prm.matrix_min_rows = (p->shape.dtype == APAR_BF16) ? p->matrix_min_rows : 0;
+    // (the 32x32 kernels read bf16 tiles only)
+    prm.matrix_min_rows = (p->shape.dtype == APAR_BF16 && !p->shape.fp8_sealed) ? p->matrix_min_rows : 0;
     prm.matrix_min_blocks = p->matrix_min_blocks;
     prm.inline_shared = p->inline_shared;
     int rc = build_plan(p->views.data(), n, p->ref.data(), p->seg_of.data(), prm, ph);
@@ -324,6 +325,8 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     info.path_tokens = ph.path_tokens;
     info.algorithmic_bytes = ph.unique_tokens * 2 * p->shape.n_kv * p->shape.d * e +
                              2 * (int64_t)n * n_cand * p->shape.n_q * p->shape.d * e;
+    if (p->shape.fp8_sealed)  // full blocks: one byte per element and two scales per (block, kv head)
+        info.algorithmic_bytes -= ph.full_blocks * ((int64_t)kBlockTokens * p->shape.n_kv * p->shape.d * 2 - 8 * p->shape.n_kv);
     if (spec) info.algorithmic_bytes += 2 * (int64_t)n * n_cand * p->shape.n_kv * p->shape.d * e;
     p->plan_geom[0] = prm.rows_per_thread;
     p->plan_geom[2] = (prm.rows_per_thread + 15) / 16;
@@ -551,7 +554,7 @@ int prefill_common(apar_pool* p, const void* q, const apar_thread* ids, const in
     // (its fixed cost per workgroup is spread over many super-blocks); short walks stay on the row-tile kernel,
     // whose plan also reads a prefix shared by sibling threads once for all of them.
     p->last_prefill_kernel = APAR_PREFILL_ROW_TILES;
-    if (!p->dry_run && p->shape.dtype == APAR_BF16 && 16 % p->shape.group == 0 &&
+    if (!p->dry_run && p->shape.dtype == APAR_BF16 && !p->shape.fp8_sealed && 16 % p->shape.group == 0 &&
         (p->prefill_kernel == APAR_PREFILL_MATRIX ||
          (p->prefill_kernel == APAR_PREFILL_AUTO && attended >= kMatrixPrefillMeanWalk * rows))) {
         p->last_prefill_kernel = APAR_PREFILL_MATRIX;
@@ -626,9 +629,9 @@ int apar_pool_create(const apar_pool_config* cfg, void* kv_dev, size_t kv_bytes,
     if (cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return APAR_ERR_INVALID_ARG;
     if (cfg->num_blocks < 1 || cfg->num_blocks > kMaxPoolBlocks || cfg->max_threads < 1)
         return APAR_ERR_INVALID_ARG;
-    if (cfg->dtype != APAR_F32 && cfg->dtype != APAR_BF16) return APAR_ERR_INVALID_ARG;
+    if (cfg->dtype != APAR_F32 && cfg->dtype != APAR_BF16 && cfg->dtype != APAR_BF16_FP8KV) return APAR_ERR_INVALID_ARG;
     if (!(cfg->softmax_scale >= 0.0f) || !std::isfinite(cfg->softmax_scale)) return APAR_ERR_INVALID_ARG;
-    if (cfg->dtype == APAR_BF16 && cfg->head_dim != 128) return APAR_ERR_UNSUPPORTED;
+    if (cfg->dtype != APAR_F32 && cfg->head_dim != 128) return APAR_ERR_UNSUPPORTED;
     if (cfg->dtype == APAR_F32 && cfg->head_dim != 64 && cfg->head_dim != 128) return APAR_ERR_UNSUPPORTED;
     if (cfg->n_q_heads / cfg->n_kv_heads > 16) return APAR_ERR_UNSUPPORTED;
     const int64_t e = cfg->dtype == APAR_F32 ? 4 : 2;
@@ -670,7 +673,8 @@ int apar_pool_create(const apar_pool_config* cfg, void* kv_dev, size_t kv_bytes,
     p->shape.n_kv = cfg->n_kv_heads;
     p->shape.d = cfg->head_dim;
     p->shape.group = cfg->n_q_heads / cfg->n_kv_heads;
-    p->shape.dtype = cfg->dtype;
+    p->shape.dtype = cfg->dtype == APAR_F32 ? APAR_F32 : APAR_BF16;
+    p->shape.fp8_sealed = cfg->dtype == APAR_BF16_FP8KV ? 1 : 0;
     p->shape.scale_log2e = scale * 1.4426950408889634f;
     p->shape.tile_bytes = tile;
     p->shape.block_bytes = block;

@@ -37,6 +37,13 @@
 // operand order; such tiles - at most one per segment - take a slower path: K
 // pieces are gathered row by row and V goes through a padded LDS transpose.
 //
+// fp8 pools (template parameter F8): a full block holds fp8 codes in the same element order, half the
+// bytes, and one power-of-two scale per half.  Its tiles are fetched with two 16-byte loads per lane and
+// half, staged in LDS as they are, and turned into the bf16 operands on their way into the registers by
+// the hardware conversion that multiplies by the scale (exact: a code times a power of two is a bf16
+// value).  Everything after that - products, softmax, accumulation - is the code of the bf16 pool.
+// Blocks that are still filling are bf16 rows on either pool.
+//
 // Softmax runs in base 2 with a lazily updated reference: a row's reference
 // logit m only moves when some logit exceeds it by more than kSlack, which
 // keeps the cross-lane maximum and the rescale of the accumulators off the
@@ -94,6 +101,19 @@ __device__ __forceinline__ void mask_tokens(f32x4& s, uint32_t tok_mask, int g4)
 __device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {  // round to nearest even, one instruction
     const f32x2 x = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+}
+
+// Two 16-byte pieces of fp8 codes (one half of a sealed fp8 tile as this lane holds it) times the half's
+// power-of-two scale -> the four bf16 operand pieces of the half.
+__device__ __forceinline__ void fp8_operands(const u32x4 (&raw)[2], float scale, Frag (&f)[4]) {
+#pragma unroll
+    for (int rp = 0; rp < 2; ++rp)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            Frag& dst = f[2 * rp + (w >> 1)];
+            dst.u[2 * (w & 1)] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[rp][w], scale, false));
+            dst.u[2 * (w & 1) + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[rp][w], scale, true));
+        }
 }
 
 // Online softmax step, first half: if some row's logits ran away from its reference (always so for a
@@ -192,7 +212,8 @@ constexpr int kOpenRowStride = 264;                 // padded, so the four token
 constexpr int kOpenScratch = 16 * kOpenRowStride;   // one wavefront's row-major V half
 
 // NT = 16-row tiles per wavefront (1 or 2 are instantiated): a workgroup carries up to 64 * NT query rows.
-template <int NT>
+// F8: full blocks hold fp8 codes and two scales (APAR_BF16_FP8KV pools).
+template <int NT, bool F8>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3 : 2))) void attention_bf16(const char* __restrict__ pool, const uint16_t* __restrict__ q,
                                                       PlanDev plan, int wg_first, int n_cand, int n_q, int n_kv,
                                                       int group, float scale_log2e, PartialBuf part,
@@ -296,18 +317,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         // the stand-alone units of a segment with many rows) and is worth a place in L2, a private tile is
         // read exactly once.  Measured: plain loads here take 6-10 % off the HBM traffic of the speculative
         // loop and 2 % off the headline launch; plain loads for the private tiles cost 8 %.
+        f32x2 rsc = {1.0f, 1.0f};  // fp8 pools: the scales of the tile in flight
         auto fetch_full = [&](int t) {
             const char* tile = head_base + coop[t].blk * block_stride + lane * 16;
+            if constexpr (F8) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                rk[r] = *reinterpret_cast<const u32x4*>(tile + r * 1024);
-                rv[r] = *reinterpret_cast<const u32x4*>(tile + 4096 + r * 1024);
+                for (int rp = 0; rp < 2; ++rp) {
+                    rk[rp] = *reinterpret_cast<const u32x4*>(tile + rp * 1024);
+                    rv[rp] = *reinterpret_cast<const u32x4*>(tile + kFp8HalfBytes + rp * 1024);
+                }
+                rsc = *reinterpret_cast<const f32x2*>(tile - lane * 16 + kFp8ScaleOfs);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    rk[r] = *reinterpret_cast<const u32x4*>(tile + r * 1024);
+                    rv[r] = *reinterpret_cast<const u32x4*>(tile + 4096 + r * 1024);
+                }
             }
         };
         auto fetch_any = [&](int t) {
             if (t >= n_coop) return;
             const int fill = (coop[t].meta >> 20) & 31;
-            if (fill == 16) {
+            if (!F8 && fill == 16) {  // (a list holds its full tiles first: none of them comes through here on an fp8 pool)
                 fetch_full(t);
             } else {
                 // an open block is row-major: piece r of this lane belongs to token row 4r + g4.  Rows past the
@@ -322,12 +353,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
                 }
             }
         };
-        auto to_stage = [&]() {
+        auto to_stage = [&](auto full_tile) {
             char* dst = stage[wave] + lane * 16;
+            if constexpr (F8 && decltype(full_tile)::value) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                *reinterpret_cast<u32x4*>(dst + r * 1024) = rk[r];
-                *reinterpret_cast<u32x4*>(dst + 4096 + r * 1024) = rv[r];
+                for (int rp = 0; rp < 2; ++rp) {
+                    *reinterpret_cast<u32x4*>(dst + rp * 1024) = rk[rp];
+                    *reinterpret_cast<u32x4*>(dst + kFp8HalfBytes + rp * 1024) = rv[rp];
+                }
+                if (lane == 0) *reinterpret_cast<f32x2*>(stage[wave] + kFp8ScaleOfs) = rsc;
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    *reinterpret_cast<u32x4*>(dst + r * 1024) = rk[r];
+                    *reinterpret_cast<u32x4*>(dst + 4096 + r * 1024) = rv[r];
+                }
+            }
+        };
+        // the operands of a staged full tile
+        auto staged_operands = [&](const char* sb, Frag (&ks)[4], Frag (&vs)[4]) {
+            if constexpr (F8) {
+                u32x4 kraw[2], vraw[2];
+#pragma unroll
+                for (int rp = 0; rp < 2; ++rp) kraw[rp] = *reinterpret_cast<const u32x4*>(sb + rp * 1024 + lane * 16);
+#pragma unroll
+                for (int rp = 0; rp < 2; ++rp) vraw[rp] = *reinterpret_cast<const u32x4*>(sb + kFp8HalfBytes + rp * 1024 + lane * 16);
+                const f32x2 sc = *reinterpret_cast<const f32x2*>(sb + kFp8ScaleOfs);
+                fp8_operands(kraw, sc.x, ks);
+                fp8_operands(vraw, sc.y, vs);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
             }
         };
         auto consume = [&](int t, const char* sb, auto full_only) {
@@ -338,11 +396,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             // does the tile touch any row group of this wavefront?
             if (wi.n_grp == 0 || lo >= wi.n_grp || hi <= 0) return;
             Frag ks[4], vs[4];
-            if (kFull || valid == 16) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
+            if (kFull || (!F8 && valid == 16)) {
+                staged_operands(sb, ks, vs);
             } else {  // an open block: row-major in the stage buffer
 #pragma unroll
                 for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + c * 256 + g4 * 64 + r * 16);
@@ -376,10 +431,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         auto consume_seen_by_all = [&](const char* sb) {
             if (wi.n_grp == 0) return;
             Frag ks[4], vs[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
+            staged_operands(sb, ks, vs);
             f32x4 s[NT];
             float top[NT];
             bool ran_away = false;
@@ -403,14 +455,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         auto consume_two_seen_by_all = [&](const char* sa, const char* sb) {
             if (wi.n_grp == 0) return;
             Frag ka[4], kb[4], va[4], vb[4];
+            if constexpr (F8) {
+                staged_operands(sa, ka, va);
+                staged_operands(sb, kb, vb);
+            } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) ka[r].u = *reinterpret_cast<const u32x4*>(sa + r * 1024 + lane * 16);
+                for (int r = 0; r < 4; ++r) ka[r].u = *reinterpret_cast<const u32x4*>(sa + r * 1024 + lane * 16);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) kb[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
+                for (int r = 0; r < 4; ++r) kb[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) va[r].u = *reinterpret_cast<const u32x4*>(sa + 4096 + r * 1024 + lane * 16);
+                for (int r = 0; r < 4; ++r) va[r].u = *reinterpret_cast<const u32x4*>(sa + 4096 + r * 1024 + lane * 16);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) vb[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
+                for (int r = 0; r < 4; ++r) vb[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
+            }
             f32x4 s0[NT], s1[NT];
             float top[NT];
             bool ran_away = false;
@@ -458,7 +515,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             int t0 = 0;
             for (; t0 < n_fast; t0 += 4) {
                 if (t0 > 0) __syncthreads();  // everyone is done reading the previous group
-                if (t0 + wave < n_coop_full) to_stage();
+                if (t0 + wave < n_coop_full) to_stage(std::true_type{});
                 __syncthreads();
                 if (t0 + 4 + wave < n_coop_full) fetch_full(t0 + 4 + wave);
                 const int n_here = min(4, n_coop_full - t0);
@@ -468,7 +525,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             }
             for (; t0 < n_coop_full; t0 += 4) {
                 if (t0 > 0) __syncthreads();
-                if (t0 + wave < n_coop_full) to_stage();
+                if (t0 + wave < n_coop_full) to_stage(std::true_type{});
                 __syncthreads();
                 if (t0 + 4 + wave < n_coop_full) fetch_full(t0 + 4 + wave);
                 const int n_here = min(4, n_coop_full - t0);
@@ -481,7 +538,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             settle_queries();
             for (int t0 = n_coop_full; t0 < n_coop; t0 += 4) {
                 if (t0 > n_coop_full) __syncthreads();
-                if (t0 + wave < n_coop) to_stage();
+                if (t0 + wave < n_coop) to_stage(std::false_type{});
                 __syncthreads();
                 fetch_any(t0 + 4 + wave);
                 const int n_here = min(4, n_coop - t0);
@@ -497,15 +554,40 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
     // apart inside the lane's own 64 bytes of its token's row.  The V half is fetched raw either way.
     // K registers are refilled right after the K.Q^T products and V registers after the V^T.P^T products.
     Frag k[4], v[4];
+    // fp8 pools: the codes of a full tile's halves as fetched, and the halves' scales; they become k, v just
+    // before use (k_ready, v_ready), so that the codes of the next tile can be in flight meanwhile
+    u32x4 k8[2], v8[2];
+    float k8s = 1.0f, v8s = 1.0f;
     auto issue_k_full = [&](const char* tile) {
         const char* p = tile + lane * 16;
+        if constexpr (F8) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) k[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + r * 1024));
+            for (int rp = 0; rp < 2; ++rp) k8[rp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + rp * 1024));
+            k8s = *reinterpret_cast<const float*>(tile + kFp8ScaleOfs);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) k[r].u = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + r * 1024));
+        }
     };
     auto issue_v_full = [&](const char* tile) {
-        const u32x4* p = reinterpret_cast<const u32x4*>(tile + 4096) + lane;
+        if constexpr (F8) {
+            const char* p = tile + kFp8HalfBytes + lane * 16;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(p + r * 64);
+            for (int rp = 0; rp < 2; ++rp) v8[rp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + rp * 1024));
+            v8s = *reinterpret_cast<const float*>(tile + kFp8ScaleOfs + 4);
+        } else {
+            const u32x4* p = reinterpret_cast<const u32x4*>(tile + 4096) + lane;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r].u = __builtin_nontemporal_load(p + r * 64);
+        }
+    };
+    auto k_ready = [&](int valid) {  // (valid is wavefront-uniform)
+        if constexpr (F8)
+            if (valid == 16) fp8_operands(k8, k8s, k);
+    };
+    auto v_ready = [&](int valid) {
+        if constexpr (F8)
+            if (valid == 16) fp8_operands(v8, v8s, v);
     };
     // Only the filled rows of an open tile are read: a lane whose row lies past the fill count re-reads
     // row 0 (no branch around the loads, no extra traffic), and the masked logits give the slot probability 0.
@@ -546,6 +628,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             const char* tn = head_base + mine[t + 1].blk * block_stride;
             const int meta_n = mine[t + 1].meta;
             f32x4 s[NT];
+            k_ready(16);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
                 if (NT == 1 || touches(nt, lo, hi)) s[nt] = products(k, st[nt]);
@@ -558,6 +641,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
                 if (on[nt] && (meta >> 30)) mask_tokens(s[nt], visible(meta, my_j[nt] - lo), g4);
             }
             move_references<NT>(st, s, on, in_range, scale_log2e);
+            v_ready(16);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
                 if (on[nt]) weigh_values(v, st[nt], s[nt], in_range[nt], scale_log2e);
@@ -581,6 +665,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             meta_n = mine[t + 1].meta;
         }
         f32x4 s[NT];
+        k_ready(valid);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
             if (NT == 1 || touches(nt, lo, hi)) s[nt] = products(k, st[nt]);
@@ -596,6 +681,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
             v_operands_from_rows(scratch, kOpenRowStride, g4, c, v);
             __builtin_amdgcn_wave_barrier();
         }
+        v_ready(valid);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             if (NT > 1 && !touches(nt, lo, hi)) continue;
@@ -771,12 +857,17 @@ hipError_t launch_attention_bf16(const Shape& s, const void* pool, const void* q
             if ((e = hipStreamWaitEvent(on, cs.fork, 0)) != hipSuccess) return e;
         }
         const unsigned n_wg = (unsigned)count * (unsigned)s.n_kv;
-#define APAR_LAUNCH(NTV)                                                                                          \
-    hipLaunchKernelGGL((attention_bf16<NTV>), dim3(n_wg), dim3(256), 0, on, (const char*)pool, (const uint16_t*)q, \
-                       plan, first[cls], n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part,                      \
+#define APAR_LAUNCH(NTV, F8V)                                                                                           \
+    hipLaunchKernelGGL((attention_bf16<NTV, F8V>), dim3(n_wg), dim3(256), 0, on, (const char*)pool, (const uint16_t*)q, \
+                       plan, first[cls], n_cand, s.n_q, s.n_kv, s.group, s.scale_log2e, part,                           \
                        (const uint16_t*)cand_k, (const uint16_t*)cand_v, mask, (uint16_t*)out)
-        if (cls == 1) APAR_LAUNCH(2);
-        else APAR_LAUNCH(1);
+        if (s.fp8_sealed) {
+            if (cls == 1) APAR_LAUNCH(2, true);
+            else APAR_LAUNCH(1, true);
+        } else {
+            if (cls == 1) APAR_LAUNCH(2, false);
+            else APAR_LAUNCH(1, false);
+        }
 #undef APAR_LAUNCH
         if ((e = hipGetLastError()) != hipSuccess) return e;
         if (cls != last && side_by_side) {

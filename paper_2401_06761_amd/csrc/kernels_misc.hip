@@ -77,6 +77,71 @@ __global__ __launch_bounds__(256) void seal_blocks_bf16(char* __restrict__ pool,
     reinterpret_cast<uint4*>(tile)[256 + t] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// fp8 pools: a block that just became full is rewritten from bf16 rows into fp8 codes in matrix-core order,
+// with one power-of-two scale for its K half and one for its V half: the smallest power of two s for which
+// max |x| / s <= 448, the largest e4m3 magnitude (1 if the half is all zeros), so that the codes use the top
+// binade of the format.  Codes are rounded to nearest even by the hardware conversion.  One workgroup per
+// (block, kv head); the 8 KiB of rows go through LDS.
+__device__ __forceinline__ float fp8_scale_for(float amax) {
+    if (!(amax > 0.0f) || !(amax < INFINITY)) return 1.0f;
+    int k;
+    const float f = frexpf(amax, &k);            // amax = f * 2^k, f in [0.5, 1); 448 = 0.875 * 2^9
+    const int e = (f <= 0.875f) ? k - 9 : k - 8;
+    return ldexpf(1.0f, e < -126 ? -126 : e);
+}
+
+__global__ __launch_bounds__(256) void seal_blocks_fp8(char* __restrict__ pool, const int32_t* __restrict__ blocks,
+                                                       int n_kv, int64_t tile_bytes) {
+    __shared__ __attribute__((aligned(16))) char raw[8192];
+    __shared__ float wave_max[2][4];
+    const int t = threadIdx.x;
+    char* tile = pool + ((int64_t)blocks[blockIdx.x] * n_kv + blockIdx.y) * tile_bytes;
+    const uint4 a = reinterpret_cast<const uint4*>(tile)[t], b = reinterpret_cast<const uint4*>(tile)[256 + t];
+    reinterpret_cast<uint4*>(raw)[t] = a;
+    reinterpret_cast<uint4*>(raw)[256 + t] = b;
+    // largest magnitude of either half (thread t holds 8 K elements in a and 8 V elements in b)
+    float mk = 0.0f, mv = 0.0f;
+    const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        mk = fmaxf(mk, fmaxf(fabsf(__uint_as_float(aw[i] << 16)), fabsf(__uint_as_float(aw[i] & 0xffff0000u))));
+        mv = fmaxf(mv, fmaxf(fabsf(__uint_as_float(bw[i] << 16)), fabsf(__uint_as_float(bw[i] & 0xffff0000u))));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        mk = fmaxf(mk, __shfl_xor(mk, o, 64));
+        mv = fmaxf(mv, __shfl_xor(mv, o, 64));
+    }
+    if ((t & 63) == 0) wave_max[0][t >> 6] = mk, wave_max[1][t >> 6] = mv;
+    __syncthreads();
+    const float ks = fp8_scale_for(fmaxf(fmaxf(wave_max[0][0], wave_max[0][1]), fmaxf(wave_max[0][2], wave_max[0][3])));
+    const float vs = fp8_scale_for(fmaxf(fmaxf(wave_max[1][0], wave_max[1][1]), fmaxf(wave_max[1][2], wave_max[1][3])));
+    const float kinv = 1.0f / ks, vinv = 1.0f / vs;  // powers of two: exact
+    // thread t writes the 8 bytes of piece r of lane `lane` of each half: r = t / 64
+    const int r = t >> 6, lane = t & 63, g = lane >> 4, c = lane & 15;
+    const uint16_t* kr = reinterpret_cast<const uint16_t*>(raw) + c * 128 + 32 * g + 8 * r;  // K[token c][dims 32g + 8r ..]
+    const uint16_t* vr = reinterpret_cast<const uint16_t*>(raw + 4096);
+    float kx[8], vx[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) kx[i] = bf16_to_f32(kr[i]) * kinv;
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vx[4 * hh + i] = bf16_to_f32(vr[(4 * g + i) * 128 + 32 * r + 16 * hh + c]) * vinv;
+    uint32_t kw[2], vw[2];
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        kw[w] = __builtin_amdgcn_cvt_pk_fp8_f32(kx[4 * w], kx[4 * w + 1], 0, false);
+        kw[w] = __builtin_amdgcn_cvt_pk_fp8_f32(kx[4 * w + 2], kx[4 * w + 3], kw[w], true);
+        vw[w] = __builtin_amdgcn_cvt_pk_fp8_f32(vx[4 * w], vx[4 * w + 1], 0, false);
+        vw[w] = __builtin_amdgcn_cvt_pk_fp8_f32(vx[4 * w + 2], vx[4 * w + 3], vw[w], true);
+    }
+    const int ofs = (r >> 1) * 1024 + lane * 16 + (r & 1) * 8;
+    *reinterpret_cast<uint2*>(tile + ofs) = make_uint2(kw[0], kw[1]);
+    *reinterpret_cast<uint2*>(tile + kFp8HalfBytes + ofs) = make_uint2(vw[0], vw[1]);
+    if (t == 0) *reinterpret_cast<float2*>(tile + kFp8ScaleOfs) = make_float2(ks, vs);
+}
+
 __global__ __launch_bounds__(64) void append_rows_f32(char* __restrict__ pool, const float* __restrict__ k,
                                                       const float* __restrict__ v, const int32_t* __restrict__ codes,
                                                       const int32_t* __restrict__ src_rows, int n_kv, int d,
@@ -96,7 +161,7 @@ __global__ __launch_bounds__(64) void append_rows_f32(char* __restrict__ pool, c
 
 __global__ __launch_bounds__(64) void read_rows_bf16(const char* __restrict__ pool, uint16_t* __restrict__ k,
                                                      uint16_t* __restrict__ v, const int32_t* __restrict__ codes,
-                                                     int n_kv, int64_t tile_bytes) {
+                                                     int n_kv, int64_t tile_bytes, int fp8_sealed) {
     const int row = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
     const int32_t code = codes[row];
     const bool sealed = (code & kCodeSealed) != 0;  // the row's block is full, hence in matrix-core order
@@ -104,6 +169,18 @@ __global__ __launch_bounds__(64) void read_rows_bf16(const char* __restrict__ po
     const char* tile = pool + ((int64_t)((code & ~kCodeSealed) >> 4) * n_kv + h) * tile_bytes;
     uint16_t* kdst = k + ((int64_t)row * n_kv + h) * 128;
     uint16_t* vdst = v + ((int64_t)row * n_kv + h) * 128;
+    if (sealed && fp8_sealed) {  // fp8 codes times the half's power-of-two scale: exact in bf16
+        const float2 sc = *reinterpret_cast<const float2*>(tile + kFp8ScaleOfs);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int dim = lane + 64 * e;
+            const uint32_t kc = *reinterpret_cast<const uint8_t*>(tile + fp8_k_offset(slot, dim));
+            const uint32_t vc = *reinterpret_cast<const uint8_t*>(tile + kFp8HalfBytes + fp8_v_offset(slot, dim));
+            kdst[dim] = f32_to_bf16_rne(__builtin_amdgcn_cvt_f32_fp8(kc, 0) * sc.x);
+            vdst[dim] = f32_to_bf16_rne(__builtin_amdgcn_cvt_f32_fp8(vc, 0) * sc.y);
+        }
+        return;
+    }
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
         const int dim = lane + 64 * e;
@@ -418,8 +495,12 @@ hipError_t launch_seal_blocks(const Shape& s, void* pool, const int32_t* blocks,
     const int kSlice = 1 << 20;
     for (int b0 = 0; b0 < n_blocks; b0 += kSlice) {
         const int nb = n_blocks - b0 < kSlice ? n_blocks - b0 : kSlice;
-        hipLaunchKernelGGL(seal_blocks_bf16, dim3(nb, s.n_kv), dim3(256), 0, st, (char*)pool, blocks + b0, s.n_kv,
-                           s.tile_bytes);
+        if (s.fp8_sealed)
+            hipLaunchKernelGGL(seal_blocks_fp8, dim3(nb, s.n_kv), dim3(256), 0, st, (char*)pool, blocks + b0, s.n_kv,
+                               s.tile_bytes);
+        else
+            hipLaunchKernelGGL(seal_blocks_bf16, dim3(nb, s.n_kv), dim3(256), 0, st, (char*)pool, blocks + b0, s.n_kv,
+                               s.tile_bytes);
     }
     return hipGetLastError();
 }
@@ -439,7 +520,7 @@ hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src
     dim3 grid(n_rows, s.n_kv);
     if (s.dtype == APAR_BF16)
         hipLaunchKernelGGL(read_rows_bf16, grid, dim3(64), 0, st, (const char*)pool, (uint16_t*)k_out,
-                           (uint16_t*)v_out, src_codes, s.n_kv, s.tile_bytes);
+                           (uint16_t*)v_out, src_codes, s.n_kv, s.tile_bytes, s.fp8_sealed);
     else
         hipLaunchKernelGGL(read_rows_f32, grid, dim3(64), 0, st, (const char*)pool, (float*)k_out, (float*)v_out,
                            src_codes, s.n_kv, s.d, s.tile_bytes);

@@ -40,7 +40,7 @@ void PlanHost::clear() {
     wgs.clear(), tiles.clear(), dfs_threads.clear(), path_ofs.clear(), path_ids.clear();
     segs.clear(), thread_last_seg.clear(), end_threads.clear(), order.clear(), stack.clear();
     path_len.clear(), narrow_items.clear(), wide_items.clear(), open_tmp.clear();
-    n_partial_rows = n_segments = unique_blocks = unique_tokens = path_tokens = n_direct_threads = 0;
+    n_partial_rows = n_segments = unique_blocks = unique_tokens = path_tokens = n_direct_threads = full_blocks = 0;
     any_partial = false;
 }
 
@@ -517,6 +517,7 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         PlanHost::Segment& s = segs[m];
         ph.unique_blocks += s.n_blk;
         ph.unique_tokens += (int64_t)(s.n_blk - 1) * B + s.last_valid;
+        ph.full_blocks += s.n_blk - (s.last_valid < B ? 1 : 0);
         if (s.unit >= 0) continue;  // part of a subtree that was cut by rank
         const int32_t par = s.parent;
         if (par >= 0 && segs[par].unit >= 0) {

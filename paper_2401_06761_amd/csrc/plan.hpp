@@ -24,6 +24,7 @@ struct PlanHost {
     std::vector<int32_t> path_ofs, path_ids;
     // totals
     int64_t n_partial_rows = 0, n_segments = 0, unique_blocks = 0, unique_tokens = 0, path_tokens = 0;
+    int64_t full_blocks = 0;            // of the unique blocks, those with all sixteen slots filled
     int64_t n_direct_threads = 0;
     bool any_partial = false;
 

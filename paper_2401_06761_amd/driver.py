@@ -80,8 +80,8 @@ class TreeRun:
         hd = w.heads
         n = len(self.live)
         self.banks = [(rows_device(w, TAG_Q, b, (n, hd.n_q_heads, hd.head_dim), self.device),
-                       rows_device(w, TAG_K, b, (n, hd.n_kv_heads, hd.head_dim), self.device),
-                       rows_device(w, TAG_V, b, (n, hd.n_kv_heads, hd.head_dim), self.device))
+                       rows_device(w, TAG_K, b, (n, hd.n_kv_heads, hd.head_dim), self.device, kv=True),
+                       rows_device(w, TAG_V, b, (n, hd.n_kv_heads, hd.head_dim), self.device, kv=True))
                       for b in range(self.n_banks)]
         self.out = self.torch.empty_like(self.banks[0][0])
         self.torch.cuda.synchronize()
@@ -213,13 +213,13 @@ class SpecRun:
     def candidates_for(self, step: int, n: int):
         hd, C = self.w.heads, self.C
         return (rows_device(self.w, self.TAG_CQ, step + 1, (n, C, hd.n_q_heads, hd.head_dim), self.device),
-                rows_device(self.w, self.TAG_CK, step + 1, (n, C, hd.n_kv_heads, hd.head_dim), self.device),
-                rows_device(self.w, self.TAG_CV, step + 1, (n, C, hd.n_kv_heads, hd.head_dim), self.device))
+                rows_device(self.w, self.TAG_CK, step + 1, (n, C, hd.n_kv_heads, hd.head_dim), self.device, kv=True),
+                rows_device(self.w, self.TAG_CV, step + 1, (n, C, hd.n_kv_heads, hd.head_dim), self.device, kv=True))
 
     def child_rows_for(self, step: int, n: int):
         hd = self.w.heads
-        return (rows_device(self.w, self.TAG_CHILD_K, step + 1, (n, hd.n_kv_heads, hd.head_dim), self.device),
-                rows_device(self.w, self.TAG_CHILD_V, step + 1, (n, hd.n_kv_heads, hd.head_dim), self.device))
+        return (rows_device(self.w, self.TAG_CHILD_K, step + 1, (n, hd.n_kv_heads, hd.head_dim), self.device, kv=True),
+                rows_device(self.w, self.TAG_CHILD_V, step + 1, (n, hd.n_kv_heads, hd.head_dim), self.device, kv=True))
 
     def draw_ahead(self, n_steps: int) -> None:
         """Draws the step plans of the next n_steps iterations now (the plan depends on nothing the library

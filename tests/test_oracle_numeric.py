@@ -422,3 +422,66 @@ def test_prefill_rejects_bad_lengths():
     for m in (0, 4):
         with pytest.raises(ValueError):
             o.prefill(np.ones((max(m, 1), 1, 2)), [t], [m])
+
+
+# -- fp8 blocks: the rounding the oracle takes from torch, pinned to the format's definition ----------------
+def _e4m3_values():
+    """All finite values of OCP e4m3 from the definition: sign, 4 exponent bits (bias 7), 3 mantissa bits;
+    exponent 0 is subnormal (mantissa / 8 * 2^-6); exponent 15 with mantissa 7 is NaN, everything else finite."""
+    vals = []
+    for e in range(16):
+        for m in range(8):
+            if e == 15 and m == 7:
+                continue
+            vals.append(m / 8 * 2.0 ** -6 if e == 0 else (1 + m / 8) * 2.0 ** (e - 7))
+    return np.array(sorted(set(vals)))
+
+
+def test_fp8_rounding_is_round_to_nearest_even_on_the_e4m3_grid():
+    from oracle import fp8
+
+    grid = _e4m3_values()
+    assert len(grid) == 127 and grid[0] == 0.0 and grid[-1] == 448.0 and grid[1] == 2.0 ** -9
+    # every value of the format is a fixed point, both signs
+    assert np.array_equal(fp8.round_e4m3(grid), grid) and np.array_equal(fp8.round_e4m3(-grid), -grid)
+    # brute force: a dense sweep against "nearest grid value, ties to the one with an even mantissa"
+    rng = np.random.default_rng(0)
+    ys = np.concatenate([rng.uniform(-460, 460, 20000), rng.uniform(-1, 1, 20000), rng.uniform(-0.02, 0.02, 20000)])
+    # the exact midpoints between neighbours are the ties
+    mids = (grid[:-1] + grid[1:]) / 2
+    ys = np.concatenate([ys, mids, -mids])
+    ys = ys.astype(np.float32).astype(np.float64)   # what a float32 input holds
+    got = fp8.round_e4m3(ys)
+    idx = np.searchsorted(grid, np.abs(ys).clip(max=448.0))
+    lo, hi = grid[np.maximum(idx - 1, 0)], grid[np.minimum(idx, len(grid) - 1)]
+    a = np.abs(ys).clip(max=448.0)
+    pick_hi = (hi - a < a - lo) | ((hi - a == a - lo) & (np.minimum(idx, len(grid) - 1) % 2 == 0))
+    # (grid index parity = mantissa parity: index = 8 * exponent field + mantissa)
+    want = np.sign(ys) * np.where(pick_hi, hi, lo)
+    assert np.array_equal(got, want)
+
+
+def test_fp8_tile_scale_and_lossless_grid():
+    from apar_workloads import quantise
+    from oracle import fp8
+
+    assert fp8.tile_scale(np.zeros(4)) == 1.0
+    for amax, s in ((448.0, 1.0), (448.5, 2.0), (224.0, 0.5), (224.1, 1.0), (1.0, 2.0 ** -8), (0.9, 2.0 ** -8), (0.875, 2.0 ** -9), (0.8, 2.0 ** -9),
+                    (7.0, 2.0 ** -6), (3.6e-5, 2.0 ** -23)):
+        assert fp8.tile_scale(np.array([0.0, -amax, amax / 3])) == s, amax
+    # rows drawn for an fp8 pool sit on a grid that the tile rounding leaves alone, whatever rows share the tile
+    rng = np.random.default_rng(1)
+    for sigma in (1.0, 0.5, 1 / np.sqrt(128)):
+        x = quantise((sigma * rng.standard_normal((64, 16, 128))).astype(np.float32), "bf16_fp8kv", kv=True)
+        assert np.array_equal(quantise(x, "bf16"), x)          # bf16 can carry them to the library
+        for tile in x:
+            assert np.array_equal(fp8.sealed_tile(tile), tile.astype(np.float64))
+        # also next to much larger or much smaller neighbours from the same grid
+        mixed = x[0].copy()
+        mixed[3] = quantise(np.full(128, 6.9, dtype=np.float32), "bf16_fp8kv", kv=True)
+        assert np.array_equal(fp8.sealed_tile(mixed), mixed.astype(np.float64))
+    # and plain bf16 data is NOT left alone (the test above would be vacuous otherwise)
+    y = quantise(rng.standard_normal((16, 128)).astype(np.float32), "bf16")
+    assert np.abs(fp8.sealed_tile(y) - y).max() > 1e-3
+    K, V = fp8.cached_rows(np.tile(y[:, None, :], (3, 2, 1))[:40], np.tile(y[:, None, :], (3, 2, 1))[:40])
+    assert np.array_equal(K[32:], np.tile(y[:, None, :], (3, 2, 1))[32:40]) and not np.array_equal(K[:16, 0], y)
