@@ -617,7 +617,73 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
     const int n_full = min(wg->n_full[wave], wi.n_tiles);
     int t = 0;
     int meta = 16 << 20;
-    if (n_full > 0) {
+    if (F8 && n_full > 2) {
+        // fp8 pools: a tile is half the bytes, so one tile in flight per wavefront is half the bytes in flight,
+        // too little to keep the memory system busy.  The full tiles but the last go through a pipeline two
+        // tiles deep: two sets of raw registers, A (k8, v8) and B, tile j of the pipeline in one of them by
+        // turns, each refilled with tile j + 2 as soon as its codes have been widened.  The last full tile L is
+        // left in flight in set A for the loop below, as the one-deep loop leaves it.
+        if constexpr (F8) {
+            const int L = n_full - 1;
+            u32x4 k8b[2], v8b[2];
+            float k8sb = 1.0f, v8sb = 1.0f;
+            auto load_raw = [&](const char* tile, u32x4 (&kk)[2], u32x4 (&vv)[2], float& ks, float& vs, bool want_k, bool want_v) {
+                const char* p = tile + lane * 16;
+                if (want_k) {
+#pragma unroll
+                    for (int rp = 0; rp < 2; ++rp) kk[rp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + rp * 1024));
+                    ks = *reinterpret_cast<const float*>(tile + kFp8ScaleOfs);
+                }
+                if (want_v) {
+#pragma unroll
+                    for (int rp = 0; rp < 2; ++rp)
+                        vv[rp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + kFp8HalfBytes + rp * 1024));
+                    vs = *reinterpret_cast<const float*>(tile + kFp8ScaleOfs + 4);
+                }
+            };
+            // tile j, whose codes are in (kk, vv); then (refill): tile j + 2 into the same registers
+            auto step = [&](int j, u32x4 (&kk)[2], u32x4 (&vv)[2], float& ks, float& vs, bool refill) {
+                const int mt = mine[j].meta;
+                const int lo = mt & 1023, hi = (mt >> 10) & 1023;
+                const char* tn = refill ? head_base + mine[j + 2].blk * block_stride : nullptr;
+                f32x4 sj[NT];
+                fp8_operands(kk, ks, k);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    if (NT == 1 || touches(nt, lo, hi)) sj[nt] = products(k, st[nt]);
+                if (refill) load_raw(tn, kk, vv, ks, vs, true, false);
+                bool on[NT], in_range[NT];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    on[nt] = NT == 1 || touches(nt, lo, hi);
+                    in_range[nt] = my_j[nt] >= lo && my_j[nt] < hi;
+                    if (on[nt] && (mt >> 30)) mask_tokens(sj[nt], visible(mt, my_j[nt] - lo), g4);
+                }
+                move_references<NT>(st, sj, on, in_range, scale_log2e);
+                fp8_operands(vv, vs, v);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    if (on[nt]) weigh_values(v, st[nt], sj[nt], in_range[nt], scale_log2e);
+                if (refill) load_raw(tn, kk, vv, ks, vs, false, true);
+            };
+            load_raw(head_base + mine[0].blk * block_stride, k8, v8, k8s, v8s, true, true);
+            if (L & 1) {  // an odd number of tiles before the last: one of them alone, so that the rest go in pairs
+                step(0, k8, v8, k8s, v8s, false);
+                load_raw(head_base + mine[1].blk * block_stride, k8, v8, k8s, v8s, true, true);
+                t = 1;
+            }
+            // L - t is even and at least 2: tiles t (in A) and t + 1 (into B) start the pairs
+            load_raw(head_base + mine[t + 1].blk * block_stride, k8b, v8b, k8sb, v8sb, true, true);
+            for (; t + 2 < L; t += 2) {
+                step(t, k8, v8, k8s, v8s, true);
+                step(t + 1, k8b, v8b, k8sb, v8sb, true);
+            }
+            step(t, k8, v8, k8s, v8s, true);          // refills A with tile L
+            step(t + 1, k8b, v8b, k8sb, v8sb, false);
+            t = L;
+            meta = mine[L].meta;
+        }
+    } else if (n_full > 0) {
         // full tiles whose successor is full too: nothing but unconditional loads in this loop
         meta = mine[0].meta;
         const char* first = head_base + mine[0].blk * block_stride;
