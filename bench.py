@@ -156,6 +156,8 @@ def spec_loop(args, w, K=None, warmup=None) -> dict:
     run.build()
     if args.chunk:
         ap.apar_set_chunk_blocks(run.h, args.chunk)
+    if args.no_plan_reuse:
+        ap.apar_set_plan_reuse(run.h, False)
     if args.matrix_units:
         ap.apar_set_matrix_units(run.h, *(int(x) for x in args.matrix_units.split(",")))
     run.draw_ahead(warmup + K)  # the synthetic step plans (masks, accepted chains, coins) exist before the clock starts
@@ -420,6 +422,8 @@ def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None, kv_fp8
     t_build = time.perf_counter() - t_build
     if args.chunk:
         ap.apar_set_chunk_blocks(run.h, args.chunk)
+    if args.no_plan_reuse:
+        ap.apar_set_plan_reuse(run.h, False)
     if args.matrix_units:
         ap.apar_set_matrix_units(run.h, *(int(x) for x in args.matrix_units.split(",")))
     st0 = ap.apar_pool_stats(run.h)
@@ -436,6 +440,7 @@ def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None, kv_fp8
     torch.cuda.synchronize()
     ap.apar_profile_read(run.h)
     ap.apar_profile_enable(run.h, True)
+    plans0 = ap.apar_plan_counts(run.h)
     alg_bytes = 0
     unique_tokens = path_tokens = 0
     n_queries = 0
@@ -456,6 +461,7 @@ def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None, kv_fp8
     ap.apar_profile_enable(run.h, False)
     st1 = ap.apar_pool_stats(run.h)
     info = ap.apar_last_plan_info(run.h)
+    plans = [a - b for a, b in zip(ap.apar_plan_counts(run.h), plans0)]
 
     K = steps
     attn_ms = prof.attention_kernel_ms / K
@@ -521,7 +527,8 @@ def tree_bench(args, name: str, steps: int, warmup: int, n_requests=None, kv_fp8
             "vanilla_after_build": st0.bytes_vanilla,
         },
         "plan": {"segments": info.n_segments, "units": info.n_units, "partial_rows": info.n_partial_rows,
-                 "unique_blocks": info.unique_blocks},
+                 "unique_blocks": info.unique_blocks,
+                 "calls_that_built_it": plans[0], "calls_that_carried_the_previous_one_over": plans[1]},
         "build_s": t_build,
     }
     run.close()
@@ -547,6 +554,8 @@ def main() -> int:
     ap_.add_argument("--requests", type=int, default=None, help="first n requests only (debugging)")
     ap_.add_argument("--chunk", type=int, default=None, help="blocks per work unit")
     ap_.add_argument("--churn", type=float, default=0.01)
+    ap_.add_argument("--no-plan-reuse", action="store_true",
+                     help="build every decode call's plan afresh instead of carrying the previous call's over")
     ap_.add_argument("--cpu-requests", type=int, default=128,
                      help="requests of the workload the oracle decodes for the cpu_baseline leg")
     ap_.add_argument("--no-cpu-baseline", action="store_true",

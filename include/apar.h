@@ -455,10 +455,15 @@ APAR_API int apar_plan_record_version(void);
  *   APAR_PLAN_DFS_THREADS rank -> index into the listed threads;
  *   APAR_PLAN_PATH_OFS    [n+1] offsets into PATH_IDS by listed index;  APAR_PLAN_PATH_IDS  the
  *                         partial-result rows merged for each listed thread (none: written directly);
- *   APAR_PLAN_GEOMETRY    rows per thread, rows per slice, slices.
+ *   APAR_PLAN_GEOMETRY    rows per thread, rows per slice, slices;
+ *   APAR_PLAN_CHANGED_WORKGROUP_WORDS, APAR_PLAN_CHANGED_TILE_WORDS  if the last call carried its plan over
+ *                         (apar_set_plan_reuse): which ints of the two tables it changed - the ints it rewrites
+ *                         in the copy of the tables on the device, every other int staying as the previous call
+ *                         left it (an int may be named twice); empty after a call that built its plan.
  * Stores the element count in n_out; INVALID_ARG if cap is too small. */
 enum { APAR_PLAN_WORKGROUPS = 0, APAR_PLAN_TILES = 1, APAR_PLAN_DFS_THREADS = 2, APAR_PLAN_PATH_OFS = 3,
-       APAR_PLAN_PATH_IDS = 4, APAR_PLAN_GEOMETRY = 5 };
+       APAR_PLAN_PATH_IDS = 4, APAR_PLAN_GEOMETRY = 5, APAR_PLAN_CHANGED_WORKGROUP_WORDS = 6,
+       APAR_PLAN_CHANGED_TILE_WORDS = 7 };
 APAR_API int apar_last_plan_export(apar_pool* pool, int which, int32_t* out, int64_t cap, int64_t* n_out);
 /* Tuning knob: the most blocks one wavefront is given in one work unit (1..65536; default 512).
  * Sharing subtrees with more blocks than that are cut into several units whose partial results are
@@ -496,6 +501,19 @@ APAR_API int apar_last_prefill_kernel(apar_pool* pool);
  * a bug in the library's bookkeeping: the call returns APAR_ERR_INTERNAL and launches nothing.  The
  * check runs on bookkeeping-only pools as well. */
 APAR_API int apar_set_write_checks(apar_pool* pool, int on);
+
+/* Plans carried over (on by default).  A decode call that lists, position by position, the threads of the
+ * previous decode call on the pool - or threads forked from them since - with the same candidate count does
+ * not build its plan afresh: the previous one is brought up to date along each thread's last blocks (fill
+ * counts, a copy-on-write copy in place of the block it copied, one new block per thread) - the per-step
+ * loop of Alg. 1 changes nothing else between two steps.  Any other change (another set of threads, a
+ * thread appended to while it shares its last blocks with another listed thread, more than one new block
+ * for a thread, a knob of this section moved) makes the call build a new plan, as does turning this off.
+ * Both kinds of plan read exactly the listed threads' tables; apar_plan_info describes the plan that ran,
+ * its n_segments as counted when it was last built.  apar_plan_counts: decode calls so far that built
+ * their plan, and that carried one over. */
+APAR_API int apar_set_plan_reuse(apar_pool* pool, int on);
+APAR_API int apar_plan_counts(apar_pool* pool, int64_t* n_built, int64_t* n_carried);
 
 APAR_API const char* apar_status_string(int status);
 /* Text of the last HIP error seen on this host thread by the library ("" if none). */

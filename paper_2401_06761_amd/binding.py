@@ -3,7 +3,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import List, Optional, Sequence
+from typing import List, Optional, Sequence, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libapar.so")
@@ -120,6 +120,8 @@ def _load() -> C.CDLL:
         "apar_set_matrix_units": [P, I, I],
         "apar_set_inline_shared": [P, I],
         "apar_set_write_checks": [P, I],
+        "apar_set_plan_reuse": [P, I],
+        "apar_plan_counts": [P, C.POINTER(C.c_int64), C.POINTER(C.c_int64)],
         "apar_last_prefill_kernel": [P],
         "apar_append_kv_gather": [P, I32P, I32P, I, V, V, V],
         "apar_server_create": [P, C.POINTER(AparServerConfig), C.POINTER(P)],
@@ -339,7 +341,7 @@ def apar_last_plan_info(pool) -> AparPlanInfo:
 
 
 (APAR_PLAN_WORKGROUPS, APAR_PLAN_TILES, APAR_PLAN_DFS_THREADS, APAR_PLAN_PATH_OFS, APAR_PLAN_PATH_IDS,
- APAR_PLAN_GEOMETRY) = range(6)
+ APAR_PLAN_GEOMETRY, APAR_PLAN_CHANGED_WORKGROUP_WORDS, APAR_PLAN_CHANGED_TILE_WORDS) = range(8)
 
 
 def apar_last_plan_export(pool, which: int) -> List[int]:
@@ -388,6 +390,17 @@ def apar_set_inline_shared(pool, on: bool) -> None:
 
 def apar_set_write_checks(pool, on: bool) -> None:
     _check(_L().apar_set_write_checks(pool, 1 if on else 0), "apar_set_write_checks")
+
+
+def apar_set_plan_reuse(pool, on: bool) -> None:
+    _check(_L().apar_set_plan_reuse(pool, 1 if on else 0), "apar_set_plan_reuse")
+
+
+def apar_plan_counts(pool) -> Tuple[int, int]:
+    """(decode calls that built their plan, decode calls that carried the previous one over)."""
+    built, carried = C.c_int64(0), C.c_int64(0)
+    _check(_L().apar_plan_counts(pool, C.byref(built), C.byref(carried)), "apar_plan_counts")
+    return int(built.value), int(carried.value)
 
 
 APAR_PLAN_RECORD_VERSION = 2  # the layout apar_last_plan_export's readers here were written for

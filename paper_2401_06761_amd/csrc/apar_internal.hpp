@@ -172,6 +172,8 @@ hipError_t launch_append_rows(const Shape& s, void* pool, const void* k, const v
 hipError_t launch_block_copies(const Shape& s, void* pool, const int32_t* src_dst_pairs, int n_pairs,
                                hipStream_t st);
 hipError_t launch_seal_blocks(const Shape& s, void* pool, const int32_t* blocks, int n_blocks, hipStream_t st);
+// words[pairs[2 i]] = pairs[2 i + 1] for i < n_pairs (device pointers; `pairs` 8-byte aligned)
+hipError_t launch_scatter_words(int32_t* words, const int32_t* pairs, int n_pairs, hipStream_t st);
 hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src_codes, int n_rows, void* k_out,
                             void* v_out, hipStream_t st);
 hipError_t launch_attention_partial(const Shape& s, const void* pool, const void* q, const PlanDev& plan, int n_cand,

@@ -33,6 +33,7 @@ bool hip_ok(hipError_t e, const char* what) {
 
 struct Thread {
     bool live = false;
+    int32_t forked_from = -1;  // the thread it was forked from (kept after either is released)
     int64_t len = 0;
     std::vector<int32_t> table;
 };
@@ -90,11 +91,26 @@ struct apar_pool {
     std::vector<int32_t> scratch_codes, scratch_copies, scratch_seals, scratch_commit_src;
     std::vector<apar_thread> scratch_commit_ids;
     apar_plan_info last_plan{};
-    PlanHost plan;  // the last plan, kept for reuse of its storage and for inspection
+    PlanHost plan;  // the last plan, kept for the next call to carry over, for reuse of its storage and for inspection
+    // the call that plan was made or last carried over for: its listed threads, its parameters, and how many
+    // threads the pool had ever created by then (a thread with an id from there on was forked since)
+    std::vector<apar_thread> plan_ids;
+    PlanParams plan_prm{};
+    size_t plan_threads_then = 0;
+    int64_t plan_copies_then = 0;  // copy-on-write copies the pool had made by then
+    bool plan_reuse = true;
+    int64_t n_plans_built = 0, n_plans_carried = 0;
     int32_t plan_geom[3] = {1, 1, 1};  // rows per thread, rows per slice, slices of the last plan
 
     StageSlot stage[kStageSlots];
     int next_slot = 0;
+    // The staging slot whose device half holds the tables of `plan`, as long as that is so: a call that carries
+    // the plan over rewrites the changed words there instead of staging every table again.  Kept out of the
+    // rotation meanwhile.  resident_behind: the host tables have moved on and the slot has not caught up yet
+    // (set while a call is between the two; a call that fails there leaves it set and the slot is dropped).
+    StageSlot* resident = nullptr;
+    size_t resident_bytes = 0;
+    bool resident_behind = false;
     PartialBuf part{};
     size_t part_slots_cap = 0;
     ClassStreams class_streams;
@@ -141,6 +157,7 @@ int32_t pop_block(apar_pool* p) {
 }
 
 int acquire_stage(apar_pool* p, size_t bytes, StageSlot** out) {
+    if (&p->stage[p->next_slot] == p->resident) p->next_slot = (p->next_slot + 1) % kStageSlots;
     StageSlot& s = p->stage[p->next_slot];
     p->next_slot = (p->next_slot + 1) % kStageSlots;
     if (s.pending) {
@@ -274,6 +291,12 @@ int run_append(apar_pool* p, const std::vector<int32_t>& codes, const std::vecto
     return APAR_OK;
 }
 
+bool same_params(const PlanParams& a, const PlanParams& b) {
+    return a.rows_per_thread == b.rows_per_thread && a.max_unit_tiles == b.max_unit_tiles && a.allow_direct == b.allow_direct &&
+           a.fuse == b.fuse && a.inline_shared == b.inline_shared && a.matrix_min_rows == b.matrix_min_rows &&
+           a.matrix_min_blocks == b.matrix_min_blocks;
+}
+
 // fixed: the plan and the partial results go to the device's static workspace, nothing is allocated, no
 // stream or event is created and profiling is off for the call.
 int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* cand_v, const uint8_t* mask,
@@ -292,15 +315,13 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     const auto t0 = std::chrono::steady_clock::now();
     p->wait_in_call_ms = 0.0;
 
+    p->views.resize(n);
     for (int i = 0; i < n; ++i) {
+        if (i + 16 < n && ids[i + 16] >= 0 && (size_t)ids[i + 16] < p->threads.size()) __builtin_prefetch(&p->threads[ids[i + 16]]);
         Thread* t = live_thread(p, ids[i]);
         if (!t) return APAR_ERR_INVALID_THREAD;
         if (t->len == 0) return APAR_ERR_INVALID_ARG;
-    }
-    p->views.resize(n);
-    for (int i = 0; i < n; ++i) {
-        const Thread& t = p->threads[ids[i]];
-        p->views[i] = PlanThreadView{t.table.data(), (int32_t)t.table.size(), t.len};
+        p->views[i] = PlanThreadView{t->table.data(), (int32_t)t->table.size(), t->len};
     }
     PlanHost& ph = p->plan;
     PlanParams prm;
@@ -312,8 +333,31 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     prm.matrix_min_rows = (p->shape.dtype == APAR_BF16 && !p->shape.fp8_sealed) ? p->matrix_min_rows : 0;
     prm.matrix_min_blocks = p->matrix_min_blocks;
     prm.inline_shared = p->inline_shared;
-    int rc = build_plan(p->views.data(), n, p->ref.data(), p->seg_of.data(), prm, ph);
-    if (rc != APAR_OK) return rc;
+    // Decode calls of a loop list the same threads step after step - each a few rows longer, a few replaced
+    // by a thread forked from them - and the plan of the previous call then only needs its tails brought up
+    // to date.  A table never changes before its last block, and a thread forked since the previous call
+    // started from a copy of its parent's table as it was then or later, so "position by position the same
+    // thread or one forked from it since" is all that has to hold for patch_plan to apply.
+    bool carried = false;
+    if (p->plan_reuse && ph.reusable && (size_t)n == p->plan_ids.size() && same_params(prm, p->plan_prm)) {
+        bool same = true;
+        for (int i = 0; i < n && same; ++i) {
+            int32_t t = ids[i];
+            while (t != p->plan_ids[i] && t >= 0 && (size_t)t >= p->plan_threads_then) t = p->threads[t].forked_from;
+            same = t == p->plan_ids[i];
+        }
+        carried = same && patch_plan(p->views.data(), n, p->cow_copies == p->plan_copies_then, ph);
+    }
+    int rc = carried ? APAR_OK : build_plan(p->views.data(), n, p->ref.data(), p->seg_of.data(), prm, ph);
+    if (rc != APAR_OK) {
+        ph.reusable = false;
+        return rc;
+    }
+    p->plan_ids.assign(ids, ids + n);
+    p->plan_prm = prm;
+    p->plan_threads_then = p->threads.size();
+    p->plan_copies_then = p->cow_copies;
+    (carried ? p->n_plans_carried : p->n_plans_built) += 1;
     const int64_t e = p->shape.dtype == APAR_F32 ? 4 : 2;
     apar_plan_info info{};
     info.n_threads = n;
@@ -350,7 +394,35 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     StageSlot* s = nullptr;
     char *host = nullptr, *dev = nullptr;
     PartialBuf part = p->part;
-    if (fixed) {
+    if (p->resident_behind) p->resident = nullptr;
+    p->resident_behind = false;
+    // a carried-over plan whose tables are still on the device from the previous call: only the words that
+    // changed are sent, and written in place once the previous call's kernels are through
+    const bool in_place = carried && !fixed && p->resident && p->resident_bytes == ofs[5];
+    if (!in_place) p->resident = nullptr;
+    if (in_place) {
+        p->resident_behind = true;
+        StageSlot* res = p->resident;
+        const size_t n_pairs = ph.dirty_wg_words.size() + ph.dirty_tile_words.size();
+        if (n_pairs > 0) {
+            StageSlot* ps = nullptr;
+            if ((rc = acquire_stage(p, n_pairs * 2 * sizeof(int32_t), &ps)) != APAR_OK) return rc;
+            int32_t* pairs = (int32_t*)ps->host;
+            const int32_t* wg_words = (const int32_t*)ph.wgs.data();
+            const int32_t* tile_words = (const int32_t*)ph.tiles.data();
+            const int32_t wg_base = (int32_t)(ofs[0] / 4), tile_base = (int32_t)(ofs[1] / 4);
+            for (int32_t w : ph.dirty_wg_words) *pairs++ = wg_base + w, *pairs++ = wg_words[w];
+            for (int32_t w : ph.dirty_tile_words) *pairs++ = tile_base + w, *pairs++ = tile_words[w];
+            if ((rc = upload(p, ps, n_pairs * 2 * sizeof(int32_t), st)) != APAR_OK) return rc;
+            if (res->pending) HIP_TRY(hipStreamWaitEvent(st, res->ev, 0));  // (a no-op on the stream of the previous call)
+            HIP_TRY(launch_scatter_words((int32_t*)res->dev, (const int32_t*)ps->dev, (int)n_pairs, st));
+            HIP_TRY(hipEventRecord(ps->ev, st));
+            ps->pending = true;
+        }
+        p->resident_behind = false;
+        s = res;
+        dev = res->dev;
+    } else if (fixed) {
         // the workspace has a fixed size: a plan or a set of partial results beyond it is refused
         const size_t slot_bytes = (size_t)(p->shape.d + 2) * sizeof(float);
         const size_t cap_slots = kFixedPartBytes / slot_bytes;
@@ -368,11 +440,13 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
         host = s->host;
         dev = s->dev;
     }
-    memcpy(host + ofs[0], ph.wgs.data(), ph.wgs.size() * sizeof(WgDesc));
-    memcpy(host + ofs[1], ph.tiles.data(), ph.tiles.size() * sizeof(TileRef));
-    memcpy(host + ofs[2], ph.dfs_threads.data(), ph.dfs_threads.size() * 4);
-    memcpy(host + ofs[3], ph.path_ofs.data(), ph.path_ofs.size() * 4);
-    if (!ph.path_ids.empty()) memcpy(host + ofs[4], ph.path_ids.data(), ph.path_ids.size() * 4);
+    if (!in_place) {
+        memcpy(host + ofs[0], ph.wgs.data(), ph.wgs.size() * sizeof(WgDesc));
+        memcpy(host + ofs[1], ph.tiles.data(), ph.tiles.size() * sizeof(TileRef));
+        memcpy(host + ofs[2], ph.dfs_threads.data(), ph.dfs_threads.size() * 4);
+        memcpy(host + ofs[3], ph.path_ofs.data(), ph.path_ofs.size() * 4);
+        if (!ph.path_ids.empty()) memcpy(host + ofs[4], ph.path_ids.data(), ph.path_ids.size() * 4);
+    }
 
     // partial-result buffer
     if (!fixed && slots > p->part_slots_cap) {
@@ -388,7 +462,9 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
         part = p->part;
     }
 
-    if (fixed) {
+    if (in_place) {
+        // (already there)
+    } else if (fixed) {
         HIP_TRY(hipMemcpyAsync(dev, host, ofs[5], hipMemcpyHostToDevice, st));
         HIP_TRY(hipEventRecord(p->fixed_up, st));
         p->fixed_pending = true;
@@ -432,6 +508,8 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     if (s) {
         HIP_TRY(hipEventRecord(s->ev, st));
         s->pending = true;
+        p->resident = s;
+        p->resident_bytes = ofs[5];
     }
     p->last_plan = info;
     if (profiling)
@@ -741,6 +819,7 @@ int apar_fork(apar_pool* p, apar_thread parent, int n_children, apar_thread* chi
         const Thread& par = p->threads[parent];
         child.live = true;
         child.len = par.len;
+        child.forked_from = parent;
         child.table = par.table;
         children_out[c] = (apar_thread)(p->threads.size() - 1);
     }
@@ -962,6 +1041,8 @@ int apar_last_plan_export(apar_pool* p, int which, int32_t* out, int64_t cap, in
         case APAR_PLAN_PATH_OFS: src = ph.path_ofs.data(), n = (int64_t)ph.path_ofs.size(); break;
         case APAR_PLAN_PATH_IDS: src = ph.path_ids.data(), n = (int64_t)ph.path_ids.size(); break;
         case APAR_PLAN_GEOMETRY: src = p->plan_geom, n = 3; break;
+        case APAR_PLAN_CHANGED_WORKGROUP_WORDS: src = ph.dirty_wg_words.data(), n = (int64_t)ph.dirty_wg_words.size(); break;
+        case APAR_PLAN_CHANGED_TILE_WORDS: src = ph.dirty_tile_words.data(), n = (int64_t)ph.dirty_tile_words.size(); break;
         default: return APAR_ERR_INVALID_ARG;
     }
     *n_out = n;
@@ -1049,6 +1130,19 @@ int apar_profile_attention_calls(apar_pool* p, float* ms_out, int64_t cap, int64
 }
 
 int apar_plan_record_version(void) { return APAR_PLAN_RECORD_VERSION; }
+
+int apar_set_plan_reuse(apar_pool* p, int on) {
+    if (!p) return APAR_ERR_INVALID_ARG;
+    p->plan_reuse = on != 0;
+    return APAR_OK;
+}
+
+int apar_plan_counts(apar_pool* p, int64_t* n_built, int64_t* n_carried) {
+    if (!p || !n_built || !n_carried) return APAR_ERR_INVALID_ARG;
+    *n_built = p->n_plans_built;
+    *n_carried = p->n_plans_carried;
+    return APAR_OK;
+}
 
 int apar_set_write_checks(apar_pool* p, int on) {
     if (!p) return APAR_ERR_INVALID_ARG;

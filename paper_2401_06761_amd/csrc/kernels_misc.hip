@@ -514,6 +514,21 @@ hipError_t launch_block_copies(const Shape& s, void* pool, const int32_t* pairs,
     return hipGetLastError();
 }
 
+// words[pairs[2 i]] = pairs[2 i + 1]: brings staged plan tables up to date word by word.  Pairs that name the
+// same word carry the same value.
+__global__ __launch_bounds__(256) void scatter_words(int32_t* __restrict__ words, const int32_t* __restrict__ pairs, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int2 p = reinterpret_cast<const int2*>(pairs)[i];
+    words[p.x] = p.y;
+}
+
+hipError_t launch_scatter_words(int32_t* words, const int32_t* pairs, int n_pairs, hipStream_t st) {
+    if (n_pairs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(scatter_words, dim3((n_pairs + 255) / 256), dim3(256), 0, st, words, pairs, n_pairs);
+    return hipGetLastError();
+}
+
 hipError_t launch_read_rows(const Shape& s, const void* pool, const int32_t* src_codes, int n_rows, void* k_out,
                             void* v_out, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;

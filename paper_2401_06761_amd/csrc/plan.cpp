@@ -42,6 +42,10 @@ void PlanHost::clear() {
     path_len.clear(), narrow_items.clear(), wide_items.clear(), open_tmp.clear();
     n_partial_rows = n_segments = unique_blocks = unique_tokens = path_tokens = n_direct_threads = full_blocks = 0;
     any_partial = false;
+    tails.clear(), tile_owner.clear(), spare.clear(), item_wg.clear(), item_slot.clear();
+    dirty_wg_words.clear(), dirty_tile_words.clear();
+    reusable = false;
+    n_patched = 0;
 }
 
 namespace {
@@ -88,6 +92,23 @@ struct Builder {
         }
     }
 
+    // Segment sg is the last of its one listed holder: remember which item's list (wide item and wavefront
+    // 0..3 or kSharedList; kNarrowItem: the narrow item's only list) reads the thread's own last blocks, for
+    // which row groups; build_plan turns the item into the workgroup it ends up in.
+    static constexpr int32_t kNarrowItem = 8;
+    static bool is_tail(const PlanHost::Segment& sg) { return sg.n_shr == 1 && sg.n_end == 1; }
+    void note_tail(const PlanHost::Segment& sg, size_t item, int32_t slot, int lo, int hi) {
+        PlanHost::Tail& t = ph.tails[ph.end_threads[sg.end_ofs]];
+        t.wg = (int32_t)item;
+        t.slot = slot;
+        t.lohi = make_meta(lo, hi, 0);
+    }
+    void leave_slack(int n_tails) { ph.tiles.resize(ph.tiles.size() + (size_t)n_tails * PlanHost::kTailSlack); }
+    void push_wide(PlanHost::WideItem& wi) {
+        wi.id = (int32_t)ph.wide_items.size();
+        ph.wide_items.push_back(wi);
+    }
+
     void emit_narrow(int32_t tile_ofs, int32_t n_tiles, int32_t n_full, int32_t grp_lo, int32_t n_grp,
                      int32_t part_base, int32_t flags) {
         PlanHost::NarrowItem it;
@@ -123,6 +144,7 @@ struct Builder {
         ph.n_partial_rows += (int64_t)nch * s.n_shr;
         ph.any_partial = true;
         const int32_t grp0 = s.t_lo * n_sl;
+        const bool tail_seg = is_tail(s);  // (one holder: every chunk is a single item)
         // the chunk's tiles for row groups [0, hi) of a list owner
         auto chunk_tiles = [&](int, int b0, int nb, int hi) {
             ph.open_tmp.clear();
@@ -131,12 +153,15 @@ struct Builder {
         for (int c = 0; c < nch; ++c) {
             const int b0 = c == 0 ? 0 : first_nb + (c - 1) * chunk, nb = c == 0 ? first_nb : std::min(chunk, s.n_blk - b0);
             const int32_t pbase = part0[sid] + c * s.n_shr;
+            const bool tail_here = tail_seg && c == nch - 1;
             if (groups <= cap) {
                 const int32_t ofs = (int32_t)ph.tiles.size();
                 chunk_tiles(c, b0, nb, groups);
                 const int32_t n_full = (int32_t)ph.tiles.size() - ofs;
                 ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
+                if (tail_here) note_tail(s, ph.narrow_items.size(), kNarrowItem, 0, groups);
                 emit_narrow(ofs, (int32_t)ph.tiles.size() - ofs, n_full, grp0, groups, pbase, 0);
+                if (tail_here) leave_slack(1);
             } else if (prm.matrix_min_rows > 0 && (int64_t)s.n_shr * prm.rows_per_thread >= prm.matrix_min_rows &&
                        s.n_blk >= prm.matrix_min_blocks) {
                 // matrix units: whole threads, as evenly over the workgroups as they go
@@ -156,7 +181,11 @@ struct Builder {
                     for (int k = 1; k < 4; ++k) wi.wg.w[k] = WaveItem{0, 0, 0, 0, -1, 0};
                     wi.cost = wi.wg.n_coop;
                     wi.family = -1;
-                    ph.wide_items.push_back(wi);
+                    if (tail_here) {
+                        note_tail(s, ph.wide_items.size(), PlanHost::kSharedList, 0, nt * n_sl);
+                        leave_slack(1);
+                    }
+                    push_wide(wi);
                 }
             } else {
                 const int nt = pick_row_tiles(groups), wcap = nt * cap;
@@ -176,7 +205,11 @@ struct Builder {
                     }
                     wi.cost = 2 * wi.wg.n_coop * nt;
                     wi.family = -1;
-                    ph.wide_items.push_back(wi);
+                    if (tail_here) {
+                        note_tail(s, ph.wide_items.size(), PlanHost::kSharedList, 0, gn);
+                        leave_slack(1);
+                    }
+                    push_wide(wi);
                 }
             }
         }
@@ -225,13 +258,19 @@ struct Builder {
         if (groups <= cap) {
             const int32_t ofs = (int32_t)ph.tiles.size();
             ph.open_tmp.clear();
+            int n_tails = 0;
             for_unit_segments(u, [&](int32_t m, int lo, int hi) {
                 const PlanHost::Segment& sg = ph.segs[m];
                 push_tiles(ph.tiles, ph.open_tmp, sg, 0, sg.n_blk, lo, hi);
+                if (is_tail(sg)) {
+                    note_tail(sg, ph.narrow_items.size(), kNarrowItem, lo, hi);
+                    ++n_tails;
+                }
             });
             const int32_t n_full = (int32_t)ph.tiles.size() - ofs;
             ph.tiles.insert(ph.tiles.end(), ph.open_tmp.begin(), ph.open_tmp.end());
             emit_narrow(ofs, (int32_t)ph.tiles.size() - ofs, n_full, grp0, groups, pbase, flags);
+            leave_slack(n_tails);
             return pbase;
         }
         // several wavefronts: give each a contiguous range of row groups, keeping subtrees that fit
@@ -290,6 +329,7 @@ struct Builder {
         // first pass: who owns each segment the unit reads (a wavefront whose row groups contain all its
         // rows here, else the shared list), and how long the lists get; second pass: write the tiles in place
         int n_plain[5] = {0, 0, 0, 0, 0}, n_open[5] = {0, 0, 0, 0, 0};  // [0]: shared list, [1 + k]: wavefront k
+        int n_tails[5] = {0, 0, 0, 0, 0};
         std::vector<int32_t>& visit = ph.order;
         visit.clear();
         for_unit_segments(u, [&](int32_t m, int lo, int hi) {
@@ -304,6 +344,7 @@ struct Builder {
             const bool open = sg.last_valid < B;
             n_plain[owner + 1] += sg.n_blk - (open ? 1 : 0);
             n_open[owner + 1] += open ? 1 : 0;
+            n_tails[owner + 1] += is_tail(sg) ? 1 : 0;
         });
         const size_t base = ph.tiles.size();
         size_t total = 0;
@@ -311,7 +352,7 @@ struct Builder {
         size_t list_ofs[5];
         for (int l = 0; l < 5; ++l) {
             list_ofs[l] = base + total;
-            total += (size_t)n_plain[l] + n_open[l];
+            total += (size_t)n_plain[l] + n_open[l] + (size_t)n_tails[l] * PlanHost::kTailSlack;
         }
         ph.tiles.resize(base + total);
         for (int l = 0; l < 5; ++l) {
@@ -330,6 +371,7 @@ struct Builder {
             for (int b2 = 0; b2 < np; ++b2) dst[b2] = TileRef{sg.blocks[b2], meta};
             plain_at[owner + 1] += np;
             if (open) *open_at[owner + 1]++ = TileRef{sg.blocks[np], make_meta(lo, hi, sg.last_valid)};
+            if (is_tail(sg)) note_tail(sg, ph.wide_items.size(), owner >= 0 ? owner : PlanHost::kSharedList, lo, hi);
         }
         PlanHost::WideItem wi{};
         wi.wg.coop_ofs = (int32_t)list_ofs[0];
@@ -346,7 +388,7 @@ struct Builder {
         }
         wi.cost = nt * (2 * wi.wg.n_coop + longest);
         wi.family = u.family;
-        ph.wide_items.push_back(wi);
+        push_wide(wi);
         return pbase;
     }
 
@@ -512,6 +554,11 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
     bld.part0.assign(n_seg, -1);
     bld.n_chunks.assign(n_seg, 0);
     bld.seg_mark.clear();
+    {
+        PlanHost::Tail none{};
+        none.wg = none.slot = none.tile = -1;
+        ph.tails.assign(n, none);
+    }
     const int cap = bld.cap, n_sl = bld.n_sl;
     for (int32_t m = 0; m < n_seg; ++m) {
         PlanHost::Segment& s = segs[m];
@@ -603,6 +650,8 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         ph.n_wg_class[(w.wg.row_tiles & 255) == kMatrixUnitRows ? 0 : (w.wg.row_tiles & 255) == 2 ? 1 : 2] += 1;
     }
     const size_t n_wide = ph.wgs.size();
+    ph.item_wg.assign(ph.narrow_items.size(), -1);
+    ph.item_slot.assign(ph.narrow_items.size(), -1);
     {
         // counting sort by cost, descending
         int32_t max_cost = 0;
@@ -627,6 +676,9 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
                 wg.w[j] = WaveItem{it.tile_ofs + b, e - b, it.grp_lo, it.n_grp, it.part_base, it.flags | kWaveSplit};
                 wg.n_full[j] = std::max(0, std::min(e, item_full) - b);
             }
+            // the item's open tiles, and the entries left free behind them, belong to the last quarter (if they all do)
+            ph.item_wg[slot[k]] = (int32_t)ph.wgs.size();
+            ph.item_slot[slot[k]] = item_full >= (int32_t)((int64_t)it.n_tiles * 3 / 4) ? 3 : -1;
             ph.wgs.push_back(wg);
         }
         for (; k < slot.size(); k += 4) {
@@ -635,6 +687,8 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
                 if (k + j < slot.size()) {
                     wg.w[j] = ph.narrow_items[slot[k + j]].item;
                     wg.n_full[j] = ph.narrow_items[slot[k + j]].n_full;
+                    ph.item_wg[slot[k + j]] = (int32_t)ph.wgs.size();
+                    ph.item_slot[slot[k + j]] = j;
                 } else {
                     wg.w[j] = WaveItem{0, 0, 0, 0, -1, 0};
                 }
@@ -645,7 +699,156 @@ int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, in
         }
     }
     ph.n_wg_class[2] += (int32_t)(ph.wgs.size() - n_wide);
+
+    // 8. what patch_plan needs: each thread's table as the plan covers it, the list its own last blocks are on
+    // (items have become workgroups by now), the tile of a last block that is still filling
+    {
+        std::vector<int32_t>& wide_pos = ph.order;  // order of emission -> workgroup
+        wide_pos.assign(n_wide, 0);
+        for (size_t k = 0; k < n_wide; ++k) wide_pos[ph.wide_items[k].id] = (int32_t)k;
+        ph.tile_owner.assign(ph.tiles.size(), -1);
+        ph.spare.assign(ph.wgs.size() * 5, 0);
+        for (int i = 0; i < n; ++i) {
+            PlanHost::Tail& t = ph.tails[i];
+            const PlanThreadView& v = threads[i];
+            t.len = v.len;
+            t.n_blocks = v.n_blocks;
+            t.tail_block = v.table[v.n_blocks - 1];
+            t.tile = -1;
+            if (t.slot == Builder::kNarrowItem) {
+                const int32_t item = t.wg;
+                t.wg = ph.item_wg[item];
+                t.slot = ph.item_slot[item];
+            } else if (t.slot >= 0) {
+                t.wg = wide_pos[t.wg];
+            }
+            if (t.slot < 0) {
+                t.wg = -1;
+                continue;
+            }
+            ph.spare[(size_t)t.wg * 5 + t.slot] += PlanHost::kTailSlack;
+            if (v.len - (int64_t)(v.n_blocks - 1) * B < B) {
+                const WgDesc& wg = ph.wgs[t.wg];
+                const bool shared = t.slot == PlanHost::kSharedList;
+                const int32_t ofs = shared ? wg.coop_ofs : wg.w[t.slot].tile_ofs;
+                const int32_t cnt = shared ? wg.n_coop : wg.w[t.slot].n_tiles;
+                for (int32_t k = ofs + (shared ? wg.row_tiles >> 8 : wg.n_full[t.slot]); k < ofs + cnt; ++k)
+                    if (ph.tiles[k].blk == t.tail_block) t.tile = k;
+                if (t.tile < 0) t.wg = -1;
+                else ph.tile_owner[t.tile] = i;
+            }
+        }
+        ph.reusable = true;
+    }
     return APAR_OK;
+}
+
+namespace {
+
+struct ListView {
+    int32_t ofs, n, n_full;
+};
+inline ListView list_of(const WgDesc& wg, int slot) {
+    if (slot == PlanHost::kSharedList) return ListView{wg.coop_ofs, wg.n_coop, wg.row_tiles >> 8};
+    return ListView{wg.w[slot].tile_ofs, wg.w[slot].n_tiles, wg.n_full[slot]};
+}
+
+}  // namespace
+
+bool patch_plan(const PlanThreadView* threads, int n, bool no_copies, PlanHost& ph) {
+    if (!ph.reusable || (size_t)n != ph.tails.size()) return false;
+    ph.dirty_wg_words.clear(), ph.dirty_tile_words.clear();
+    auto tile_changed = [&ph](int32_t idx, bool block_too = true) {
+        if (block_too) ph.dirty_tile_words.push_back(2 * idx);
+        ph.dirty_tile_words.push_back(2 * idx + 1);
+    };
+    // (the word a list's length or its count of full tiles is kept in: see WgDesc)
+    auto count_changed = [&ph](int32_t wg, int slot, bool n_full) {
+        const int word = slot == PlanHost::kSharedList ? (n_full ? 3 : 1) : (n_full ? 28 + slot : 4 + 6 * slot + 1);
+        ph.dirty_wg_words.push_back(wg * 32 + word);
+    };
+    auto give_up = [&ph] {
+        ph.reusable = false;
+        return false;
+    };
+    // The tile at `idx` of a list now reads a full block: it changes places with the list's first open tile.
+    auto to_full_part = [&](int32_t wg_index, int slot, int32_t idx) {
+        WgDesc& wg = ph.wgs[wg_index];
+        const ListView l = list_of(wg, slot);
+        const int32_t f = l.ofs + l.n_full;
+        if (f != idx) {
+            std::swap(ph.tiles[f], ph.tiles[idx]);
+            std::swap(ph.tile_owner[f], ph.tile_owner[idx]);
+            if (ph.tile_owner[idx] >= 0) ph.tails[ph.tile_owner[idx]].tile = idx;
+            tile_changed(f);
+            tile_changed(idx);
+        }
+        ph.tile_owner[f] = -1;
+        if (slot == PlanHost::kSharedList) wg.row_tiles += 1 << 8;
+        else wg.n_full[slot] += 1;
+        count_changed(wg_index, slot, true);
+        ph.full_blocks += 1;
+    };
+    for (int i = 0; i < n; ++i) {
+        if (i + 8 < n) {
+            const PlanHost::Tail& ahead = ph.tails[i + 8];
+            if (!no_copies) __builtin_prefetch(threads[i + 8].table + std::min(ahead.n_blocks, threads[i + 8].n_blocks) - 1);
+            if (ahead.tile >= 0) __builtin_prefetch(&ph.tiles[ahead.tile], 1);
+            else if (ahead.wg >= 0) __builtin_prefetch(&ph.wgs[ahead.wg], 1);  // a full last block: the next row opens a new one
+        }
+        PlanHost::Tail& t = ph.tails[i];
+        const PlanThreadView& v = threads[i];
+        if (v.n_blocks < t.n_blocks || v.len < t.len) return give_up();
+        // (without a copy-on-write copy anywhere since, the block is the one it was)
+        const int32_t at_tail = no_copies ? t.tail_block : v.table[t.n_blocks - 1];
+        if (v.len == t.len) {
+            if (v.n_blocks != t.n_blocks || at_tail != t.tail_block) return give_up();
+            continue;
+        }
+        const int dn = v.n_blocks - t.n_blocks;
+        if (t.wg < 0 || dn > 1) return give_up();
+        WgDesc& wg = ph.wgs[t.wg];
+        if (t.len - (int64_t)(t.n_blocks - 1) * B < B) {
+            // the block that was filling: more rows, perhaps in its copy-on-write copy, perhaps full now
+            if (t.tile < 0) return give_up();
+            const int now = dn ? B : (int)(v.len - (int64_t)(v.n_blocks - 1) * B);
+            ph.tiles[t.tile] = TileRef{at_tail, t.lohi | (now << 20)};
+            tile_changed(t.tile, at_tail != t.tail_block);
+            if (now == B) {
+                to_full_part(t.wg, t.slot, t.tile);
+                t.tile = -1;
+            }
+        } else if (dn == 0 || at_tail != t.tail_block) {
+            return give_up();  // (a full last block stays as it is)
+        }
+        if (dn) {
+            int32_t& left = ph.spare[(size_t)t.wg * 5 + t.slot];
+            if (left <= 0) return give_up();
+            left -= 1;
+            const ListView l = list_of(wg, t.slot);
+            const int32_t idx = l.ofs + l.n;
+            const int now = (int)(v.len - (int64_t)(v.n_blocks - 1) * B);
+            ph.tiles[idx] = TileRef{v.table[v.n_blocks - 1], t.lohi | (now << 20)};
+            ph.tile_owner[idx] = i;
+            tile_changed(idx);
+            if (t.slot == PlanHost::kSharedList) wg.n_coop += 1;
+            else wg.w[t.slot].n_tiles += 1;
+            count_changed(t.wg, t.slot, false);
+            t.tile = idx;
+            ph.unique_blocks += 1;
+            if (now == B) {
+                to_full_part(t.wg, t.slot, idx);
+                t.tile = -1;
+            }
+        }
+        ph.unique_tokens += v.len - t.len;
+        ph.path_tokens += v.len - t.len;
+        t.len = v.len;
+        t.n_blocks = v.n_blocks;
+        t.tail_block = v.table[v.n_blocks - 1];
+    }
+    ph.n_patched += 1;
+    return true;
 }
 
 int build_prefill_plan(const PrefillThreadView* threads, int n, int group, PlanHost& ph) {

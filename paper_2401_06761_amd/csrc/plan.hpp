@@ -52,11 +52,36 @@ struct PlanHost {
     struct WideItem {
         WgDesc wg;
         int32_t cost;
+        int32_t id;          // position in the order of emission
         int32_t family;      // top segment of the subtree the unit was cut out of by rank (-1: none): units of one family
                              // are launched next to each other, so that the segments they all read are found in L2
         int32_t family_cost; // cost of the family's heaviest unit (its own cost if it has no family)
     };
     std::vector<WideItem> wide_items;
+
+    // What the next call needs to carry this plan over instead of building another (patch_plan): of every
+    // listed thread, the table the plan covers and where the tile of its last block sits.
+    struct Tail {
+        int64_t len;         // the thread's length when the plan was made or last patched
+        int32_t n_blocks;    // its table's length then
+        int32_t tail_block;  // table[n_blocks - 1]
+        int32_t tile;        // index in `tiles` of that block's tile while the block is filling, -1 once it is full
+        int32_t wg, slot;    // the list its own last blocks are on: workgroup, and wavefront 0..3 or kSharedList;
+                             // wg < 0: not known (the thread's last segment has another listed holder, or the list is
+                             // one that cannot be grown in place)
+        int32_t lohi;        // row groups of its tiles relative to that list's owner: lo | hi << 10
+    };
+    static constexpr int32_t kSharedList = 4;
+    static constexpr int32_t kTailSlack = 4;  // unused tile entries left behind a list per thread whose tail is on it
+    std::vector<Tail> tails;
+    std::vector<int32_t> tile_owner;   // per entry of `tiles`: the listed thread whose filling last block it reads, else -1
+    std::vector<int32_t> spare;        // per (workgroup, list): unused tile entries behind the list
+    std::vector<int32_t> item_wg, item_slot;  // build scratch: where each narrow item / wide item ended up
+    // what the last patch_plan changed, for a copy of the tables that is brought up to date instead of
+    // written again: indices of 32-bit words of `wgs` and of `tiles` (a word may be listed twice)
+    std::vector<int32_t> dirty_wg_words, dirty_tile_words;
+    bool reusable = false;             // tails, tile_owner and spare describe wgs and tiles as they stand
+    int32_t n_patched = 0;             // calls that carried this plan over since it was built
 
     void clear();
 };
@@ -90,5 +115,17 @@ int build_prefill_plan(const PrefillThreadView* threads, int n, int group, PlanH
 // Returns 0, or a negative apar_status.
 int build_plan(const PlanThreadView* threads, int n, const int32_t* refcount, int32_t* seg_of, const PlanParams& prm,
                PlanHost& ph);
+
+// Carries the plan in `ph` over to a call that lists, position by position, the same threads as the call it
+// was built (or last patched) for - or threads forked from them since - with the same parameters; the caller
+// vouches for that.  Tables only ever change from their last block on, so all there is to do is to follow
+// each thread's tail: new fill counts, a last block replaced by its copy-on-write copy, a block that filled
+// up and moves to the full part of its list, one new block put in an entry left free behind the list.
+// Returns false - and the plan must then be built afresh - when a thread changed in any other way (its
+// last segment has several listed holders, more than one new block, no entry left).  The totals in `ph`
+// follow; its segment records do not (they describe the plan as it was built).
+// no_copies: the caller knows that no block was replaced by a copy-on-write copy since that call, so that a
+// table that has not grown need not be looked at.
+bool patch_plan(const PlanThreadView* threads, int n, bool no_copies, PlanHost& ph);
 
 }  // namespace apar

@@ -159,6 +159,37 @@ def random_forest(rng, n_roots, max_nodes):
     return parents, segs
 
 
+class PlanTablesOnDevice:
+    """What the device's copy of the plan tables holds when a call that carries its plan over rewrites only the
+    ints the library names as changed: follow() after every decode call keeps the copy the same way and compares
+    it with the tables the library holds on the host (the ones the coverage check reads)."""
+
+    def __init__(self, handle):
+        self.handle = handle
+        self.wgs = self.tiles = None
+        self.carried = ap.apar_plan_counts(handle)[1]
+
+    def follow(self) -> bool:
+        h = self.handle
+        wgs = np.array(ap.apar_last_plan_export(h, ap.APAR_PLAN_WORKGROUPS), dtype=np.int64)
+        tiles = np.array(ap.apar_last_plan_export(h, ap.APAR_PLAN_TILES), dtype=np.int64)
+        changed_w = np.array(ap.apar_last_plan_export(h, ap.APAR_PLAN_CHANGED_WORKGROUP_WORDS), dtype=np.int64)
+        changed_t = np.array(ap.apar_last_plan_export(h, ap.APAR_PLAN_CHANGED_TILE_WORDS), dtype=np.int64)
+        carried = ap.apar_plan_counts(h)[1]
+        was_carried = carried > self.carried
+        self.carried = carried
+        if was_carried and self.wgs is not None:
+            assert self.wgs.shape == wgs.shape and self.tiles.shape == tiles.shape, "a carried plan keeps its layout"
+            self.wgs[changed_w] = wgs[changed_w]
+            self.tiles[changed_t] = tiles[changed_t]
+            assert np.array_equal(self.wgs, wgs), "workgroup ints changed that the library does not rewrite on the device"
+            assert np.array_equal(self.tiles, tiles), "tile ints changed that the library does not rewrite on the device"
+        else:
+            assert was_carried or (len(changed_w) == 0 and len(changed_t) == 0)
+            self.wgs, self.tiles = wgs, tiles
+        return was_carried
+
+
 def check_plan_covers_tables(handle, threads: Sequence[int], n_kv: int, rows_per_thread: int = 1) -> Dict[str, int]:
     """The exported plan must read, on behalf of every row group of every listed thread, exactly the
     blocks of that thread's table (each once, with the right fill counts); a thread is either written

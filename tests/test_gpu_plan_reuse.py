@@ -1,0 +1,175 @@
+"""Plans carried over from one decode call to the next (GPU only).
+
+A decode loop lists the same threads step after step; the library then brings the previous call's plan up to
+date - on the host and, word by word, in the copy the kernels read - instead of building and staging another.
+Here the benchmark's driver runs such loops long enough for every kind of change to occur (rows added to a
+filling block, blocks that fill up and move to the full part of their list, new blocks, threads replaced by a
+thread forked from them), and after EVERY step all output rows are compared with the oracle over the very
+tensors the library was given, and the exported plan with the threads' tables.
+"""
+import numpy as np
+import pytest
+
+import paper_2401_06761_amd as ap
+from apar_workloads import make_config, node_kv_device
+from oracle import attend, fp8
+from paper_2401_06761_amd.driver import TreeRun
+
+from harness import PlanTablesOnDevice, assert_close, check_plan_covers_tables
+
+pytestmark = pytest.mark.gpu
+
+
+def _rows_of(w, run, t, cache):
+    """K, V of thread t as float64: its root path's segments (as handed to the library) and the rows the steps added."""
+    node = run.node_of[t]
+    ks, vs = [], []
+    for a in w.root_path(node):
+        if a not in cache:
+            k, v = node_kv_device(w, a)
+            cache[a] = (k.float().cpu().numpy().astype(np.float64), v.float().cpu().numpy().astype(np.float64))
+        ks.append(cache[a][0])
+        vs.append(cache[a][1])
+    for bank, row in run.extra_rows[t]:
+        ks.append(cache[("bank", bank)][0][row:row + 1])
+        vs.append(cache[("bank", bank)][1][row:row + 1])
+    return np.concatenate(ks), np.concatenate(vs)
+
+
+@pytest.mark.parametrize("name,n_req,kv_fp8,reuse", [("ht256", 4, False, True), ("gqa1024", 2, False, True),
+                                                     ("mha64", 4, True, True), ("ht256", 2, False, False)])
+def test_every_step_of_a_decode_loop_matches_the_oracle(name, n_req, kv_fp8, reuse):
+    import torch
+
+    steps = 36
+    w = make_config(name, n_requests=n_req, data_scale=1.0, kv_fp8=kv_fp8)
+    hd = w.heads
+    run = TreeRun(w, headroom_steps=steps + 4, churn=0.04)
+    try:
+        run.build()
+        ap.apar_set_plan_reuse(run.h, reuse)
+        cache = {}
+        for b, (_, k, v) in enumerate(run.banks):
+            cache[("bank", b)] = (k.float().cpu().numpy().astype(np.float64), v.float().cpu().numpy().astype(np.float64))
+        scale = 1.0 / np.sqrt(hd.head_dim)
+        worst = 0.0
+        on_device = PlanTablesOnDevice(run.h)
+        for step in range(steps):
+            run.step(record=True)
+            torch.cuda.synchronize()
+            rec = run.records[-1]
+            out = run.out.float().cpu().numpy().astype(np.float64)
+            q_bank = run.banks[rec.bank][0].float().cpu().numpy().astype(np.float64)
+            wants = []
+            for pos, t in enumerate(rec.live):
+                K, V = _rows_of(w, run, t, cache)
+                assert K.shape[0] == ap.apar_thread_len(run.h, t)
+                if kv_fp8:
+                    K, V = fp8.cached_rows(K, V)
+                wants.append(attend(q_bank[pos], K, V, scale))
+            worst = max(worst, assert_close(out[:len(rec.live)], np.stack(wants), hd.dtype, f"{name} step {step}"))
+            on_device.follow()
+            if step % 4 == 0 or step > steps - 4:
+                check_plan_covers_tables(run.h, rec.live, hd.n_kv_heads, hd.n_q_heads // hd.n_kv_heads)
+        built, carried = ap.apar_plan_counts(run.h)
+        assert built + carried == steps
+        # every thread takes a new block within 16 steps and the lists leave room for several: one plan lasts the loop
+        assert (built <= 2 and carried >= steps - 2) if reuse else carried == 0
+        print(f"{w.name}: {len(run.live)} threads, {steps} steps, plans built {built}, carried over {carried}, "
+              f"max abs err {worst:.2e}")
+    finally:
+        run.close()
+
+
+def test_a_carried_plan_follows_copy_on_write_and_gives_way_to_other_changes():
+    """Hand-made loop on one pool: a listed thread whose filling last block is also held by a thread that is not
+    listed (the library copies it on the next append and the carried plan must read the copy); then changes a
+    carried plan cannot follow - another thread listed, a thread appended to while its last block is shared with
+    another listed thread, many rows at once - after which the call builds a new plan.  Outputs against the oracle
+    every time."""
+    import torch
+
+    from apar_workloads import HeadConfig
+    from oracle import DenseThreads
+
+    heads = HeadConfig(8, 2, 128, "bf16")
+    rng = np.random.default_rng(3)
+    dense = DenseThreads(heads.n_q_heads, heads.n_kv_heads, heads.head_dim)
+    from apar_workloads import quantise
+
+    def rows(n):
+        k = quantise(rng.standard_normal((n, 2, 128)).astype(np.float32), "bf16")
+        v = quantise(rng.standard_normal((n, 2, 128)).astype(np.float32), "bf16")
+        return k, v
+
+    def dev(x):
+        return torch.from_numpy(x).cuda().to(torch.bfloat16)
+
+    with ap.Pool(8, 2, 128, "bf16", 256, max_threads=64) as pool:
+        h = pool.handle
+        ap.apar_set_write_checks(h, True)
+
+        def append(t, n):
+            k, v = rows(n)
+            ap.apar_append_kv(h, t, dev(k), dev(v), n)
+            dense.append(t, k.astype(np.float64), v.astype(np.float64))
+
+        def fork(t, n):
+            kids = ap.apar_fork(h, t, n)
+            assert tuple(dense.fork(t, n)) == tuple(kids)
+            return list(kids)
+
+        def decode(listed, expect_carried):
+            before = ap.apar_plan_counts(h)
+            q = quantise(rng.standard_normal((len(listed), 8, 128)).astype(np.float32), "bf16")
+            qd = dev(q)
+            out = torch.empty_like(qd)
+            ap.apar_decode_attention(h, qd, np.asarray(listed, dtype=np.int32), out)
+            torch.cuda.synchronize()
+            after = ap.apar_plan_counts(h)
+            assert (after[1] - before[1] == 1) == expect_carried and sum(after) - sum(before) == 1
+            check_plan_covers_tables(h, listed, 2, 4)
+            assert_close(out.float().cpu().numpy().astype(np.float64), dense.decode(q.astype(np.float64), listed), "bf16",
+                         f"listed {listed}")
+
+        root = ap.apar_thread_create(h)
+        assert dense.create() == root
+        append(root, 37)
+        a, b, c = fork(root, 3)
+        for t, n in ((a, 5), (b, 20), (c, 1)):
+            append(t, n)
+        listed = [a, b, c]
+        decode(listed, False)
+        decode(listed, True)                      # nothing changed at all
+        for t in listed:
+            append(t, 1)
+        decode(listed, True)
+        (shadow,) = fork(a, 1)                    # a's filling last block now has a second holder, not listed
+        append(a, 1)                              # ... so this row goes to a copy
+        assert ap.apar_pool_stats(h).cow_copies >= 4
+        decode(listed, True)
+        for _ in range(20):                       # through a block boundary for each of them
+            for t in listed:
+                append(t, 1)
+            decode(listed, True)
+        (a2,) = fork(a, 1)                        # a replaced by a thread forked from it
+        ap.apar_free_thread(h, a)
+        dense.free(a)
+        listed = [a2, b, c]
+        append(a2, 3)
+        decode(listed, True)
+        append(b, 40)                             # more than one new block: a new plan
+        decode(listed, False)
+        decode(listed + [shadow], False)          # another thread listed
+        decode(listed + [shadow], True)
+        d1, d2 = fork(c, 2)                       # two listed threads sharing their last block ...
+        listed = [a2, b, d1, d2]
+        decode(listed, False)
+        decode(listed, True)                      # ... can be carried while neither grows
+        append(d1, 1)
+        decode(listed, False)
+        decode(listed, True)
+        ap.apar_set_chunk_blocks(h, 2)            # a planning knob moved
+        decode(listed, False)
+        ap.apar_set_plan_reuse(h, False)
+        decode(listed, False)

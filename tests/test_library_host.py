@@ -10,7 +10,7 @@ import paper_2401_06761_amd as ap
 from apar_workloads import HeadConfig, make_config, manual_tree, tiny_tree
 from oracle import BlockLedger
 
-from harness import (blocks_upper_bound, books_equal, check_plan_covers_tables, nested_wide_tree, pool_for, random_forest,
+from harness import (PlanTablesOnDevice, blocks_upper_bound, books_equal, check_plan_covers_tables, nested_wide_tree, pool_for, random_forest,
                      replay_trace)
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -313,6 +313,68 @@ def test_random_forest_plans_cover_every_table(seed):
             else:
                 ap.apar_decode_attention_spec(h, None, None, None, None, C, listed, None)
             check_plan_covers_tables(h, listed, n_kv, C * group)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_plans_carried_over_a_decode_loop_cover_every_table(seed):
+    """Decode loops on bookkeeping-only pools over random forests (Alg. 1's per-step loop: the same threads, each
+    a row longer, a few replaced by a thread forked from them): from the second step on the plan is the previous
+    one brought up to date, and after every step it must show every row group exactly its thread's blocks with
+    the right fill counts, like a plan built afresh.  Planner knobs, head grouping and candidate counts vary; some
+    loops commit several rows per step, fork threads that are not listed (their parent's next row then goes to a
+    copy-on-write copy) or grow a thread by several blocks at once (which a carried plan cannot follow: that call
+    builds a new one)."""
+    rng = np.random.default_rng(9000 + seed)
+    n_kv = int(rng.choice([1, 2]))
+    group = int(rng.choice([1, 2, 4, 8, 16]))
+    parents, segs = random_forest(rng, int(rng.integers(1, 4)), int(rng.integers(8, 120)))
+    w = manual_tree(parents, segs, HeadConfig(n_kv * group, n_kv, 128, "bf16"), seed=seed)
+    steps = 40
+    n_leaves = len(w.leaves())
+    N = blocks_upper_bound(w) + n_leaves * (steps // 4 + 8) + 256
+    with pool_for(w, N, dry_run=True, max_threads=len(parents) + n_leaves * (steps + 8) + 64) as pool:
+        h = pool.handle
+        live, _ = replay_trace(w, pool, None, dry_run=True)
+        listed = [int(x) for x in rng.permutation(live)]
+        ap.apar_set_chunk_blocks(h, int(rng.choice([2, 5, 16, 512])))
+        ap.apar_set_matrix_units(h, int(rng.choice([0, 1, 64])), int(rng.choice([1, 3, 128])))
+        ap.apar_set_inline_shared(h, bool(rng.integers(0, 2)))
+        C = int(rng.choice([1, 1, 2, 4]))
+        if C * group > 64:
+            C = 1
+        spec = C > 1 or bool(rng.integers(0, 2))
+        rough = seed % 3 == 2  # loops with the changes a carried plan cannot follow
+        expected_built = 1
+        on_device = PlanTablesOnDevice(h)
+        for step in range(steps):
+            changed_shape = False
+            for pos in range(len(listed)):
+                coin = rng.integers(0, 40)
+                if coin == 0:    # a thread finishes and one forked from it carries on in its place
+                    (child,) = ap.apar_fork(h, listed[pos], 1)
+                    ap.apar_free_thread(h, listed[pos])
+                    listed[pos] = child
+                elif coin == 1:  # forked, the fork not listed
+                    ap.apar_fork(h, listed[pos], 1)
+                elif coin == 2 and rough and step > 0:
+                    ap.apar_append_kv(h, listed[pos], None, None, 33)
+                    changed_shape = True
+            if spec and rng.integers(0, 2):
+                masks = rng.integers(0, 1 << min(C, 3), size=len(listed)).astype(np.uint8)
+                ap.apar_commit_candidates(h, listed, None, None, C, masks)
+            else:
+                ap.apar_append_kv_batch(h, listed, None, None)
+            if spec:
+                ap.apar_decode_attention_spec(h, None, None, None, None, C, listed, None)
+            else:
+                ap.apar_decode_attention(h, None, listed, None)
+            check_plan_covers_tables(h, listed, n_kv, C * group)
+            on_device.follow()
+            expected_built += 1 if changed_shape else 0
+        built, carried = ap.apar_plan_counts(h)
+        assert built + carried == steps
+        # besides the calls that had to, a new plan is only built when a list has no free entry left behind it
+        assert expected_built <= built <= expected_built + 3, (built, carried, expected_built)
 
 
 def _sanitizer_build(tmp_path, name, sources, extra=()):
