@@ -104,6 +104,7 @@ struct apar_pool {
 
     StageSlot stage[kStageSlots];
     int next_slot = 0;
+    size_t stage_want = 0;  // the largest staging request so far
     // The staging slot whose device half holds the tables of `plan`, as long as that is so: a call that carries
     // the plan over rewrites the changed words there instead of staging every table again.  Kept out of the
     // rotation meanwhile.  resident_behind: the host tables have moved on and the slot has not caught up yet
@@ -168,12 +169,17 @@ int acquire_stage(apar_pool* p, size_t bytes, StageSlot** out) {
         if (p->profiling) p->host_wait_ms += p->wait_in_call_ms;
     }
     if (!s.ev) HIP_TRY(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
+    // Growing a slot frees device memory, which waits for the GPU to drain: a slot grows to what the largest
+    // request so far would need, not just to this one, so that the slots of a loop whose calls alternate
+    // between small and large tables (row codes, plan updates) stop growing after one round.
+    p->stage_want = std::max(p->stage_want, bytes);
     if (s.cap < bytes) {
+        bytes = p->stage_want;
         if (s.host) HIP_TRY(hipHostFree(s.host));
         if (s.dev) HIP_TRY(hipFree(s.dev));
         s.host = s.dev = nullptr;
         s.cap = 0;
-        size_t cap = align_up(std::max(bytes + bytes / 2, (size_t)1 << 16), 4096);
+        size_t cap = align_up(std::max(bytes + bytes / 2, (size_t)1 << 20), 4096);
         HIP_TRY(hipHostMalloc((void**)&s.host, cap, hipHostMallocDefault));
         HIP_TRY(hipMalloc((void**)&s.dev, cap));
         s.cap = cap;
