@@ -7,7 +7,9 @@ apar_free_thread), every live thread appends the new token's K,V row (apar_appen
 with copy-on-write where a tail is shared), and all live threads attend over their root
 paths (apar_decode_attention).  Inputs are resident in HBM before the timed region.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value, unit, the step counts and times, `roofline` (the attention kernel's
+algorithmic bytes over its measured duration against the HBM peak), `cpu_baseline` (the oracle timed on the host),
+a breakdown of the step, the KV bytes resident, and the other configurations under `secondary`.
 """
 from __future__ import annotations
 
@@ -584,8 +586,8 @@ def main() -> int:
                      help="also run one plain 4 GiB device copy (reference for HBM byte counters)")
     args = ap_.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by request with no exchange; "
-              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (the path would shard by request, each GPU with a pool of "
+              "its own and nothing to exchange); --gpus must be 1", file=sys.stderr)
         return 2
     special = args.shared_prefix or args.serving or args.prefill
     headline_default = not special and args.config == "ht256" and args.requests is None and not args.kv_fp8
