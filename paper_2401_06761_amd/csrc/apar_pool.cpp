@@ -404,7 +404,8 @@ int decode_common(apar_pool* p, const void* q, const void* cand_k, const void* c
     p->resident_behind = false;
     // a carried-over plan whose tables are still on the device from the previous call: only the words that
     // changed are sent, and written in place once the previous call's kernels are through
-    const bool in_place = carried && !fixed && p->resident && p->resident_bytes == ofs[5];
+    // (small tables are staged whole instead: one copy, against a copy and a launch)
+    const bool in_place = carried && !fixed && p->resident && p->resident_bytes == ofs[5] && ofs[5] >= kCopyStreamMinBytes;
     if (!in_place) p->resident = nullptr;
     if (in_place) {
         p->resident_behind = true;
