@@ -184,3 +184,77 @@ def test_a_carried_plan_follows_copy_on_write_and_gives_way_to_other_changes():
         decode(listed, False)
         ap.apar_set_plan_reuse(h, False)
         decode(listed, False)
+
+
+def test_carried_plans_between_other_calls_and_across_streams():
+    """A loop whose plan tables are large enough to be updated in place on the device, with other users of the
+    pool's staging memory and of its plan storage in between: the entry point that allocates nothing (it stages
+    whole tables in the static workspace and leaves the device copy behind), a prefill call (it builds a plan of its
+    own), a read-back of rows, and decode calls issued on another stream than the previous one.  A seeded sample of
+    threads is compared with the oracle after every decode call."""
+    import torch
+
+    w = make_config("ht256", n_requests=170, data_scale=1.0)
+    hd = w.heads
+    run = TreeRun(w, headroom_steps=24, churn=0.02)
+    try:
+        run.build()
+        h = run.h
+        cache = {}
+        for b, (_, k, v) in enumerate(run.banks):
+            cache[("bank", b)] = (k.float().cpu().numpy().astype(np.float64), v.float().cpu().numpy().astype(np.float64))
+        scale = 1.0 / np.sqrt(hd.head_dim)
+        which = sorted(int(x) for x in np.random.default_rng(2).choice(len(run.live), size=24, replace=False))
+        side = torch.cuda.Stream()  # (default priority)
+
+        def check(out, what):
+            torch.cuda.synchronize()
+            rec = run.records[-1]
+            got = out.float().cpu().numpy().astype(np.float64)
+            q_bank = run.banks[rec.bank][0].float().cpu().numpy().astype(np.float64)
+            wants = []
+            for pos in which:
+                K, V = _rows_of(w, run, rec.live[pos], cache)
+                wants.append(attend(q_bank[pos], K, V, scale))
+            assert_close(got[which], np.stack(wants), hd.dtype, what)
+
+        def carried_since(before):
+            return ap.apar_plan_counts(h)[1] - before[1]
+
+        run.step(record=True)
+        check(run.out, "first step")
+        c0 = ap.apar_plan_counts(h)
+        run.step(record=True)
+        check(run.out, "carried, tables updated in place")
+        assert carried_since(c0) == 1
+        # the same threads through the entry point that allocates nothing: carried on the host, staged whole
+        ids = np.asarray(run.records[-1].live, dtype=np.int32)
+        q = run.banks[run.records[-1].bank][0]
+        out2 = torch.empty_like(run.out)
+        ap.apar_decode_attention_fixed(h, q, ids, out2)
+        check(out2, "fixed entry point on a carried plan")
+        assert carried_since(c0) == 2
+        run.step(record=True)   # the device copy was left behind by the fixed call: whole tables again
+        check(run.out, "carried after the fixed call")
+        run.step(record=True)
+        check(run.out, "carried, in place again")
+        assert carried_since(c0) == 4
+        # a prefill call uses the pool's plan storage: the next decode call builds
+        t0 = int(run.live[0])
+        m = min(8, ap.apar_thread_len(h, t0))
+        qp = run.banks[0][0][:m].contiguous()
+        ap.apar_prefill_attention(h, qp, [t0], [m], torch.empty_like(qp))
+        kk = torch.empty((4, hd.n_kv_heads, hd.head_dim), dtype=torch.bfloat16, device="cuda")
+        ap.apar_read_kv_rows(h, t0, 0, 4, kk, torch.empty_like(kk))
+        b0 = ap.apar_plan_counts(h)
+        run.step(record=True)
+        check(run.out, "built after a prefill call")
+        assert ap.apar_plan_counts(h)[0] - b0[0] == 1
+        # decode calls on alternating streams: the in-place update waits for the previous call's kernels
+        for k in range(4):
+            with torch.cuda.stream(side if k % 2 == 0 else torch.cuda.default_stream()):
+                run.step(record=True)
+            check(run.out, f"carried on stream {k % 2}")
+        assert ap.apar_plan_counts(h)[0] - b0[0] == 1
+    finally:
+        run.close()
