@@ -356,12 +356,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         auto to_stage = [&](auto full_tile) {
             char* dst = stage[wave] + lane * 16;
             if constexpr (F8 && decltype(full_tile)::value) {
+                // the codes are widened once, by the wavefront that fetched them: what is staged is the bf16 tile in
+                // operand order, as on a bf16 pool, and the four consumers read it as such
+                Frag ks[4], vs[4];
+                const u32x4 kraw[2] = {rk[0], rk[1]}, vraw[2] = {rv[0], rv[1]};
+                fp8_operands(kraw, rsc.x, ks);
+                fp8_operands(vraw, rsc.y, vs);
 #pragma unroll
-                for (int rp = 0; rp < 2; ++rp) {
-                    *reinterpret_cast<u32x4*>(dst + rp * 1024) = rk[rp];
-                    *reinterpret_cast<u32x4*>(dst + kFp8HalfBytes + rp * 1024) = rv[rp];
+                for (int r = 0; r < 4; ++r) {
+                    *reinterpret_cast<u32x4*>(dst + r * 1024) = ks[r].u;
+                    *reinterpret_cast<u32x4*>(dst + 4096 + r * 1024) = vs[r].u;
                 }
-                if (lane == 0) *reinterpret_cast<f32x2*>(stage[wave] + kFp8ScaleOfs) = rsc;
             } else {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -372,21 +377,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         };
         // the operands of a staged full tile
         auto staged_operands = [&](const char* sb, Frag (&ks)[4], Frag (&vs)[4]) {
-            if constexpr (F8) {
-                u32x4 kraw[2], vraw[2];
 #pragma unroll
-                for (int rp = 0; rp < 2; ++rp) kraw[rp] = *reinterpret_cast<const u32x4*>(sb + rp * 1024 + lane * 16);
+            for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
 #pragma unroll
-                for (int rp = 0; rp < 2; ++rp) vraw[rp] = *reinterpret_cast<const u32x4*>(sb + kFp8HalfBytes + rp * 1024 + lane * 16);
-                const f32x2 sc = *reinterpret_cast<const f32x2*>(sb + kFp8ScaleOfs);
-                fp8_operands(kraw, sc.x, ks);
-                fp8_operands(vraw, sc.y, vs);
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) ks[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
-            }
+            for (int r = 0; r < 4; ++r) vs[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
         };
         auto consume = [&](int t, const char* sb, auto full_only) {
             constexpr bool kFull = decltype(full_only)::value;
@@ -455,19 +449,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NT == 1 ? 3
         auto consume_two_seen_by_all = [&](const char* sa, const char* sb) {
             if (wi.n_grp == 0) return;
             Frag ka[4], kb[4], va[4], vb[4];
-            if constexpr (F8) {
-                staged_operands(sa, ka, va);
-                staged_operands(sb, kb, vb);
-            } else {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) ka[r].u = *reinterpret_cast<const u32x4*>(sa + r * 1024 + lane * 16);
+            for (int r = 0; r < 4; ++r) ka[r].u = *reinterpret_cast<const u32x4*>(sa + r * 1024 + lane * 16);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) kb[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
+            for (int r = 0; r < 4; ++r) kb[r].u = *reinterpret_cast<const u32x4*>(sb + r * 1024 + lane * 16);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) va[r].u = *reinterpret_cast<const u32x4*>(sa + 4096 + r * 1024 + lane * 16);
+            for (int r = 0; r < 4; ++r) va[r].u = *reinterpret_cast<const u32x4*>(sa + 4096 + r * 1024 + lane * 16);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) vb[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
-            }
+            for (int r = 0; r < 4; ++r) vb[r].u = *reinterpret_cast<const u32x4*>(sb + 4096 + r * 1024 + lane * 16);
             f32x4 s0[NT], s1[NT];
             float top[NT];
             bool ran_away = false;
