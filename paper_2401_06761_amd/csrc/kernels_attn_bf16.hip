@@ -39,9 +39,10 @@
 //
 // fp8 pools (template parameter F8): a full block holds fp8 codes in the same element order, half the
 // bytes, and one power-of-two scale per half.  Its tiles are fetched with two 16-byte loads per lane and
-// half, staged in LDS as they are, and turned into the bf16 operands on their way into the registers by
-// the hardware conversion that multiplies by the scale (exact: a code times a power of two is a bf16
-// value).  Everything after that - products, softmax, accumulation - is the code of the bf16 pool.
+// half and turned into the bf16 operands by the hardware conversion that multiplies by the scale (exact: a
+// code times a power of two is a bf16 value) - private tiles on their way into the operand registers,
+// shared tiles once, by the wavefront that stages them, so that LDS holds the bf16 tile.  Everything after
+// that - products, softmax, accumulation - is the code of the bf16 pool.
 // Blocks that are still filling are bf16 rows on either pool.
 //
 // Softmax runs in base 2 with a lazily updated reference: a row's reference
