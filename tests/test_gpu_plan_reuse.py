@@ -45,7 +45,7 @@ def _rows_of(w, run, t, cache):
 def test_every_step_of_a_decode_loop_matches_the_oracle(name, n_req, kv_fp8, reuse, sample):
     import torch
 
-    steps = 36
+    steps = 26
     w = make_config(name, n_requests=n_req, data_scale=1.0, kv_fp8=kv_fp8)
     hd = w.heads
     run = TreeRun(w, headroom_steps=steps + 4, churn=0.04)
