@@ -258,3 +258,55 @@ def test_carried_plans_between_other_calls_and_across_streams():
         assert ap.apar_plan_counts(h)[0] - b0[0] == 1
     finally:
         run.close()
+
+
+@pytest.mark.parametrize("seed,n_q,n_kv,C", [(0, 8, 2, 3), (1, 4, 4, 5), (2, 16, 2, 2)])
+def test_multi_candidate_loop_over_one_list_carries_its_plans(seed, n_q, n_kv, C):
+    """The multi-candidate step (Sec. 3.2, App. C.1) in a loop over one list of threads on a random forest: attention
+    over the cache and the visible candidates, then the accepted candidates (0 to C rows per thread) are committed;
+    now and then a thread is replaced by a thread forked from it.  Every step's rows against the oracle; the plan is
+    built once and carried from then on (several rows per thread and step, several row slices per thread)."""
+    import torch
+
+    from apar_workloads import HeadConfig, draw_candidate_tree, manual_tree, mask_rows_from_parents, quantise
+    from oracle import DenseThreads
+
+    from harness import blocks_upper_bound, pool_for, random_forest, replay_trace, to_dev, to_host
+
+    rng = np.random.default_rng(7700 + seed)
+    parents, segs = random_forest(rng, 2, 40)
+    w = manual_tree(parents, segs, HeadConfig(n_q, n_kv, 128, "bf16"), seed=seed, data_scale=0.5)
+    steps = 14
+    n_leaves = len(w.leaves())
+    N = blocks_upper_bound(w) + n_leaves * (steps * C // 16 + 4) + 64
+    with pool_for(w, N, max_threads=len(parents) + n_leaves * (steps + 4) + 16) as pool:
+        h = pool.handle
+        dense = DenseThreads(n_q, n_kv, 128)
+        live, _ = replay_trace(w, pool, None, dense)
+        listed = [int(x) for x in rng.permutation(live)]
+        on_device = PlanTablesOnDevice(h)
+        for step in range(steps):
+            n = len(listed)
+            q = quantise(0.5 * rng.standard_normal((n, C, n_q, 128)).astype(np.float32), "bf16")
+            ck = quantise(0.5 * rng.standard_normal((n, C, n_kv, 128)).astype(np.float32), "bf16")
+            cv = quantise(0.5 * rng.standard_normal((n, C, n_kv, 128)).astype(np.float32), "bf16")
+            masks = np.stack([mask_rows_from_parents(draw_candidate_tree(rng, C)) for _ in range(n)])
+            qd, ckd, cvd = to_dev(q, "bf16"), to_dev(ck, "bf16"), to_dev(cv, "bf16")
+            out = torch.empty_like(qd)
+            ap.apar_decode_attention_spec(h, qd, ckd, cvd, torch.from_numpy(masks).cuda(), C, listed, out)
+            torch.cuda.synchronize()
+            assert_close(to_host(out), dense.decode_spec(q, ck, cv, masks, listed), "bf16", f"step {step}")
+            check_plan_covers_tables(h, listed, n_kv, C * (n_q // n_kv))
+            on_device.follow()
+            accept = rng.integers(0, 1 << C, size=n).astype(np.uint8)
+            ap.apar_commit_candidates(h, listed, ckd, cvd, C, accept)
+            dense.commit_candidates(listed, ck, cv, accept)
+            if step % 3 == 1:  # a thread finishes and one forked from it carries on in its place
+                pos = int(rng.integers(0, n))
+                (child,) = ap.apar_fork(h, listed[pos], 1)
+                assert dense.fork(listed[pos], 1) == [child]
+                ap.apar_free_thread(h, listed[pos])
+                dense.free(listed[pos])
+                listed[pos] = child
+        built, carried = ap.apar_plan_counts(h)
+        assert built + carried == steps and built <= 2, (built, carried)
